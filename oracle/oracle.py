@@ -1,0 +1,177 @@
+"""ctypes wrapper around oracle/snn_oracle.c (test infrastructure only).
+
+All arrays are host numpy arrays.  Nothing here touches a GPU or the HIP library.
+"""
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "snn_oracle.c")
+_LIB = os.path.join(_HERE, "libsnn_oracle.so")
+_lib = None
+
+
+def build(force=False):
+    """Compile the oracle with gcc.  -ffp-contract=off keeps every fp32 operation a
+    separately rounded IEEE operation (the scale multiply and the projection sums)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-std=c99", "-fopenmp", "-ffp-contract=off", "-fPIC", "-shared",
+               "-Wall", "-Wextra", "-o", _LIB, _SRC]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        _lib = ctypes.CDLL(_LIB)
+        _lib.snn_oracle_threads.restype = ctypes.c_int
+        _lib.snn_oracle_out_size.restype = ctypes.c_int
+        _lib.snn_oracle_two_stage_bin.restype = ctypes.c_int
+        _lib.snn_oracle_two_stage_f32.restype = ctypes.c_int
+    return _lib
+
+
+def _p(a):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _c(a, dtype):
+    a = np.ascontiguousarray(a, dtype=dtype)
+    return a
+
+
+def threads():
+    return int(_load().snn_oracle_threads())
+
+
+def out_size(n, stride):
+    return int(_load().snn_oracle_out_size(ctypes.c_int(n), ctypes.c_int(stride)))
+
+
+def decode(code):
+    """9-bit code -> (3,3) int8 array of +-1."""
+    w = np.zeros(9, dtype=np.int8)
+    _load().snn_oracle_decode(ctypes.c_uint16(int(code)), _p(w))
+    return w.reshape(3, 3)
+
+
+def sign(x):
+    x = _c(x, np.float32)
+    s = np.empty(x.shape, dtype=np.int8)
+    _load().snn_oracle_sign(_p(x), _p(s), ctypes.c_int64(x.size))
+    return s
+
+
+def pack_rows(x):
+    x = _c(x, np.float32)
+    N, C, H, W = x.shape
+    out = np.empty((N, C, H, (W + 31) // 32), dtype=np.uint32)
+    _load().snn_oracle_pack_rows(_p(x), _p(out), N, C, H, W)
+    return out
+
+
+def pack_channels(x):
+    x = _c(x, np.float32)
+    N, C, H, W = x.shape
+    out = np.empty((N, H, W, (C + 31) // 32), dtype=np.uint32)
+    _load().snn_oracle_pack_channels(_p(x), _p(out), N, C, H, W)
+    return out
+
+
+def expand(codebook, idx):
+    codebook = _c(codebook, np.uint16)
+    idx = _c(idx, np.uint16)
+    assert idx.size == 0 or int(idx.max()) < codebook.size
+    codes = np.empty(idx.shape, dtype=np.uint16)
+    _load().snn_oracle_expand(_p(codebook), _p(idx), ctypes.c_int64(idx.size), _p(codes))
+    return codes
+
+
+def _conv_args(x, codes, alpha, stride):
+    N, C_in, H, W = x.shape
+    codes = _c(codes, np.uint16)
+    C_out = codes.shape[0]
+    assert codes.shape == (C_out, C_in)
+    assert codes.size == 0 or int(codes.max()) < 512
+    alpha = _c(alpha, np.float32)
+    assert alpha.shape == (C_out,)
+    assert stride in (1, 2)
+    Ho, Wo = (H - 1) // stride + 1, (W - 1) // stride + 1
+    return N, C_in, C_out, H, W, Ho, Wo, codes, alpha
+
+
+def conv_bin(xs, codes, alpha, stride=1):
+    """Direct convolution, +-1 activations.  xs: int8 NCHW in {+1,-1}; codes: [C_out][C_in]
+    9-bit kernels.  Returns (S int32, Y float32), both [N][C_out][Ho][Wo]."""
+    xs = _c(xs, np.int8)
+    N, C_in, C_out, H, W, Ho, Wo, codes, alpha = _conv_args(xs, codes, alpha, stride)
+    S = np.empty((N, C_out, Ho, Wo), dtype=np.int32)
+    Y = np.empty((N, C_out, Ho, Wo), dtype=np.float32)
+    _load().snn_oracle_conv_bin(_p(xs), N, C_in, C_out, H, W, stride, _p(codes), _p(alpha), _p(S), _p(Y))
+    return S, Y
+
+
+def conv_f32(x, codes, alpha, stride=1):
+    """Direct convolution, fp32 activations, float64 accumulation.
+    Returns (S float64, Y float32)."""
+    x = _c(x, np.float32)
+    N, C_in, C_out, H, W, Ho, Wo, codes, alpha = _conv_args(x, codes, alpha, stride)
+    S = np.empty((N, C_out, Ho, Wo), dtype=np.float64)
+    Y = np.empty((N, C_out, Ho, Wo), dtype=np.float32)
+    _load().snn_oracle_conv_f32(_p(x), N, C_in, C_out, H, W, stride, _p(codes), _p(alpha), _p(S), _p(Y))
+    return S, Y
+
+
+def _two_stage_args(x, codebook, idx, alpha, stride):
+    N, C_in, H, W = x.shape
+    codebook = _c(codebook, np.uint16)
+    idx = _c(idx, np.uint16)
+    C_out = idx.shape[0]
+    assert idx.shape == (C_out, C_in)
+    K = codebook.size
+    assert idx.size == 0 or int(idx.max()) < K
+    alpha = _c(alpha, np.float32)
+    Ho, Wo = (H - 1) // stride + 1, (W - 1) // stride + 1
+    return N, C_in, C_out, H, W, Ho, Wo, K, codebook, idx, alpha
+
+
+def two_stage_bin(xs, codebook, idx, alpha, stride=1):
+    xs = _c(xs, np.int8)
+    N, C_in, C_out, H, W, Ho, Wo, K, codebook, idx, alpha = _two_stage_args(xs, codebook, idx, alpha, stride)
+    S = np.empty((N, C_out, Ho, Wo), dtype=np.int32)
+    Y = np.empty((N, C_out, Ho, Wo), dtype=np.float32)
+    rc = _load().snn_oracle_two_stage_bin(_p(xs), N, C_in, C_out, H, W, stride, _p(codebook), K,
+                                          _p(idx), _p(alpha), _p(S), _p(Y))
+    if rc != 0:
+        raise MemoryError("oracle two-stage temporary")
+    return S, Y
+
+
+def two_stage_f32(x, codebook, idx, alpha, stride=1):
+    x = _c(x, np.float32)
+    N, C_in, C_out, H, W, Ho, Wo, K, codebook, idx, alpha = _two_stage_args(x, codebook, idx, alpha, stride)
+    S = np.empty((N, C_out, Ho, Wo), dtype=np.float64)
+    Y = np.empty((N, C_out, Ho, Wo), dtype=np.float32)
+    rc = _load().snn_oracle_two_stage_f32(_p(x), N, C_in, C_out, H, W, stride, _p(codebook), K,
+                                          _p(idx), _p(alpha), _p(S), _p(Y))
+    if rc != 0:
+        raise MemoryError("oracle two-stage temporary")
+    return S, Y
+
+
+def project(w, codebook):
+    """Nearest subset member for every 3x3 kernel.  w: [..., 9] or [..., 3, 3] float32.
+    Returns (idx uint16 [n], score float32 [n])."""
+    w = _c(w, np.float32).reshape(-1, 9)
+    codebook = _c(codebook, np.uint16)
+    assert 1 <= codebook.size <= 512
+    n = w.shape[0]
+    idx = np.empty(n, dtype=np.uint16)
+    score = np.empty(n, dtype=np.float32)
+    _load().snn_oracle_project(_p(w), ctypes.c_int64(n), _p(codebook), int(codebook.size), _p(idx), _p(score))
+    return idx, score
