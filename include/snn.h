@@ -1,0 +1,148 @@
+/*
+ * snn.h - C ABI of the MI355X (gfx950) sub-bit binary 3x3 convolution library.
+ *
+ * The library implements the inference/forward hot path of "Sub-bit Neural Networks"
+ * (arXiv 2110.09195): a 3x3 convolution whose +-1 kernels are members of a small per-layer
+ * subset P (the "codebook", K = 2^tau binary 3x3 kernels out of 512) addressed by an index
+ * per (output channel, input channel) pair, evaluated in the two stages of Sec. 4.5 / Fig. 6
+ * (each input channel is convolved once with each of the K kernels; each output channel then
+ * gathers the pre-computed responses by index and sums them along c_in), plus the 1-bit
+ * XNOR/popcount convolution it is compared with (Sec. 3), the sign/bit-packing of
+ * activations (Alg. 1 forward) and the nearest-subset-member projection (Eq. 2 / Eq. 5).
+ *
+ * General rules for every entry point
+ *   - Every data pointer is a DEVICE pointer owned by the caller (hipMalloc / a torch CUDA
+ *     tensor's data_ptr).  Descriptor structs are HOST pointers, read before the call returns.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Every call only
+ *     enqueues work on that stream and returns without synchronising.
+ *   - The library never allocates, frees or keeps device memory; scratch space is the
+ *     caller's `workspace` (size from snn_workspace_bytes), used only during the call.
+ *     Two calls that share a workspace must be ordered (same stream, or synchronised).
+ *   - Return value: SNN_OK (0) or a negative SNN_ERR_* code.  On error nothing has been
+ *     enqueued.  No exceptions, no aborts, nothing printed.
+ *   - Values of idx[] must be < K and values of codebook[] / w9[] must be < 512; this is
+ *     not checked on the device (out-of-range values give undefined results, but only
+ *     memory inside the library's own tables is read with them: they are masked).
+ *
+ * Conventions (identical in the CPU oracle the library is tested against)
+ *   - Kernel code (Sec. 4.1): a binary 3x3 kernel is flattened row-major, +1 -> bit 1,
+ *     -1 -> bit 0, first element most significant.  code = paper index - 1, so 0 is the
+ *     all(-1) kernel and 511 the all(+1) kernel.  Tap t = 3*dy + dx is bit (8 - t).
+ *   - Convolution (Sec. 3): cross-correlation (no kernel flip), 3x3, zero padding 1,
+ *     stride 1 or 2, H_out = (H - 1) / stride + 1, no bias.  Taps that fall outside the
+ *     image contribute 0, also for +-1 activations.
+ *   - Activation sign (Alg. 1 forward): x >= 0 -> +1 (bit 1), otherwise -1 (bit 0); NaN -> -1.
+ *   - Output: fp32 NCHW, y[n][co][ho][wo] = (float)S * alpha[co] for +-1 activations (S the
+ *     exact integer sum, one fp32 multiply) and alpha[co] * S with S accumulated in fp32 for
+ *     fp32 activations.
+ */
+#ifndef SNN_H
+#define SNN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* status codes */
+#define SNN_OK               0
+#define SNN_ERR_INVALID_ARG (-1)  /* null pointer, non-positive size, K outside 1..512, bad enum */
+#define SNN_ERR_UNSUPPORTED (-2)  /* a valid request this build has no kernel for (listed per call) */
+#define SNN_ERR_WORKSPACE   (-3)  /* workspace pointer null or ws_bytes too small */
+#define SNN_ERR_LAUNCH      (-4)  /* the HIP runtime refused a launch */
+
+/* activation layouts (snn_conv_desc.act and the `layout` argument of snn_pack_activations) */
+#define SNN_ACT_BIN_ROWS     0    /* uint32 [N][C][H][ceil(W/32)], bit (w % 32) of word (w / 32) */
+#define SNN_ACT_BIN_CHANNELS 1    /* uint32 [N][H][W][ceil(C/32)], bit (c % 32) of word (c / 32) */
+#define SNN_ACT_F32          2    /* float  [N][C][H][W] (weight-only variant, W/A = x/32)       */
+/* In both packed layouts bit 1 means +1, and the unused high bits of a last word are 0. */
+
+/* which entry point a workspace is for */
+#define SNN_WS_SUBBIT 0
+#define SNN_WS_BNN    1
+
+/* One 3x3 layer (Sec. 3 notation: c_in, c_out, H, W of the input). */
+typedef struct snn_conv_desc {
+    int32_t N;       /* batch                                   */
+    int32_t C_in;    /* input channels  (1 .. 4096)             */
+    int32_t C_out;   /* output channels (>= 1)                  */
+    int32_t H, W;    /* input height and width                  */
+    int32_t stride;  /* 1 or 2                                  */
+    int32_t K;       /* subset size 1 .. 512 (ignored by snn_bnn_conv2d) */
+    int32_t act;     /* SNN_ACT_*                               */
+} snn_conv_desc;
+
+/*
+ * Alg. 1 forward, sign(a^{i-1}): binarise fp32 activations and pack them 32 per word.
+ *   x_nchw  device, float [N][C][H][W]
+ *   packed  device, snn_packed_bytes(N, C, H, W, layout) bytes, layout SNN_ACT_BIN_ROWS or
+ *           SNN_ACT_BIN_CHANNELS; fully overwritten.
+ * Errors: INVALID_ARG (null pointers, sizes < 1, layout not one of the two packed ones).
+ */
+int snn_pack_activations(const float *x_nchw, void *packed, int N, int C, int H, int W,
+                         int layout, void *stream);
+
+/*
+ * Eq. 2 / Eq. 5 / Alg. 1 forward: for each real-valued 3x3 kernel, the index of the nearest
+ * member of the subset, arg min_k ||P_k - w||^2 = arg max_k <P_k, w> (all members have the
+ * same norm).  The inner product is accumulated in fp32 from 0 over taps 0..8 in order,
+ * adding w_t where the member's tap is +1 and subtracting it where it is -1; among equal
+ * scores the lowest index wins.
+ *   w         device, float [n][9] (row-major 3x3 kernels, any (c_out, c_in) order)
+ *   codebook  device, uint16 [K], 9-bit codes (distinct, as Sec. 4.3 requires; duplicates
+ *             are harmless: the lower index is returned)
+ *   idx_out   device, uint16 [n]
+ * n = 0 is allowed and does nothing.  Errors: INVALID_ARG.
+ */
+int snn_project_kernels(const float *w, int64_t n, const uint16_t *codebook, int K,
+                        uint16_t *idx_out, void *stream);
+
+/*
+ * Sec. 4.5 / Fig. 6: the sub-bit convolution.  Stage 1 convolves every input channel with the
+ * K subset kernels (responses stay on chip), stage 2 sums, for each output channel, the
+ * responses its indices select; then y = alpha * S.
+ *   desc      host; act = SNN_ACT_BIN_ROWS (+-1 activations) or SNN_ACT_F32
+ *   x         device, activations in the layout desc->act names
+ *   codebook  device, uint16 [K] 9-bit codes
+ *   idx       device, uint16 [C_out][C_in], values < K
+ *   alpha     device, float [C_out]   (the paper's channel-wise lambda)
+ *   y_nchw    device, float [N][C_out][H_out][W_out], fully overwritten
+ *   workspace device, >= snn_workspace_bytes(desc, SNN_WS_SUBBIT) bytes, 256-byte aligned
+ * Errors: INVALID_ARG; UNSUPPORTED for act = SNN_ACT_BIN_CHANNELS (pack rows instead);
+ * WORKSPACE; LAUNCH.
+ */
+int snn_subbit_conv2d(const snn_conv_desc *desc, const void *x, const uint16_t *codebook,
+                      const uint16_t *idx, const float *alpha, float *y_nchw,
+                      void *workspace, size_t ws_bytes, void *stream);
+
+/*
+ * Sec. 3: the 1-bit layer a = lambda * (w_bar o a_bar), "o" = XNOR + bit count over words of
+ * 32 input channels.  The baseline every sub-bit number is compared with.
+ *   desc      host; act = SNN_ACT_BIN_CHANNELS (+-1 activations) or SNN_ACT_F32; K ignored
+ *   x         device, activations in the layout desc->act names
+ *   w9        device, uint16 [C_out][C_in], one 9-bit code per kernel
+ *   alpha, y_nchw, workspace (SNN_WS_BNN), stream: as above
+ * Errors: INVALID_ARG; UNSUPPORTED for act = SNN_ACT_BIN_ROWS, and for C_in > 512 with
+ * packed activations; WORKSPACE; LAUNCH.
+ */
+int snn_bnn_conv2d(const snn_conv_desc *desc, const void *x, const uint16_t *w9,
+                   const float *alpha, float *y_nchw, void *workspace, size_t ws_bytes,
+                   void *stream);
+
+/* Bytes of workspace the given entry point (SNN_WS_*) needs for this layer; 0 if desc is
+ * invalid or the combination is unsupported.  Host-only, no device work. */
+size_t snn_workspace_bytes(const snn_conv_desc *desc, int which);
+
+/* Bytes of a packed activation tensor in the given layout (also valid for SNN_ACT_F32);
+ * 0 for invalid arguments.  Host-only. */
+size_t snn_packed_bytes(int N, int C, int H, int W, int layout);
+
+/* Static, human-readable name of a status code. */
+const char *snn_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SNN_H */

@@ -1,0 +1,180 @@
+"""Thin ctypes binding of the C ABI in include/snn.h.
+
+Argument marshalling only: every function takes torch CUDA tensors (device memory) and passes
+their pointers, sizes and the current HIP stream to the library entry point of the same name.
+Nothing is computed here, and there is no fallback: if libsnn_hip.so has not been built the
+first call raises.
+"""
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libsnn_hip.so")
+
+SNN_OK = 0
+SNN_ERR_INVALID_ARG = -1
+SNN_ERR_UNSUPPORTED = -2
+SNN_ERR_WORKSPACE = -3
+SNN_ERR_LAUNCH = -4
+
+SNN_ACT_BIN_ROWS = 0
+SNN_ACT_BIN_CHANNELS = 1
+SNN_ACT_F32 = 2
+
+SNN_WS_SUBBIT = 0
+SNN_WS_BNN = 1
+
+EXPORTS = ("snn_pack_activations", "snn_project_kernels", "snn_subbit_conv2d", "snn_bnn_conv2d",
+           "snn_workspace_bytes", "snn_packed_bytes", "snn_status_string")
+
+
+class snn_conv_desc(ctypes.Structure):
+    _fields_ = [("N", ctypes.c_int32), ("C_in", ctypes.c_int32), ("C_out", ctypes.c_int32),
+                ("H", ctypes.c_int32), ("W", ctypes.c_int32), ("stride", ctypes.c_int32),
+                ("K", ctypes.c_int32), ("act", ctypes.c_int32)]
+
+
+class SnnError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = status
+        super().__init__("%s failed: %s (%d)" % (where, status_string(status), status))
+
+
+_lib = None
+
+
+def lib():
+    """Load libsnn_hip.so (built by `python -m paper_2110_09195_amd.build`)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError("HIP library not built: %s is missing; run "
+                               "`python -m paper_2110_09195_amd.build` (there is no CPU fallback)" % LIB_PATH)
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i32, i64, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_int64, ctypes.c_size_t
+        dp = ctypes.POINTER(snn_conv_desc)
+        L.snn_pack_activations.argtypes = [vp, vp, i32, i32, i32, i32, i32, vp]
+        L.snn_pack_activations.restype = i32
+        L.snn_project_kernels.argtypes = [vp, i64, vp, i32, vp, vp]
+        L.snn_project_kernels.restype = i32
+        L.snn_subbit_conv2d.argtypes = [dp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.snn_subbit_conv2d.restype = i32
+        L.snn_bnn_conv2d.argtypes = [dp, vp, vp, vp, vp, vp, sz, vp]
+        L.snn_bnn_conv2d.restype = i32
+        L.snn_workspace_bytes.argtypes = [dp, i32]
+        L.snn_workspace_bytes.restype = sz
+        L.snn_packed_bytes.argtypes = [i32, i32, i32, i32, i32]
+        L.snn_packed_bytes.restype = sz
+        L.snn_status_string.argtypes = [i32]
+        L.snn_status_string.restype = ctypes.c_char_p
+        _lib = L
+    return _lib
+
+
+def status_string(status):
+    return lib().snn_status_string(int(status)).decode()
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _check(status, where):
+    if status != SNN_OK:
+        raise SnnError(status, where)
+
+
+def _dev(t, dtype, name):
+    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.dtype == dtype and t.is_contiguous()):
+        raise TypeError("%s must be a contiguous CUDA tensor of %s" % (name, dtype))
+    return t
+
+
+def make_desc(N, C_in, C_out, H, W, stride=1, K=32, act=SNN_ACT_BIN_ROWS):
+    return snn_conv_desc(N, C_in, C_out, H, W, stride, K, act)
+
+
+def out_hw(desc):
+    return (desc.H - 1) // desc.stride + 1, (desc.W - 1) // desc.stride + 1
+
+
+def snn_packed_bytes(N, C, H, W, layout):
+    return int(lib().snn_packed_bytes(N, C, H, W, layout))
+
+
+def snn_workspace_bytes(desc, which):
+    return int(lib().snn_workspace_bytes(ctypes.byref(desc), which))
+
+
+def alloc_workspace(desc, which, device="cuda"):
+    n = snn_workspace_bytes(desc, which)
+    return torch.empty(max(n, 256), dtype=torch.uint8, device=device)
+
+
+def snn_pack_activations(x, layout, out=None):
+    """x: float32 [N][C][H][W] on the GPU -> packed int32 tensor (flat words) in `layout`."""
+    _dev(x, torch.float32, "x")
+    N, C, H, W = x.shape
+    nbytes = snn_packed_bytes(N, C, H, W, layout)
+    if out is None:
+        out = torch.empty(nbytes // 4, dtype=torch.int32, device=x.device)
+    _dev(out, torch.int32, "out")
+    if out.numel() * 4 < nbytes:
+        raise ValueError("packed buffer too small")
+    _check(lib().snn_pack_activations(_ptr(x), _ptr(out), N, C, H, W, layout, _stream()), "snn_pack_activations")
+    return out
+
+
+def snn_project_kernels(w, codebook, out=None):
+    """w: float32 [n][9]; codebook: int16 [K] (9-bit codes) -> int16 [n] indices."""
+    _dev(w, torch.float32, "w")
+    _dev(codebook, torch.int16, "codebook")
+    n = w.numel() // 9
+    if out is None:
+        out = torch.empty(n, dtype=torch.int16, device=w.device)
+    _dev(out, torch.int16, "out")
+    _check(lib().snn_project_kernels(_ptr(w), n, _ptr(codebook), codebook.numel(), _ptr(out), _stream()),
+           "snn_project_kernels")
+    return out
+
+
+def _conv_out(desc, y, device):
+    Ho, Wo = out_hw(desc)
+    if y is None:
+        y = torch.empty((desc.N, desc.C_out, Ho, Wo), dtype=torch.float32, device=device)
+    _dev(y, torch.float32, "y")
+    if y.numel() != desc.N * desc.C_out * Ho * Wo:
+        raise ValueError("y has the wrong size")
+    return y
+
+
+def snn_subbit_conv2d(desc, x, codebook, idx, alpha, y=None, workspace=None):
+    """x: packed int32 (rows layout) or float32 NCHW per desc.act; codebook int16 [K];
+    idx int16 [C_out][C_in]; alpha float32 [C_out] -> y float32 [N][C_out][Ho][Wo]."""
+    _dev(codebook, torch.int16, "codebook")
+    _dev(idx, torch.int16, "idx")
+    _dev(alpha, torch.float32, "alpha")
+    y = _conv_out(desc, y, x.device)
+    if workspace is None:
+        workspace = alloc_workspace(desc, SNN_WS_SUBBIT, x.device)
+    _check(lib().snn_subbit_conv2d(ctypes.byref(desc), _ptr(x), _ptr(codebook), _ptr(idx), _ptr(alpha), _ptr(y),
+                                   _ptr(workspace), workspace.numel(), _stream()), "snn_subbit_conv2d")
+    return y
+
+
+def snn_bnn_conv2d(desc, x, w9, alpha, y=None, workspace=None):
+    """x: packed int32 (channels layout) or float32 NCHW per desc.act; w9 int16 [C_out][C_in]."""
+    _dev(w9, torch.int16, "w9")
+    _dev(alpha, torch.float32, "alpha")
+    y = _conv_out(desc, y, x.device)
+    if workspace is None:
+        workspace = alloc_workspace(desc, SNN_WS_BNN, x.device)
+    _check(lib().snn_bnn_conv2d(ctypes.byref(desc), _ptr(x), _ptr(w9), _ptr(alpha), _ptr(y), _ptr(workspace),
+                                workspace.numel(), _stream()), "snn_bnn_conv2d")
+    return y

@@ -1,0 +1,231 @@
+// The 1-bit convolution of Sec. 3: a = lambda * (w_bar o a_bar), "o" = XNOR + bit count over
+// words of 32 input channels.  It is the denominator of every speed-up the sub-bit kernel
+// reports, so it is written to the same standard.
+//
+// Packed activations (SNN_ACT_BIN_CHANNELS): one lane owns one output pixel and keeps its whole
+// 3x3 x C_in window in registers (9 * C_in/32 words); output channels are walked in a loop whose
+// weight words are wave-uniform (scalar loads), so the inner loop is v_xor + v_bcnt_u32_b32 with
+// accumulate: 2 lane-ops per 32 multiply-adds.  Taps outside the image are loaded as 0 and the
+// mismatches they fake are taken out again with a per-(channel, border type) table.
+//
+// fp32 activations (SNN_ACT_F32, the W/A = 1/32 rows): the same direct loop with add/subtract.
+#include "snn_internal.h"
+
+namespace snn {
+
+namespace {
+
+constexpr int BNN_THREADS = 256;
+
+// workspace layout (packed activations):  wplanes [C_out][9][CWT] u32 | corr [C_out][16] i32
+// workspace layout (fp32 activations):    flips   [C_out][C_in]    u32 (bit t = tap t is -1)
+
+__global__ void bnn_prep_bin_kernel(const uint16_t *__restrict__ w9, int C_out, int C_in, int CWT,
+                                    uint32_t *__restrict__ wplanes, int32_t *__restrict__ corr)
+{
+    const int gid = blockIdx.x * blockDim.x + threadIdx.x;
+    const int nplane = C_out * 9 * CWT;
+    if (gid < nplane) {
+        const int cw = gid % CWT;
+        const int t = (gid / CWT) % 9;
+        const int co = gid / (9 * CWT);
+        uint32_t word = 0;
+        for (int c = 0; c < 32; ++c) {
+            const int ci = cw * 32 + c;
+            if (ci < C_in)
+                word |= (uint32_t)((w9[(int64_t)co * C_in + ci] >> (8 - t)) & 1) << c;
+        }
+        wplanes[gid] = word;
+    } else if (gid < nplane + C_out * 16) {
+        const int q = gid - nplane;
+        const int co = q >> 4, type = q & 15;
+        const uint32_t inv = border_invalid_window(type);
+        int32_t s = 0;
+        if (inv)
+            for (int ci = 0; ci < C_in; ++ci)
+                s += __popc(code_to_window_order(w9[(int64_t)co * C_in + ci] & 511u) & inv);
+        corr[q] = s;
+    }
+}
+
+__global__ void bnn_prep_f32_kernel(const uint16_t *__restrict__ w9, int64_t n, uint32_t *__restrict__ flips)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n)
+        flips[i] = (~code_to_window_order(w9[i] & 511u)) & 511u;
+}
+
+template <int CWT>
+__global__ __launch_bounds__(BNN_THREADS)
+void bnn_bin_kernel(const uint32_t *__restrict__ x, const uint32_t *__restrict__ wplanes,
+                    const int32_t *__restrict__ corr, const float *__restrict__ alpha, float *__restrict__ y,
+                    Geom g, int co_per_block)
+{
+    const int64_t p_raw = (int64_t)blockIdx.x * BNN_THREADS + threadIdx.x;
+    const bool active = p_raw < g.P;
+    const int64_t p = active ? p_raw : g.P - 1;
+    const int n = (int)(p / g.HoWo);
+    const int r = (int)(p - (int64_t)n * g.HoWo);
+    const int ho = r / g.Wo, wo = r - ho * g.Wo;
+    const int hc = ho * g.stride, wc = wo * g.stride;
+
+    uint32_t xr[9][CWT];
+#pragma unroll
+    for (int t = 0; t < 9; ++t) {
+        const int h = hc + t / 3 - 1, w = wc + t % 3 - 1;
+        const bool valid = (h >= 0) && (h < g.H) && (w >= 0) && (w < g.W);
+        const uint32_t *src = x + (((int64_t)n * g.H + (valid ? h : 0)) * g.W + (valid ? w : 0)) * g.CW;
+#pragma unroll
+        for (int cw = 0; cw < CWT; ++cw)
+            xr[t][cw] = (valid && cw < g.CW) ? src[cw] : 0u;
+    }
+    const int type = border_type(ho, wo, g.H, g.W, g.stride);
+    const int base = border_valid_taps(type) * g.C_in;
+
+    const int co0 = blockIdx.y * co_per_block;
+    const int co1 = min(co0 + co_per_block, g.C_out);
+    float *yp = y + ((int64_t)n * g.C_out) * g.HoWo + r;
+    for (int co = co0; co < co1; ++co) {
+        const uint32_t *wp = wplanes + (int64_t)co * 9 * CWT;   // wave-uniform
+        int mm = 0;
+#pragma unroll
+        for (int t = 0; t < 9; ++t)
+#pragma unroll
+            for (int cw = 0; cw < CWT; ++cw)
+                mm += __popc(xr[t][cw] ^ wp[t * CWT + cw]);
+        const int S = base - 2 * (mm - corr[co * 16 + type]);
+        if (active)
+            yp[(int64_t)co * g.HoWo] = (float)S * alpha[co];
+    }
+}
+
+constexpr int F32_CO = 8;    // output channels accumulated per lane
+constexpr int F32_CI = 4;    // input channels whose windows are held in registers
+
+__global__ __launch_bounds__(BNN_THREADS)
+void bnn_f32_kernel(const float *__restrict__ x, const uint32_t *__restrict__ flips,
+                    const float *__restrict__ alpha, float *__restrict__ y, Geom g)
+{
+    const int64_t p_raw = (int64_t)blockIdx.x * BNN_THREADS + threadIdx.x;
+    const bool active = p_raw < g.P;
+    const int64_t p = active ? p_raw : g.P - 1;
+    const int n = (int)(p / g.HoWo);
+    const int r = (int)(p - (int64_t)n * g.HoWo);
+    const int ho = r / g.Wo, wo = r - ho * g.Wo;
+    const int hc = ho * g.stride, wc = wo * g.stride;
+    const int co0 = blockIdx.y * F32_CO;
+
+    int off[9];
+    bool valid[9];
+#pragma unroll
+    for (int t = 0; t < 9; ++t) {
+        const int h = hc + t / 3 - 1, w = wc + t % 3 - 1;
+        valid[t] = (h >= 0) && (h < g.H) && (w >= 0) && (w < g.W);
+        off[t] = valid[t] ? h * g.W + w : 0;
+    }
+    float acc[F32_CO];
+#pragma unroll
+    for (int j = 0; j < F32_CO; ++j) acc[j] = 0.0f;
+
+    const int64_t plane = (int64_t)g.H * g.W;
+    for (int ci0 = 0; ci0 < g.C_in; ci0 += F32_CI) {
+        float xv[F32_CI][9];
+#pragma unroll
+        for (int c = 0; c < F32_CI; ++c) {
+            const bool cok = ci0 + c < g.C_in;
+            const float *src = x + ((int64_t)n * g.C_in + (cok ? ci0 + c : 0)) * plane;
+#pragma unroll
+            for (int t = 0; t < 9; ++t)
+                xv[c][t] = (cok && valid[t]) ? src[off[t]] : 0.0f;
+        }
+#pragma unroll
+        for (int j = 0; j < F32_CO; ++j) {
+            const int co = min(co0 + j, g.C_out - 1);
+#pragma unroll
+            for (int c = 0; c < F32_CI; ++c) {
+                const int ci = min(ci0 + c, g.C_in - 1);
+                const uint32_t fl = flips[(int64_t)co * g.C_in + ci];   // wave-uniform
+#pragma unroll
+                for (int t = 0; t < 9; ++t)
+                    acc[j] += __uint_as_float(__float_as_uint(xv[c][t]) ^ (((fl >> t) & 1u) << 31));
+            }
+        }
+    }
+    if (active) {
+#pragma unroll
+        for (int j = 0; j < F32_CO; ++j)
+            if (co0 + j < g.C_out)
+                y[((int64_t)n * g.C_out + co0 + j) * g.HoWo + r] = alpha[co0 + j] * acc[j];
+    }
+}
+
+int pow2_words(int CW)
+{
+    int c = 1;
+    while (c < CW) c <<= 1;
+    return c;
+}
+
+}  // namespace
+
+size_t bnn_workspace_bytes(const Geom &g, int act)
+{
+    if (act == SNN_ACT_F32) return align_up((size_t)g.C_out * g.C_in * sizeof(uint32_t), 256);
+    const int CWT = pow2_words(g.CW);
+    return align_up((size_t)g.C_out * 9 * CWT * sizeof(uint32_t), 256) + align_up((size_t)g.C_out * 16 * sizeof(int32_t), 256);
+}
+
+int launch_bnn(const Geom &g, int act, const void *x, const uint16_t *w9, const float *alpha, float *y,
+               void *ws, hipStream_t s)
+{
+    const int64_t pblocks = (g.P + BNN_THREADS - 1) / BNN_THREADS;
+    if (pblocks > 0x7fffffffLL) return SNN_ERR_INVALID_ARG;
+
+    if (act == SNN_ACT_F32) {
+        uint32_t *flips = (uint32_t *)ws;
+        const int64_t nk = (int64_t)g.C_out * g.C_in;
+        const int cgroups = (g.C_out + F32_CO - 1) / F32_CO;
+        if (cgroups > 65535) return SNN_ERR_UNSUPPORTED;
+        hipLaunchKernelGGL(bnn_prep_f32_kernel, dim3((unsigned)((nk + 255) / 256)), dim3(256), 0, s, w9, nk, flips);
+        hipLaunchKernelGGL(bnn_f32_kernel, dim3((unsigned)pblocks, (unsigned)cgroups), dim3(BNN_THREADS), 0, s,
+                           (const float *)x, flips, alpha, y, g);
+        return check_launch();
+    }
+
+    const int CWT = pow2_words(g.CW);
+    if (CWT > 16) return SNN_ERR_UNSUPPORTED;
+    uint32_t *wplanes = (uint32_t *)ws;
+    int32_t *corr = (int32_t *)((char *)ws + align_up((size_t)g.C_out * 9 * CWT * sizeof(uint32_t), 256));
+
+    // Enough workgroups to fill 256 CUs several times over: split the output channels when
+    // there are few pixels.
+    int co_per_block = g.C_out;
+    while (co_per_block > 16 && pblocks * ((g.C_out + co_per_block - 1) / co_per_block) < 2048)
+        co_per_block = (co_per_block + 1) / 2;
+    const int cgroups = (g.C_out + co_per_block - 1) / co_per_block;
+    if (cgroups > 65535) return SNN_ERR_UNSUPPORTED;
+
+    const int64_t nprep = (int64_t)g.C_out * 9 * CWT + (int64_t)g.C_out * 16;
+    hipLaunchKernelGGL(bnn_prep_bin_kernel, dim3((unsigned)((nprep + 255) / 256)), dim3(256), 0, s, w9, g.C_out,
+                       g.C_in, CWT, wplanes, corr);
+    const dim3 grid((unsigned)pblocks, (unsigned)cgroups), block(BNN_THREADS);
+    const uint32_t *xp = (const uint32_t *)x;
+#define SNN_BNN_CASE(CWT_)                                                                                   \
+    case CWT_:                                                                                               \
+        hipLaunchKernelGGL(bnn_bin_kernel<CWT_>, grid, block, 0, s, xp, wplanes, corr, alpha, y, g,           \
+                           co_per_block);                                                                    \
+        break;
+    switch (CWT) {
+        SNN_BNN_CASE(1)
+        SNN_BNN_CASE(2)
+        SNN_BNN_CASE(4)
+        SNN_BNN_CASE(8)
+        SNN_BNN_CASE(16)
+    default:
+        return SNN_ERR_UNSUPPORTED;
+    }
+#undef SNN_BNN_CASE
+    return check_launch();
+}
+
+}  // namespace snn

@@ -1,0 +1,119 @@
+// C entry points of the library: argument checks, workspace sizing, dispatch.
+#include "snn_internal.h"
+
+using namespace snn;
+
+namespace {
+
+bool desc_ok(const snn_conv_desc *d, bool need_K)
+{
+    if (!d) return false;
+    if (d->N < 1 || d->C_in < 1 || d->C_out < 1 || d->H < 1 || d->W < 1) return false;
+    if (d->C_in > 4096) return false;
+    if (d->stride != 1 && d->stride != 2) return false;
+    if (need_K && (d->K < 1 || d->K > 512)) return false;
+    if (d->act != SNN_ACT_BIN_ROWS && d->act != SNN_ACT_BIN_CHANNELS && d->act != SNN_ACT_F32) return false;
+    // element counts must fit the 32-bit pixel arithmetic of the kernels
+    const int64_t in_elems = (int64_t)d->N * d->C_in * d->H * d->W;
+    const int64_t out_elems = (int64_t)d->N * d->C_out * ((d->H - 1) / d->stride + 1) * ((d->W - 1) / d->stride + 1);
+    if (in_elems >= ((int64_t)1 << 40) || out_elems >= ((int64_t)1 << 40)) return false;
+    if ((int64_t)d->N * d->H * d->W >= ((int64_t)1 << 31)) return false;
+    return true;
+}
+
+bool subbit_act_supported(int act) { return act == SNN_ACT_BIN_ROWS || act == SNN_ACT_F32; }
+
+bool bnn_supported(const snn_conv_desc *d)
+{
+    if (d->act == SNN_ACT_F32) return true;
+    return d->act == SNN_ACT_BIN_CHANNELS && d->C_in <= 512;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *snn_status_string(int status)
+{
+    switch (status) {
+    case SNN_OK: return "SNN_OK";
+    case SNN_ERR_INVALID_ARG: return "SNN_ERR_INVALID_ARG";
+    case SNN_ERR_UNSUPPORTED: return "SNN_ERR_UNSUPPORTED";
+    case SNN_ERR_WORKSPACE: return "SNN_ERR_WORKSPACE";
+    case SNN_ERR_LAUNCH: return "SNN_ERR_LAUNCH";
+    default: return "SNN_ERR_UNKNOWN";
+    }
+}
+
+size_t snn_packed_bytes(int N, int C, int H, int W, int layout)
+{
+    if (N < 1 || C < 1 || H < 1 || W < 1) return 0;
+    switch (layout) {
+    case SNN_ACT_BIN_ROWS: return (size_t)N * C * H * ((W + 31) / 32) * sizeof(uint32_t);
+    case SNN_ACT_BIN_CHANNELS: return (size_t)N * H * W * ((C + 31) / 32) * sizeof(uint32_t);
+    case SNN_ACT_F32: return (size_t)N * C * H * W * sizeof(float);
+    default: return 0;
+    }
+}
+
+size_t snn_workspace_bytes(const snn_conv_desc *desc, int which)
+{
+    if (which == SNN_WS_SUBBIT) {
+        if (!desc_ok(desc, true) || !subbit_act_supported(desc->act)) return 0;
+        return subbit_workspace_bytes(make_geom(*desc), desc->act);
+    }
+    if (which == SNN_WS_BNN) {
+        if (!desc_ok(desc, false) || !bnn_supported(desc)) return 0;
+        return bnn_workspace_bytes(make_geom(*desc), desc->act);
+    }
+    return 0;
+}
+
+int snn_pack_activations(const float *x_nchw, void *packed, int N, int C, int H, int W, int layout,
+                         void *stream)
+{
+    if (!x_nchw || !packed || N < 1 || C < 1 || H < 1 || W < 1) return SNN_ERR_INVALID_ARG;
+    if ((int64_t)N * C * H * W >= ((int64_t)1 << 40) || (int64_t)H * W >= ((int64_t)1 << 31))
+        return SNN_ERR_INVALID_ARG;
+    hipStream_t s = (hipStream_t)stream;
+    if (layout == SNN_ACT_BIN_ROWS)
+        return launch_pack_rows(x_nchw, (uint32_t *)packed, (int64_t)N * C * H, W, s);
+    if (layout == SNN_ACT_BIN_CHANNELS)
+        return launch_pack_channels(x_nchw, (uint32_t *)packed, N, C, H, W, s);
+    return SNN_ERR_INVALID_ARG;
+}
+
+int snn_project_kernels(const float *w, int64_t n, const uint16_t *codebook, int K, uint16_t *idx_out,
+                        void *stream)
+{
+    if (n < 0 || K < 1 || K > 512 || !codebook) return SNN_ERR_INVALID_ARG;
+    if (n == 0) return SNN_OK;
+    if (!w || !idx_out) return SNN_ERR_INVALID_ARG;
+    if (n >= ((int64_t)1 << 40)) return SNN_ERR_INVALID_ARG;
+    return launch_project(w, n, codebook, K, idx_out, (hipStream_t)stream);
+}
+
+int snn_subbit_conv2d(const snn_conv_desc *desc, const void *x, const uint16_t *codebook,
+                      const uint16_t *idx, const float *alpha, float *y_nchw, void *workspace,
+                      size_t ws_bytes, void *stream)
+{
+    if (!desc_ok(desc, true) || !x || !codebook || !idx || !alpha || !y_nchw) return SNN_ERR_INVALID_ARG;
+    if (!subbit_act_supported(desc->act)) return SNN_ERR_UNSUPPORTED;
+    const Geom g = make_geom(*desc);
+    const size_t need = subbit_workspace_bytes(g, desc->act);
+    if (need > 0 && (!workspace || ws_bytes < need)) return SNN_ERR_WORKSPACE;
+    return launch_subbit(g, desc->act, x, codebook, idx, alpha, y_nchw, workspace, (hipStream_t)stream);
+}
+
+int snn_bnn_conv2d(const snn_conv_desc *desc, const void *x, const uint16_t *w9, const float *alpha,
+                   float *y_nchw, void *workspace, size_t ws_bytes, void *stream)
+{
+    if (!desc_ok(desc, false) || !x || !w9 || !alpha || !y_nchw) return SNN_ERR_INVALID_ARG;
+    if (!bnn_supported(desc)) return SNN_ERR_UNSUPPORTED;
+    const Geom g = make_geom(*desc);
+    const size_t need = bnn_workspace_bytes(g, desc->act);
+    if (need > 0 && (!workspace || ws_bytes < need)) return SNN_ERR_WORKSPACE;
+    return launch_bnn(g, desc->act, x, w9, alpha, y_nchw, workspace, (hipStream_t)stream);
+}
+
+}  // extern "C"

@@ -1,0 +1,92 @@
+// Internal declarations shared by the HIP translation units of the library (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "snn.h"
+
+namespace snn {
+
+// Geometry of one layer as the kernels see it.
+struct Geom {
+    int N, C_in, C_out, H, W, stride, K;
+    int Ho, Wo;          // output height and width
+    int HoWo;            // Ho * Wo
+    int64_t P;           // N * Ho * Wo output pixels
+    int WW;              // words per packed row  (rows layout)
+    int CW;              // words per packed pixel (channels layout)
+};
+
+inline Geom make_geom(const snn_conv_desc &d)
+{
+    Geom g;
+    g.N = d.N; g.C_in = d.C_in; g.C_out = d.C_out; g.H = d.H; g.W = d.W;
+    g.stride = d.stride; g.K = d.K;
+    g.Ho = (d.H - 1) / d.stride + 1;
+    g.Wo = (d.W - 1) / d.stride + 1;
+    g.HoWo = g.Ho * g.Wo;
+    g.P = (int64_t)d.N * g.HoWo;
+    g.WW = (d.W + 31) / 32;
+    g.CW = (d.C_in + 31) / 32;
+    return g;
+}
+
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// Border type of an output pixel: which rows / columns of its 3x3 window lie outside the image.
+//   bit 0: top row, bit 1: bottom row, bit 2: left column, bit 3: right column.
+__host__ __device__ inline int border_type(int ho, int wo, int H, int W, int stride)
+{
+    const int hc = ho * stride, wc = wo * stride;
+    return (hc == 0 ? 1 : 0) | (hc + 1 >= H ? 2 : 0) | (wc == 0 ? 4 : 0) | (wc + 1 >= W ? 8 : 0);
+}
+
+__host__ __device__ inline int border_valid_taps(int type)
+{
+    return (3 - (type & 1) - ((type >> 1) & 1)) * (3 - ((type >> 2) & 1) - ((type >> 3) & 1));
+}
+
+// Window mask of the taps that lie outside the image, in "window order": bit (3*dy + dx).
+__host__ __device__ inline uint32_t border_invalid_window(int type)
+{
+    uint32_t m = 0;
+    if (type & 1) m |= 0x007u;   // dy = 0
+    if (type & 2) m |= 0x1C0u;   // dy = 2
+    if (type & 4) m |= 0x049u;   // dx = 0
+    if (type & 8) m |= 0x124u;   // dx = 2
+    return m;
+}
+
+// A 9-bit kernel code has tap t at bit (8 - t); kernels work on windows with tap t at bit t.
+__host__ __device__ inline uint32_t code_to_window_order(uint32_t code)
+{
+    uint32_t r = 0;
+    for (int t = 0; t < 9; ++t)
+        r |= ((code >> (8 - t)) & 1u) << t;
+    return r;
+}
+
+// ---- launchers (each validates nothing: the C entry points did) -----------------------------
+
+int launch_pack_rows(const float *x, uint32_t *out, int64_t rows, int W, hipStream_t s);
+int launch_pack_channels(const float *x, uint32_t *out, int N, int C, int H, int W, hipStream_t s);
+
+int launch_project(const float *w, int64_t n, const uint16_t *codebook, int K, uint16_t *idx_out,
+                   hipStream_t s);
+
+size_t bnn_workspace_bytes(const Geom &g, int act);
+int launch_bnn(const Geom &g, int act, const void *x, const uint16_t *w9, const float *alpha,
+               float *y, void *ws, hipStream_t s);
+
+size_t subbit_workspace_bytes(const Geom &g, int act);
+int launch_subbit(const Geom &g, int act, const void *x, const uint16_t *codebook,
+                  const uint16_t *idx, const float *alpha, float *y, void *ws, hipStream_t s);
+
+inline int check_launch()
+{
+    return hipGetLastError() == hipSuccess ? SNN_OK : SNN_ERR_LAUNCH;
+}
+
+}  // namespace snn

@@ -1,0 +1,89 @@
+"""Helpers for the GPU parity tests: move seeded numpy inputs to the device, call the library
+through its binding (which only marshals arguments), bring results back."""
+import numpy as np
+import torch
+
+from paper_2110_09195_amd import binding as B
+
+
+def dev(a):
+    a = np.ascontiguousarray(a)
+    if a.dtype == np.uint16:
+        a = a.view(np.int16)
+    if a.dtype == np.uint32:
+        a = a.view(np.int32)
+    return torch.from_numpy(a).cuda()
+
+
+def host_u32(t):
+    return t.cpu().numpy().view(np.uint32)
+
+
+def host_u16(t):
+    return t.cpu().numpy().view(np.uint16)
+
+
+def pack(x, layout):
+    N, C, H, W = x.shape
+    out = B.snn_pack_activations(dev(x), layout)
+    torch.cuda.synchronize()
+    words = host_u32(out)
+    if layout == B.SNN_ACT_BIN_ROWS:
+        return words.reshape(N, C, H, (W + 31) // 32)
+    return words.reshape(N, H, W, (C + 31) // 32)
+
+
+def subbit_bin(x, codebook, idx, alpha, stride=1, packed=None):
+    """x: fp32 NCHW (its sign is the activation).  Packs with the library unless `packed`
+    (uint32 rows layout from the oracle) is given."""
+    N, C_in, H, W = x.shape
+    C_out = idx.shape[0]
+    d = B.make_desc(N, C_in, C_out, H, W, stride, int(codebook.size), B.SNN_ACT_BIN_ROWS)
+    xp = dev(packed) if packed is not None else B.snn_pack_activations(dev(x), B.SNN_ACT_BIN_ROWS)
+    y = B.snn_subbit_conv2d(d, xp, dev(codebook), dev(idx), dev(alpha))
+    torch.cuda.synchronize()
+    return y.cpu().numpy()
+
+
+def subbit_f32(x, codebook, idx, alpha, stride=1):
+    N, C_in, H, W = x.shape
+    C_out = idx.shape[0]
+    d = B.make_desc(N, C_in, C_out, H, W, stride, int(codebook.size), B.SNN_ACT_F32)
+    y = B.snn_subbit_conv2d(d, dev(x), dev(codebook), dev(idx), dev(alpha))
+    torch.cuda.synchronize()
+    return y.cpu().numpy()
+
+
+def bnn_bin(x, w9, alpha, stride=1):
+    N, C_in, H, W = x.shape
+    C_out = w9.shape[0]
+    d = B.make_desc(N, C_in, C_out, H, W, stride, 512, B.SNN_ACT_BIN_CHANNELS)
+    xp = B.snn_pack_activations(dev(x), B.SNN_ACT_BIN_CHANNELS)
+    y = B.snn_bnn_conv2d(d, xp, dev(w9), dev(alpha))
+    torch.cuda.synchronize()
+    return y.cpu().numpy()
+
+
+def bnn_f32(x, w9, alpha, stride=1):
+    N, C_in, H, W = x.shape
+    C_out = w9.shape[0]
+    d = B.make_desc(N, C_in, C_out, H, W, stride, 512, B.SNN_ACT_F32)
+    y = B.snn_bnn_conv2d(d, dev(x), dev(w9), dev(alpha))
+    torch.cuda.synchronize()
+    return y.cpu().numpy()
+
+
+def project(w, codebook):
+    out = B.snn_project_kernels(dev(w.reshape(-1, 9)), dev(codebook))
+    torch.cuda.synchronize()
+    return host_u16(out)
+
+
+def assert_f32_close(y, ref_y, ref_S_times_alpha=None, tol=1e-5):
+    """|y - ref| <= tol * max(|ref|, rms(ref)), element-wise (fp32-activation paths)."""
+    ref = ref_y.astype(np.float64)
+    rms = np.sqrt((ref ** 2).mean())
+    bound = tol * np.maximum(np.abs(ref), rms)
+    err = np.abs(y.astype(np.float64) - ref)
+    bad = err > bound
+    assert not bad.any(), "max err/bound = %g at %s" % ((err / bound).max(), np.argwhere(bad)[:4])

@@ -1,0 +1,292 @@
+"""GPU parity: the HIP library (through its C ABI) against the CPU oracle, element by element,
+on the same seeded inputs.  Bit-exact for +-1 activations, packing and projection indices;
+|y - ref| <= 1e-5 * max(|ref|, rms(ref)) for fp32 activations."""
+import sys
+
+import numpy as np
+import pytest
+
+from paper_2110_09195_amd import binding as B
+from paper_2110_09195_amd import synth
+from tests import gpu_util as G
+
+pytestmark = pytest.mark.gpu
+
+
+def _say(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def _inputs(seed, N, C_in, C_out, H, W, K, dist="uniform"):
+    g = np.random.default_rng(seed)
+    x = g.standard_normal((N, C_in, H, W), dtype=np.float32)
+    cb = synth.codebook(g, K)
+    idx = synth.indices(g, C_out, C_in, K, dist)
+    alpha = synth.alpha(g, C_out)
+    return x, cb, idx, alpha
+
+
+# ---- packing -------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("shape", [(2, 3, 4, 1), (2, 3, 5, 7), (3, 5, 14, 14), (2, 4, 3, 31), (8, 16, 32, 32),
+                                   (2, 3, 4, 33), (2, 2, 56, 56), (1, 2, 3, 64), (1, 3, 2, 100), (1, 1, 2, 8192),
+                                   (1, 1, 2, 9000), (1, 2, 1, 20000), (64, 8, 7, 7)])
+def test_pack_rows(oracle, shape):
+    _say("pack_rows", shape)
+    g = np.random.default_rng(hash(shape) % 2**32)
+    x = g.standard_normal(shape, dtype=np.float32)
+    x.flat[:: 7] = 0.0
+    x.flat[3:: 11] = -0.0
+    assert (G.pack(x, B.SNN_ACT_BIN_ROWS) == oracle.pack_rows(x)).all()
+
+
+@pytest.mark.parametrize("shape", [(2, 1, 4, 5), (2, 16, 32, 32), (3, 32, 7, 7), (2, 40, 5, 3), (2, 64, 8, 8),
+                                   (1, 100, 3, 3), (2, 256, 14, 14), (1, 512, 7, 7), (1, 33, 1, 1)])
+def test_pack_channels(oracle, shape):
+    _say("pack_channels", shape)
+    g = np.random.default_rng(hash(shape) % 2**32)
+    x = g.standard_normal(shape, dtype=np.float32)
+    x.flat[:: 5] = 0.0
+    assert (G.pack(x, B.SNN_ACT_BIN_CHANNELS) == oracle.pack_channels(x)).all()
+
+
+def test_pack_special_values(oracle):
+    x = np.array([0.0, -0.0, 1e-30, -1e-30, np.nan, np.inf, -np.inf, 1.0] * 8, dtype=np.float32).reshape(1, 1, 2, 32)
+    assert (G.pack(x, B.SNN_ACT_BIN_ROWS) == oracle.pack_rows(x)).all()
+    assert (G.pack(x, B.SNN_ACT_BIN_CHANNELS) == oracle.pack_channels(x)).all()
+
+
+# ---- 1-bit baseline ------------------------------------------------------------------------------------
+
+BNN_CASES = [
+    # N, C_in, C_out, H, W, stride
+    (2, 32, 16, 6, 6, 1), (2, 16, 16, 32, 32, 1), (3, 40, 10, 7, 9, 1), (2, 64, 24, 8, 8, 2), (2, 100, 7, 5, 4, 2),
+    (1, 1, 1, 1, 1, 1), (1, 3, 2, 1, 5, 1), (1, 3, 2, 5, 1, 2), (4, 256, 64, 14, 14, 1), (2, 512, 48, 7, 7, 1),
+    (2, 128, 32, 15, 13, 2), (3, 300, 9, 3, 3, 1),
+]
+
+
+@pytest.mark.parametrize("case", BNN_CASES)
+def test_bnn_bin(oracle, case):
+    _say("bnn_bin", case)
+    N, C_in, C_out, H, W, stride = case
+    g = np.random.default_rng(sum(case))
+    x = g.standard_normal((N, C_in, H, W), dtype=np.float32)
+    w9 = g.integers(0, 512, size=(C_out, C_in)).astype(np.uint16)
+    alpha = synth.alpha(g, C_out)
+    _, Y = oracle.conv_bin(oracle.sign(x), w9, alpha, stride)
+    y = G.bnn_bin(x, w9, alpha, stride)
+    assert y.shape == Y.shape
+    assert (y == Y).all(), np.argwhere(y != Y)[:5]
+
+
+@pytest.mark.parametrize("case", [(2, 8, 8, 6, 6, 1), (3, 13, 9, 7, 5, 2), (4, 64, 64, 8, 8, 1), (1, 1, 1, 1, 1, 1)])
+def test_bnn_f32(oracle, case):
+    _say("bnn_f32", case)
+    N, C_in, C_out, H, W, stride = case
+    g = np.random.default_rng(sum(case) + 1)
+    x = g.standard_normal((N, C_in, H, W), dtype=np.float32)
+    w9 = g.integers(0, 512, size=(C_out, C_in)).astype(np.uint16)
+    alpha = synth.alpha(g, C_out)
+    _, Y = oracle.conv_f32(x, w9, alpha, stride)
+    G.assert_f32_close(G.bnn_f32(x, w9, alpha, stride), Y)
+
+
+# ---- sub-bit convolution, +-1 activations ------------------------------------------------------------------
+
+SUBBIT_CASES = [
+    # N, C_in, C_out, H, W, stride, K, dist
+    (2, 8, 8, 6, 6, 1, 32, "uniform"),
+    (8, 16, 16, 32, 32, 1, 32, "uniform"),        # configuration 1 in full
+    (3, 40, 10, 7, 9, 1, 16, "uniform"),          # ragged channels, ragged tile tail
+    (2, 64, 24, 8, 8, 2, 64, "uniform"),
+    (2, 100, 7, 5, 4, 2, 5, "zipf"),              # K not a power of two
+    (1, 1, 1, 1, 1, 1, 1, "uniform"),             # everything degenerate
+    (1, 3, 2, 1, 5, 1, 2, "uniform"),             # H = 1: top and bottom outside at once
+    (1, 3, 2, 5, 1, 2, 2, "uniform"),             # W = 1
+    (2, 64, 64, 14, 14, 1, 32, "zipf"),
+    (2, 30, 130, 9, 9, 1, 32, "uniform"),         # more than one channel block per lane set
+    (1, 29, 300, 7, 7, 1, 32, "uniform"),         # C_out above the largest block: two channel blocks
+    (2, 57, 33, 35, 33, 1, 32, "uniform"),        # W crosses a packed word
+    (2, 20, 20, 66, 65, 2, 16, "uniform"),        # three packed words per row, stride 2
+    (2, 24, 16, 6, 6, 1, 100, "uniform"),         # K > 64: direct stage 1
+    (1, 16, 16, 5, 5, 1, 512, "uniform"),         # full subset through the sub-bit path
+    (3, 128, 128, 7, 7, 1, 32, "uniform"),        # 49-pixel images: unaligned float4 rows
+]
+
+
+@pytest.mark.parametrize("case", SUBBIT_CASES)
+def test_subbit_bin(oracle, case):
+    _say("subbit_bin", case)
+    N, C_in, C_out, H, W, stride, K, dist = case
+    x, cb, idx, alpha = _inputs(sum(case[:7]), N, C_in, C_out, H, W, K, dist)
+    _, Y = oracle.conv_bin(oracle.sign(x), oracle.expand(cb, idx), alpha, stride)
+    y = G.subbit_bin(x, cb, idx, alpha, stride)
+    assert y.shape == Y.shape
+    assert (y == Y).all(), np.argwhere(y != Y)[:5]
+
+
+def test_subbit_bin_takes_oracle_packed_input(oracle):
+    """The conv consumes the documented layout, whoever packed it."""
+    x, cb, idx, alpha = _inputs(77, 2, 12, 12, 9, 37, 32)
+    _, Y = oracle.conv_bin(oracle.sign(x), oracle.expand(cb, idx), alpha, 1)
+    y = G.subbit_bin(x, cb, idx, alpha, 1, packed=oracle.pack_rows(x))
+    assert (y == Y).all()
+
+
+def test_subbit_bin_all_indices_equal_and_extreme_codes(oracle):
+    g = np.random.default_rng(5)
+    x = g.standard_normal((2, 64, 6, 6), dtype=np.float32)
+    cb = np.array([0, 511, 0b101010101, 0b010101010], dtype=np.uint16)
+    alpha = np.ones(8, dtype=np.float32)
+    for k in range(4):
+        idx = np.full((8, 64), k, dtype=np.uint16)
+        S, Y = oracle.conv_bin(oracle.sign(x), oracle.expand(cb, idx), alpha, 1)
+        y = G.subbit_bin(x, cb, idx, alpha, 1)
+        assert (y == Y).all()
+    # all-(+1) input and kernel: the closed form 9/6/4 * C_in
+    ones = np.ones((1, 64, 6, 6), dtype=np.float32)
+    y = G.subbit_bin(ones, cb, np.full((8, 64), 1, dtype=np.uint16), alpha, 1)
+    assert y[0, 0, 2, 2] == 9 * 64 and y[0, 0, 0, 2] == 6 * 64 and y[0, 0, 0, 0] == 4 * 64
+
+
+def test_subbit_bin_many_input_channels_widening(oracle):
+    """C_in large enough for many byte -> 16-bit widenings, with the all-match worst case."""
+    N, C_in, C_out, H, W = 1, 512, 16, 5, 5
+    ones = np.ones((N, C_in, H, W), dtype=np.float32)
+    cb = np.array([511, 0], dtype=np.uint16)
+    idx = np.zeros((C_out, C_in), dtype=np.uint16)
+    idx[1::2] = 1
+    alpha = np.ones(C_out, dtype=np.float32)
+    _, Y = oracle.conv_bin(oracle.sign(ones), oracle.expand(cb, idx), alpha, 1)
+    y = G.subbit_bin(ones, cb, idx, alpha, 1)
+    assert (y == Y).all()
+    assert y[0, 0, 2, 2] == 9 * 512 and y[0, 1, 2, 2] == -9 * 512
+
+
+def test_full_subset_equals_one_bit_kernel(oracle):
+    """Sec. 4.1: the subset of all 512 kernels with idx = code is the 1-bit layer; the two GPU
+    kernels must agree with each other and with the oracle."""
+    g = np.random.default_rng(9)
+    N, C_in, C_out, H, W = 2, 64, 32, 8, 8
+    x = g.standard_normal((N, C_in, H, W), dtype=np.float32)
+    w9 = g.integers(0, 512, size=(C_out, C_in)).astype(np.uint16)
+    alpha = synth.alpha(g, C_out)
+    _, Y = oracle.conv_bin(oracle.sign(x), w9, alpha, 1)
+    y_bnn = G.bnn_bin(x, w9, alpha, 1)
+    y_sub = G.subbit_bin(x, np.arange(512, dtype=np.uint16), w9, alpha, 1)
+    assert (y_bnn == Y).all() and (y_sub == Y).all()
+
+
+# ---- sub-bit convolution, fp32 activations ----------------------------------------------------------------
+
+@pytest.mark.parametrize("case", [(2, 8, 8, 6, 6, 1, 32), (3, 13, 9, 7, 5, 2, 16), (2, 24, 70, 9, 9, 1, 7),
+                                  (1, 1, 1, 1, 1, 1, 1), (2, 16, 200, 4, 4, 1, 64), (1, 8, 8, 5, 5, 1, 512)])
+def test_subbit_f32(oracle, case):
+    _say("subbit_f32", case)
+    N, C_in, C_out, H, W, stride, K = case
+    x, cb, idx, alpha = _inputs(sum(case) + 3, N, C_in, C_out, H, W, K)
+    _, Y = oracle.conv_f32(x, oracle.expand(cb, idx), alpha, stride)
+    G.assert_f32_close(G.subbit_f32(x, cb, idx, alpha, stride), Y)
+
+
+def test_config2_full(oracle):
+    """ResNet-20 last stage, weight-only sub-bit (W/A 0.56/32): batch 256, 64 -> 64, 8x8, K = 32."""
+    L = synth.CFG2
+    x, cb, idx, alpha = synth.layer_inputs(L, 2)
+    _, Y = oracle.conv_f32(x, oracle.expand(cb, idx), alpha, 1)
+    G.assert_f32_close(G.subbit_f32(x, cb, idx, alpha, 1), Y)
+    G.assert_f32_close(G.bnn_f32(x, oracle.expand(cb, idx), alpha, 1), Y)
+
+
+# ---- full-size configurations, sampled images ---------------------------------------------------------------
+
+def _sampled_images(oracle, L, config, layer_no, images, K=None, w9_baseline=True):
+    x, cb, idx, alpha = synth.layer_inputs(L, config, layer_no)
+    y = G.subbit_bin(x, cb, idx, alpha, L.stride)
+    codes = oracle.expand(cb, idx)
+    _, Y = oracle.conv_bin(oracle.sign(x[images]), codes, alpha, L.stride)
+    assert (y[images] == Y).all()
+    if w9_baseline:
+        yb = G.bnn_bin(x, codes, alpha, L.stride)
+        assert (yb[images] == Y).all()
+        assert (yb == y).all()          # the two kernels agree on every output, not only the sampled ones
+
+
+def test_config3_sampled(oracle):
+    """ResNet-18 stage 3: batch 128, 256 -> 256, 14x14, K = 32, Zipf indices; oracle on 6 images,
+    the two GPU kernels against each other on all 128."""
+    _sampled_images(oracle, synth.CFG3, 3, 0, [0, 1, 63, 64, 126, 127])
+
+
+@pytest.mark.parametrize("K", [16, 32, 64])
+def test_config4_sampled(oracle, K):
+    """ResNet-34 stage 4: batch 256, 512 -> 512, 7x7."""
+    _sampled_images(oracle, synth.cfg4(K), 4, K, [0, 127, 255])
+
+
+@pytest.mark.parametrize("layer_no", [0, 4, 8, 12, 15])
+def test_config5_layers_sampled(oracle, layer_no):
+    """ResNet-18 stack at batch 64: one layer of each shape (incl. the three stride-2 layers)."""
+    L = synth.resnet18_stack(N=64)[layer_no]
+    _sampled_images(oracle, L, 5, layer_no, [0, 63])
+
+
+# ---- projection ------------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("n,K", [(1, 32), (255, 32), (256, 16), (257, 64), (5000, 1), (3000, 512), (70000, 32)])
+def test_project(oracle, n, K):
+    _say("project", n, K)
+    g = np.random.default_rng(n + K)
+    w = synth.real_kernels(g, n)
+    cb = g.permutation(512)[:K].astype(np.uint16)       # unsorted on purpose
+    ref, _ = oracle.project(w, cb)
+    assert (G.project(w, cb) == ref).all()
+
+
+def test_project_ties_zeros_and_members(oracle):
+    g = np.random.default_rng(1)
+    cb = synth.codebook(g, 32)
+    w = np.zeros((600, 9), dtype=np.float32)
+    w[100:200] = np.sign(g.standard_normal((100, 9))).astype(np.float32)       # +-1 kernels
+    w[200:300, 4] = g.standard_normal(100).astype(np.float32)                  # one non-zero tap
+    w[300:400] = np.round(g.standard_normal((100, 9)) * 2).astype(np.float32)  # small integers: many ties
+    w[400:432] = np.array([[1.0 if (c >> (8 - t)) & 1 else -1.0 for t in range(9)] for c in cb], dtype=np.float32)
+    w[432:] = g.standard_normal((168, 9)).astype(np.float32) * 1e-20
+    ref, score = oracle.project(w, cb)
+    got = G.project(w, cb)
+    assert (got == ref).all()
+    assert (got[400:432] == np.arange(32)).all() and (score[400:432] == 9).all()
+    assert (got[:100] == 0).all()
+
+
+def test_project_config5_all_kernels(oracle):
+    """All 1 220 608 kernels of the ResNet-18 stack, each layer onto its own K = 32 subset."""
+    for i, L in enumerate(synth.resnet18_stack()):
+        g = synth.rng(5, 100 + i)
+        w = synth.real_kernels(g, L.C_in * L.C_out)
+        cb = synth.codebook(g, 32)
+        ref, _ = oracle.project(w, cb)
+        assert (G.project(w, cb) == ref).all(), i
+
+
+def test_project_empty():
+    import torch
+    w = torch.empty((0, 9), dtype=torch.float32, device="cuda")
+    cb = G.dev(np.arange(4, dtype=np.uint16))
+    assert B.snn_project_kernels(w, cb).numel() == 0
+
+
+# ---- error paths that need device pointers -----------------------------------------------------------------------
+
+def test_workspace_too_small_is_reported():
+    import torch
+    d = B.make_desc(1, 32, 32, 8, 8, 1, 32, B.SNN_ACT_BIN_ROWS)
+    x = torch.zeros(B.snn_packed_bytes(1, 32, 8, 8, B.SNN_ACT_BIN_ROWS) // 4, dtype=torch.int32, device="cuda")
+    cb = G.dev(np.arange(32, dtype=np.uint16))
+    idx = G.dev(np.zeros((32, 32), dtype=np.uint16))
+    alpha = torch.ones(32, device="cuda")
+    small = torch.empty(64, dtype=torch.uint8, device="cuda")
+    with pytest.raises(B.SnnError) as e:
+        B.snn_subbit_conv2d(d, x, cb, idx, alpha, workspace=small)
+    assert e.value.status == B.SNN_ERR_WORKSPACE
