@@ -1,0 +1,299 @@
+#!/usr/bin/env python3
+"""Benchmark of the sub-bit 3x3 convolution path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload resnet18|cfg3|cfg4] [--no-cpu]
+
+One "step" is one pass of the whole path over one batch of synthetic input, i.e. the forward
+lines of Alg. 1 for every 3x3 layer of the workload: project the real-valued kernels onto the
+layer's subset (snn_project_kernels), binarise and pack the activations (snn_pack_activations),
+run the sub-bit convolution (snn_subbit_conv2d: stage 1, stage 2, alpha scaling).  Inputs are
+resident in HBM before the timed region.  The same layers are then run through the library's
+1-bit XNOR/popcount kernel (snn_bnn_conv2d on the decoded kernels) for the speed-up.
+
+Prints ONE JSON line (metric of the benchmark spec: GOPS-equivalent of the dense convolution the
+layers equal, plus the speed-up over the 1-bit kernel), with a `roofline` object for the
+dominant kernel and a `cpu_baseline` object (the CPU oracle timed on a bounded sample).
+Per-layer detail goes to stderr.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+# MI355X: 256 CUs x 4 SIMD x 16 lanes x 2.4 GHz plain 32-bit VALU operations per second
+# (= the 157.3 TFLOP/s fp32 vector peak / 2 for FMA / 2 for the packed form).
+VALU_PEAK_LANE_OPS = 256 * 4 * 16 * 2.4e9
+# LDS: 128 bytes per clock per CU.
+LDS_PEAK_BYTES = 256 * 128 * 2.4e9
+HBM_PEAK_BYTES = 8.0e12
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="resnet18", choices=["resnet18", "cfg3", "cfg4", "cfg1"])
+    ap.add_argument("--K", type=int, default=32)
+    ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    return ap.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU only (the path shards over the batch without "
+              "communication; see DESIGN.md); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    from paper_2110_09195_amd import accounting, synth
+    from paper_2110_09195_amd import binding as B
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    torch.cuda.set_device(0)
+    B.lib()
+
+    if args.workload == "resnet18":
+        layers = synth.resnet18_stack(N=64, K=args.K)
+        wname = "ResNet-18 3x3 conv stack (16 layers), batch 64, 224x224 shapes, binary activations, K=%d" % args.K
+        cfg_no = 5
+    elif args.workload == "cfg3":
+        layers = [synth.CFG3]
+        wname = "ResNet-18 stage-3 layer, batch 128, 256->256, 14x14, K=32, Zipf indices"
+        cfg_no = 3
+    elif args.workload == "cfg4":
+        layers = [synth.cfg4(args.K)]
+        wname = "ResNet-34 stage-4 layer, batch 256, 512->512, 7x7, K=%d" % args.K
+        cfg_no = 4
+    else:
+        layers = [synth.CFG1]
+        wname = "ResNet-20 stage-1 layer, batch 8, 16->16, 32x32, K=32"
+        cfg_no = 1
+
+    def dev(a):
+        a = np.ascontiguousarray(a)
+        if a.dtype == np.uint16:
+            a = a.view(np.int16)
+        return torch.from_numpy(a).cuda()
+
+    # ---- resident inputs and buffers -------------------------------------------------------------
+    st = []
+    for i, L in enumerate(layers):
+        g = synth.rng(cfg_no, i)
+        s = {"L": L}
+        s["x"] = dev(synth.activations(g, L.N, L.C_in, L.H, L.W))
+        s["cb"] = dev(synth.codebook(g, L.K))
+        if args.workload == "cfg3":
+            # Zipf-skewed indices: real-valued kernels are drawn around the subset members the
+            # skewed indices name, so that projection reproduces a skewed index map
+            idx0 = synth.indices(g, L.C_out, L.C_in, L.K, "zipf")
+            cbh = s["cb"].cpu().numpy().view(np.uint16)
+            members = np.array([[1.0 if (int(c) >> (8 - t)) & 1 else -1.0 for t in range(9)] for c in cbh], dtype=np.float32)
+            w = members[idx0.reshape(-1)] + 0.3 * synth.real_kernels(g, L.C_out * L.C_in)
+        else:
+            w = synth.real_kernels(g, L.C_out * L.C_in)
+        s["w"] = dev(w.astype(np.float32))
+        s["alpha"] = dev(synth.alpha(g, L.C_out))
+        s["idx"] = torch.empty(L.C_out * L.C_in, dtype=torch.int16, device="cuda")
+        s["d_sub"] = B.make_desc(L.N, L.C_in, L.C_out, L.H, L.W, L.stride, L.K, B.SNN_ACT_BIN_ROWS)
+        s["d_bnn"] = B.make_desc(L.N, L.C_in, L.C_out, L.H, L.W, L.stride, 512, B.SNN_ACT_BIN_CHANNELS)
+        s["xr"] = torch.empty(B.snn_packed_bytes(L.N, L.C_in, L.H, L.W, B.SNN_ACT_BIN_ROWS) // 4, dtype=torch.int32, device="cuda")
+        s["xc"] = torch.empty(B.snn_packed_bytes(L.N, L.C_in, L.H, L.W, B.SNN_ACT_BIN_CHANNELS) // 4, dtype=torch.int32, device="cuda")
+        s["y"] = torch.empty((L.N, L.C_out, L.H_out, L.W_out), dtype=torch.float32, device="cuda")
+        s["yb"] = torch.empty_like(s["y"])
+        s["ws_sub"] = B.alloc_workspace(s["d_sub"], B.SNN_WS_SUBBIT)
+        s["ws_bnn"] = B.alloc_workspace(s["d_bnn"], B.SNN_WS_BNN)
+        st.append(s)
+    torch.cuda.synchronize()
+
+    def project(s):
+        B.snn_project_kernels(s["w"], s["cb"], out=s["idx"])
+
+    def pack_rows(s):
+        B.snn_pack_activations(s["x"], B.SNN_ACT_BIN_ROWS, out=s["xr"])
+
+    def pack_channels(s):
+        B.snn_pack_activations(s["x"], B.SNN_ACT_BIN_CHANNELS, out=s["xc"])
+
+    def conv_sub(s):
+        L = s["L"]
+        B.snn_subbit_conv2d(s["d_sub"], s["xr"], s["cb"], s["idx"].view(L.C_out, L.C_in), s["alpha"], y=s["y"],
+                            workspace=s["ws_sub"])
+
+    def conv_bnn(s):
+        B.snn_bnn_conv2d(s["d_bnn"], s["xc"], s["w9"], s["alpha"], y=s["yb"], workspace=s["ws_bnn"])
+
+    def step():
+        for s in st:
+            project(s)
+            pack_rows(s)
+            conv_sub(s)
+
+    def step_bnn():
+        for s in st:
+            pack_channels(s)
+            conv_bnn(s)
+
+    # decoded kernels for the 1-bit baseline (input preparation, outside every timed region)
+    for s in st:
+        project(s)
+    torch.cuda.synchronize()
+    for s in st:
+        L = s["L"]
+        s["w9"] = s["cb"][s["idx"].long()].view(L.C_out, L.C_in).contiguous()
+    torch.cuda.synchronize()
+
+    # ---- the timed region: exactly K steps between two synchronisations -------------------------------
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+
+    for _ in range(args.warmup):
+        step_bnn()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step_bnn()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step_bnn = (t1 - t0) * 1e3 / args.steps
+
+    # the two kernels must agree (same decoded weights): a cheap end-to-end sanity check
+    for s in st:
+        assert torch.equal(s["y"], s["yb"]), "sub-bit and 1-bit kernels disagree on " + s["L"].name
+
+    # ---- per-call device time with HIP events on the launch stream ---------------------------------------
+    def event_time(fn, reps):
+        """Average device milliseconds of fn(s) per layer over `reps` repetitions."""
+        out = []
+        for s in st:
+            e0 = [torch.cuda.Event(enable_timing=True) for _ in range(reps)]
+            e1 = [torch.cuda.Event(enable_timing=True) for _ in range(reps)]
+            fn(s)
+            torch.cuda.synchronize()
+            for r in range(reps):
+                e0[r].record()
+                fn(s)
+                e1[r].record()
+            torch.cuda.synchronize()
+            ts = sorted(a.elapsed_time(b) for a, b in zip(e0, e1))
+            out.append(sum(ts) / len(ts))
+        return out
+
+    reps = max(10, args.steps)
+    t_sub = event_time(conv_sub, reps)
+    t_bnn = event_time(conv_bnn, reps)
+    t_proj = event_time(project, reps)
+    t_pr = event_time(pack_rows, reps)
+    t_pc = event_time(pack_channels, reps)
+
+    dense_ops = sum(L.dense_ops for L in layers)
+    gather_adds = sum(accounting.stage2_gather_adds(L) for L in layers)
+    responses = sum(accounting.stage1_responses(L) for L in layers)
+    out_bytes = sum(L.pixels * L.C_out * 4 for L in layers)
+    in_bytes = sum(L.N * L.C_in * L.H * ((L.W + 31) // 32) * 4 for L in layers)
+    idx_bytes = sum(L.C_in * L.C_out * 2 for L in layers)
+
+    # Algorithmic work of the sub-bit kernel: stage 2 is one add per (pixel,
+    # c_out, c_in) with four pixels per 32-bit lane operation; stage 1 one response per (pixel,
+    # c_in, k), four per lane operation.  Every gathered response is one byte read from LDS.
+    alg_lane_ops = (gather_adds + responses) / 4.0
+    alg_lds_bytes = float(gather_adds)
+    alg_hbm_bytes = float(out_bytes + in_bytes + idx_bytes)
+    sub_s = sum(t_sub) * 1e-3
+    roofline = {
+        "kernel": "subbit_bin_kernel (all %d launches of a step; duration is the snn_subbit_conv2d call, "
+                  "which includes its small index-preparation kernel)" % len(layers),
+        "bound": "alu",
+        "achieved": alg_lane_ops / sub_s / 1e12,
+        "peak": VALU_PEAK_LANE_OPS / 1e12,
+        "unit": "T lane-op/s",
+        "frac": alg_lane_ops / sub_s / VALU_PEAK_LANE_OPS,
+        "traffic": None,
+        "lds": {"achieved": alg_lds_bytes / sub_s / 1e12, "peak": LDS_PEAK_BYTES / 1e12, "unit": "TB/s",
+                "frac": alg_lds_bytes / sub_s / LDS_PEAK_BYTES},
+        "hbm": {"achieved": alg_hbm_bytes / sub_s / 1e9, "peak": HBM_PEAK_BYTES / 1e9, "unit": "GB/s",
+                "frac": alg_hbm_bytes / sub_s / HBM_PEAK_BYTES},
+        "avg_launch_ms": sum(t_sub) / len(t_sub),
+    }
+
+    print("%-18s %9s %6s %5s | %9s %9s %7s | %8s %8s %8s" % ("layer", "pixels", "C", "K", "subbit us", "bnn us", "speedup",
+                                                             "proj us", "packR us", "packC us"), file=sys.stderr)
+    for L, a, b, c, d, e in zip(layers, t_sub, t_bnn, t_proj, t_pr, t_pc):
+        print("%-18s %9d %3d>%-3d %4d | %9.1f %9.1f %7.2f | %8.1f %8.1f %8.1f" % (
+            L.name, L.pixels, L.C_in, L.C_out, L.K, a * 1e3, b * 1e3, b / a, c * 1e3, d * 1e3, e * 1e3), file=sys.stderr)
+    print("sum: subbit %.1f us, bnn %.1f us, project %.1f us, pack rows %.1f us, pack channels %.1f us; "
+          "step %.1f us, bnn step %.1f us" % (sum(t_sub) * 1e3, sum(t_bnn) * 1e3, sum(t_proj) * 1e3, sum(t_pr) * 1e3,
+                                                sum(t_pc) * 1e3, ms_per_step * 1e3, ms_per_step_bnn * 1e3), file=sys.stderr)
+
+    # ---- cpu_baseline: the oracle on a bounded sample of the same workload --------------------------------
+    cpu = None
+    if not args.no_cpu:
+        import oracle
+        oracle.build()
+        n_img = 2 if args.workload == "resnet18" else 4
+        t_cpu = 0.0
+        ops_cpu = 0
+        for s in st:
+            L = s["L"]
+            x = s["x"][:n_img].cpu().numpy()
+            w = s["w"].cpu().numpy()
+            cb = s["cb"].cpu().numpy().view(np.uint16)
+            alpha = s["alpha"].cpu().numpy()
+            c0 = time.perf_counter()
+            idx, _ = oracle.project(w, cb)
+            xs = oracle.sign(x)
+            _, Y = oracle.conv_bin(xs, oracle.expand(cb, idx.reshape(L.C_out, L.C_in)), alpha, L.stride)
+            t_cpu += time.perf_counter() - c0
+            ops_cpu += L.dense_ops // L.N * n_img
+            assert (s["y"][:n_img].cpu().numpy() == Y).all(), "GPU result differs from the oracle on " + L.name
+        cpu = {"value": ops_cpu / t_cpu / 1e9, "unit": "GOPS-equivalent", "cores": oracle.threads(), "kind": "oracle",
+               "sample": "same %d layers, first %d images of the batch (project + sign + direct conv), %.1f s" % (
+                   len(layers), n_img, t_cpu)}
+
+    result = {
+        "metric": "sub-bit 3x3 conv GOPS-equivalent (2*9*C_in*C_out*N*H_out*W_out per layer / step time) and "
+                  "speed-up vs the 1-bit XNOR/popcount kernel",
+        "value": dense_ops / (ms_per_step * 1e-3) / 1e9,
+        "unit": "GOPS-equivalent",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "u8",
+        "data": "synthetic",
+        "config": {"workload": wname, "step": "per layer: snn_project_kernels + snn_pack_activations + snn_subbit_conv2d"},
+        "conv_only_gops_eq": dense_ops / sub_s / 1e9,
+        "bnn_conv_only_gops_eq": dense_ops / (sum(t_bnn) * 1e-3) / 1e9,
+        "speedup_vs_bnn_conv": sum(t_bnn) / sum(t_sub),
+        "speedup_vs_bnn_step": ms_per_step_bnn / ms_per_step,
+        "bnn_ms_per_step": ms_per_step_bnn,
+        "breakdown_us": {"subbit_conv": sum(t_sub) * 1e3, "bnn_conv": sum(t_bnn) * 1e3, "project": sum(t_proj) * 1e3,
+                         "pack_rows": sum(t_pr) * 1e3, "pack_channels": sum(t_pc) * 1e3},
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()
