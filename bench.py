@@ -40,6 +40,7 @@ def parse():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="resnet18", choices=["resnet18", "cfg3", "cfg4", "cfg1"])
     ap.add_argument("--K", type=int, default=32)
+    ap.add_argument("--layer", default=None, help="one custom layer instead of a workload: N,C_in,C_out,H,W,stride")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     return ap.parse_args()
 
@@ -63,7 +64,12 @@ def main():
     torch.cuda.set_device(0)
     B.lib()
 
-    if args.workload == "resnet18":
+    if args.layer:
+        N, Ci, Co, H, W, st_ = [int(v) for v in args.layer.split(",")]
+        layers = [synth.Layer("custom", N=N, C_in=Ci, C_out=Co, H=H, W=W, stride=st_, K=args.K)]
+        wname = "custom layer %s, K=%d" % (args.layer, args.K)
+        cfg_no = 9
+    elif args.workload == "resnet18":
         layers = synth.resnet18_stack(N=64, K=args.K)
         wname = "ResNet-18 3x3 conv stack (16 layers), batch 64, 224x224 shapes, binary activations, K=%d" % args.K
         cfg_no = 5

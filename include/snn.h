@@ -110,8 +110,8 @@ int snn_project_kernels(const float *w, int64_t n, const uint16_t *codebook, int
  *   alpha     device, float [C_out]   (the paper's channel-wise lambda)
  *   y_nchw    device, float [N][C_out][H_out][W_out], fully overwritten
  *   workspace device, >= snn_workspace_bytes(desc, SNN_WS_SUBBIT) bytes, 256-byte aligned
- * Errors: INVALID_ARG; UNSUPPORTED for act = SNN_ACT_BIN_CHANNELS (pack rows instead);
- * WORKSPACE; LAUNCH.
+ * Errors: INVALID_ARG; UNSUPPORTED for act = SNN_ACT_BIN_CHANNELS (pack rows instead) and for
+ * packed inputs of 2^31 words (8 GiB) or more; WORKSPACE; LAUNCH.
  */
 int snn_subbit_conv2d(const snn_conv_desc *desc, const void *x, const uint16_t *codebook,
                       const uint16_t *idx, const float *alpha, float *y_nchw,

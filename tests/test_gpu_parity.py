@@ -112,6 +112,11 @@ SUBBIT_CASES = [
     (2, 24, 16, 6, 6, 1, 100, "uniform"),         # K > 64: direct stage 1
     (1, 16, 16, 5, 5, 1, 512, "uniform"),         # full subset through the sub-bit path
     (3, 128, 128, 7, 7, 1, 32, "uniform"),        # 49-pixel images: unaligned float4 rows
+    (2, 24, 40, 56, 56, 1, 32, "uniform"),        # W_out multiple of 4, two packed words per row
+    (2, 24, 40, 56, 56, 2, 16, "uniform"),        # same, stride 2 (28x28 out)
+    (3, 16, 70, 12, 64, 1, 64, "zipf"),           # window rows straddle packed words
+    (2, 9, 12, 15, 15, 2, 32, "uniform"),         # stride 2, 8x8 out
+    (5, 70, 600, 4, 4, 1, 32, "uniform"),         # more than 512 output channels: channel blocks
 ]
 
 
@@ -124,6 +129,35 @@ def test_subbit_bin(oracle, case):
     y = G.subbit_bin(x, cb, idx, alpha, stride)
     assert y.shape == Y.shape
     assert (y == Y).all(), np.argwhere(y != Y)[:5]
+
+
+@pytest.mark.parametrize("variant", ["wave", "workgroup"])
+@pytest.mark.parametrize("case", [c for c in SUBBIT_CASES if c[6] <= 64])
+def test_subbit_bin_both_kernel_variants(oracle, case, variant, monkeypatch):
+    """The library picks between a wave-private and a workgroup-tile kernel by layer size; force
+    each of them on every case (the tuning override is read at every call)."""
+    _say("subbit_bin", variant, case)
+    monkeypatch.setenv("SNN_SUBBIT_WAVE", "1" if variant == "wave" else "0")
+    N, C_in, C_out, H, W, stride, K, dist = case
+    x, cb, idx, alpha = _inputs(sum(case[:7]), N, C_in, C_out, H, W, K, dist)
+    _, Y = oracle.conv_bin(oracle.sign(x), oracle.expand(cb, idx), alpha, stride)
+    y = G.subbit_bin(x, cb, idx, alpha, stride)
+    assert (y == Y).all(), np.argwhere(y != Y)[:5]
+
+
+@pytest.mark.parametrize("tile", ["4,1,8", "4,2,8", "2,1,8", "2,2,8", "1,1,4", "1,1,8", "4,1,1", "1,1,1"])
+def test_subbit_bin_every_tile_shape(oracle, tile, monkeypatch):
+    """Every instantiated tile of the workgroup kernel, forced on a layer with ragged edges."""
+    monkeypatch.setenv("SNN_SUBBIT_WAVE", "0")
+    monkeypatch.setenv("SNN_SUBBIT_TILE", tile)
+    x, cb, idx, alpha = _inputs(123, 3, 45, 150, 13, 11, 32)
+    _, Y = oracle.conv_bin(oracle.sign(x), oracle.expand(cb, idx), alpha, 1)
+    assert (G.subbit_bin(x, cb, idx, alpha, 1) == Y).all()
+    x, cb, idx, alpha = _inputs(124, 2, 20, 70, 16, 12, 32)       # W_out multiple of 4: the row-string window path
+    _, Y = oracle.conv_bin(oracle.sign(x), oracle.expand(cb, idx), alpha, 1)
+    assert (G.subbit_bin(x, cb, idx, alpha, 1) == Y).all()
+    _, Y = oracle.conv_bin(oracle.sign(x), oracle.expand(cb, idx), alpha, 2)
+    assert (G.subbit_bin(x, cb, idx, alpha, 2) == Y).all()
 
 
 def test_subbit_bin_takes_oracle_packed_input(oracle):
