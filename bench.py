@@ -42,7 +42,25 @@ def parse():
     ap.add_argument("--K", type=int, default=32)
     ap.add_argument("--layer", default=None, help="one custom layer instead of a workload: N,C_in,C_out,H,W,stride")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 256 MiB elementwise copy kernel once (reference for the HBM byte counters)")
     return ap.parse_args()
+
+
+def _measured_traffic(args):
+    """HBM bytes per step of the sub-bit kernels from the committed rocprofv3 --pmc passes
+    (FETCH_SIZE + WRITE_SIZE, scaled by a plain copy kernel; profiles/subbit_stack_resnet18_b64_hbm_traffic.txt).
+    Only for the workload they were taken on; None otherwise."""
+    path = os.path.join(ROOT, "profiles", "subbit_stack_resnet18_b64_hbm_traffic.txt")
+    if args.layer or args.workload != "resnet18" or args.K != 32 or not os.path.exists(path):
+        return None
+    try:
+        with open(path) as f:
+            d = json.loads("".join(l for l in f if not l.startswith("#")))
+        return {"bytes": d["bytes"], "fetch_bytes": d["fetch_bytes"], "write_bytes": d["write_bytes"],
+                "unit": "HBM bytes per step, all 16 launches (rocprofv3 FETCH_SIZE/WRITE_SIZE, copy-kernel scaled)"}
+    except (OSError, ValueError, KeyError):
+        return None
 
 
 def main():
@@ -91,6 +109,15 @@ def main():
         if a.dtype == np.uint16:
             a = a.view(np.int16)
         return torch.from_numpy(a).cuda()
+
+    if args.calibrate_copy:
+        # 64 Mi floats read + 64 Mi floats written by one elementwise kernel: the known-size reference that
+        # FETCH_SIZE / WRITE_SIZE readings of the conv kernels are scaled by (see the design doc / profiles/)
+        ca = torch.zeros(64 * 1024 * 1024, dtype=torch.float32, device="cuda")
+        cb = torch.empty_like(ca)
+        torch.add(ca, 1.0, out=cb)
+        torch.cuda.synchronize()
+        del ca, cb
 
     # ---- resident inputs and buffers -------------------------------------------------------------
     st = []
@@ -186,7 +213,7 @@ def main():
 
     # ---- per-call device time with HIP events on the launch stream ---------------------------------------
     def event_time(fn, reps):
-        """Average device milliseconds of fn(s) per layer over `reps` repetitions."""
+        """Median device milliseconds of fn(s) per layer over `reps` back-to-back repetitions."""
         out = []
         for s in st:
             e0 = [torch.cuda.Event(enable_timing=True) for _ in range(reps)]
@@ -199,7 +226,7 @@ def main():
                 e1[r].record()
             torch.cuda.synchronize()
             ts = sorted(a.elapsed_time(b) for a, b in zip(e0, e1))
-            out.append(sum(ts) / len(ts))
+            out.append(ts[len(ts) // 2])          # median: the first repetitions wait for the host
         return out
 
     reps = max(10, args.steps)
@@ -231,7 +258,7 @@ def main():
         "peak": VALU_PEAK_LANE_OPS / 1e12,
         "unit": "T lane-op/s",
         "frac": alg_lane_ops / sub_s / VALU_PEAK_LANE_OPS,
-        "traffic": None,
+        "traffic": _measured_traffic(args),
         "lds": {"achieved": alg_lds_bytes / sub_s / 1e12, "peak": LDS_PEAK_BYTES / 1e12, "unit": "TB/s",
                 "frac": alg_lds_bytes / sub_s / LDS_PEAK_BYTES},
         "hbm": {"achieved": alg_hbm_bytes / sub_s / 1e9, "peak": HBM_PEAK_BYTES / 1e9, "unit": "GB/s",

@@ -124,8 +124,8 @@ int snn_subbit_conv2d(const snn_conv_desc *desc, const void *x, const uint16_t *
  *   x         device, activations in the layout desc->act names
  *   w9        device, uint16 [C_out][C_in], one 9-bit code per kernel
  *   alpha, y_nchw, workspace (SNN_WS_BNN), stream: as above
- * Errors: INVALID_ARG; UNSUPPORTED for act = SNN_ACT_BIN_ROWS, and for C_in > 512 with
- * packed activations; WORKSPACE; LAUNCH.
+ * Errors: INVALID_ARG; UNSUPPORTED for act = SNN_ACT_BIN_ROWS and for packed inputs of 2^31
+ * words (8 GiB) or more; WORKSPACE; LAUNCH.
  */
 int snn_bnn_conv2d(const snn_conv_desc *desc, const void *x, const uint16_t *w9,
                    const float *alpha, float *y_nchw, void *workspace, size_t ws_bytes,

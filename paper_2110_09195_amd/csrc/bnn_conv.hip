@@ -2,11 +2,13 @@
 // words of 32 input channels.  It is the denominator of every speed-up the sub-bit kernel
 // reports, so it is written to the same standard.
 //
-// Packed activations (SNN_ACT_BIN_CHANNELS): one lane owns one output pixel and keeps its whole
-// 3x3 x C_in window in registers (9 * C_in/32 words); output channels are walked in a loop whose
-// weight words are wave-uniform (scalar loads), so the inner loop is v_xor + v_bcnt_u32_b32 with
-// accumulate: 2 lane-ops per 32 multiply-adds.  Taps outside the image are loaded as 0 and the
-// mismatches they fake are taken out again with a per-(channel, border type) table.
+// Packed activations (SNN_ACT_BIN_CHANNELS): one lane owns PXL output pixels and keeps the
+// mismatch counts of a block of COG output channels in registers.  The loop runs over the
+// 9 * C_in/32 words of the window: the lane loads its pixel's word, the COG weight words that
+// meet it are wave-uniform (one or two wide scalar loads from a [channel block][tap][word][COG]
+// table), and the body is v_xor + v_bcnt_u32_b32 with accumulate: 2 lane-ops per 32
+// multiply-adds.  Taps outside the image are loaded as 0 and the mismatches they fake are taken
+// out again with a per-(channel, border type) table.
 //
 // fp32 activations (SNN_ACT_F32, the W/A = 1/32 rows): the same direct loop with add/subtract.
 #include "snn_internal.h"
@@ -20,31 +22,40 @@ constexpr int BNN_THREADS = 256;
 // workspace layout (packed activations):  wplanes [C_out][9][CWT] u32 | corr [C_out][16] i32
 // workspace layout (fp32 activations):    flips   [C_out][C_in]    u32 (bit t = tap t is -1)
 
-__global__ void bnn_prep_bin_kernel(const uint16_t *__restrict__ w9, int C_out, int C_in, int CWT,
-                                    uint32_t *__restrict__ wplanes, int32_t *__restrict__ corr)
+// One wave per output channel: 64 kernels' codes at a time, one ballot per tap gives two words of
+// that tap's bit-plane; the population counts of the planes give the border corrections.
+// Layout written: wq[(co / COG)][tap][word][co % COG]; channels past C_out are zero.
+__global__ __launch_bounds__(256)
+void bnn_prep_bin_kernel(const uint16_t *__restrict__ w9, int C_out, int COP, int C_in, int CW, int COG,
+                         uint32_t *__restrict__ wq, int32_t *__restrict__ corr)   // COG = 1: plain [co][tap][word]
 {
-    const int gid = blockIdx.x * blockDim.x + threadIdx.x;
-    const int nplane = C_out * 9 * CWT;
-    if (gid < nplane) {
-        const int cw = gid % CWT;
-        const int t = (gid / CWT) % 9;
-        const int co = gid / (9 * CWT);
-        uint32_t word = 0;
-        for (int c = 0; c < 32; ++c) {
-            const int ci = cw * 32 + c;
-            if (ci < C_in)
-                word |= (uint32_t)((w9[(int64_t)co * C_in + ci] >> (8 - t)) & 1) << c;
+    const int co = blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    if (co >= COP) return;
+    uint32_t *wp = wq + (int64_t)(co / COG) * 9 * CW * COG + (co % COG);
+    int ones[9];
+#pragma unroll
+    for (int t = 0; t < 9; ++t) ones[t] = 0;
+    for (int b = 0; 2 * b < CW; ++b) {
+        const int ci = 64 * b + lane;
+        const uint32_t code = (co < C_out && ci < C_in) ? (w9[(int64_t)co * C_in + ci] & 511u) : 0u;
+#pragma unroll
+        for (int t = 0; t < 9; ++t) {
+            const unsigned long long m = __ballot((code >> (8 - t)) & 1u);
+            ones[t] += __popcll(m);
+            if (lane == 0) {
+                wp[(t * CW + 2 * b) * COG] = (uint32_t)m;
+                if (2 * b + 1 < CW) wp[(t * CW + 2 * b + 1) * COG] = (uint32_t)(m >> 32);
+            }
         }
-        wplanes[gid] = word;
-    } else if (gid < nplane + C_out * 16) {
-        const int q = gid - nplane;
-        const int co = q >> 4, type = q & 15;
-        const uint32_t inv = border_invalid_window(type);
-        int32_t s = 0;
-        if (inv)
-            for (int ci = 0; ci < C_in; ++ci)
-                s += __popc(code_to_window_order(w9[(int64_t)co * C_in + ci] & 511u) & inv);
-        corr[q] = s;
+    }
+    if (lane < 16) {
+        const uint32_t inv = border_invalid_window(lane);
+        int s = 0;
+#pragma unroll
+        for (int t = 0; t < 9; ++t)
+            if ((inv >> t) & 1u) s += ones[t];
+        corr[co * 16 + lane] = s;
     }
 }
 
@@ -55,9 +66,12 @@ __global__ void bnn_prep_f32_kernel(const uint16_t *__restrict__ w9, int64_t n, 
         flips[i] = (~code_to_window_order(w9[i] & 511u)) & 511u;
 }
 
+// Variant for C_in <= 512: one lane owns one output pixel and keeps its whole 3x3 x C_in window in
+// registers (9 * C_in/32 words); output channels are walked in a loop whose weight words are
+// wave-uniform scalar loads from a [channel][tap][word] table.
 template <int CWT>
 __global__ __launch_bounds__(BNN_THREADS)
-void bnn_bin_kernel(const uint32_t *__restrict__ x, const uint32_t *__restrict__ wplanes,
+void bnn_regs_kernel(const uint32_t *__restrict__ x, const uint32_t *__restrict__ wplanes,
                     const int32_t *__restrict__ corr, const float *__restrict__ alpha, float *__restrict__ y,
                     Geom g, int co_per_block)
 {
@@ -96,6 +110,74 @@ void bnn_bin_kernel(const uint32_t *__restrict__ x, const uint32_t *__restrict__
         const int S = base - 2 * (mm - corr[co * 16 + type]);
         if (active)
             yp[(int64_t)co * g.HoWo] = (float)S * alpha[co];
+    }
+}
+
+template <int PXL, int COG>
+__global__ __launch_bounds__(BNN_THREADS)
+void bnn_bin_kernel(const uint32_t *__restrict__ x, const uint32_t *__restrict__ wq,
+                    const int32_t *__restrict__ corr, const float *__restrict__ alpha, float *__restrict__ y,
+                    Geom g)
+{
+    const int cog = blockIdx.y;
+    int off[PXL][9];                // word offset of each tap's first word; -1 if the tap is outside
+    int type[PXL], base[PXL], nn[PXL], rr[PXL];
+    bool active[PXL];
+#pragma unroll
+    for (int q = 0; q < PXL; ++q) {
+        const int64_t p_raw = ((int64_t)blockIdx.x * PXL + q) * BNN_THREADS + threadIdx.x;
+        active[q] = p_raw < g.P;
+        const int64_t p = active[q] ? p_raw : g.P - 1;
+        const int n = (int)(p / g.HoWo);
+        const int r = (int)(p - (int64_t)n * g.HoWo);
+        const int ho = r / g.Wo, wo = r - ho * g.Wo;
+        const int hc = ho * g.stride, wc = wo * g.stride;
+        nn[q] = n;
+        rr[q] = r;
+#pragma unroll
+        for (int t = 0; t < 9; ++t) {
+            const int h = hc + t / 3 - 1, w = wc + t % 3 - 1;
+            const bool valid = (h >= 0) && (h < g.H) && (w >= 0) && (w < g.W);
+            off[q][t] = valid ? ((n * g.H + h) * g.W + w) * g.CW : -1;
+        }
+        type[q] = border_type(ho, wo, g.H, g.W, g.stride);
+        base[q] = border_valid_taps(type[q]) * g.C_in;
+    }
+
+    int mm[PXL][COG];
+#pragma unroll
+    for (int q = 0; q < PXL; ++q)
+#pragma unroll
+        for (int c = 0; c < COG; ++c) mm[q][c] = 0;
+
+    const uint32_t *wt = wq + (int64_t)cog * 9 * g.CW * COG;        // wave-uniform
+#pragma unroll
+    for (int t = 0; t < 9; ++t) {
+        for (int cw = 0; cw < g.CW; ++cw) {
+            uint32_t xw[PXL];
+#pragma unroll
+            for (int q = 0; q < PXL; ++q) xw[q] = off[q][t] >= 0 ? x[off[q][t] + cw] : 0u;
+            const uint32_t *wv = wt + (t * g.CW + cw) * COG;
+#pragma unroll
+            for (int c = 0; c < COG; ++c) {
+                const uint32_t w = wv[c];
+#pragma unroll
+                for (int q = 0; q < PXL; ++q) mm[q][c] += __popc(xw[q] ^ w);
+            }
+        }
+    }
+
+#pragma unroll
+    for (int c = 0; c < COG; ++c) {
+        const int co = cog * COG + c;
+        if (co >= g.C_out) break;
+        const float a = alpha[co];
+#pragma unroll
+        for (int q = 0; q < PXL; ++q) {
+            const int cr = type[q] ? corr[co * 16 + type[q]] : 0;
+            const int S = base[q] - 2 * (mm[q][c] - cr);
+            if (active[q]) y[((int64_t)nn[q] * g.C_out + co) * g.HoWo + rr[q]] = (float)S * a;
+        }
     }
 }
 
@@ -159,20 +241,34 @@ void bnn_f32_kernel(const float *__restrict__ x, const uint32_t *__restrict__ fl
     }
 }
 
-int pow2_words(int CW)
-{
-    int c = 1;
-    while (c < CW) c <<= 1;
-    return c;
-}
-
 }  // namespace
+
+// Channel block and pixels per lane: aim for several waves per SIMD (>= 4096 waves).
+struct BnnCfg {
+    int PXL, COG;
+};
+
+BnnCfg bnn_cfg(const Geom &g)
+{
+    static const BnnCfg cands[] = {{2, 32}, {1, 32}, {1, 16}, {1, 8}};
+    for (const BnnCfg &c : cands) {
+        const int64_t waves = (g.P + 64 * c.PXL - 1) / (64 * c.PXL) * ((g.C_out + c.COG - 1) / c.COG);
+        if (waves >= 4096) return c;
+    }
+    return cands[3];
+}
 
 size_t bnn_workspace_bytes(const Geom &g, int act)
 {
     if (act == SNN_ACT_F32) return align_up((size_t)g.C_out * g.C_in * sizeof(uint32_t), 256);
-    const int CWT = pow2_words(g.CW);
-    return align_up((size_t)g.C_out * 9 * CWT * sizeof(uint32_t), 256) + align_up((size_t)g.C_out * 16 * sizeof(int32_t), 256);
+    if (g.CW <= 16) {
+        int CWT = 1;
+        while (CWT < g.CW) CWT <<= 1;
+        return align_up((size_t)g.C_out * 9 * CWT * sizeof(uint32_t), 256) + align_up((size_t)g.C_out * 16 * sizeof(int32_t), 256);
+    }
+    const BnnCfg c = bnn_cfg(g);
+    const int COP = (g.C_out + c.COG - 1) / c.COG * c.COG;
+    return align_up((size_t)COP * 9 * g.CW * sizeof(uint32_t), 256) + align_up((size_t)COP * 16 * sizeof(int32_t), 256);
 }
 
 int launch_bnn(const Geom &g, int act, const void *x, const uint16_t *w9, const float *alpha, float *y,
@@ -192,39 +288,61 @@ int launch_bnn(const Geom &g, int act, const void *x, const uint16_t *w9, const 
         return check_launch();
     }
 
-    const int CWT = pow2_words(g.CW);
-    if (CWT > 16) return SNN_ERR_UNSUPPORTED;
-    uint32_t *wplanes = (uint32_t *)ws;
-    int32_t *corr = (int32_t *)((char *)ws + align_up((size_t)g.C_out * 9 * CWT * sizeof(uint32_t), 256));
-
-    // Enough workgroups to fill 256 CUs several times over: split the output channels when
-    // there are few pixels.
-    int co_per_block = g.C_out;
-    while (co_per_block > 16 && pblocks * ((g.C_out + co_per_block - 1) / co_per_block) < 2048)
-        co_per_block = (co_per_block + 1) / 2;
-    const int cgroups = (g.C_out + co_per_block - 1) / co_per_block;
-    if (cgroups > 65535) return SNN_ERR_UNSUPPORTED;
-
-    const int64_t nprep = (int64_t)g.C_out * 9 * CWT + (int64_t)g.C_out * 16;
-    hipLaunchKernelGGL(bnn_prep_bin_kernel, dim3((unsigned)((nprep + 255) / 256)), dim3(256), 0, s, w9, g.C_out,
-                       g.C_in, CWT, wplanes, corr);
-    const dim3 grid((unsigned)pblocks, (unsigned)cgroups), block(BNN_THREADS);
-    const uint32_t *xp = (const uint32_t *)x;
+    if (g.CW <= 16) {
+        // register-resident windows (C_in <= 512)
+        int CWT = 1;
+        while (CWT < g.CW) CWT <<= 1;
+        uint32_t *wplanes = (uint32_t *)ws;
+        int32_t *corr = (int32_t *)((char *)ws + align_up((size_t)g.C_out * 9 * CWT * sizeof(uint32_t), 256));
+        if ((int64_t)g.N * g.H * g.W * g.CW >= ((int64_t)1 << 31)) return SNN_ERR_UNSUPPORTED;
+        int co_per_block = g.C_out;
+        while (co_per_block > 16 && pblocks * ((g.C_out + co_per_block - 1) / co_per_block) < 2048)
+            co_per_block = (co_per_block + 1) / 2;
+        const int cgroups = (g.C_out + co_per_block - 1) / co_per_block;
+        if (cgroups > 65535) return SNN_ERR_UNSUPPORTED;
+        hipLaunchKernelGGL(bnn_prep_bin_kernel, dim3((unsigned)((g.C_out + 3) / 4)), dim3(256), 0, s, w9, g.C_out,
+                           g.C_out, g.C_in, CWT, 1, wplanes, corr);
+        const dim3 grid((unsigned)pblocks, (unsigned)cgroups), block(BNN_THREADS);
+        const uint32_t *xp = (const uint32_t *)x;
 #define SNN_BNN_CASE(CWT_)                                                                                   \
     case CWT_:                                                                                               \
-        hipLaunchKernelGGL(bnn_bin_kernel<CWT_>, grid, block, 0, s, xp, wplanes, corr, alpha, y, g,           \
+        hipLaunchKernelGGL(bnn_regs_kernel<CWT_>, grid, block, 0, s, xp, wplanes, corr, alpha, y, g,          \
                            co_per_block);                                                                    \
         break;
-    switch (CWT) {
-        SNN_BNN_CASE(1)
-        SNN_BNN_CASE(2)
-        SNN_BNN_CASE(4)
-        SNN_BNN_CASE(8)
-        SNN_BNN_CASE(16)
-    default:
-        return SNN_ERR_UNSUPPORTED;
-    }
+        switch (CWT) {
+            SNN_BNN_CASE(1)
+            SNN_BNN_CASE(2)
+            SNN_BNN_CASE(4)
+            SNN_BNN_CASE(8)
+            SNN_BNN_CASE(16)
+        }
 #undef SNN_BNN_CASE
+        return check_launch();
+    }
+
+    const BnnCfg c = bnn_cfg(g);
+    const int COP = (g.C_out + c.COG - 1) / c.COG * c.COG;
+    uint32_t *wq = (uint32_t *)ws;
+    int32_t *corr = (int32_t *)((char *)ws + align_up((size_t)COP * 9 * g.CW * sizeof(uint32_t), 256));
+    const int64_t pb = (g.P + (int64_t)BNN_THREADS * c.PXL - 1) / ((int64_t)BNN_THREADS * c.PXL);
+    const int cgroups = COP / c.COG;
+    if (pb > 0x7fffffffLL || cgroups > 65535) return SNN_ERR_UNSUPPORTED;
+    // the kernel addresses the packed input with 32-bit word offsets
+    if ((int64_t)g.N * g.H * g.W * g.CW >= ((int64_t)1 << 31)) return SNN_ERR_UNSUPPORTED;
+
+    hipLaunchKernelGGL(bnn_prep_bin_kernel, dim3((unsigned)((COP + 3) / 4)), dim3(256), 0, s, w9, g.C_out, COP, g.C_in,
+                       g.CW, c.COG, wq, corr);
+
+    const dim3 grid((unsigned)pb, (unsigned)cgroups), block(BNN_THREADS);
+    const uint32_t *xp = (const uint32_t *)x;
+    if (c.PXL == 2)
+        hipLaunchKernelGGL((bnn_bin_kernel<2, 32>), grid, block, 0, s, xp, wq, corr, alpha, y, g);
+    else if (c.COG == 32)
+        hipLaunchKernelGGL((bnn_bin_kernel<1, 32>), grid, block, 0, s, xp, wq, corr, alpha, y, g);
+    else if (c.COG == 16)
+        hipLaunchKernelGGL((bnn_bin_kernel<1, 16>), grid, block, 0, s, xp, wq, corr, alpha, y, g);
+    else
+        hipLaunchKernelGGL((bnn_bin_kernel<1, 8>), grid, block, 0, s, xp, wq, corr, alpha, y, g);
     return check_launch();
 }
 

@@ -7,7 +7,7 @@ namespace snn {
 namespace {
 
 constexpr int PACK_THREADS = 256;
-constexpr int PACK_CHUNK = 8192;   // elements whose sign bits are staged in LDS per pass
+constexpr int PACK_CHUNK = 2048;   // elements whose sign bits are staged in LDS per pass (8 loads per thread)
 
 // Coalesced loads -> wave ballots -> a flat bit stream in LDS -> one output word per thread,
 // cut out of the stream at the row's bit offset (rows need not be multiples of 32 wide).
@@ -27,14 +27,23 @@ void pack_rows_kernel(const float *__restrict__ x, uint32_t *__restrict__ out, i
     for (int seg = 0; seg < row_len; seg += PACK_CHUNK) {
         const int cnt = min(PACK_CHUNK, row_len - seg);
         const float *src = x + r0 * W + seg;
-        const int cnt64 = (cnt + 63) & ~63;
-#pragma unroll 4
-        for (int i = tid; i < cnt64; i += PACK_THREADS) {
-            const bool b = (i < cnt) && (src[i] >= 0.0f);
-            const unsigned long long m = __ballot(b);
-            if ((tid & 63) == 0) {
-                bits[(i >> 6) * 2] = (uint32_t)m;
-                bits[(i >> 6) * 2 + 1] = (uint32_t)(m >> 32);
+        // eight independent loads in flight per thread, then eight ballots
+        constexpr int U = 8;
+        for (int base = 0; base < cnt; base += PACK_THREADS * U) {
+            float v[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int i = base + u * PACK_THREADS + tid;
+                v[u] = i < cnt ? src[i] : -1.0f;
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int i = base + u * PACK_THREADS + tid;
+                const unsigned long long m = __ballot(v[u] >= 0.0f);
+                if ((tid & 63) == 0 && (i & ~63) < cnt) {
+                    bits[(i >> 6) * 2] = (uint32_t)m;
+                    bits[(i >> 6) * 2 + 1] = (uint32_t)(m >> 32);
+                }
             }
         }
         __syncthreads();

@@ -10,48 +10,76 @@ namespace snn {
 namespace {
 
 constexpr int PROJ_THREADS = 256;
+constexpr int PROJ_PER = 2;                  // kernels per thread: one coefficient read serves two chains
+constexpr int PROJ_BLOCK = PROJ_THREADS * PROJ_PER;
 
 __global__ __launch_bounds__(PROJ_THREADS)
 void project_kernel(const float *__restrict__ w, int64_t n, const uint16_t *__restrict__ codebook, int K,
                     uint16_t *__restrict__ idx_out)
 {
-    extern __shared__ float lds[];
-    float *coef = lds;                       // [K][9]  +1.0f / -1.0f
-    float *wl = lds + K * 9;                 // [PROJ_THREADS][9] staged kernels
+    extern __shared__ __align__(16) float lds[];
+    float *coef = lds;                       // [K][12]  +1.0f / -1.0f, taps 0..8 (+3 pad): three 16-byte reads
+    float *wl = lds + K * 12;                // [PROJ_BLOCK][9] staged kernels
     const int tid = threadIdx.x;
 
-    for (int i = tid; i < K * 9; i += PROJ_THREADS) {
-        const int k = i / 9, t = i - 9 * k;
-        coef[i] = ((codebook[k] >> (8 - t)) & 1) ? 1.0f : -1.0f;
+    for (int i = tid; i < K * 12; i += PROJ_THREADS) {
+        const int k = i / 12, t = i - 12 * k;
+        coef[i] = (t < 9 && ((codebook[k] >> (8 - t)) & 1)) ? 1.0f : -1.0f;
     }
 
-    const int64_t c0 = (int64_t)blockIdx.x * PROJ_THREADS;
-    const int cnt = (int)min((int64_t)PROJ_THREADS, n - c0);
+    const int64_t c0 = (int64_t)blockIdx.x * PROJ_BLOCK;
+    const int cnt = (int)min((int64_t)PROJ_BLOCK, n - c0);
     const float *src = w + c0 * 9;
-    for (int i = tid; i < cnt * 9; i += PROJ_THREADS)
-        wl[i] = src[i];
-    __syncthreads();
-    if (tid >= cnt) return;
-
-    float wt[9];
+    if (cnt == PROJ_BLOCK && (((uintptr_t)w) & 15) == 0) {
+        // full block: 16-byte loads (the block starts at a multiple of 16 bytes)
+        const float4 *s4 = (const float4 *)src;
 #pragma unroll
-    for (int t = 0; t < 9; ++t)
-        wt[t] = wl[tid * 9 + t];
+        for (int i = tid; i < PROJ_BLOCK * 9 / 4; i += PROJ_THREADS) ((float4 *)wl)[i] = s4[i];
+    } else {
+        for (int i = tid; i < cnt * 9; i += PROJ_THREADS) wl[i] = src[i];
+    }
+    __syncthreads();
 
-    int best = 0;
-    float best_score = 0.0f;
-    for (int k = 0; k < K; ++k) {
-        const float *ck = coef + k * 9;
-        float acc = 0.0f;
+    // thread handles kernels tid and tid + 256 of the block (stride-9 LDS reads: no conflicts)
+    float wt[PROJ_PER][9];
+#pragma unroll
+    for (int q = 0; q < PROJ_PER; ++q)
 #pragma unroll
         for (int t = 0; t < 9; ++t)
-            acc = __builtin_fmaf(wt[t], ck[t], acc);
-        if (k == 0 || acc > best_score) {
-            best = k;
-            best_score = acc;
+            wt[q][t] = (q * PROJ_THREADS + tid < cnt) ? wl[(q * PROJ_THREADS + tid) * 9 + t] : 0.0f;
+
+    int best[PROJ_PER];
+    float best_score[PROJ_PER];
+#pragma unroll
+    for (int q = 0; q < PROJ_PER; ++q) {
+        best[q] = 0;
+        best_score[q] = 0.0f;
+    }
+    for (int k = 0; k < K; ++k) {
+        const float4 ca = *(const float4 *)(coef + k * 12);          // wave-uniform address: broadcast
+        const float4 cb = *(const float4 *)(coef + k * 12 + 4);
+        const float c8 = coef[k * 12 + 8];
+#pragma unroll
+        for (int q = 0; q < PROJ_PER; ++q) {
+            float acc = 0.0f;
+            acc = __builtin_fmaf(wt[q][0], ca.x, acc);
+            acc = __builtin_fmaf(wt[q][1], ca.y, acc);
+            acc = __builtin_fmaf(wt[q][2], ca.z, acc);
+            acc = __builtin_fmaf(wt[q][3], ca.w, acc);
+            acc = __builtin_fmaf(wt[q][4], cb.x, acc);
+            acc = __builtin_fmaf(wt[q][5], cb.y, acc);
+            acc = __builtin_fmaf(wt[q][6], cb.z, acc);
+            acc = __builtin_fmaf(wt[q][7], cb.w, acc);
+            acc = __builtin_fmaf(wt[q][8], c8, acc);
+            if (k == 0 || acc > best_score[q]) {
+                best[q] = k;
+                best_score[q] = acc;
+            }
         }
     }
-    idx_out[c0 + tid] = (uint16_t)best;
+#pragma unroll
+    for (int q = 0; q < PROJ_PER; ++q)
+        if (q * PROJ_THREADS + tid < cnt) idx_out[c0 + q * PROJ_THREADS + tid] = (uint16_t)best[q];
 }
 
 }  // namespace
@@ -59,9 +87,9 @@ void project_kernel(const float *__restrict__ w, int64_t n, const uint16_t *__re
 int launch_project(const float *w, int64_t n, const uint16_t *codebook, int K, uint16_t *idx_out,
                    hipStream_t s)
 {
-    const int64_t blocks = (n + PROJ_THREADS - 1) / PROJ_THREADS;
+    const int64_t blocks = (n + PROJ_BLOCK - 1) / PROJ_BLOCK;
     if (blocks > 0x7fffffffLL) return SNN_ERR_INVALID_ARG;
-    const size_t lds = (size_t)(K * 9 + PROJ_THREADS * 9) * sizeof(float);   // <= 27.6 KB
+    const size_t lds = (size_t)(K * 12 + PROJ_BLOCK * 9) * sizeof(float);    // <= 43 KB
     hipLaunchKernelGGL(project_kernel, dim3((unsigned)blocks), dim3(PROJ_THREADS), lds, s, w, n, codebook, K,
                        idx_out);
     return check_launch();

@@ -25,8 +25,7 @@ bool subbit_act_supported(int act) { return act == SNN_ACT_BIN_ROWS || act == SN
 
 bool bnn_supported(const snn_conv_desc *d)
 {
-    if (d->act == SNN_ACT_F32) return true;
-    return d->act == SNN_ACT_BIN_CHANNELS && d->C_in <= 512;
+    return d->act == SNN_ACT_F32 || d->act == SNN_ACT_BIN_CHANNELS;
 }
 
 }  // namespace

@@ -163,15 +163,11 @@ struct WinGeom {
     uint32_t mlo[3], mhi[3];
 };
 
-// p: first output pixel whose window starts at this geometry (one pixel, or an aligned group of four
-// pixels of one output row).
-__device__ inline WinGeom win_geom(int64_t p, const Geom &g)
+// (n, ho, wo): first output pixel whose window starts at this geometry (one pixel, or an aligned
+// group of four pixels of one output row).
+__device__ inline WinGeom win_geom_at(int n, int ho, int wo, const Geom &g)
 {
     WinGeom q;
-    if (p >= g.P) p = g.P - 1;
-    const int n = (int)(p / g.HoWo);
-    const int r = (int)(p - (int64_t)n * g.HoWo);
-    const int ho = r / g.Wo, wo = r - ho * g.Wo;
     const int hc = ho * g.stride, wc = wo * g.stride;
     const uint32_t plane0 = (uint32_t)n * (uint32_t)g.C_in * (uint32_t)(g.H * g.WW);
     const int c = wc - 1;
@@ -204,10 +200,21 @@ __device__ inline WinGeom win_geom(int64_t p, const Geom &g)
     return q;
 }
 
+__device__ inline WinGeom win_geom(int64_t p, const Geom &g)
+{
+    if (p >= g.P) p = g.P - 1;
+    const int n = (int)(p / g.HoWo);
+    const int r = (int)(p - (int64_t)n * g.HoWo);
+    const int ho = r / g.Wo;
+    return win_geom_at(n, ho, r - ho * g.Wo, g);
+}
+
 struct WinRaw {
     uint32_t lo[3], hi[3];
 };
 
+// W1: packed rows are one word wide, so the "next word" is the same word and is not loaded again.
+template <bool W1>
 __device__ inline WinRaw win_load(const uint32_t *__restrict__ x, const WinGeom &q, uint32_t ci_bytes)
 {
     WinRaw r;
@@ -215,7 +222,7 @@ __device__ inline WinRaw win_load(const uint32_t *__restrict__ x, const WinGeom 
 #pragma unroll
     for (int dy = 0; dy < 3; ++dy) {
         r.lo[dy] = *(const uint32_t *)(xb + (size_t)(q.off_lo[dy] + ci_bytes));
-        r.hi[dy] = *(const uint32_t *)(xb + (size_t)(q.off_hi[dy] + ci_bytes));
+        r.hi[dy] = W1 ? r.lo[dy] : *(const uint32_t *)(xb + (size_t)(q.off_hi[dy] + ci_bytes));
     }
     return r;
 }
@@ -237,10 +244,14 @@ __device__ inline uint32_t win_pick(const uint32_t row[3], int shift)
 // QUAD: W_out is a multiple of 4, so every aligned group of four tile pixels lies in one output
 // row and stage 1 cuts its four windows out of three funnel-shifted row strings.  Otherwise the
 // windows are extracted one pixel at a time and staged through LDS.
-template <int G, int J, int NW, int KP, int CIC, bool QUAD>
+// MODE: 0 = windows one pixel at a time; 1 = the same with one-word rows; 2 = QUAD; 3 = QUAD with
+// one-word rows.
+template <int G, int J, int NW, int KP, int CIC, int MODE>
 __global__ __launch_bounds__(NW * 64)
 void subbit_lut_kernel(const SbParams p)
 {
+    constexpr bool QUAD = MODE >= 2;
+    constexpr bool W1 = (MODE & 1) != 0;
     constexpr int NT = NW * 64;
     constexpr int TP = 16 * G;                     // pixels per tile
     constexpr int WPT = 4 * G;                     // 4-pixel words per tile row
@@ -292,7 +303,7 @@ void subbit_lut_kernel(const SbParams p)
             const int ci_l = (tid + m * NT) / WPT;
             const int ci = chunk * CIC + (ci_l < CIC ? ci_l : 0);
             qok |= (ci < g.C_in ? 1u : 0u) << m;
-            qraw[m] = win_load(p.x, geo, (uint32_t)min(ci, g.C_in - 1) * plane_bytes);   // always a valid address
+            qraw[m] = win_load<W1>(p.x, geo, (uint32_t)min(ci, g.C_in - 1) * plane_bytes);   // always a valid address
         }
     };
     auto load_windows = [&](int chunk) {
@@ -302,7 +313,7 @@ void subbit_lut_kernel(const SbParams p)
             const int ci_l = tid / TP + m * (NT / TP);
             const int ci = chunk * CIC + (ci_l < CIC ? ci_l : 0);
             raw_ok |= (ci < g.C_in ? 1u : 0u) << m;
-            raw[m] = win_load(p.x, geo, (uint32_t)min(ci, g.C_in - 1) * plane_bytes);
+            raw[m] = win_load<W1>(p.x, geo, (uint32_t)min(ci, g.C_in - 1) * plane_bytes);
         }
     };
     // input channels past C_in get window 512, the all-zero table row
@@ -524,10 +535,12 @@ void subbit_lut_kernel(const SbParams p)
 constexpr int WV_NW = 8;       // waves per workgroup
 constexpr int WV_CIC = 8;      // input channels per chunk
 
-template <int J, int KP, bool QUAD>
+template <int J, int KP, int MODE>
 __global__ __launch_bounds__(WV_NW * 64)
 void subbit_wave_kernel(const SbParams p)
 {
+    constexpr bool QUAD = MODE >= 2;
+    constexpr bool W1 = (MODE & 1) != 0;
     constexpr int NT = WV_NW * 64;
     constexpr int CIC = WV_CIC;
     constexpr int KV = KP / 16;
@@ -542,7 +555,8 @@ void subbit_wave_kernel(const SbParams p)
     extern __shared__ __align__(16) unsigned char smem[];
     unsigned char *lut = smem;                                            // [513][LROW]
     const int tid = threadIdx.x;
-    const int lane = tid & 63, wave = tid >> 6;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);            // scalar: per-tile geometry stays on the SALU
     unsigned char *T = lut + 513 * LROW + wave * (CIC * TS + CIC * 16 * 2);   // this wave's [CIC][TS]
     uint16_t *wbuf = (uint16_t *)(T + CIC * TS);                          // this wave's [CIC][16] windows (!QUAD)
 
@@ -559,10 +573,37 @@ void subbit_wave_kernel(const SbParams p)
     const int64_t tstride = (int64_t)gridDim.x * WV_NW;
     for (int64_t tile = (int64_t)blockIdx.x * WV_NW + wave; tile < ntiles; tile += tstride) {
     const int64_t p_tile = tile * 16;
+    // coordinates of the tile's first pixel (wave-uniform, scalar divisions)
+    const int t_n = (int)(p_tile / g.HoWo);
+    const int t_r = (int)(p_tile - (int64_t)t_n * g.HoWo);
+    const int t_ho = t_r / g.Wo, t_wo = t_r - t_ho * g.Wo;
 
     // stage-1 item m of this lane: it = lane + 64 m -> wd = it % 4, kv = (it / 4) % KV, ci_l = it / (4 KV)
     // QUAD: all items of the lane share the pixel group wd = lane % 4.
-    const WinGeom geo = win_geom(QUAD ? p_tile + 4 * (lane & 3) : p_tile + (lane & 15), g);
+    // The lane's pixel is at most 15 past the tile's first one: with rows of 16 or more pixels that
+    // is at most one row (and one image) further, otherwise fall back to dividing.
+    WinGeom geo;
+    {
+        const int d = QUAD ? 4 * (lane & 3) : (lane & 15);
+        if (g.Wo >= 16) {
+            int n = t_n, ho = t_ho, wo = t_wo + d;
+            if (wo >= g.Wo) {
+                wo -= g.Wo;
+                if (++ho == g.Ho) {
+                    ho = 0;
+                    ++n;
+                }
+            }
+            if (n >= g.N) {          // past the last pixel: any valid pixel will do, nothing is stored
+                n = g.N - 1;
+                ho = 0;
+                wo = 0;
+            }
+            geo = win_geom_at(n, ho, wo, g);
+        } else {
+            geo = win_geom(p_tile + d, g);
+        }
+    }
     WinRaw qraw[QUAD ? SM : 1];
     uint32_t qok = 0;
     WinRaw raw[WM];
@@ -574,7 +615,7 @@ void subbit_wave_kernel(const SbParams p)
             const int ci_l = (lane + 64 * m) / (4 * KV);
             const int ci = chunk * CIC + (ci_l < CIC ? ci_l : 0);
             qok |= (ci < g.C_in ? 1u : 0u) << m;
-            qraw[m] = win_load(p.x, geo, (uint32_t)min(ci, g.C_in - 1) * plane_bytes);
+            qraw[m] = win_load<W1>(p.x, geo, (uint32_t)min(ci, g.C_in - 1) * plane_bytes);
         }
     };
     // !QUAD: lane extracts pixel (lane % 16) for input channels lane / 16 + 4 m
@@ -584,7 +625,7 @@ void subbit_wave_kernel(const SbParams p)
         for (int m = 0; m < WM; ++m) {
             const int ci = chunk * CIC + (lane >> 4) + 4 * m;
             raw_ok |= (ci < g.C_in ? 1u : 0u) << m;
-            raw[m] = win_load(p.x, geo, (uint32_t)min(ci, g.C_in - 1) * plane_bytes);
+            raw[m] = win_load<W1>(p.x, geo, (uint32_t)min(ci, g.C_in - 1) * plane_bytes);
         }
     };
     auto store_windows = [&]() {
@@ -721,9 +762,7 @@ void subbit_wave_kernel(const SbParams p)
     float a[J];
 #pragma unroll
     for (int j = 0; j < J; ++j) a[j] = lane_co + j < g.C_out ? p.alpha[lane_co + j] : 0.0f;
-    int n = (int)(p_tile / g.HoWo);
-    int r = (int)(p_tile - (int64_t)n * g.HoWo);
-    int ho = r / g.Wo, wo = r - ho * g.Wo;
+    int n = t_n, r = t_r, ho = t_ho, wo = t_wo;         // wave-uniform
 #pragma unroll
     for (int w = 0; w < 4; ++w) {
         float out[J][4];
@@ -734,15 +773,24 @@ void subbit_wave_kernel(const SbParams p)
             ok[b] = p_tile + 4 * w + b < g.P;
             rr[b] = r;
             nn[b] = n;
-            const int type = border_type(ho, wo, g.H, g.W, g.stride);      // wave-uniform
+            const int type = border_type(ho, wo, g.H, g.W, g.stride);
             const int base = border_valid_taps(type) * g.C_in;
+            if (type == 0) {                            // interior pixel: nothing to correct
 #pragma unroll
-            for (int j = 0; j < J; ++j) {
-                const uint32_t pair = (b & 1) ? wide_o[j][w] : wide_e[j][w];
-                const int M = (int)((pair >> (16 * (b >> 1))) & 0xffffu);
-                const int co = lane_co + j;
-                const int cr = (type != 0 && co < g.C_out) ? p.corr[co * 16 + type] : 0;
-                out[j][b] = (float)(2 * (M - cr) - base) * a[j];
+                for (int j = 0; j < J; ++j) {
+                    const uint32_t pair = (b & 1) ? wide_o[j][w] : wide_e[j][w];
+                    const int M = (int)((pair >> (16 * (b >> 1))) & 0xffffu);
+                    out[j][b] = (float)(2 * M - base) * a[j];
+                }
+            } else {
+#pragma unroll
+                for (int j = 0; j < J; ++j) {
+                    const uint32_t pair = (b & 1) ? wide_o[j][w] : wide_e[j][w];
+                    const int M = (int)((pair >> (16 * (b >> 1))) & 0xffffu);
+                    const int co = lane_co + j;
+                    const int cr = co < g.C_out ? p.corr[co * 16 + type] : 0;
+                    out[j][b] = (float)(2 * (M - cr) - base) * a[j];
+                }
             }
             if (++wo == g.Wo) {
                 wo = 0;
@@ -753,18 +801,19 @@ void subbit_wave_kernel(const SbParams p)
                 ++n;
             }
         }
+        if (p.vec4 && ok[3]) {
+            float *dst = p.y + ((int64_t)nn[0] * g.C_out + lane_co) * g.HoWo + rr[0];
 #pragma unroll
-        for (int j = 0; j < J; ++j) {
-            const int co = lane_co + j;
-            if (co >= g.C_out) continue;
-            if (p.vec4 && ok[3]) {
-                float4 *dst = (float4 *)(p.y + ((int64_t)nn[0] * g.C_out + co) * g.HoWo + rr[0]);
-                *dst = make_float4(out[j][0], out[j][1], out[j][2], out[j][3]);
-            } else {
+            for (int j = 0; j < J; ++j)
+                if (lane_co + j < g.C_out)
+                    *(float4 *)(dst + (int64_t)j * g.HoWo) = make_float4(out[j][0], out[j][1], out[j][2], out[j][3]);
+        } else {
+#pragma unroll
+            for (int j = 0; j < J; ++j)
 #pragma unroll
                 for (int b = 0; b < 4; ++b)
-                    if (ok[b]) p.y[((int64_t)nn[b] * g.C_out + co) * g.HoWo + rr[b]] = out[j][b];
-            }
+                    if (ok[b] && lane_co + j < g.C_out)
+                        p.y[((int64_t)nn[b] * g.C_out + lane_co + j) * g.HoWo + rr[b]] = out[j][b];
         }
     }
     }   // tile loop
@@ -1018,10 +1067,10 @@ SbPlan make_plan(const Geom &g)
     return pl;
 }
 
-template <int J, int KP, bool QUAD>
+template <int J, int KP, int MODE>
 int launch_wave_q(const SbPlan &pl, const SbParams &prm, dim3 grid, hipStream_t s)
 {
-    auto kern = subbit_wave_kernel<J, KP, QUAD>;
+    auto kern = subbit_wave_kernel<J, KP, MODE>;
     if (pl.lds > 64 * 1024 &&
         hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)pl.lds) != hipSuccess)
         return SNN_ERR_LAUNCH;
@@ -1033,11 +1082,14 @@ template <int J>
 int launch_wave(const SbPlan &pl, const SbParams &prm, dim3 grid, hipStream_t s)
 {
     const int KP = round16(prm.g.K);
-    const bool quad = (prm.g.Wo & 3) == 0;
+    const int mode = ((prm.g.Wo & 3) == 0 ? 2 : 0) | (prm.g.WW == 1 ? 1 : 0);
 #define SNN_WAVE_KP(KP_)                                                              \
-    if (KP == KP_)                                                                    \
-        return quad ? launch_wave_q<J, KP_, true>(pl, prm, grid, s)                   \
-                    : launch_wave_q<J, KP_, false>(pl, prm, grid, s);
+    if (KP == KP_) switch (mode) {                                                    \
+        case 0: return launch_wave_q<J, KP_, 0>(pl, prm, grid, s);                    \
+        case 1: return launch_wave_q<J, KP_, 1>(pl, prm, grid, s);                    \
+        case 2: return launch_wave_q<J, KP_, 2>(pl, prm, grid, s);                    \
+        default: return launch_wave_q<J, KP_, 3>(pl, prm, grid, s);                   \
+        }
     SNN_WAVE_KP(32)
 #ifndef SNN_FAST_BUILD
     SNN_WAVE_KP(16)
@@ -1048,10 +1100,10 @@ int launch_wave(const SbPlan &pl, const SbParams &prm, dim3 grid, hipStream_t s)
     return SNN_ERR_UNSUPPORTED;
 }
 
-template <int G, int J, int NW, int KP, int CIC, bool QUAD>
+template <int G, int J, int NW, int KP, int CIC, int MODE>
 int launch_lut_w(const SbPlan &pl, const SbParams &prm, dim3 grid, hipStream_t s)
 {
-    auto kern = subbit_lut_kernel<G, J, NW, KP, CIC, QUAD>;
+    auto kern = subbit_lut_kernel<G, J, NW, KP, CIC, MODE>;
     if (pl.lds > 64 * 1024 &&
         hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)pl.lds) != hipSuccess)
         return SNN_ERR_LAUNCH;
@@ -1062,8 +1114,13 @@ int launch_lut_w(const SbPlan &pl, const SbParams &prm, dim3 grid, hipStream_t s
 template <int G, int J, int NW, int KP, int CIC>
 int launch_lut_one(const SbPlan &pl, const SbParams &prm, dim3 grid, hipStream_t s)
 {
-    return (prm.g.Wo & 3) == 0 ? launch_lut_w<G, J, NW, KP, CIC, true>(pl, prm, grid, s)
-                               : launch_lut_w<G, J, NW, KP, CIC, false>(pl, prm, grid, s);
+    const int mode = ((prm.g.Wo & 3) == 0 ? 2 : 0) | (prm.g.WW == 1 ? 1 : 0);
+    switch (mode) {
+    case 0: return launch_lut_w<G, J, NW, KP, CIC, 0>(pl, prm, grid, s);
+    case 1: return launch_lut_w<G, J, NW, KP, CIC, 1>(pl, prm, grid, s);
+    case 2: return launch_lut_w<G, J, NW, KP, CIC, 2>(pl, prm, grid, s);
+    default: return launch_lut_w<G, J, NW, KP, CIC, 3>(pl, prm, grid, s);
+    }
 }
 
 template <int G, int J, int NW>

@@ -63,6 +63,7 @@ BNN_CASES = [
     (2, 32, 16, 6, 6, 1), (2, 16, 16, 32, 32, 1), (3, 40, 10, 7, 9, 1), (2, 64, 24, 8, 8, 2), (2, 100, 7, 5, 4, 2),
     (1, 1, 1, 1, 1, 1), (1, 3, 2, 1, 5, 1), (1, 3, 2, 5, 1, 2), (4, 256, 64, 14, 14, 1), (2, 512, 48, 7, 7, 1),
     (2, 128, 32, 15, 13, 2), (3, 300, 9, 3, 3, 1),
+    (2, 600, 20, 5, 5, 1), (1, 1030, 40, 3, 4, 2), (64, 520, 33, 7, 7, 1),      # C_in > 512: the streaming kernel
 ]
 
 
