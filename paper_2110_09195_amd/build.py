@@ -13,10 +13,12 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libsnn_hip.so")
-SOURCES = ["snn_api.hip", "pack.hip", "project.hip", "bnn_conv.hip", "subbit_conv.hip", "subbit_f32.hip"]
+SOURCES = ["snn_api.hip", "pack.hip", "project.hip", "bnn_conv.hip", "subbit_conv.hip", "subbit_f32.hip", "subbit_mfma.hip"]
 
 # Packed-fp32 VALU forms are switched off for all device code of this library.
 FAST = ["-DSNN_FAST_BUILD"] if os.environ.get("SNN_FAST_BUILD") else []
+if os.environ.get("SNN_TUNE_BUILD"):
+    FAST = ["-DSNN_FAST_BUILD"] + os.environ["SNN_TUNE_BUILD"].split()
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-fno-gpu-rdc",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wall", "-Wno-unused-function",

@@ -84,6 +84,12 @@ size_t subbit_workspace_bytes(const Geom &g, int act);
 int launch_subbit(const Geom &g, int act, const void *x, const uint16_t *codebook,
                   const uint16_t *idx, const float *alpha, float *y, void *ws, hipStream_t s);
 
+// matrix-core variant of the sub-bit convolution (+-1 activations, K <= 64)
+bool subbit_mfma_supported(const Geom &g);
+size_t subbit_mfma_workspace_bytes(const Geom &g);
+int launch_subbit_mfma(const Geom &g, const void *x, const uint16_t *codebook, const uint16_t *idx,
+                       const float *alpha, float *y, void *ws, hipStream_t s);
+
 inline int check_launch()
 {
     return hipGetLastError() == hipSuccess ? SNN_OK : SNN_ERR_LAUNCH;

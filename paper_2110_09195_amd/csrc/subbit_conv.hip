@@ -1158,16 +1158,28 @@ int launch_subbit_f32(const Geom &g, const void *x, const uint16_t *codebook, co
                       const float *alpha, float *y, void *ws, hipStream_t s);
 size_t subbit_f32_workspace_bytes(const Geom &g);
 
+// The matrix-core kernel takes every layer it supports; SNN_SUBBIT_MFMA=0 (a tuning override)
+// sends those layers to the LDS-gather kernels of this file instead.
+static bool use_mfma(const Geom &g)
+{
+    const char *e = getenv("SNN_SUBBIT_MFMA");
+    return subbit_mfma_supported(g) && !(e && e[0] == '0');
+}
+
 size_t subbit_workspace_bytes(const Geom &g, int act)
 {
     if (act == SNN_ACT_F32) return subbit_f32_workspace_bytes(g);
-    return make_plan(g).bytes;
+    // sized for either kernel family, so that the override cannot outgrow a workspace
+    const size_t a = make_plan(g).bytes;
+    const size_t b = subbit_mfma_supported(g) ? subbit_mfma_workspace_bytes(g) : 0;
+    return a > b ? a : b;
 }
 
 int launch_subbit(const Geom &g, int act, const void *x, const uint16_t *codebook, const uint16_t *idx,
                   const float *alpha, float *y, void *ws, hipStream_t s)
 {
     if (act == SNN_ACT_F32) return launch_subbit_f32(g, x, codebook, idx, alpha, y, ws, s);
+    if (use_mfma(g)) return launch_subbit_mfma(g, x, codebook, idx, alpha, y, ws, s);
 
     const SbPlan pl = make_plan(g);
     const SbCfg &c = pl.cfg;

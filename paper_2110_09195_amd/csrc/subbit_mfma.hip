@@ -1,0 +1,659 @@
+// Sub-bit 3x3 convolution for K <= 32 on the matrix cores (Sec. 4.5 / Fig. 6).
+//
+// Stage 1 (responses of the K subset kernels, once per input channel and pixel) is a table
+// lookup: the 9-bit window of +-1 activations selects a row of K match counts
+// m_k = 9 - popcount(window ^ code_k) in [0, 9], taps outside the image forced to "no match" and
+// corrected at the end.  Stage 2 (gather by index, sum over c_in) is written as a product with a
+// one-hot matrix, contracted over (c_in, k):
+//     M[co][pixel] = sum_ci sum_k  onehot(idx[co][ci])[k] * m_k(window[ci][pixel])
+// One v_mfma_scale_f32_32x32x64_f8f6f4 covers 32 output channels x 32 pixels x TWO input channels:
+// its 64 contraction slots are (channel parity, subset member k); lanes 0-31 supply the slots of
+// the even channel, lanes 32-63 those of the odd one.
+//   A operand (FP4 e2m1): the one-hot row of an output channel, 32 nibbles, made from a
+//     pre-computed byte selector with four v_perm_b32;
+//   B operand (FP6 e2m3): the table row itself, stored as m_k - 4 in [-4, 5] (exact in e2m3), read
+//     from LDS as it is: the responses never need transposing or a trip through LDS;
+//   accumulation in fp32 is exact (integers far below 2^24).
+// S = 2 * (M' + 4 C_in - corr[co][border type]) - C_in * valid_taps with M' the accumulated sum,
+// y = float(S) * alpha[co].
+//
+// A wave owns PB blocks of 32 pixels x CB blocks of 32 output channels and a range of input
+// channel pairs; the KS waves that split the channels of one tile sit in one workgroup and add
+// their partial sums through LDS.
+#include "snn_internal.h"
+
+namespace snn {
+
+namespace {
+
+typedef int v8i __attribute__((ext_vector_type(8)));
+typedef float v16f __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) const u32x4 lds_cu32x4;
+typedef __attribute__((address_space(3))) const u32x2 lds_cu32x2;
+typedef __attribute__((address_space(3))) u32x4 lds_u32x4;
+
+constexpr int MF_WAVES = 4;                    // waves per workgroup
+constexpr uint32_t MF_SEL_NONE = 0x0c0c0c0cu;  // v_perm_b32 selector bytes that produce 0x00
+constexpr int MF_LROW = 48;                    // table row stride: 24 bytes used, an odd number of 16-byte pieces
+
+struct MfParams {
+    const uint32_t *x;        // packed rows [N][C_in][H][WW]
+    const uint4 *lut;         // [512][MF_LROW] bytes: row = window, 32 FP6 values m_k - 4 packed little-endian
+    const uint32_t *sel;      // [pairs][2][COP] selector words for the one-hot operand
+    const uint2 *fin;         // [COP][16] per (output channel, border type): {2 corr + C_in (valid_taps - 8), alpha bits}
+    float *y;
+    Geom g;
+    int COP;                  // C_out padded to whole wave tiles
+    int KS;                   // waves that split the channel pairs of one tile: 1, 2 or 4
+    int npairs;               // (C_in + 1) / 2 steps of two input channels
+    int pairs_per_split;
+    int n_cotiles;
+    long long n_tiles;        // pixel tiles * channel tiles
+#ifdef SNN_MF_DBG
+    int dbg;                  // timing experiments: 1 = no loads in the loop, 2 = no MFMA, 4 = no table reads
+    unsigned long long *trace;
+#endif
+};
+#ifdef SNN_MF_DBG
+#define MF_TRACE(slot)                                                                          \
+    do {                                                                                        \
+        if ((blockIdx.x == 3 || blockIdx.x == gridDim.x / 2) && (threadIdx.x & 63) == 0)        \
+            p.trace[((blockIdx.x == 3 ? 0 : 4) + (threadIdx.x >> 6)) * 16 + (slot)] = wall_clock64(); \
+    } while (0)
+#else
+#define MF_TRACE(slot) do { } while (0)
+#endif
+
+// FP6 e2m3 code of an integer in [-7, 7]
+__host__ __device__ inline uint32_t fp6_of_int(int v)
+{
+    const uint32_t s = v < 0 ? 32u : 0u;
+    const int a = v < 0 ? -v : v;
+    // 0; 1 = 1.000 x 2^0; 2, 3 = 1.m x 2^1; 4 .. 7 = 1.m x 2^2  (bias 1, three mantissa bits)
+    const uint32_t mag = a == 0 ? 0u : a == 1 ? 8u : a < 4 ? 16u + 4u * (uint32_t)(a - 2) : 24u + 2u * (uint32_t)(a - 4);
+    return s | mag;
+}
+
+// ---- preparation: selector tables, finishing table, lookup table -----------------------------------
+// Step c of the convolution handles channels (2c, 2c+1); for odd C_in the last step handles
+// (C_in-2, C_in-1) and its first half is switched off.
+//   sel[c][h][co]: k = idx[co][channel h of step c]; nibble k of the 32-nibble one-hot row is byte
+//     k / 2 (word k / 8), low or high nibble.  Byte p of the selector is
+//     (p == (k / 2) % 4) ? 2 (k / 8) + k % 2 : 0x0c, so that v_perm_b32 with the 8-byte constant
+//     {0x02 at byte 2 j, 0x20 at byte 2 j + 1} yields word j of the row (FP4 1.0 = 0b0010).
+//   fin[co][type] = {2 corr + C_in * (valid_taps(type) - 8), alpha[co]} with corr = sum over c_in of the
+//     zero bits of the selected code at the taps that border type `type` puts outside the image
+//   lut[window] = 32 FP6 codes of m_k - 4 (0 for k >= K)
+__global__ __launch_bounds__(256)
+void subbit_mfma_prep_kernel(const uint16_t *__restrict__ codebook, const uint16_t *__restrict__ idx, int C_in,
+                             int C_out, int COP, int CB, int K, int sel_blocks, int lut_blocks,
+                             const float *__restrict__ alpha, uint32_t *__restrict__ sel, uint2 *__restrict__ fin,
+                             uint32_t *__restrict__ lut)
+{
+    const int tid = threadIdx.x;
+    const int b = blockIdx.x;
+    if (b < sel_blocks) {
+        // tile of 32 output channels x 32 input channels: read along c_in, write along c_out
+        __shared__ uint16_t tile[32][33];
+        const int cot = COP / 32;
+        const int co0 = (b % cot) * 32, ci0 = (b / cot) * 32;
+        for (int e = tid; e < 1024; e += 256) {
+            const int co = co0 + e / 32, ci = ci0 + e % 32;
+            tile[e / 32][e % 32] = (co < C_out && ci < C_in) ? (uint16_t)min((int)idx[(int64_t)co * C_in + ci], K - 1) : 0xffffu;
+        }
+        __syncthreads();
+        const int npairs = (C_in + 1) / 2;
+        for (int e = tid; e < 1024; e += 256) {
+            const int co_l = e % 32, ci_l = e / 32;
+            const int ci = ci0 + ci_l;
+            if (ci >= C_in) continue;
+            const uint32_t k = tile[co_l][ci_l];
+            uint32_t s = MF_SEL_NONE;
+            if (k != 0xffffu) {
+                const uint32_t code = 2u * ((k >> 3) & 3u) + (k & 1u);
+                const int sh = 8 * ((k >> 1) & 3u);
+                s = (s & ~(0xffu << sh)) | (code << sh);
+            }
+            // channel ci is half (ci % 2) of step ci / 2, except the last channel of an odd C_in
+            int c = ci >> 1, h = ci & 1;
+            // position inside a row of COP selectors: [wave tile][channel in block][block]
+            const int co = co0 + co_l, tilew = 32 * CB;
+            const int pos = (co / tilew) * tilew + (co % 32) * CB + (co % tilew) / 32;
+            if ((C_in & 1) && ci == C_in - 1) {
+                c = npairs - 1;
+                h = 1;
+                sel[((int64_t)c * 2 + 0) * COP + pos] = MF_SEL_NONE;
+            }
+            sel[((int64_t)c * 2 + h) * COP + pos] = s;
+        }
+        return;
+    }
+    if (b >= (int)gridDim.x - lut_blocks) {
+        // one thread per 32-bit word of the table; a row is 6 words of 32 FP6 codes and 6 of padding
+        const int wpr = MF_LROW / 4;
+        const int i = (b - ((int)gridDim.x - lut_blocks)) * 256 + tid;
+        if (i < 512 * wpr) {
+            const int win = i / wpr, w = i - win * wpr;
+            uint32_t word = 0;
+            if (w < 6)
+                for (int k = (32 * w) / 6; k <= (32 * w + 31) / 6 && k < K; ++k) {
+                    const int m = 9 - __popc((uint32_t)win ^ code_to_window_order(codebook[k] & 511u));
+                    const int at = 6 * k - 32 * w;                 // position of the code's bit 0 in this word
+                    const uint32_t code = fp6_of_int(m - 4);
+                    word |= at >= 0 ? code << at : code >> -at;
+                }
+            lut[i] = word;
+        }
+        return;
+    }
+    const int co = (b - sel_blocks) * 4 + (tid >> 6);          // one wave per output channel
+    const int lane = tid & 63;
+    if (co >= COP) return;
+    int zeros[9];
+#pragma unroll
+    for (int t = 0; t < 9; ++t) zeros[t] = 0;
+    if (co < C_out)
+        for (int c0 = 0; c0 < C_in; c0 += 64) {
+            const int ci = c0 + lane;
+            uint32_t z = 0;
+            if (ci < C_in) {
+                const int k = min((int)idx[(int64_t)co * C_in + ci], K - 1);
+                z = ~code_to_window_order(codebook[k] & 511u) & 511u;
+            }
+#pragma unroll
+            for (int t = 0; t < 9; ++t) zeros[t] += __popcll(__ballot((z >> t) & 1u));
+        }
+    if (lane < 16) {
+        const uint32_t inv = border_invalid_window(lane);
+        int s = 0;
+#pragma unroll
+        for (int t = 0; t < 9; ++t)
+            if ((inv >> t) & 1u) s += zeros[t];
+        const float a = co < C_out ? alpha[co] : 0.0f;
+        fin[co * 16 + lane] = make_uint2((uint32_t)(2 * s + (border_valid_taps(lane) - 8) * C_in), __float_as_uint(a));
+    }
+}
+
+// Buffer accesses: a scalar resource descriptor and scalar offset carry the wave-uniform part of the
+// address (tensor base, input channel / output channel), the lane supplies a 32-bit byte offset: no
+// address arithmetic in the vector ALU.  Lane offsets past the end of the buffer read as zero
+// and are not stored.
+__device__ inline __amdgpu_buffer_rsrc_t make_rsrc(const void *base, uint32_t bytes)
+{
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, (int)bytes, 0x00020000);
+}
+__device__ inline void buf_store(__amdgpu_buffer_rsrc_t r, float v, uint32_t lane_off, uint32_t uniform_off)
+{
+    __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(v), r, (int)lane_off, (int)uniform_off, 0);
+}
+typedef uint32_t u32x3 __attribute__((ext_vector_type(3)));
+__device__ inline u32x2 buf_load2(__amdgpu_buffer_rsrc_t r, uint32_t lane_off, uint32_t uniform_off)
+{
+    return __builtin_amdgcn_raw_buffer_load_b64(r, (int)lane_off, (int)uniform_off, 0);
+}
+__device__ inline u32x3 buf_load3(__amdgpu_buffer_rsrc_t r, uint32_t lane_off, uint32_t uniform_off)
+{
+    return __builtin_amdgcn_raw_buffer_load_b96(r, (int)lane_off, (int)uniform_off, 0);
+}
+__device__ inline u32x4 buf_load4(__amdgpu_buffer_rsrc_t r, uint32_t lane_off, uint32_t uniform_off)
+{
+    return __builtin_amdgcn_raw_buffer_load_b128(r, (int)lane_off, (int)uniform_off, 0);
+}
+
+// ---- the convolution ------------------------------------------------------------------------------
+// PB, CB: blocks of 32 pixels / 32 output channels per wave.  WM: words per packed row, 1 or 2
+// (the three window rows of a lane are then one contiguous load), or 0 for wider rows.
+template <int PB, int CB, int WM>
+__global__ __launch_bounds__(MF_WAVES * 64, 2)
+void subbit_mfma_kernel(const MfParams p)
+{
+    constexpr int NBLK = PB * CB;
+    const Geom &g = p.g;
+
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int n_l = lane & 31, h = lane >> 5;
+
+    const int KS = p.KS;
+    const int split = wave & (KS - 1);
+    const int tile_in_wg = wave / KS;
+    const long long tile = (long long)blockIdx.x * (MF_WAVES / KS) + tile_in_wg;
+    const bool active = tile < p.n_tiles;                       // wave-uniform
+    const long long tl = active ? tile : p.n_tiles - 1;
+    const int co_tile = (int)(tl % p.n_cotiles);
+    const long long p_tile = (tl / p.n_cotiles) * (32 * PB);
+    const int co0 = co_tile * (32 * CB);
+
+    MF_TRACE(0);
+
+    // ---- per-lane window geometry of the PB pixels (pixel n_l of every block) ----------------------
+    // This lane looks at input channel (2 c + h) in step c.  It loads three consecutive packed rows
+    // starting at row max(hc - 1, 0), words (jlo, jlo + 1), and cuts row dy of the window out of the
+    // 64-bit string {hi, lo} at bit `sh`.  Two cases are folded into a final shift `lsh` of the
+    // 9-bit window so that no load starts before the tensor:
+    //   top image row   : the rows loaded are (hc, hc + 1, hc + 2), i.e. window rows 1, 2, 3 -> shift by 3;
+    //   first image column: the bits cut out are columns (0, 1, 2) -> keep two (`m7` = 3), shift by 1.
+    // Nothing else is clamped: words from outside the row, the image or the tensor (the latter read
+    // as zero) only reach window bits whose taps lie outside the image, and `vm` masks those off.
+    const uint32_t plane_bytes = (uint32_t)(g.H * g.WW) * 4u;
+    uint32_t xoff[PB];                             // byte offset of the first word loaded, channel h of the pixel's image
+    uint32_t sh[PB], m7[PB], lsh[PB], vm[PB];
+    uint32_t yoff[PB];                             // byte offset of y[n][4 h][pixel], out of range for pixels past the end
+    int ptype[PB];                                 // border type
+    const int P32 = (int)g.P;
+#pragma unroll
+    for (int pb = 0; pb < PB; ++pb) {
+        int pp = (int)p_tile + pb * 32 + n_l;
+        const bool ok = pp < P32;
+        if (!ok) pp = P32 - 1;
+        const int n = pp / g.HoWo;
+        const int r = pp - n * g.HoWo;
+        const int ho = r / g.Wo, wo = r - ho * g.Wo;
+        yoff[pb] = ok ? (uint32_t)((n * g.C_out + 4 * h) * g.HoWo + r) * 4u : 0xffffffffu;
+        ptype[pb] = border_type(ho, wo, g.H, g.W, g.stride);
+        vm[pb] = ~border_invalid_window(ptype[pb]) & 0x1ffu;
+        const int hc = ho * g.stride, first = wo * g.stride - 1;
+        const int col = first < 0 ? 0 : first;     // column of the first bit cut out
+        const int jlo = WM == 1 ? 0 : col >> 5;
+        sh[pb] = (uint32_t)(col & 31);
+        m7[pb] = first < 0 ? 3u : 7u;
+        lsh[pb] = (first < 0 ? 1u : 0u) + (hc == 0 ? 3u : 0u);
+        xoff[pb] = (uint32_t)(((n * g.C_in + h) * g.H + (hc == 0 ? 0 : hc - 1)) * g.WW + jlo) * 4u;
+    }
+    const __amdgpu_buffer_rsrc_t xres = make_rsrc(p.x, (uint32_t)g.N * (uint32_t)g.C_in * plane_bytes);
+    const uint32_t lut_base = (uint32_t)(uintptr_t)smem;
+
+    struct Raw {
+        uint32_t lo[PB][3], hi[WM == 1 ? 1 : PB][3];
+    };
+    // step c -> first channel of the pair (the last step of an odd C_in starts one channel early)
+    const int last_first = g.C_in - 2;
+    const uint32_t row_bytes = (uint32_t)g.WW * 4u;
+    auto load_raw = [&](int c, Raw &r) {
+        const uint32_t co = (uint32_t)min(2 * c, last_first) * plane_bytes;
+#pragma unroll
+        for (int pb = 0; pb < PB; ++pb) {
+            if constexpr (WM == 1) {                 // rows are consecutive words
+                const u32x3 v = buf_load3(xres, xoff[pb], co);
+                r.lo[pb][0] = v.x;
+                r.lo[pb][1] = v.y;
+                r.lo[pb][2] = v.z;
+            } else if constexpr (WM == 2) {          // rows are consecutive word pairs
+                const u32x4 v = buf_load4(xres, xoff[pb], co);
+                const u32x2 w = buf_load2(xres, xoff[pb] + 16u, co);
+                r.lo[pb][0] = v.x;
+                r.hi[pb][0] = v.y;
+                r.lo[pb][1] = v.z;
+                r.hi[pb][1] = v.w;
+                r.lo[pb][2] = w.x;
+                r.hi[pb][2] = w.y;
+            } else {
+#pragma unroll
+                for (int dy = 0; dy < 3; ++dy) {
+                    const u32x2 v = buf_load2(xres, xoff[pb] + (uint32_t)dy * row_bytes, co);
+                    r.lo[pb][dy] = v.x;
+                    r.hi[pb][dy] = v.y;
+                }
+            }
+        }
+    };
+    // selectors of the lane's CB channel blocks are contiguous: [step][half][tile][channel in block][block]
+    const uint32_t sel_step_bytes = 2u * (uint32_t)p.COP * 4u;
+    const __amdgpu_buffer_rsrc_t sres = make_rsrc(p.sel, (uint32_t)p.npairs * sel_step_bytes);
+    const uint32_t sel_lane = (uint32_t)(h * p.COP + co0 + n_l * CB) * 4u;
+    auto load_sel = [&](int c, uint32_t (&s)[CB]) {
+        static_assert(CB == 2 || CB == 4, "selector loads are 8 or 16 bytes");
+        if constexpr (CB == 4) {
+            const u32x4 v = buf_load4(sres, sel_lane, (uint32_t)c * sel_step_bytes);
+            s[0] = v.x;
+            s[1] = v.y;
+            s[2] = v.z;
+            s[3] = v.w;
+        } else {
+            const u32x2 v = buf_load2(sres, sel_lane, (uint32_t)c * sel_step_bytes);
+            s[0] = v.x;
+            s[1] = v.y;
+        }
+    };
+    // table rows of the PB pixels -> B operands (24 bytes: 32 FP6 values)
+    auto make_B = [&](const Raw &r, v8i (&B)[PB]) {
+#pragma unroll
+        for (int pb = 0; pb < PB; ++pb) {
+            uint32_t row[3];
+#pragma unroll
+            for (int dy = 0; dy < 3; ++dy)
+                row[dy] = __builtin_amdgcn_alignbit(WM == 1 ? r.lo[pb][dy] : r.hi[pb][dy], r.lo[pb][dy], sh[pb]);
+            const uint32_t m = m7[pb];
+            const uint32_t w = (((row[0] & m) | ((row[1] & m) << 3) | ((row[2] & m) << 6)) << lsh[pb]) & vm[pb];
+            const uint32_t addr = lut_base + w * MF_LROW;
+            const u32x4 q0 = *(lds_cu32x4 *)(uintptr_t)addr;
+            const u32x2 q1 = *(lds_cu32x2 *)(uintptr_t)(addr + 16);
+            B[pb] = (v8i){(int)q0.x, (int)q0.y, (int)q0.z, (int)q0.w, (int)q1.x, (int)q1.y, 0, 0};
+        }
+    };
+    auto make_A = [&](const uint32_t (&s)[CB], v8i (&A)[CB]) {
+#pragma unroll
+        for (int cb = 0; cb < CB; ++cb)
+            A[cb] = (v8i){(int)__builtin_amdgcn_perm(0u, 0x00002002u, s[cb]), (int)__builtin_amdgcn_perm(0u, 0x20020000u, s[cb]),
+                          (int)__builtin_amdgcn_perm(0x00002002u, 0u, s[cb]), (int)__builtin_amdgcn_perm(0x20020000u, 0u, s[cb]),
+                          0, 0, 0, 0};
+    };
+
+    v16f acc[CB][PB];
+#pragma unroll
+    for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+        for (int pb = 0; pb < PB; ++pb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[cb][pb][r] = 0.0f;
+
+    // this wave's steps
+    const int c_begin = min(split * p.pairs_per_split, p.npairs);
+    const int c_end = active ? min(c_begin + p.pairs_per_split, p.npairs) : c_begin;
+    const int last = p.npairs - 1;
+
+    // pipeline: memory loads two steps ahead, operands one step ahead
+    Raw raw0, raw1;
+    uint32_t s0[CB], s1[CB];
+    v8i A0[CB], A1[CB], B0[PB], B1[PB];
+    load_raw(min(c_begin, last), raw0);
+    load_sel(min(c_begin, last), s0);
+    __builtin_amdgcn_sched_barrier(0);
+    load_raw(min(c_begin + 1, last), raw1);
+    load_sel(min(c_begin + 1, last), s1);
+    __builtin_amdgcn_sched_barrier(0);
+    // the lookup table image was built once by the preparation kernel; copy it into LDS
+    for (int i = tid; i < 512 * MF_LROW / 16; i += MF_WAVES * 64) ((uint4 *)smem)[i] = p.lut[i];
+    MF_TRACE(1);
+    __syncthreads();                               // table visible
+    MF_TRACE(2);
+
+    if (c_begin < c_end) {
+        make_B(raw0, B0);
+        make_A(s0, A0);
+        __builtin_amdgcn_sched_barrier(0);
+        // One step: the matrix instructions of step c, and between them (the matrix pipe takes ~50
+        // cycles per instruction, during which the wave can issue other work) the loads of step
+        // c + 2 and the operand preparation of step c + 1.  The scheduling groups spell out that
+        // interleaving; left alone, the compiler keeps the matrix instructions back to back and
+        // moves the loads next to their uses.
+        auto step = [&](int c, Raw &rcur, uint32_t (&scur)[CB], Raw &rnext, uint32_t (&snext)[CB], v8i (&Acur)[CB],
+                        v8i (&Bcur)[PB], v8i (&Anext)[CB], v8i (&Bnext)[PB]) {
+            // rcur / scur held step c (now in Acur / Bcur) and are reloaded; rnext / snext hold step c + 1
+#ifdef SNN_MF_DBG
+            if (!(p.dbg & 1))
+#endif
+            {
+                load_raw(min(c + 2, last), rcur);
+                load_sel(min(c + 2, last), scur);
+            }
+#ifdef SNN_MF_DBG
+            if (!(p.dbg & 4))
+#endif
+            make_B(rnext, Bnext);
+            make_A(snext, Anext);
+#ifdef SNN_MF_DBG
+            if (!(p.dbg & 2))
+#endif
+#pragma unroll
+            for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+                for (int pb = 0; pb < PB; ++pb)
+                    acc[cb][pb] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(Acur[cb], Bcur[pb], acc[cb][pb], 4 /* A: FP4 */,
+                                                                                  2 /* B: FP6 e2m3 */, 0, 127, 0, 127);
+            constexpr int NMF = CB * PB;
+            constexpr int NVM = PB * (WM == 1 ? 1 : WM == 2 ? 2 : 3) + 1;   // loads of a step
+            constexpr int NVA = PB * 11 + CB * 4 + 4;                       // vector ALU instructions of a step (estimate)
+            constexpr int VM_PER = (NVM + NMF - 1) / NMF, VA_PER = (NVA + NMF - 1) / NMF;
+#pragma unroll
+            for (int m = 0; m < NMF; ++m) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);          // one matrix instruction
+                __builtin_amdgcn_sched_group_barrier(0x020, VM_PER, 0);     // loads first: they have the longest way to go
+                __builtin_amdgcn_sched_group_barrier(0x002, VA_PER, 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);          // table rows as soon as their windows exist
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        };
+        int c = c_begin;
+        for (; c + 1 < c_end; c += 2) {
+            step(c, raw0, s0, raw1, s1, A0, B0, A1, B1);
+            step(c + 1, raw1, s1, raw0, s0, A1, B1, A0, B0);
+        }
+        if (c < c_end) step(c, raw0, s0, raw1, s1, A0, B0, A1, B1);
+    }
+
+    MF_TRACE(3);
+    // ---- partial sums of the KS waves of a tile ---------------------------------------------------------
+    // Block q of the tile is finished by the wave with split == q % KS; the other waves pass their
+    // partial sums for it through LDS.
+    if (KS > 1) {
+        constexpr int NPASS = NBLK > 4 ? 2 : 1;    // blocks are reduced NBLK / NPASS at a time to bound the LDS
+        constexpr int BPP = NBLK / NPASS;
+        // slot of 4 KB: [tile in workgroup][block in pass][writer rank 0 .. KS-2][4 pieces][64 lanes x 16 bytes]
+        const uint32_t red_lane = (uint32_t)(uintptr_t)smem + (uint32_t)lane * 16u;
+#pragma unroll
+        for (int pass = 0; pass < NPASS; ++pass) {
+            __syncthreads();                       // table (or the previous pass) no longer read
+#pragma unroll
+            for (int ql = 0; ql < BPP; ++ql) {
+                const int q = pass * BPP + ql, cb = q / PB, pb = q % PB;
+                const int owner = q & (KS - 1);
+                if (owner != split) {
+                    const int rank = ((split - owner) & (KS - 1)) - 1;
+                    const uint32_t a = red_lane + (uint32_t)((((tile_in_wg * BPP + ql) * (KS - 1)) + rank) * 4096);
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        u32x4 t;
+                        t.x = __float_as_uint(acc[cb][pb][4 * v]);
+                        t.y = __float_as_uint(acc[cb][pb][4 * v + 1]);
+                        t.z = __float_as_uint(acc[cb][pb][4 * v + 2]);
+                        t.w = __float_as_uint(acc[cb][pb][4 * v + 3]);
+                        *(lds_u32x4 *)(uintptr_t)(a + v * 1024) = t;
+                    }
+                }
+            }
+            __syncthreads();
+#pragma unroll
+            for (int ql = 0; ql < BPP; ++ql) {
+                const int q = pass * BPP + ql, cb = q / PB, pb = q % PB;
+                if ((q & (KS - 1)) == split) {
+                    for (int rank = 0; rank < KS - 1; ++rank) {
+                        const uint32_t a = red_lane + (uint32_t)((((tile_in_wg * BPP + ql) * (KS - 1)) + rank) * 4096);
+#pragma unroll
+                        for (int v = 0; v < 4; ++v) {
+                            const u32x4 t = *(lds_cu32x4 *)(uintptr_t)(a + v * 1024);
+                            acc[cb][pb][4 * v] += __uint_as_float(t.x);
+                            acc[cb][pb][4 * v + 1] += __uint_as_float(t.y);
+                            acc[cb][pb][4 * v + 2] += __uint_as_float(t.z);
+                            acc[cb][pb][4 * v + 3] += __uint_as_float(t.w);
+                        }
+                    }
+                }
+            }
+        }
+    }
+    MF_TRACE(4);
+    // ---- epilogue: S = 2 M' - fin.x, y = float(S) * alpha ---------------------------------------------
+    // The {correction, alpha} pairs of the wave's output channels go through LDS (one 8-byte read
+    // per output); stores use a scalar channel offset.  Register r of a block: output channel
+    // 8 * (r / 4) + 4 * h + r % 4, pixel n_l.
+    __syncthreads();                               // table / partial sums no longer read
+    MF_TRACE(5);
+    constexpr int FIN_BYTES = 32 * CB * 16 * 8;
+    const uint32_t fin_wave = (uint32_t)(uintptr_t)smem + (uint32_t)wave * FIN_BYTES;
+    {
+        const uint4 *src = (const uint4 *)(p.fin + (size_t)co0 * 16);
+#pragma unroll
+        for (int i = 0; i < FIN_BYTES / 1024; ++i) {
+            const uint4 v = src[i * 64 + lane];
+            u32x4 t;
+            t.x = v.x; t.y = v.y; t.z = v.z; t.w = v.w;
+            *(lds_u32x4 *)(uintptr_t)(fin_wave + (uint32_t)(i * 64 + lane) * 16u) = t;
+        }
+    }
+    if (!active) return;
+    MF_TRACE(6);
+    const __amdgpu_buffer_rsrc_t yres = make_rsrc(p.y, (uint32_t)((size_t)g.N * g.C_out * g.HoWo * 4u));
+    const uint32_t chan_bytes = (uint32_t)g.HoWo * 4u;
+#pragma unroll
+    for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+        for (int pb = 0; pb < PB; ++pb) {
+            const int q = cb * PB + pb;
+            if (KS > 1 && (q & (KS - 1)) != split) continue;
+            const uint32_t fin_lane = fin_wave + (uint32_t)(((cb * 32 + 4 * h) * 16 + ptype[pb]) * 8);
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int cs = co0 + cb * 32 + 8 * (r / 4) + (r % 4);          // wave-uniform part of the channel
+                const u32x2 f = *(lds_cu32x2 *)(uintptr_t)(fin_lane + (uint32_t)((8 * (r / 4) + (r % 4)) * 128));
+                const float v = (float)(2 * (int)acc[cb][pb][r] - (int)f.x) * __uint_as_float(f.y);
+                if (cs + 4 * h < g.C_out) buf_store(yres, v, yoff[pb], (uint32_t)cs * chan_bytes);
+            }
+        }
+    MF_TRACE(7);
+}
+
+// ---- host side -------------------------------------------------------------------------------------
+
+struct MfCfg {
+    int PB, CB;
+};
+
+struct MfPlan {
+    MfCfg cfg;
+    int KS, COP, n_cotiles, npairs;
+    long long n_pxtiles, n_tiles, n_wgs;
+    size_t lds;
+    size_t off_sel, off_fin, off_lut, bytes;
+};
+
+int env_int(const char *name, int dflt)
+{
+    const char *e = getenv(name);
+    return e ? atoi(e) : dflt;
+}
+
+MfPlan mf_plan(const Geom &g)
+{
+    MfPlan pl;
+    // tile of a wave: 128 accumulator registers (PB x CB = 8); few channels -> more pixels per wave
+    if (g.C_out <= 64) pl.cfg = {4, 2};
+    else pl.cfg = {2, 4};
+    // tuning override "PB,CB"
+    if (const char *e = getenv("SNN_MFMA_TILE")) {
+        int a = 0, b = 0;
+        if (sscanf(e, "%d,%d", &a, &b) == 2 && ((a == 4 && b == 2) || (a == 2 && b == 4) || (a == 2 && b == 2) || (a == 1 && b == 4) || (a == 1 && b == 2)))
+            pl.cfg = {a, b};
+    }
+    const int cow = 32 * pl.cfg.CB, pxw = 32 * pl.cfg.PB;
+    pl.COP = (g.C_out + cow - 1) / cow * cow;
+    pl.n_cotiles = pl.COP / cow;
+    pl.n_pxtiles = (g.P + pxw - 1) / pxw;
+    pl.n_tiles = pl.n_pxtiles * pl.n_cotiles;
+    pl.npairs = (g.C_in + 1) / 2;
+    // split the channel pairs over waves while the tiles alone leave SIMDs idle (1024 SIMDs, two waves each)
+    int KS = 1;
+    while (KS < 4 && pl.n_tiles * KS < 1536 && pl.npairs / (2 * KS) >= 8) KS *= 2;
+    const int ks_env = env_int("SNN_MFMA_KS", 0);
+    if (ks_env == 1 || ks_env == 2 || ks_env == 4) KS = ks_env;
+    pl.KS = KS;
+    pl.n_wgs = (pl.n_tiles * KS + MF_WAVES - 1) / MF_WAVES;
+    const size_t lut_bytes = (size_t)512 * MF_LROW;
+    const int nblk = pl.cfg.PB * pl.cfg.CB;
+    const size_t red_bytes = KS > 1 ? (size_t)(MF_WAVES / KS) * (nblk > 4 ? nblk / 2 : nblk) * (KS - 1) * 4096 : 0;
+    const size_t fin_bytes = (size_t)MF_WAVES * 32 * pl.cfg.CB * 16 * 8;
+    pl.lds = lut_bytes > red_bytes ? lut_bytes : red_bytes;
+    if (fin_bytes > pl.lds) pl.lds = fin_bytes;
+    size_t o = 0;
+#ifdef SNN_MF_DBG
+    o += 4096;                // clock samples
+#endif
+    pl.off_sel = o;
+    o += align_up((size_t)pl.npairs * 2 * pl.COP * sizeof(uint32_t), 256);
+    pl.off_fin = o;
+    o += align_up((size_t)pl.COP * 16 * sizeof(uint2), 256);
+    pl.off_lut = o;
+    o += align_up(lut_bytes, 256);
+    pl.bytes = o;
+    return pl;
+}
+
+template <int PB, int CB, int WM>
+int launch_mf_one(const MfPlan &pl, const MfParams &prm, hipStream_t s)
+{
+    auto kern = subbit_mfma_kernel<PB, CB, WM>;
+    if (pl.lds > 64 * 1024 &&
+        hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)pl.lds) != hipSuccess)
+        return SNN_ERR_LAUNCH;
+    hipLaunchKernelGGL(kern, dim3((unsigned)pl.n_wgs), dim3(MF_WAVES * 64), pl.lds, s, prm);
+    return check_launch();
+}
+
+template <int PB, int CB>
+int launch_mf(const MfPlan &pl, const MfParams &prm, hipStream_t s)
+{
+    if (prm.g.WW == 1) return launch_mf_one<PB, CB, 1>(pl, prm, s);
+    if (prm.g.WW == 2) return launch_mf_one<PB, CB, 2>(pl, prm, s);
+    return launch_mf_one<PB, CB, 0>(pl, prm, s);
+}
+
+}  // namespace
+
+bool subbit_mfma_supported(const Geom &g)
+{
+    // one FP6 table row of 32 subset members and two input channels per matrix instruction;
+    // 32-bit byte offsets into the packed input, the selector table and the output
+    const int64_t x_words = (int64_t)g.N * g.C_in * g.H * g.WW;
+    const int64_t sel_words = (int64_t)(g.C_in + 1) * (g.C_out + 127);
+    const int64_t y_words = (int64_t)g.P * g.C_out;
+    return g.K <= 32 && g.C_in >= 2 && x_words < ((int64_t)1 << 30) && sel_words < ((int64_t)1 << 30) &&
+           y_words < ((int64_t)1 << 30) && g.P < ((int64_t)1 << 31) - 4096;
+}
+
+size_t subbit_mfma_workspace_bytes(const Geom &g) { return mf_plan(g).bytes; }
+
+int launch_subbit_mfma(const Geom &g, const void *x, const uint16_t *codebook, const uint16_t *idx,
+                       const float *alpha, float *y, void *ws, hipStream_t s)
+{
+    const MfPlan pl = mf_plan(g);
+    if (pl.n_wgs > 0x7fffffffLL || pl.lds > 160 * 1024) return SNN_ERR_UNSUPPORTED;
+
+    MfParams prm;
+    prm.x = (const uint32_t *)x;
+    prm.sel = (const uint32_t *)((char *)ws + pl.off_sel);
+    prm.fin = (const uint2 *)((char *)ws + pl.off_fin);
+    prm.lut = (const uint4 *)((char *)ws + pl.off_lut);
+    prm.y = y;
+    prm.g = g;
+    prm.COP = pl.COP;
+    prm.KS = pl.KS;
+    prm.npairs = pl.npairs;
+    prm.pairs_per_split = (pl.npairs + pl.KS - 1) / pl.KS;
+    prm.n_cotiles = pl.n_cotiles;
+    prm.n_tiles = pl.n_tiles;
+#ifdef SNN_MF_DBG
+    prm.dbg = env_int("SNN_MF_DBG", 0);
+    prm.trace = (unsigned long long *)ws;
+#endif
+
+    const int sel_blocks = (pl.COP / 32) * ((g.C_in + 31) / 32);
+    const int corr_blocks = (pl.COP + 3) / 4;
+    const int lut_blocks = (512 * (MF_LROW / 4) + 255) / 256;
+    hipLaunchKernelGGL(subbit_mfma_prep_kernel, dim3((unsigned)(sel_blocks + corr_blocks + lut_blocks)), dim3(256), 0, s,
+                       codebook, idx, g.C_in, g.C_out, pl.COP, pl.cfg.CB, g.K, sel_blocks, lut_blocks, alpha,
+                       (uint32_t *)prm.sel, (uint2 *)prm.fin, (uint32_t *)prm.lut);
+
+    const MfCfg &c = pl.cfg;
+    if (c.PB == 4 && c.CB == 2) return launch_mf<4, 2>(pl, prm, s);
+    if (c.PB == 2 && c.CB == 4) return launch_mf<2, 4>(pl, prm, s);
+    if (c.PB == 2 && c.CB == 2) return launch_mf<2, 2>(pl, prm, s);
+    if (c.PB == 1 && c.CB == 4) return launch_mf<1, 4>(pl, prm, s);
+    if (c.PB == 1 && c.CB == 2) return launch_mf<1, 2>(pl, prm, s);
+    return SNN_ERR_UNSUPPORTED;
+}
+
+}  // namespace snn

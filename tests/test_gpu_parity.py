@@ -132,12 +132,32 @@ def test_subbit_bin(oracle, case):
     assert (y == Y).all(), np.argwhere(y != Y)[:5]
 
 
+@pytest.mark.parametrize("tile", ["4,2", "2,4", "2,2", "1,4", "1,2"])
+@pytest.mark.parametrize("split", [1, 2, 4])
+def test_subbit_bin_matrix_core_kernel_every_tile_and_split(oracle, tile, split, monkeypatch):
+    """Every instantiated wave tile of the matrix-core kernel (K <= 32) and every split of the
+    input channels over waves, forced on layers with ragged edges: odd and even C_in, C_out not
+    a multiple of 32, rows of one, two and three packed words, both strides, a pixel tail."""
+    monkeypatch.setenv("SNN_MFMA_TILE", tile)
+    monkeypatch.setenv("SNN_MFMA_KS", str(split))
+    for seed, (N, C_in, C_out, H, W, stride, K) in enumerate([(3, 45, 150, 13, 11, 1, 32), (2, 20, 70, 16, 12, 2, 32),
+                                                             (2, 34, 40, 9, 40, 1, 20), (1, 8, 33, 5, 70, 1, 32),
+                                                             (2, 130, 96, 8, 8, 2, 7), (1, 2, 3, 1, 1, 1, 2)]):
+        _say("subbit_bin matrix-core", tile, split, (N, C_in, C_out, H, W, stride, K))
+        x, cb, idx, alpha = _inputs(900 + seed, N, C_in, C_out, H, W, K)
+        _, Y = oracle.conv_bin(oracle.sign(x), oracle.expand(cb, idx), alpha, stride)
+        y = G.subbit_bin(x, cb, idx, alpha, stride)
+        assert (y == Y).all(), np.argwhere(y != Y)[:5]
+
+
 @pytest.mark.parametrize("variant", ["wave", "workgroup"])
 @pytest.mark.parametrize("case", [c for c in SUBBIT_CASES if c[6] <= 64])
 def test_subbit_bin_both_kernel_variants(oracle, case, variant, monkeypatch):
-    """The library picks between a wave-private and a workgroup-tile kernel by layer size; force
-    each of them on every case (the tuning override is read at every call)."""
+    """With the matrix-core kernel switched off the library picks between a wave-private and a
+    workgroup-tile LDS-gather kernel by layer size; force each of them on every case (the tuning
+    overrides are read at every call)."""
     _say("subbit_bin", variant, case)
+    monkeypatch.setenv("SNN_SUBBIT_MFMA", "0")
     monkeypatch.setenv("SNN_SUBBIT_WAVE", "1" if variant == "wave" else "0")
     N, C_in, C_out, H, W, stride, K, dist = case
     x, cb, idx, alpha = _inputs(sum(case[:7]), N, C_in, C_out, H, W, K, dist)
@@ -148,7 +168,8 @@ def test_subbit_bin_both_kernel_variants(oracle, case, variant, monkeypatch):
 
 @pytest.mark.parametrize("tile", ["4,1,8", "4,2,8", "2,1,8", "2,2,8", "1,1,4", "1,1,8", "4,1,1", "1,1,1"])
 def test_subbit_bin_every_tile_shape(oracle, tile, monkeypatch):
-    """Every instantiated tile of the workgroup kernel, forced on a layer with ragged edges."""
+    """Every instantiated tile of the workgroup LDS-gather kernel, forced on a layer with ragged edges."""
+    monkeypatch.setenv("SNN_SUBBIT_MFMA", "0")
     monkeypatch.setenv("SNN_SUBBIT_WAVE", "0")
     monkeypatch.setenv("SNN_SUBBIT_TILE", tile)
     x, cb, idx, alpha = _inputs(123, 3, 45, 150, 13, 11, 32)
