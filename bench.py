@@ -31,6 +31,8 @@ VALU_PEAK_LANE_OPS = 256 * 4 * 16 * 2.4e9
 # LDS: 128 bytes per clock per CU.
 LDS_PEAK_BYTES = 256 * 128 * 2.4e9
 HBM_PEAK_BYTES = 8.0e12
+# Dense matrix-core peak for FP6 / FP4 operands (the sub-bit kernel's v_mfma_scale_f32_32x32x64_f8f6f4).
+MFMA_FP6_FP4_PEAK_FLOPS = 10.1e15
 
 
 def parse():
@@ -166,6 +168,10 @@ def main():
     def conv_bnn(s):
         B.snn_bnn_conv2d(s["d_bnn"], s["xc"], s["w9"], s["alpha"], y=s["yb"], workspace=s["ws_bnn"])
 
+    # One step = every layer's project + pack + conv, back to back on one stream.  (Putting the
+    # small project / pack kernels on side streams, eagerly or as a captured HIP graph, was
+    # measured and is slower here: the eager form is bound by the host's launch rate, the graph
+    # replay runs the kernels no closer together than the single stream does.)
     def step():
         for s in st:
             project(s)
@@ -243,28 +249,47 @@ def main():
     in_bytes = sum(L.N * L.C_in * L.H * ((L.W + 31) // 32) * 4 for L in layers)
     idx_bytes = sum(L.C_in * L.C_out * 2 for L in layers)
 
-    # Algorithmic work of the sub-bit kernel: stage 2 is one add per (pixel,
-    # c_out, c_in) with four pixels per 32-bit lane operation; stage 1 one response per (pixel,
-    # c_in, k), four per lane operation.  Every gathered response is one byte read from LDS.
-    alg_lane_ops = (gather_adds + responses) / 4.0
-    alg_lds_bytes = float(gather_adds)
     alg_hbm_bytes = float(out_bytes + in_bytes + idx_bytes)
     sub_s = sum(t_sub) * 1e-3
-    roofline = {
-        "kernel": "subbit_bin_kernel (all %d launches of a step; duration is the snn_subbit_conv2d call, "
-                  "which includes its small index-preparation kernel)" % len(layers),
-        "bound": "alu",
-        "achieved": alg_lane_ops / sub_s / 1e12,
-        "peak": VALU_PEAK_LANE_OPS / 1e12,
-        "unit": "T lane-op/s",
-        "frac": alg_lane_ops / sub_s / VALU_PEAK_LANE_OPS,
-        "traffic": _measured_traffic(args),
-        "lds": {"achieved": alg_lds_bytes / sub_s / 1e12, "peak": LDS_PEAK_BYTES / 1e12, "unit": "TB/s",
-                "frac": alg_lds_bytes / sub_s / LDS_PEAK_BYTES},
-        "hbm": {"achieved": alg_hbm_bytes / sub_s / 1e9, "peak": HBM_PEAK_BYTES / 1e9, "unit": "GB/s",
-                "frac": alg_hbm_bytes / sub_s / HBM_PEAK_BYTES},
-        "avg_launch_ms": sum(t_sub) / len(t_sub),
-    }
+    hbm = {"achieved": alg_hbm_bytes / sub_s / 1e9, "peak": HBM_PEAK_BYTES / 1e9, "unit": "GB/s",
+           "frac": alg_hbm_bytes / sub_s / HBM_PEAK_BYTES}
+    if all(L.K <= 32 and L.C_in >= 2 for L in layers):
+        # Matrix-core kernel: stage 2 is a product with a one-hot matrix whose contraction runs over
+        # (c_in, 32 subset slots), i.e. 2 * 32 flop per (pixel, c_out, c_in); stage 1 is the B operand
+        # itself (a table row), so these are all the flops of the method in this formulation.
+        alg_flops = 2.0 * 32.0 * gather_adds
+        roofline = {
+            "kernel": "subbit_mfma_kernel (all %d launches of a step; duration is the snn_subbit_conv2d call, "
+                      "which includes its small preparation kernel)" % len(layers),
+            "bound": "mfma",
+            "achieved": alg_flops / sub_s / 1e12,
+            "peak": MFMA_FP6_FP4_PEAK_FLOPS / 1e12,
+            "unit": "TFLOP/s",
+            "frac": alg_flops / sub_s / MFMA_FP6_FP4_PEAK_FLOPS,
+            "traffic": _measured_traffic(args),
+            "hbm": hbm,
+            "avg_launch_ms": sum(t_sub) / len(t_sub),
+        }
+    else:
+        # LDS-gather kernels (K > 32): stage 2 is one add per (pixel, c_out, c_in) with four pixels per
+        # 32-bit lane operation; stage 1 one response per (pixel, c_in, k), four per lane operation.
+        # Every gathered response is one byte read from LDS.
+        alg_lane_ops = (gather_adds + responses) / 4.0
+        alg_lds_bytes = float(gather_adds)
+        roofline = {
+            "kernel": "subbit_lut_kernel / subbit_wave_kernel (all %d launches of a step; duration is the "
+                      "snn_subbit_conv2d call, which includes its small index-preparation kernel)" % len(layers),
+            "bound": "alu",
+            "achieved": alg_lane_ops / sub_s / 1e12,
+            "peak": VALU_PEAK_LANE_OPS / 1e12,
+            "unit": "T lane-op/s",
+            "frac": alg_lane_ops / sub_s / VALU_PEAK_LANE_OPS,
+            "traffic": _measured_traffic(args),
+            "lds": {"achieved": alg_lds_bytes / sub_s / 1e12, "peak": LDS_PEAK_BYTES / 1e12, "unit": "TB/s",
+                    "frac": alg_lds_bytes / sub_s / LDS_PEAK_BYTES},
+            "hbm": hbm,
+            "avg_launch_ms": sum(t_sub) / len(t_sub),
+        }
 
     print("%-18s %9s %6s %5s | %9s %9s %7s | %8s %8s %8s" % ("layer", "pixels", "C", "K", "subbit us", "bnn us", "speedup",
                                                              "proj us", "packR us", "packC us"), file=sys.stderr)
@@ -280,7 +305,7 @@ def main():
     if not args.no_cpu:
         import oracle
         oracle.build()
-        n_img = 2 if args.workload == "resnet18" else 4
+        n_img = 32 if args.workload == "resnet18" else 16
         t_cpu = 0.0
         ops_cpu = 0
         for s in st:
@@ -294,11 +319,11 @@ def main():
             xs = oracle.sign(x)
             _, Y = oracle.conv_bin(xs, oracle.expand(cb, idx.reshape(L.C_out, L.C_in)), alpha, L.stride)
             t_cpu += time.perf_counter() - c0
-            ops_cpu += L.dense_ops // L.N * n_img
+            ops_cpu += L.dense_ops // L.N * x.shape[0]
             assert (s["y"][:n_img].cpu().numpy() == Y).all(), "GPU result differs from the oracle on " + L.name
         cpu = {"value": ops_cpu / t_cpu / 1e9, "unit": "GOPS-equivalent", "cores": oracle.threads(), "kind": "oracle",
                "sample": "same %d layers, first %d images of the batch (project + sign + direct conv), %.1f s" % (
-                   len(layers), n_img, t_cpu)}
+                   len(layers), min(n_img, layers[0].N), t_cpu)}
 
     result = {
         "metric": "sub-bit 3x3 conv GOPS-equivalent (2*9*C_in*C_out*N*H_out*W_out per layer / step time) and "

@@ -7,16 +7,20 @@ namespace snn {
 namespace {
 
 constexpr int PACK_THREADS = 256;
-constexpr int PACK_CHUNK = 2048;   // elements whose sign bits are staged in LDS per pass (8 loads per thread)
+constexpr int PACK_U = 4;                                  // 16-byte loads in flight per thread
+constexpr int PACK_CHUNK = PACK_THREADS * 4 * PACK_U;      // elements whose sign bits are staged in LDS per pass
 
-// Coalesced loads -> wave ballots -> a flat bit stream in LDS -> one output word per thread,
-// cut out of the stream at the row's bit offset (rows need not be multiples of 32 wide).
+// 16-byte loads -> four sign bits per lane -> eight lanes OR their nibbles into one word of a flat
+// bit stream in LDS -> one output word per thread, cut out of the stream at the row's bit offset
+// (rows need not be multiples of 32 wide).  `vec` says that every block's first element is 16-byte
+// aligned; the last, partial group of four of a segment is read element by element.
 __global__ __launch_bounds__(PACK_THREADS)
 void pack_rows_kernel(const float *__restrict__ x, uint32_t *__restrict__ out, int64_t rows, int W,
-                      int WW, int rows_per_block)
+                      int WW, int rows_per_block, int vec)
 {
     __shared__ uint32_t bits[PACK_CHUNK / 32 + 2];
     const int tid = threadIdx.x;
+    const int lane = tid & 63;
     const int64_t r0 = (int64_t)blockIdx.x * rows_per_block;
     const int nrows = (int)min((int64_t)rows_per_block, rows - r0);
     if (nrows <= 0) return;
@@ -27,24 +31,28 @@ void pack_rows_kernel(const float *__restrict__ x, uint32_t *__restrict__ out, i
     for (int seg = 0; seg < row_len; seg += PACK_CHUNK) {
         const int cnt = min(PACK_CHUNK, row_len - seg);
         const float *src = x + r0 * W + seg;
-        // eight independent loads in flight per thread, then eight ballots
-        constexpr int U = 8;
-        for (int base = 0; base < cnt; base += PACK_THREADS * U) {
-            float v[U];
+        float4 v[PACK_U];
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int i = base + u * PACK_THREADS + tid;
-                v[u] = i < cnt ? src[i] : -1.0f;
+        for (int u = 0; u < PACK_U; ++u) {
+            const int e = (u * PACK_THREADS + tid) * 4;
+            if (vec && e + 3 < cnt) {
+                v[u] = *(const float4 *)(src + e);
+            } else {
+                v[u].x = e < cnt ? src[e] : -1.0f;
+                v[u].y = e + 1 < cnt ? src[e + 1] : -1.0f;
+                v[u].z = e + 2 < cnt ? src[e + 2] : -1.0f;
+                v[u].w = e + 3 < cnt ? src[e + 3] : -1.0f;
             }
+        }
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int i = base + u * PACK_THREADS + tid;
-                const unsigned long long m = __ballot(v[u] >= 0.0f);
-                if ((tid & 63) == 0 && (i & ~63) < cnt) {
-                    bits[(i >> 6) * 2] = (uint32_t)m;
-                    bits[(i >> 6) * 2 + 1] = (uint32_t)(m >> 32);
-                }
-            }
+        for (int u = 0; u < PACK_U; ++u) {
+            const uint32_t nib = (v[u].x >= 0.0f ? 1u : 0u) | (v[u].y >= 0.0f ? 2u : 0u) | (v[u].z >= 0.0f ? 4u : 0u) |
+                                 (v[u].w >= 0.0f ? 8u : 0u);
+            uint32_t w = nib << (4 * (lane & 7));
+            w |= __shfl_xor(w, 1);
+            w |= __shfl_xor(w, 2);
+            w |= __shfl_xor(w, 4);
+            if ((lane & 7) == 0) bits[(u * PACK_THREADS + tid) >> 3] = w;
         }
         __syncthreads();
         if (W <= PACK_CHUNK) {
@@ -54,18 +62,18 @@ void pack_rows_kernel(const float *__restrict__ x, uint32_t *__restrict__ out, i
                 const int o = rl * W + 32 * j;
                 const int nb = min(32, W - 32 * j);
                 const int sh = o & 31;
-                uint32_t v = bits[o >> 5] >> sh;
-                if (sh + nb > 32) v |= bits[(o >> 5) + 1] << (32 - sh);
-                if (nb < 32) v &= (1u << nb) - 1u;
-                out[r0 * WW + q] = v;
+                uint32_t wv = bits[o >> 5] >> sh;
+                if (sh + nb > 32) wv |= bits[(o >> 5) + 1] << (32 - sh);
+                if (nb < 32) wv &= (1u << nb) - 1u;
+                out[r0 * WW + q] = wv;
             }
         } else {
             const int nwords = (cnt + 31) >> 5;
             for (int q = tid; q < nwords; q += PACK_THREADS) {
                 const int nb = min(32, cnt - 32 * q);
-                uint32_t v = bits[q];
-                if (nb < 32) v &= (1u << nb) - 1u;
-                out[r0 * WW + (seg >> 5) + q] = v;
+                uint32_t wv = bits[q];
+                if (nb < 32) wv &= (1u << nb) - 1u;
+                out[r0 * WW + (seg >> 5) + q] = wv;
             }
         }
         __syncthreads();
@@ -98,11 +106,18 @@ void pack_channels_kernel(const float *__restrict__ x, uint32_t *__restrict__ ou
 int launch_pack_rows(const float *x, uint32_t *out, int64_t rows, int W, hipStream_t s)
 {
     const int WW = (W + 31) / 32;
-    const int rows_per_block = (W <= PACK_CHUNK) ? PACK_CHUNK / W : 1;
+    // whole rows per block, a multiple of four of them so that every block starts 16-byte aligned
+    int rows_per_block = 1;
+    if (W <= PACK_CHUNK) {
+        rows_per_block = PACK_CHUNK / W;
+        if (rows_per_block >= 4) rows_per_block &= ~3;
+    }
+    const bool aligned_rows = ((int64_t)rows_per_block * W) % 4 == 0 && (W <= PACK_CHUNK || W % 4 == 0);
+    const int vec = (((uintptr_t)x & 15) == 0 && aligned_rows) ? 1 : 0;
     const int64_t blocks = (rows + rows_per_block - 1) / rows_per_block;
     if (blocks > 0x7fffffffLL) return SNN_ERR_INVALID_ARG;
     hipLaunchKernelGGL(pack_rows_kernel, dim3((unsigned)blocks), dim3(PACK_THREADS), 0, s, x, out, rows, W,
-                       WW, rows_per_block);
+                       WW, rows_per_block, vec);
     return check_launch();
 }
 

@@ -22,6 +22,8 @@
 // their partial sums through LDS.
 #include "snn_internal.h"
 
+#include <type_traits>
+
 namespace snn {
 
 namespace {
@@ -356,16 +358,21 @@ void subbit_mfma_kernel(const MfParams p)
     const int c_end = active ? min(c_begin + p.pairs_per_split, p.npairs) : c_begin;
     const int last = p.npairs - 1;
 
-    // pipeline: memory loads two steps ahead, operands one step ahead
-    Raw raw0, raw1;
-    uint32_t s0[CB], s1[CB];
-    v8i A0[CB], A1[CB], B0[PB], B1[PB];
-    load_raw(min(c_begin, last), raw0);
-    load_sel(min(c_begin, last), s0);
-    __builtin_amdgcn_sched_barrier(0);
-    load_raw(min(c_begin + 1, last), raw1);
-    load_sel(min(c_begin + 1, last), s1);
-    __builtin_amdgcn_sched_barrier(0);
+    // pipeline: memory loads RING steps ahead (a ring of RING register sets: the set of step c is
+    // free once its operands exist, which is during step c - 1), operands one step ahead (two
+    // sets).  Deeper rings where a step's loads are few registers.
+    constexpr int RAW_REGS = PB * (WM == 1 ? 3 : 6) + CB;
+    constexpr int RING = RAW_REGS <= 16 ? 3 : 2;
+    constexpr int UNROLL = RING % 2 == 0 ? RING : 2 * RING;
+    Raw raw[RING];
+    uint32_t sel[RING][CB];
+    v8i A[2][CB], B[2][PB];
+#pragma unroll
+    for (int u = 0; u < RING; ++u) {
+        load_raw(min(c_begin + u, last), raw[u]);
+        load_sel(min(c_begin + u, last), sel[u]);
+        __builtin_amdgcn_sched_barrier(0);
+    }
     // the lookup table image was built once by the preparation kernel; copy it into LDS
     for (int i = tid; i < 512 * MF_LROW / 16; i += MF_WAVES * 64) ((uint4 *)smem)[i] = p.lut[i];
     MF_TRACE(1);
@@ -373,29 +380,30 @@ void subbit_mfma_kernel(const MfParams p)
     MF_TRACE(2);
 
     if (c_begin < c_end) {
-        make_B(raw0, B0);
-        make_A(s0, A0);
+        make_B(raw[0], B[0]);
+        make_A(sel[0], A[0]);
         __builtin_amdgcn_sched_barrier(0);
         // One step: the matrix instructions of step c, and between them (the matrix pipe takes ~50
         // cycles per instruction, during which the wave can issue other work) the loads of step
-        // c + 2 and the operand preparation of step c + 1.  The scheduling groups spell out that
-        // interleaving; left alone, the compiler keeps the matrix instructions back to back and
-        // moves the loads next to their uses.
-        auto step = [&](int c, Raw &rcur, uint32_t (&scur)[CB], Raw &rnext, uint32_t (&snext)[CB], v8i (&Acur)[CB],
-                        v8i (&Bcur)[PB], v8i (&Anext)[CB], v8i (&Bnext)[PB]) {
-            // rcur / scur held step c (now in Acur / Bcur) and are reloaded; rnext / snext hold step c + 1
+        // c + RING and the operand preparation of step c + 1.  The scheduling groups spell out
+        // that interleaving; left alone, the compiler keeps the matrix instructions back to back and
+        // moves the loads next to their uses.  u = (c - c_begin) % UNROLL selects the register sets.
+        auto step = [&](int c, auto uc) {
+            constexpr int u = decltype(uc)::value;
+            constexpr int cur = u % 2, nxt = (u + 1) % 2;
+            constexpr int slot_next = (u + 1) % RING, slot_load = u % RING;
 #ifdef SNN_MF_DBG
             if (!(p.dbg & 1))
 #endif
             {
-                load_raw(min(c + 2, last), rcur);
-                load_sel(min(c + 2, last), scur);
+                load_raw(min(c + RING, last), raw[slot_load]);
+                load_sel(min(c + RING, last), sel[slot_load]);
             }
 #ifdef SNN_MF_DBG
             if (!(p.dbg & 4))
 #endif
-            make_B(rnext, Bnext);
-            make_A(snext, Anext);
+            make_B(raw[slot_next], B[nxt]);
+            make_A(sel[slot_next], A[nxt]);
 #ifdef SNN_MF_DBG
             if (!(p.dbg & 2))
 #endif
@@ -403,7 +411,7 @@ void subbit_mfma_kernel(const MfParams p)
             for (int cb = 0; cb < CB; ++cb)
 #pragma unroll
                 for (int pb = 0; pb < PB; ++pb)
-                    acc[cb][pb] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(Acur[cb], Bcur[pb], acc[cb][pb], 4 /* A: FP4 */,
+                    acc[cb][pb] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(A[cur][cb], B[cur][pb], acc[cb][pb], 4 /* A: FP4 */,
                                                                                   2 /* B: FP6 e2m3 */, 0, 127, 0, 127);
             constexpr int NMF = CB * PB;
             constexpr int NVM = PB * (WM == 1 ? 1 : WM == 2 ? 2 : 3) + 1;   // loads of a step
@@ -418,12 +426,26 @@ void subbit_mfma_kernel(const MfParams p)
             }
             __builtin_amdgcn_sched_barrier(0);
         };
+        auto group = [&](int c, auto guarded) {
+            // UNROLL consecutive steps; the guarded form (the tail) stops at c_end
+            auto run = [&](auto uc) {
+                constexpr int u = decltype(uc)::value;
+                if (!decltype(guarded)::value || c + u < c_end) step(c + u, uc);
+            };
+            run(std::integral_constant<int, 0>{});
+            run(std::integral_constant<int, 1>{});
+            if constexpr (UNROLL > 2) {
+                run(std::integral_constant<int, 2>{});
+                run(std::integral_constant<int, 3>{});
+            }
+            if constexpr (UNROLL > 4) {
+                run(std::integral_constant<int, 4>{});
+                run(std::integral_constant<int, 5>{});
+            }
+        };
         int c = c_begin;
-        for (; c + 1 < c_end; c += 2) {
-            step(c, raw0, s0, raw1, s1, A0, B0, A1, B1);
-            step(c + 1, raw1, s1, raw0, s0, A1, B1, A0, B0);
-        }
-        if (c < c_end) step(c, raw0, s0, raw1, s1, A0, B0, A1, B1);
+        for (; c + UNROLL <= c_end; c += UNROLL) group(c, std::false_type{});
+        if (c < c_end) group(c, std::true_type{});
     }
 
     MF_TRACE(3);
