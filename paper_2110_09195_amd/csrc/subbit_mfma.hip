@@ -42,7 +42,7 @@ constexpr int MF_LROW = 48;                    // table row stride: 24 bytes use
 
 struct MfParams {
     const uint32_t *x;        // packed rows [N][C_in][H][WW]
-    const uint4 *lut;         // [512][MF_LROW] bytes: row = window, 32 FP6 values m_k - 4 packed little-endian
+    const uint32_t *lut;      // [512][6] words: row = window, 32 FP6 values m_k - 4 packed little-endian
     const uint32_t *sel;      // [pairs][2][COP] selector words for the one-hot operand
     const uint2 *fin;         // [COP][16] per (output channel, border type): {2 corr + C_in (valid_taps - 8), alpha bits}
     float *y;
@@ -53,12 +53,11 @@ struct MfParams {
     int pairs_per_split;
     int n_cotiles;
     long long n_tiles;        // pixel tiles * channel tiles
-#ifdef SNN_MF_DBG
-    int dbg;                  // timing experiments: 1 = no loads in the loop, 2 = no MFMA, 4 = no table reads
-    unsigned long long *trace;
+#ifdef SNN_MF_TRACE
+    unsigned long long *trace;    // tuning builds: wall-clock samples of two workgroups, 16 per wave
 #endif
 };
-#ifdef SNN_MF_DBG
+#ifdef SNN_MF_TRACE
 #define MF_TRACE(slot)                                                                          \
     do {                                                                                        \
         if ((blockIdx.x == 3 || blockIdx.x == gridDim.x / 2) && (threadIdx.x & 63) == 0)        \
@@ -133,39 +132,46 @@ void subbit_mfma_prep_kernel(const uint16_t *__restrict__ codebook, const uint16
         return;
     }
     if (b >= (int)gridDim.x - lut_blocks) {
-        // one thread per 32-bit word of the table; a row is 6 words of 32 FP6 codes and 6 of padding
-        const int wpr = MF_LROW / 4;
+        // one thread per 32-bit word of the table; a row is 6 words of 32 FP6 codes
         const int i = (b - ((int)gridDim.x - lut_blocks)) * 256 + tid;
-        if (i < 512 * wpr) {
-            const int win = i / wpr, w = i - win * wpr;
+        if (i < 512 * 6) {
+            const int win = i / 6, w = i - win * 6;
             uint32_t word = 0;
-            if (w < 6)
-                for (int k = (32 * w) / 6; k <= (32 * w + 31) / 6 && k < K; ++k) {
-                    const int m = 9 - __popc((uint32_t)win ^ code_to_window_order(codebook[k] & 511u));
-                    const int at = 6 * k - 32 * w;                 // position of the code's bit 0 in this word
-                    const uint32_t code = fp6_of_int(m - 4);
-                    word |= at >= 0 ? code << at : code >> -at;
-                }
+            for (int k = (32 * w) / 6; k <= (32 * w + 31) / 6 && k < K; ++k) {
+                const int m = 9 - __popc((uint32_t)win ^ code_to_window_order(codebook[k] & 511u));
+                const int at = 6 * k - 32 * w;                 // position of the code's bit 0 in this word
+                const uint32_t code = fp6_of_int(m - 4);
+                word |= at >= 0 ? code << at : code >> -at;
+            }
             lut[i] = word;
         }
         return;
     }
-    const int co = (b - sel_blocks) * 4 + (tid >> 6);          // one wave per output channel
+    // one wave per output channel; the zero-bit patterns of the K codes go through LDS so that the
+    // loop over the input channels has one memory access per channel, not two dependent ones
+    __shared__ uint32_t zbits[512];
+    for (int k = tid; k < K; k += 256) zbits[k] = ~code_to_window_order(codebook[k] & 511u) & 511u;
+    __syncthreads();
+    const int co = (b - sel_blocks) * 4 + (tid >> 6);
     const int lane = tid & 63;
     if (co >= COP) return;
     int zeros[9];
 #pragma unroll
     for (int t = 0; t < 9; ++t) zeros[t] = 0;
     if (co < C_out)
-        for (int c0 = 0; c0 < C_in; c0 += 64) {
-            const int ci = c0 + lane;
-            uint32_t z = 0;
-            if (ci < C_in) {
-                const int k = min((int)idx[(int64_t)co * C_in + ci], K - 1);
-                z = ~code_to_window_order(codebook[k] & 511u) & 511u;
+        for (int c0 = 0; c0 < C_in; c0 += 256) {
+            int kk[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int ci = c0 + 64 * u + lane;
+                kk[u] = ci < C_in ? min((int)idx[(int64_t)co * C_in + ci], K - 1) : -1;
             }
 #pragma unroll
-            for (int t = 0; t < 9; ++t) zeros[t] += __popcll(__ballot((z >> t) & 1u));
+            for (int u = 0; u < 4; ++u) {
+                const uint32_t z = kk[u] >= 0 ? zbits[kk[u]] : 0u;
+#pragma unroll
+                for (int t = 0; t < 9; ++t) zeros[t] += __popcll(__ballot((z >> t) & 1u));
+            }
         }
     if (lane < 16) {
         const uint32_t inv = border_invalid_window(lane);
@@ -373,8 +379,14 @@ void subbit_mfma_kernel(const MfParams p)
         load_sel(min(c_begin + u, last), sel[u]);
         __builtin_amdgcn_sched_barrier(0);
     }
-    // the lookup table image was built once by the preparation kernel; copy it into LDS
-    for (int i = tid; i < 512 * MF_LROW / 16; i += MF_WAVES * 64) ((uint4 *)smem)[i] = p.lut[i];
+    // the lookup table image was built once by the preparation kernel; copy it into LDS, rows of
+    // 6 words spread to the padded stride
+#pragma unroll
+    for (int i = 0; i < 512 * 6 / (MF_WAVES * 64); ++i) {
+        const int e = i * (MF_WAVES * 64) + tid;
+        const int row = e / 6, col = e - row * 6;
+        ((uint32_t *)smem)[row * (MF_LROW / 4) + col] = p.lut[e];
+    }
     MF_TRACE(1);
     __syncthreads();                               // table visible
     MF_TRACE(2);
@@ -392,21 +404,10 @@ void subbit_mfma_kernel(const MfParams p)
             constexpr int u = decltype(uc)::value;
             constexpr int cur = u % 2, nxt = (u + 1) % 2;
             constexpr int slot_next = (u + 1) % RING, slot_load = u % RING;
-#ifdef SNN_MF_DBG
-            if (!(p.dbg & 1))
-#endif
-            {
-                load_raw(min(c + RING, last), raw[slot_load]);
-                load_sel(min(c + RING, last), sel[slot_load]);
-            }
-#ifdef SNN_MF_DBG
-            if (!(p.dbg & 4))
-#endif
+            load_raw(min(c + RING, last), raw[slot_load]);
+            load_sel(min(c + RING, last), sel[slot_load]);
             make_B(raw[slot_next], B[nxt]);
             make_A(sel[slot_next], A[nxt]);
-#ifdef SNN_MF_DBG
-            if (!(p.dbg & 2))
-#endif
 #pragma unroll
             for (int cb = 0; cb < CB; ++cb)
 #pragma unroll
@@ -591,7 +592,7 @@ MfPlan mf_plan(const Geom &g)
     pl.lds = lut_bytes > red_bytes ? lut_bytes : red_bytes;
     if (fin_bytes > pl.lds) pl.lds = fin_bytes;
     size_t o = 0;
-#ifdef SNN_MF_DBG
+#ifdef SNN_MF_TRACE
     o += 4096;                // clock samples
 #endif
     pl.off_sel = o;
@@ -648,7 +649,7 @@ int launch_subbit_mfma(const Geom &g, const void *x, const uint16_t *codebook, c
     prm.x = (const uint32_t *)x;
     prm.sel = (const uint32_t *)((char *)ws + pl.off_sel);
     prm.fin = (const uint2 *)((char *)ws + pl.off_fin);
-    prm.lut = (const uint4 *)((char *)ws + pl.off_lut);
+    prm.lut = (const uint32_t *)((char *)ws + pl.off_lut);
     prm.y = y;
     prm.g = g;
     prm.COP = pl.COP;
@@ -657,14 +658,13 @@ int launch_subbit_mfma(const Geom &g, const void *x, const uint16_t *codebook, c
     prm.pairs_per_split = (pl.npairs + pl.KS - 1) / pl.KS;
     prm.n_cotiles = pl.n_cotiles;
     prm.n_tiles = pl.n_tiles;
-#ifdef SNN_MF_DBG
-    prm.dbg = env_int("SNN_MF_DBG", 0);
+#ifdef SNN_MF_TRACE
     prm.trace = (unsigned long long *)ws;
 #endif
 
     const int sel_blocks = (pl.COP / 32) * ((g.C_in + 31) / 32);
     const int corr_blocks = (pl.COP + 3) / 4;
-    const int lut_blocks = (512 * (MF_LROW / 4) + 255) / 256;
+    const int lut_blocks = (512 * 6 + 255) / 256;
     hipLaunchKernelGGL(subbit_mfma_prep_kernel, dim3((unsigned)(sel_blocks + corr_blocks + lut_blocks)), dim3(256), 0, s,
                        codebook, idx, g.C_in, g.C_out, pl.COP, pl.cfg.CB, g.K, sel_blocks, lut_blocks, alpha,
                        (uint32_t *)prm.sel, (uint2 *)prm.fin, (uint32_t *)prm.lut);
