@@ -79,17 +79,4 @@ __device__ inline uint32_t window9(const uint32_t *__restrict__ x, const PixGeom
     return window_extract(window_load(x, q, ci, g), q);
 }
 
-// 4x4 byte transpose: in[i] byte b  ->  out[b] byte i.
-__device__ inline void transpose4x4(uint32_t i0, uint32_t i1, uint32_t i2, uint32_t i3, uint32_t out[4])
-{
-    const uint32_t a_lo = __builtin_amdgcn_perm(i1, i0, 0x05010400u);
-    const uint32_t a_hi = __builtin_amdgcn_perm(i1, i0, 0x07030602u);
-    const uint32_t b_lo = __builtin_amdgcn_perm(i3, i2, 0x05010400u);
-    const uint32_t b_hi = __builtin_amdgcn_perm(i3, i2, 0x07030602u);
-    out[0] = __builtin_amdgcn_perm(b_lo, a_lo, 0x05040100u);
-    out[1] = __builtin_amdgcn_perm(b_lo, a_lo, 0x07060302u);
-    out[2] = __builtin_amdgcn_perm(b_hi, a_hi, 0x05040100u);
-    out[3] = __builtin_amdgcn_perm(b_hi, a_hi, 0x07060302u);
-}
-
 }  // namespace snn

@@ -1,4 +1,4 @@
-// Sub-bit 3x3 convolution for K <= 32 on the matrix cores (Sec. 4.5 / Fig. 6).
+// Sub-bit 3x3 convolution for K <= 64 on the matrix cores (Sec. 4.5 / Fig. 6).
 //
 // Stage 1 (responses of the K subset kernels, once per input channel and pixel) is a table
 // lookup: the 9-bit window of +-1 activations selects a row of K match counts
@@ -6,9 +6,10 @@
 // corrected at the end.  Stage 2 (gather by index, sum over c_in) is written as a product with a
 // one-hot matrix, contracted over (c_in, k):
 //     M[co][pixel] = sum_ci sum_k  onehot(idx[co][ci])[k] * m_k(window[ci][pixel])
-// One v_mfma_scale_f32_32x32x64_f8f6f4 covers 32 output channels x 32 pixels x TWO input channels:
-// its 64 contraction slots are (channel parity, subset member k); lanes 0-31 supply the slots of
-// the even channel, lanes 32-63 those of the odd one.
+// One v_mfma_scale_f32_32x32x64_f8f6f4 covers 32 output channels x 32 pixels and 64 contraction
+// slots, of which lanes 0-31 supply the first 32 and lanes 32-63 the rest.  For K <= 32 the slots
+// are (channel parity, subset member k): TWO input channels per instruction, the even one in the
+// low lanes.  For 32 < K <= 64 they are the members k of ONE input channel.
 //   A operand (FP4 e2m1): the one-hot row of an output channel, 32 nibbles, made from a
 //     pre-computed byte selector with four v_perm_b32;
 //   B operand (FP6 e2m3): the table row itself, stored as m_k - 4 in [-4, 5] (exact in e2m3), read
@@ -38,18 +39,20 @@ typedef __attribute__((address_space(3))) u32x4 lds_u32x4;
 
 constexpr int MF_WAVES = 4;                    // waves per workgroup
 constexpr uint32_t MF_SEL_NONE = 0x0c0c0c0cu;  // v_perm_b32 selector bytes that produce 0x00
-constexpr int MF_LROW = 48;                    // table row stride: 24 bytes used, an odd number of 16-byte pieces
+// Table row stride in LDS: 24 bytes (32 FP6 values) per lane half, each half padded to 32 bytes in
+// the two-half form, the row padded to an odd number of 16-byte pieces (fewer bank conflicts).
+__host__ __device__ constexpr int mf_lrow(bool pair) { return pair ? 48 : 80; }
 
 struct MfParams {
     const uint32_t *x;        // packed rows [N][C_in][H][WW]
-    const uint32_t *lut;      // [512][6] words: row = window, 32 FP6 values m_k - 4 packed little-endian
-    const uint32_t *sel;      // [pairs][2][COP] selector words for the one-hot operand
+    const uint32_t *lut;      // [512][6 or 12] words: row = window, 32 (64) FP6 values m_k - 4 packed little-endian
+    const uint32_t *sel;      // [steps][2][COP] selector words for the one-hot operand
     const uint2 *fin;         // [COP][16] per (output channel, border type): {2 corr + C_in (valid_taps - 8), alpha bits}
     float *y;
     Geom g;
     int COP;                  // C_out padded to whole wave tiles
     int KS;                   // waves that split the channel pairs of one tile: 1, 2 or 4
-    int npairs;               // (C_in + 1) / 2 steps of two input channels
+    int npairs;               // steps: (C_in + 1) / 2 of two input channels (K <= 32), else C_in of one
     int pairs_per_split;
     int n_cotiles;
     long long n_tiles;        // pixel tiles * channel tiles
@@ -89,7 +92,7 @@ __host__ __device__ inline uint32_t fp6_of_int(int v)
 //   lut[window] = 32 FP6 codes of m_k - 4 (0 for k >= K)
 __global__ __launch_bounds__(256)
 void subbit_mfma_prep_kernel(const uint16_t *__restrict__ codebook, const uint16_t *__restrict__ idx, int C_in,
-                             int C_out, int COP, int CB, int K, int sel_blocks, int lut_blocks,
+                             int C_out, int COP, int CB, int K, int pair, int sel_blocks, int lut_blocks,
                              const float *__restrict__ alpha, uint32_t *__restrict__ sel, uint2 *__restrict__ fin,
                              uint32_t *__restrict__ lut)
 {
@@ -113,15 +116,22 @@ void subbit_mfma_prep_kernel(const uint16_t *__restrict__ codebook, const uint16
             const uint32_t k = tile[co_l][ci_l];
             uint32_t s = MF_SEL_NONE;
             if (k != 0xffffu) {
-                const uint32_t code = 2u * ((k >> 3) & 3u) + (k & 1u);
+                const uint32_t code = 2u * ((k >> 3) & 3u) + (k & 1u);       // k % 32 inside its lane half
                 const int sh = 8 * ((k >> 1) & 3u);
                 s = (s & ~(0xffu << sh)) | (code << sh);
             }
-            // channel ci is half (ci % 2) of step ci / 2, except the last channel of an odd C_in
-            int c = ci >> 1, h = ci & 1;
             // position inside a row of COP selectors: [wave tile][channel in block][block]
             const int co = co0 + co_l, tilew = 32 * CB;
             const int pos = (co / tilew) * tilew + (co % 32) * CB + (co % tilew) / 32;
+            if (!pair) {
+                // one channel per step; the member's half (k / 32) gets the selector, the other one nothing
+                const int hk = (k != 0xffffu && k >= 32) ? 1 : 0;
+                sel[((int64_t)ci * 2 + hk) * COP + pos] = s;
+                sel[((int64_t)ci * 2 + (hk ^ 1)) * COP + pos] = MF_SEL_NONE;
+                continue;
+            }
+            // channel ci is half (ci % 2) of step ci / 2, except the last channel of an odd C_in
+            int c = ci >> 1, h = ci & 1;
             if ((C_in & 1) && ci == C_in - 1) {
                 c = npairs - 1;
                 h = 1;
@@ -132,14 +142,18 @@ void subbit_mfma_prep_kernel(const uint16_t *__restrict__ codebook, const uint16
         return;
     }
     if (b >= (int)gridDim.x - lut_blocks) {
-        // one thread per 32-bit word of the table; a row is 6 words of 32 FP6 codes
+        // one thread per 32-bit word of the table; a row is 6 words of 32 FP6 codes per lane half
+        const int wpr = pair ? 6 : 12;
         const int i = (b - ((int)gridDim.x - lut_blocks)) * 256 + tid;
-        if (i < 512 * 6) {
-            const int win = i / 6, w = i - win * 6;
+        if (i < 512 * wpr) {
+            const int win = i / wpr, wh = i - win * wpr;
+            const int half = wh / 6, w = wh - 6 * half;
             uint32_t word = 0;
-            for (int k = (32 * w) / 6; k <= (32 * w + 31) / 6 && k < K; ++k) {
+            for (int kl = (32 * w) / 6; kl <= (32 * w + 31) / 6; ++kl) {
+                const int k = 32 * half + kl;
+                if (k >= K) break;
                 const int m = 9 - __popc((uint32_t)win ^ code_to_window_order(codebook[k] & 511u));
-                const int at = 6 * k - 32 * w;                 // position of the code's bit 0 in this word
+                const int at = 6 * kl - 32 * w;                // position of the code's bit 0 in this word
                 const uint32_t code = fp6_of_int(m - 4);
                 word |= at >= 0 ? code << at : code >> -at;
             }
@@ -213,11 +227,13 @@ __device__ inline u32x4 buf_load4(__amdgpu_buffer_rsrc_t r, uint32_t lane_off, u
 // ---- the convolution ------------------------------------------------------------------------------
 // PB, CB: blocks of 32 pixels / 32 output channels per wave.  WM: words per packed row, 1 or 2
 // (the three window rows of a lane are then one contiguous load), or 0 for wider rows.
-template <int PB, int CB, int WM>
+// PAIR: two input channels per step (K <= 32), else one (K <= 64).
+template <int PB, int CB, int WM, bool PAIR>
 __global__ __launch_bounds__(MF_WAVES * 64, 2)
 void subbit_mfma_kernel(const MfParams p)
 {
     constexpr int NBLK = PB * CB;
+    constexpr int MF_LROW = mf_lrow(PAIR);
     const Geom &g = p.g;
 
     extern __shared__ __align__(16) unsigned char smem[];
@@ -239,7 +255,7 @@ void subbit_mfma_kernel(const MfParams p)
     MF_TRACE(0);
 
     // ---- per-lane window geometry of the PB pixels (pixel n_l of every block) ----------------------
-    // This lane looks at input channel (2 c + h) in step c.  It loads three consecutive packed rows
+    // This lane looks at input channel (2 c + h) in step c (PAIR; else channel c).  It loads three consecutive packed rows
     // starting at row max(hc - 1, 0), words (jlo, jlo + 1), and cuts row dy of the window out of the
     // 64-bit string {hi, lo} at bit `sh`.  Two cases are folded into a final shift `lsh` of the
     // 9-bit window so that no load starts before the tensor:
@@ -270,7 +286,7 @@ void subbit_mfma_kernel(const MfParams p)
         sh[pb] = (uint32_t)(col & 31);
         m7[pb] = first < 0 ? 3u : 7u;
         lsh[pb] = (first < 0 ? 1u : 0u) + (hc == 0 ? 3u : 0u);
-        xoff[pb] = (uint32_t)(((n * g.C_in + h) * g.H + (hc == 0 ? 0 : hc - 1)) * g.WW + jlo) * 4u;
+        xoff[pb] = (uint32_t)(((n * g.C_in + (PAIR ? h : 0)) * g.H + (hc == 0 ? 0 : hc - 1)) * g.WW + jlo) * 4u;
     }
     const __amdgpu_buffer_rsrc_t xres = make_rsrc(p.x, (uint32_t)g.N * (uint32_t)g.C_in * plane_bytes);
     const uint32_t lut_base = (uint32_t)(uintptr_t)smem;
@@ -282,7 +298,7 @@ void subbit_mfma_kernel(const MfParams p)
     const int last_first = g.C_in - 2;
     const uint32_t row_bytes = (uint32_t)g.WW * 4u;
     auto load_raw = [&](int c, Raw &r) {
-        const uint32_t co = (uint32_t)min(2 * c, last_first) * plane_bytes;
+        const uint32_t co = (uint32_t)(PAIR ? min(2 * c, last_first) : c) * plane_bytes;
 #pragma unroll
         for (int pb = 0; pb < PB; ++pb) {
             if constexpr (WM == 1) {                 // rows are consecutive words
@@ -337,7 +353,7 @@ void subbit_mfma_kernel(const MfParams p)
                 row[dy] = __builtin_amdgcn_alignbit(WM == 1 ? r.lo[pb][dy] : r.hi[pb][dy], r.lo[pb][dy], sh[pb]);
             const uint32_t m = m7[pb];
             const uint32_t w = (((row[0] & m) | ((row[1] & m) << 3) | ((row[2] & m) << 6)) << lsh[pb]) & vm[pb];
-            const uint32_t addr = lut_base + w * MF_LROW;
+            const uint32_t addr = lut_base + w * MF_LROW + (PAIR ? 0u : 32u * (uint32_t)h);
             const u32x4 q0 = *(lds_cu32x4 *)(uintptr_t)addr;
             const u32x2 q1 = *(lds_cu32x2 *)(uintptr_t)(addr + 16);
             B[pb] = (v8i){(int)q0.x, (int)q0.y, (int)q0.z, (int)q0.w, (int)q1.x, (int)q1.y, 0, 0};
@@ -379,13 +395,15 @@ void subbit_mfma_kernel(const MfParams p)
         load_sel(min(c_begin + u, last), sel[u]);
         __builtin_amdgcn_sched_barrier(0);
     }
-    // the lookup table image was built once by the preparation kernel; copy it into LDS, rows of
-    // 6 words spread to the padded stride
+    // the lookup table image was built once by the preparation kernel; copy it into LDS, the 6 words
+    // of every lane half spread to the padded layout
+    constexpr int HALVES = PAIR ? 1 : 2;
 #pragma unroll
-    for (int i = 0; i < 512 * 6 / (MF_WAVES * 64); ++i) {
+    for (int i = 0; i < 512 * 6 * HALVES / (MF_WAVES * 64); ++i) {
         const int e = i * (MF_WAVES * 64) + tid;
-        const int row = e / 6, col = e - row * 6;
-        ((uint32_t *)smem)[row * (MF_LROW / 4) + col] = p.lut[e];
+        const int row = e / (6 * HALVES), rest = e - row * (6 * HALVES);
+        const int half = rest / 6, col = rest - 6 * half;
+        ((uint32_t *)smem)[row * (MF_LROW / 4) + half * 8 + col] = p.lut[e];
     }
     MF_TRACE(1);
     __syncthreads();                               // table visible
@@ -548,6 +566,7 @@ struct MfCfg {
 
 struct MfPlan {
     MfCfg cfg;
+    bool pair;        // K <= 32: two input channels per step
     int KS, COP, n_cotiles, npairs;
     long long n_pxtiles, n_tiles, n_wgs;
     size_t lds;
@@ -577,7 +596,8 @@ MfPlan mf_plan(const Geom &g)
     pl.n_cotiles = pl.COP / cow;
     pl.n_pxtiles = (g.P + pxw - 1) / pxw;
     pl.n_tiles = pl.n_pxtiles * pl.n_cotiles;
-    pl.npairs = (g.C_in + 1) / 2;
+    pl.pair = g.K <= 32;
+    pl.npairs = pl.pair ? (g.C_in + 1) / 2 : g.C_in;
     // split the channel pairs over waves while the tiles alone leave SIMDs idle (1024 SIMDs, two waves each)
     int KS = 1;
     while (KS < 4 && pl.n_tiles * KS < 1536 && pl.npairs / (2 * KS) >= 8) KS *= 2;
@@ -585,7 +605,7 @@ MfPlan mf_plan(const Geom &g)
     if (ks_env == 1 || ks_env == 2 || ks_env == 4) KS = ks_env;
     pl.KS = KS;
     pl.n_wgs = (pl.n_tiles * KS + MF_WAVES - 1) / MF_WAVES;
-    const size_t lut_bytes = (size_t)512 * MF_LROW;
+    const size_t lut_bytes = (size_t)512 * mf_lrow(pl.pair);
     const int nblk = pl.cfg.PB * pl.cfg.CB;
     const size_t red_bytes = KS > 1 ? (size_t)(MF_WAVES / KS) * (nblk > 4 ? nblk / 2 : nblk) * (KS - 1) * 4096 : 0;
     const size_t fin_bytes = (size_t)MF_WAVES * 32 * pl.cfg.CB * 16 * 8;
@@ -605,10 +625,10 @@ MfPlan mf_plan(const Geom &g)
     return pl;
 }
 
-template <int PB, int CB, int WM>
+template <int PB, int CB, int WM, bool PAIR>
 int launch_mf_one(const MfPlan &pl, const MfParams &prm, hipStream_t s)
 {
-    auto kern = subbit_mfma_kernel<PB, CB, WM>;
+    auto kern = subbit_mfma_kernel<PB, CB, WM, PAIR>;
     if (pl.lds > 64 * 1024 &&
         hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)pl.lds) != hipSuccess)
         return SNN_ERR_LAUNCH;
@@ -619,21 +639,26 @@ int launch_mf_one(const MfPlan &pl, const MfParams &prm, hipStream_t s)
 template <int PB, int CB>
 int launch_mf(const MfPlan &pl, const MfParams &prm, hipStream_t s)
 {
-    if (prm.g.WW == 1) return launch_mf_one<PB, CB, 1>(pl, prm, s);
-    if (prm.g.WW == 2) return launch_mf_one<PB, CB, 2>(pl, prm, s);
-    return launch_mf_one<PB, CB, 0>(pl, prm, s);
+    if (pl.pair) {
+        if (prm.g.WW == 1) return launch_mf_one<PB, CB, 1, true>(pl, prm, s);
+        if (prm.g.WW == 2) return launch_mf_one<PB, CB, 2, true>(pl, prm, s);
+        return launch_mf_one<PB, CB, 0, true>(pl, prm, s);
+    }
+    if (prm.g.WW == 1) return launch_mf_one<PB, CB, 1, false>(pl, prm, s);
+    if (prm.g.WW == 2) return launch_mf_one<PB, CB, 2, false>(pl, prm, s);
+    return launch_mf_one<PB, CB, 0, false>(pl, prm, s);
 }
 
 }  // namespace
 
 bool subbit_mfma_supported(const Geom &g)
 {
-    // one FP6 table row of 32 subset members and two input channels per matrix instruction;
-    // 32-bit byte offsets into the packed input, the selector table and the output
+    // 64 contraction slots per matrix instruction: two input channels of up to 32 subset members or
+    // one of up to 64; 32-bit byte offsets into the packed input, the selector table and the output
     const int64_t x_words = (int64_t)g.N * g.C_in * g.H * g.WW;
-    const int64_t sel_words = (int64_t)(g.C_in + 1) * (g.C_out + 127);
+    const int64_t sel_words = (int64_t)2 * (g.C_in + 1) * (g.C_out + 127);
     const int64_t y_words = (int64_t)g.P * g.C_out;
-    return g.K <= 32 && g.C_in >= 2 && x_words < ((int64_t)1 << 30) && sel_words < ((int64_t)1 << 30) &&
+    return g.K <= 64 && (g.K > 32 || g.C_in >= 2) && x_words < ((int64_t)1 << 30) && sel_words < ((int64_t)1 << 30) &&
            y_words < ((int64_t)1 << 30) && g.P < ((int64_t)1 << 31) - 4096;
 }
 
@@ -664,9 +689,9 @@ int launch_subbit_mfma(const Geom &g, const void *x, const uint16_t *codebook, c
 
     const int sel_blocks = (pl.COP / 32) * ((g.C_in + 31) / 32);
     const int corr_blocks = (pl.COP + 3) / 4;
-    const int lut_blocks = (512 * 6 + 255) / 256;
+    const int lut_blocks = (512 * (pl.pair ? 6 : 12) + 255) / 256;
     hipLaunchKernelGGL(subbit_mfma_prep_kernel, dim3((unsigned)(sel_blocks + corr_blocks + lut_blocks)), dim3(256), 0, s,
-                       codebook, idx, g.C_in, g.C_out, pl.COP, pl.cfg.CB, g.K, sel_blocks, lut_blocks, alpha,
+                       codebook, idx, g.C_in, g.C_out, pl.COP, pl.cfg.CB, g.K, pl.pair ? 1 : 0, sel_blocks, lut_blocks, alpha,
                        (uint32_t *)prm.sel, (uint2 *)prm.fin, (uint32_t *)prm.lut);
 
     const MfCfg &c = pl.cfg;

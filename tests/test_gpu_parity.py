@@ -135,14 +135,17 @@ def test_subbit_bin(oracle, case):
 @pytest.mark.parametrize("tile", ["4,2", "2,4", "2,2", "1,4", "1,2"])
 @pytest.mark.parametrize("split", [1, 2, 4])
 def test_subbit_bin_matrix_core_kernel_every_tile_and_split(oracle, tile, split, monkeypatch):
-    """Every instantiated wave tile of the matrix-core kernel (K <= 32) and every split of the
-    input channels over waves, forced on layers with ragged edges: odd and even C_in, C_out not
-    a multiple of 32, rows of one, two and three packed words, both strides, a pixel tail."""
+    """Every instantiated wave tile of the matrix-core kernel and every split of the input
+    channels over waves, forced on layers with ragged edges: odd and even C_in, C_out not a
+    multiple of 32, rows of one, two and three packed words, both strides, a pixel tail, and
+    both forms of a step (two channels of K <= 32 members, one channel of K <= 64)."""
     monkeypatch.setenv("SNN_MFMA_TILE", tile)
     monkeypatch.setenv("SNN_MFMA_KS", str(split))
     for seed, (N, C_in, C_out, H, W, stride, K) in enumerate([(3, 45, 150, 13, 11, 1, 32), (2, 20, 70, 16, 12, 2, 32),
                                                              (2, 34, 40, 9, 40, 1, 20), (1, 8, 33, 5, 70, 1, 32),
-                                                             (2, 130, 96, 8, 8, 2, 7), (1, 2, 3, 1, 1, 1, 2)]):
+                                                             (2, 130, 96, 8, 8, 2, 7), (1, 2, 3, 1, 1, 1, 2),
+                                                             (2, 24, 40, 9, 11, 1, 64), (2, 33, 70, 14, 14, 2, 40),
+                                                             (1, 1, 36, 6, 40, 1, 33), (1, 7, 8, 5, 70, 1, 64)]):
         _say("subbit_bin matrix-core", tile, split, (N, C_in, C_out, H, W, stride, K))
         x, cb, idx, alpha = _inputs(900 + seed, N, C_in, C_out, H, W, K)
         _, Y = oracle.conv_bin(oracle.sign(x), oracle.expand(cb, idx), alpha, stride)
@@ -150,36 +153,18 @@ def test_subbit_bin_matrix_core_kernel_every_tile_and_split(oracle, tile, split,
         assert (y == Y).all(), np.argwhere(y != Y)[:5]
 
 
-@pytest.mark.parametrize("variant", ["wave", "workgroup"])
-@pytest.mark.parametrize("case", [c for c in SUBBIT_CASES if c[6] <= 64])
-def test_subbit_bin_both_kernel_variants(oracle, case, variant, monkeypatch):
-    """With the matrix-core kernel switched off the library picks between a wave-private and a
-    workgroup-tile LDS-gather kernel by layer size; force each of them on every case (the tuning
-    overrides are read at every call)."""
-    _say("subbit_bin", variant, case)
+@pytest.mark.parametrize("case", SUBBIT_CASES)
+def test_subbit_bin_fallback_kernel(oracle, case, monkeypatch):
+    """With the matrix-core kernel switched off (a tuning override, read at every call) every
+    case runs through the fallback kernel that otherwise only sees K > 64 and single-channel
+    layers."""
+    _say("subbit_bin fallback", case)
     monkeypatch.setenv("SNN_SUBBIT_MFMA", "0")
-    monkeypatch.setenv("SNN_SUBBIT_WAVE", "1" if variant == "wave" else "0")
     N, C_in, C_out, H, W, stride, K, dist = case
     x, cb, idx, alpha = _inputs(sum(case[:7]), N, C_in, C_out, H, W, K, dist)
     _, Y = oracle.conv_bin(oracle.sign(x), oracle.expand(cb, idx), alpha, stride)
     y = G.subbit_bin(x, cb, idx, alpha, stride)
     assert (y == Y).all(), np.argwhere(y != Y)[:5]
-
-
-@pytest.mark.parametrize("tile", ["4,1,8", "4,2,8", "2,1,8", "2,2,8", "1,1,4", "1,1,8", "4,1,1", "1,1,1"])
-def test_subbit_bin_every_tile_shape(oracle, tile, monkeypatch):
-    """Every instantiated tile of the workgroup LDS-gather kernel, forced on a layer with ragged edges."""
-    monkeypatch.setenv("SNN_SUBBIT_MFMA", "0")
-    monkeypatch.setenv("SNN_SUBBIT_WAVE", "0")
-    monkeypatch.setenv("SNN_SUBBIT_TILE", tile)
-    x, cb, idx, alpha = _inputs(123, 3, 45, 150, 13, 11, 32)
-    _, Y = oracle.conv_bin(oracle.sign(x), oracle.expand(cb, idx), alpha, 1)
-    assert (G.subbit_bin(x, cb, idx, alpha, 1) == Y).all()
-    x, cb, idx, alpha = _inputs(124, 2, 20, 70, 16, 12, 32)       # W_out multiple of 4: the row-string window path
-    _, Y = oracle.conv_bin(oracle.sign(x), oracle.expand(cb, idx), alpha, 1)
-    assert (G.subbit_bin(x, cb, idx, alpha, 1) == Y).all()
-    _, Y = oracle.conv_bin(oracle.sign(x), oracle.expand(cb, idx), alpha, 2)
-    assert (G.subbit_bin(x, cb, idx, alpha, 2) == Y).all()
 
 
 def test_subbit_bin_takes_oracle_packed_input(oracle):
