@@ -40,7 +40,7 @@ def main(fetch_csv, write_csv):
     total_f = total_w = 0.0
     launches_per_step = {}
     for k, v in fetch.items():
-        if "subbit_wave_kernel" in k or "subbit_lut_kernel" in k or "subbit_direct_kernel" in k:
+        if "subbit_mfma_kernel" in k or "subbit_direct_kernel" in k:
             w = write.get(k, [0.0])
             # launches of this kernel per step: ResNet-18 stack -> count layers by instantiation
             out["kernels"][_short(k)] = {"launches": len(v), "fetch_bytes_per_launch": sf * sum(v) / len(v),
