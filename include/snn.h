@@ -50,7 +50,7 @@ extern "C" {
 #define SNN_OK               0
 #define SNN_ERR_INVALID_ARG (-1)  /* null pointer, non-positive size, K outside 1..512, bad enum */
 #define SNN_ERR_UNSUPPORTED (-2)  /* a valid request this build has no kernel for (listed per call) */
-#define SNN_ERR_WORKSPACE   (-3)  /* workspace pointer null or ws_bytes too small */
+#define SNN_ERR_WORKSPACE   (-3)  /* workspace null, misaligned or ws_bytes too small */
 #define SNN_ERR_LAUNCH      (-4)  /* the HIP runtime refused a launch */
 
 /* activation layouts (snn_conv_desc.act and the `layout` argument of snn_pack_activations) */

@@ -100,7 +100,7 @@ int snn_subbit_conv2d(const snn_conv_desc *desc, const void *x, const uint16_t *
     if (!subbit_act_supported(desc->act)) return SNN_ERR_UNSUPPORTED;
     const Geom g = make_geom(*desc);
     const size_t need = subbit_workspace_bytes(g, desc->act);
-    if (need > 0 && (!workspace || ws_bytes < need)) return SNN_ERR_WORKSPACE;
+    if (need > 0 && (!workspace || ws_bytes < need || ((uintptr_t)workspace & 255u))) return SNN_ERR_WORKSPACE;
     return launch_subbit(g, desc->act, x, codebook, idx, alpha, y_nchw, workspace, (hipStream_t)stream);
 }
 
@@ -111,7 +111,7 @@ int snn_bnn_conv2d(const snn_conv_desc *desc, const void *x, const uint16_t *w9,
     if (!bnn_supported(desc)) return SNN_ERR_UNSUPPORTED;
     const Geom g = make_geom(*desc);
     const size_t need = bnn_workspace_bytes(g, desc->act);
-    if (need > 0 && (!workspace || ws_bytes < need)) return SNN_ERR_WORKSPACE;
+    if (need > 0 && (!workspace || ws_bytes < need || ((uintptr_t)workspace & 255u))) return SNN_ERR_WORKSPACE;
     return launch_bnn(g, desc->act, x, w9, alpha, y_nchw, workspace, (hipStream_t)stream);
 }
 

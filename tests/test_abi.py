@@ -85,3 +85,8 @@ def test_invalid_arguments_are_status_codes_not_crashes(L):
     d.act = binding.SNN_ACT_BIN_ROWS
     assert L.snn_bnn_conv2d(ctypes.byref(d), one, one, one, one, one, 1 << 20, null) == binding.SNN_ERR_UNSUPPORTED
     assert L.snn_subbit_conv2d(ctypes.byref(d), one, one, one, one, one, one, 16, null) == binding.SNN_ERR_WORKSPACE
+    # a workspace of sufficient size at an address that is not a multiple of 256 is refused too
+    odd = ctypes.c_void_p(256 + 16)
+    assert L.snn_subbit_conv2d(ctypes.byref(d), one, one, one, one, one, odd, 1 << 30, null) == binding.SNN_ERR_WORKSPACE
+    d.act = binding.SNN_ACT_BIN_CHANNELS
+    assert L.snn_bnn_conv2d(ctypes.byref(d), one, one, one, one, odd, 1 << 30, null) == binding.SNN_ERR_WORKSPACE
