@@ -36,9 +36,13 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) const u32x4 lds_cu32x4;
 typedef __attribute__((address_space(3))) const u32x2 lds_cu32x2;
 typedef __attribute__((address_space(3))) u32x4 lds_u32x4;
+typedef __attribute__((address_space(3))) const uint32_t lds_cu32;
+typedef __attribute__((address_space(3))) uint32_t lds_u32;
 
 constexpr int MF_WAVES = 4;                    // waves per workgroup
 constexpr uint32_t MF_SEL_NONE = 0x0c0c0c0cu;  // v_perm_b32 selector bytes that produce 0x00
+constexpr int MF_STAGE_SLOTS = 32;             // packed words a wave stages per input channel and step
+constexpr int MF_STAGE_BYTES = 2 * MF_STAGE_SLOTS * 4 + 32;   // per wave: two channels + room for reads past the last slot
 // Table row stride in LDS: 24 bytes (32 FP6 values) per lane half, each half padded to 32 bytes in
 // the two-half form, the row padded to an odd number of 16-byte pieces (fewer bank conflicts).
 __host__ __device__ constexpr int mf_lrow(bool pair) { return pair ? 48 : 80; }
@@ -211,6 +215,10 @@ __device__ inline void buf_store(__amdgpu_buffer_rsrc_t r, float v, uint32_t lan
     __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(v), r, (int)lane_off, (int)uniform_off, 0);
 }
 typedef uint32_t u32x3 __attribute__((ext_vector_type(3)));
+__device__ inline uint32_t buf_load1(__amdgpu_buffer_rsrc_t r, uint32_t lane_off, uint32_t uniform_off)
+{
+    return __builtin_amdgcn_raw_buffer_load_b32(r, (int)lane_off, (int)uniform_off, 0);
+}
 __device__ inline u32x2 buf_load2(__amdgpu_buffer_rsrc_t r, uint32_t lane_off, uint32_t uniform_off)
 {
     return __builtin_amdgcn_raw_buffer_load_b64(r, (int)lane_off, (int)uniform_off, 0);
@@ -228,10 +236,19 @@ __device__ inline u32x4 buf_load4(__amdgpu_buffer_rsrc_t r, uint32_t lane_off, u
 // PB, CB: blocks of 32 pixels / 32 output channels per wave.  WM: words per packed row, 1 or 2
 // (the three window rows of a lane are then one contiguous load), or 0 for wider rows.
 // PAIR: two input channels per step (K <= 32), else one (K <= 64).
-template <int PB, int CB, int WM, bool PAIR>
+// STG: the packed rows a tile touches are few (at most MF_STAGE_SLOTS pieces per channel, WM = 1
+// or 2).  Then the lanes do not fetch their own three rows from memory, 31 of 32 of those reads
+// being the same words: per step ONE load brings every piece the wave needs (lane s of a half:
+// piece s of the run of rows that starts at the first pixel's top row), the wave passes it through
+// a private piece of LDS, and every lane reads ONE 32-bit piece per row from there.  A row of one
+// word is one piece; a row of two words is three overlapping pieces, bits [0,32), [16,48) and
+// [32,64), so that every window of three columns lies inside one of them.  The memory pipeline,
+// which otherwise bounds the layers with few output channels, sees one instruction instead of 3 PB.
+template <int PB, int CB, int WM, bool PAIR, bool STG>
 __global__ __launch_bounds__(MF_WAVES * 64, 2)
 void subbit_mfma_kernel(const MfParams p)
 {
+    static_assert(!STG || WM == 1 || WM == 2, "staging needs rows that are consecutive in memory");
     constexpr int NBLK = PB * CB;
     constexpr int MF_LROW = mf_lrow(PAIR);
     const Geom &g = p.g;
@@ -254,6 +271,15 @@ void subbit_mfma_kernel(const MfParams p)
 
     MF_TRACE(0);
 
+    // The lookup table image was built once by the preparation kernel.  Its words are requested
+    // first of all, so that they travel while the lanes work out their geometry.
+    constexpr int HALVES = PAIR ? 1 : 2;
+    constexpr int LUT_WORDS = 512 * 6 * HALVES / (MF_WAVES * 64);     // per thread
+    uint32_t lutw[LUT_WORDS];
+#pragma unroll
+    for (int i = 0; i < LUT_WORDS; ++i) lutw[i] = p.lut[i * (MF_WAVES * 64) + tid];
+    __builtin_amdgcn_sched_barrier(0);
+
     // ---- per-lane window geometry of the PB pixels (pixel n_l of every block) ----------------------
     // This lane looks at input channel (2 c + h) in step c (PAIR; else channel c).  It loads three consecutive packed rows
     // starting at row max(hc - 1, 0), words (jlo, jlo + 1), and cuts row dy of the window out of the
@@ -269,6 +295,27 @@ void subbit_mfma_kernel(const MfParams p)
     uint32_t yoff[PB];                             // byte offset of y[n][4 h][pixel], out of range for pixels past the end
     int ptype[PB];                                 // border type
     const int P32 = (int)g.P;
+    // Staging (STG): rows are numbered R = n * H + h over the whole batch; the wave stages words
+    // [0, MF_STAGE_SLOTS) of the run of rows that starts at R_first, the first row the tile's
+    // first pixel loads.  A pixel's three rows start (R - R_first) * WM + jlo words into the run.
+    const uint32_t stage_wave = (uint32_t)(uintptr_t)smem + 512u * (uint32_t)MF_LROW + (uint32_t)wave * MF_STAGE_BYTES;
+    constexpr int SW = WM == 2 ? 3 : 1;            // pieces per staged row
+    int R_first = 0;
+    uint32_t goff = 0xffffffffu;                   // byte offset of the word(s) this lane stages (channel h of the step)
+    uint32_t gshift = 0;                           // two-word rows: the piece is bits [gshift, gshift + 32) of the two words loaded
+    uint32_t loff[PB];                             // LDS address of the pixel's piece of its first row
+    if constexpr (STG) {
+        const int pt = (int)p_tile;
+        const int n0 = pt / g.HoWo;
+        const int ho0 = (pt - n0 * g.HoWo) / g.Wo;
+        const int hc0 = ho0 * g.stride;
+        R_first = n0 * g.H + (hc0 == 0 ? 0 : hc0 - 1);
+        const int R = R_first + n_l / SW, piece = n_l % SW;
+        const int n = R / g.H, hr = R - n * g.H;
+        if (n < g.N && (PAIR || h == 0))
+            goff = (uint32_t)(((n * g.C_in + (PAIR ? h : 0)) * g.H + hr) * g.WW + (piece == 2 ? 1 : 0)) * 4u;
+        gshift = piece == 1 ? 16u : 0u;
+    }
 #pragma unroll
     for (int pb = 0; pb < PB; ++pb) {
         int pp = (int)p_tile + pb * 32 + n_l;
@@ -283,16 +330,19 @@ void subbit_mfma_kernel(const MfParams p)
         const int hc = ho * g.stride, first = wo * g.stride - 1;
         const int col = first < 0 ? 0 : first;     // column of the first bit cut out
         const int jlo = WM == 1 ? 0 : col >> 5;
-        sh[pb] = (uint32_t)(col & 31);
+        const int piece = WM == 2 ? (col < 30 ? 0 : col < 46 ? 1 : 2) : 0;          // staged piece that holds columns col .. col + 2
+        sh[pb] = STG ? (uint32_t)(col - 16 * piece) : (uint32_t)(col & 31);
         m7[pb] = first < 0 ? 3u : 7u;
         lsh[pb] = (first < 0 ? 1u : 0u) + (hc == 0 ? 3u : 0u);
         xoff[pb] = (uint32_t)(((n * g.C_in + (PAIR ? h : 0)) * g.H + (hc == 0 ? 0 : hc - 1)) * g.WW + jlo) * 4u;
+        loff[pb] = stage_wave + (uint32_t)((PAIR ? h * MF_STAGE_SLOTS : 0) + (n * g.H + (hc == 0 ? 0 : hc - 1) - R_first) * SW + piece) * 4u;
     }
     const __amdgpu_buffer_rsrc_t xres = make_rsrc(p.x, (uint32_t)g.N * (uint32_t)g.C_in * plane_bytes);
     const uint32_t lut_base = (uint32_t)(uintptr_t)smem;
 
+    constexpr bool ONE_WORD = WM == 1 || STG;      // a lane cuts its window row out of one 32-bit piece
     struct Raw {
-        uint32_t lo[PB][3], hi[WM == 1 ? 1 : PB][3];
+        uint32_t lo[PB][3], hi[ONE_WORD ? 1 : PB][3];
     };
     // step c -> first channel of the pair (the last step of an odd C_in starts one channel early)
     const int last_first = g.C_in - 2;
@@ -325,6 +375,22 @@ void subbit_mfma_kernel(const MfParams p)
             }
         }
     };
+    typedef std::conditional_t<WM == 2, u32x2, uint32_t> Staged;
+    auto load_stage = [&](int c) -> Staged {
+        const uint32_t co = (uint32_t)(PAIR ? min(2 * c, last_first) : c) * plane_bytes;
+        if constexpr (WM == 2) return buf_load2(xres, goff, co);
+        else return buf_load1(xres, goff, co);
+    };
+    // the staged piece goes to LDS, the lane's rows come back (LDS serves a wave's accesses in order)
+    const uint32_t stage_lane = stage_wave + (uint32_t)lane * 4u;
+    auto restage = [&](const Staged &v, Raw &r) {
+        if constexpr (WM == 2) *(lds_u32 *)(uintptr_t)stage_lane = __builtin_amdgcn_alignbit(v.y, v.x, gshift);
+        else *(lds_u32 *)(uintptr_t)stage_lane = v;
+#pragma unroll
+        for (int pb = 0; pb < PB; ++pb)
+#pragma unroll
+            for (int dy = 0; dy < 3; ++dy) r.lo[pb][dy] = *(lds_cu32 *)(uintptr_t)(loff[pb] + (uint32_t)(dy * SW) * 4u);
+    };
     // selectors of the lane's CB channel blocks are contiguous: [step][half][tile][channel in block][block]
     const uint32_t sel_step_bytes = 2u * (uint32_t)p.COP * 4u;
     const __amdgpu_buffer_rsrc_t sres = make_rsrc(p.sel, (uint32_t)p.npairs * sel_step_bytes);
@@ -350,7 +416,7 @@ void subbit_mfma_kernel(const MfParams p)
             uint32_t row[3];
 #pragma unroll
             for (int dy = 0; dy < 3; ++dy)
-                row[dy] = __builtin_amdgcn_alignbit(WM == 1 ? r.lo[pb][dy] : r.hi[pb][dy], r.lo[pb][dy], sh[pb]);
+                row[dy] = __builtin_amdgcn_alignbit(ONE_WORD ? r.lo[pb][dy] : r.hi[pb][dy], r.lo[pb][dy], sh[pb]);
             const uint32_t m = m7[pb];
             const uint32_t w = (((row[0] & m) | ((row[1] & m) << 3) | ((row[2] & m) << 6)) << lsh[pb]) & vm[pb];
             const uint32_t addr = lut_base + w * MF_LROW + (PAIR ? 0u : 32u * (uint32_t)h);
@@ -382,34 +448,45 @@ void subbit_mfma_kernel(const MfParams p)
 
     // pipeline: memory loads RING steps ahead (a ring of RING register sets: the set of step c is
     // free once its operands exist, which is during step c - 1), operands one step ahead (two
-    // sets).  Deeper rings where a step's loads are few registers.
-    constexpr int RAW_REGS = PB * (WM == 1 ? 3 : 6) + CB;
+    // sets).  Deeper rings where a step's loads are few registers.  With staging the rows come out of
+    // LDS two steps ahead (two sets again, so that no LDS read is waited for in the step that issues
+    // it), and the one staged word per step sits in a ring of its own, SRING steps ahead.
+    constexpr int RAW_REGS = (STG ? 0 : PB * (WM == 1 ? 3 : 6)) + CB;
     constexpr int RING = RAW_REGS <= 16 ? 3 : 2;
-    constexpr int UNROLL = RING % 2 == 0 ? RING : 2 * RING;
-    Raw raw[RING];
+    constexpr int SRING = 6;
+    constexpr int UNROLL = STG ? 6 : RING % 2 == 0 ? RING : 2 * RING;
+    static_assert(UNROLL % RING == 0 && UNROLL % 2 == 0 && (!STG || UNROLL % SRING == 0), "register sets rotate with the unrolled steps");
+    Raw raw[STG ? 2 : RING];
+    Staged stg[SRING];
     uint32_t sel[RING][CB];
     v8i A[2][CB], B[2][PB];
+    if constexpr (STG) {
+#pragma unroll
+        for (int u = 0; u < SRING; ++u) stg[u] = load_stage(min(c_begin + u, last));
+    }
 #pragma unroll
     for (int u = 0; u < RING; ++u) {
-        load_raw(min(c_begin + u, last), raw[u]);
+        if constexpr (!STG) load_raw(min(c_begin + u, last), raw[u]);
         load_sel(min(c_begin + u, last), sel[u]);
         __builtin_amdgcn_sched_barrier(0);
     }
-    // the lookup table image was built once by the preparation kernel; copy it into LDS, the 6 words
-    // of every lane half spread to the padded layout
-    constexpr int HALVES = PAIR ? 1 : 2;
+    // the table into LDS, the 6 words of every lane half spread to the padded layout
 #pragma unroll
-    for (int i = 0; i < 512 * 6 * HALVES / (MF_WAVES * 64); ++i) {
+    for (int i = 0; i < LUT_WORDS; ++i) {
         const int e = i * (MF_WAVES * 64) + tid;
         const int row = e / (6 * HALVES), rest = e - row * (6 * HALVES);
         const int half = rest / 6, col = rest - 6 * half;
-        ((uint32_t *)smem)[row * (MF_LROW / 4) + half * 8 + col] = p.lut[e];
+        ((uint32_t *)smem)[row * (MF_LROW / 4) + half * 8 + col] = lutw[i];
     }
     MF_TRACE(1);
     __syncthreads();                               // table visible
     MF_TRACE(2);
 
     if (c_begin < c_end) {
+        if constexpr (STG) {
+            restage(stg[0], raw[0]);
+            restage(stg[1], raw[1]);
+        }
         make_B(raw[0], B[0]);
         make_A(sel[0], A[0]);
         __builtin_amdgcn_sched_barrier(0);
@@ -422,9 +499,17 @@ void subbit_mfma_kernel(const MfParams p)
             constexpr int u = decltype(uc)::value;
             constexpr int cur = u % 2, nxt = (u + 1) % 2;
             constexpr int slot_next = (u + 1) % RING, slot_load = u % RING;
-            load_raw(min(c + RING, last), raw[slot_load]);
-            load_sel(min(c + RING, last), sel[slot_load]);
-            make_B(raw[slot_next], B[nxt]);
+            if constexpr (STG) {
+                // rows of step c + 2 into the set that held step c's; operands of step c + 1 from the other
+                restage(stg[(u + 2) % SRING], raw[cur]);
+                stg[u % SRING] = load_stage(min(c + SRING, last));
+                load_sel(min(c + RING, last), sel[slot_load]);
+                make_B(raw[nxt], B[nxt]);
+            } else {
+                load_raw(min(c + RING, last), raw[slot_load]);
+                load_sel(min(c + RING, last), sel[slot_load]);
+                make_B(raw[slot_next], B[nxt]);
+            }
             make_A(sel[slot_next], A[nxt]);
 #pragma unroll
             for (int cb = 0; cb < CB; ++cb)
@@ -433,15 +518,18 @@ void subbit_mfma_kernel(const MfParams p)
                     acc[cb][pb] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(A[cur][cb], B[cur][pb], acc[cb][pb], 4 /* A: FP4 */,
                                                                                   2 /* B: FP6 e2m3 */, 0, 127, 0, 127);
             constexpr int NMF = CB * PB;
-            constexpr int NVM = PB * (WM == 1 ? 1 : WM == 2 ? 2 : 3) + 1;   // loads of a step
+            constexpr int NVM = (STG ? 1 : PB * (WM == 1 ? 1 : WM == 2 ? 2 : 3)) + 1;   // loads of a step
+            constexpr int NDS = 2 * PB + (STG ? PB * 2 : 0);                     // LDS reads of a step
+            constexpr int DS_PER = (NDS + NMF - 1) / NMF;
             constexpr int NVA = PB * 11 + CB * 4 + 4;                       // vector ALU instructions of a step (estimate)
             constexpr int VM_PER = (NVM + NMF - 1) / NMF, VA_PER = (NVA + NMF - 1) / NMF;
 #pragma unroll
             for (int m = 0; m < NMF; ++m) {
                 __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);          // one matrix instruction
+                if (STG && m == 0) __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);   // the staged word
                 __builtin_amdgcn_sched_group_barrier(0x020, VM_PER, 0);     // loads first: they have the longest way to go
                 __builtin_amdgcn_sched_group_barrier(0x002, VA_PER, 0);
-                __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);          // table rows as soon as their windows exist
+                __builtin_amdgcn_sched_group_barrier(0x100, STG ? DS_PER : 2, 0);   // rows and table rows as soon as their addresses exist
             }
             __builtin_amdgcn_sched_barrier(0);
         };
@@ -468,6 +556,20 @@ void subbit_mfma_kernel(const MfParams p)
     }
 
     MF_TRACE(3);
+    // The {correction, alpha} pairs of the wave's output channels are requested now (the operand
+    // registers of the loop are free) and travel during the reduction.
+    // The KS waves of a tile share one copy: each fetches a KS-th of it.
+    constexpr int FIN_BYTES = 32 * CB * 16 * 8;
+    constexpr int FIN_PIECES = FIN_BYTES / 1024;   // of 64 lanes x 16 bytes; 8 or 16, a multiple of KS
+    u32x4 finv[FIN_PIECES];
+    const int fin_first = split * (FIN_PIECES / KS);
+    {
+        const u32x4 *src = (const u32x4 *)(p.fin + (size_t)co0 * 16) + fin_first * 64 + lane;
+#pragma unroll
+        for (int i = 0; i < FIN_PIECES; ++i)
+            if (i < FIN_PIECES / KS) finv[i] = src[i * 64];
+    }
+    __builtin_amdgcn_sched_barrier(0);
     // ---- partial sums of the KS waves of a tile ---------------------------------------------------------
     // Block q of the tile is finished by the wave with split == q % KS; the other waves pass their
     // partial sums for it through LDS.
@@ -524,18 +626,11 @@ void subbit_mfma_kernel(const MfParams p)
     // 8 * (r / 4) + 4 * h + r % 4, pixel n_l.
     __syncthreads();                               // table / partial sums no longer read
     MF_TRACE(5);
-    constexpr int FIN_BYTES = 32 * CB * 16 * 8;
-    const uint32_t fin_wave = (uint32_t)(uintptr_t)smem + (uint32_t)wave * FIN_BYTES;
-    {
-        const uint4 *src = (const uint4 *)(p.fin + (size_t)co0 * 16);
+    const uint32_t fin_wave = (uint32_t)(uintptr_t)smem + (uint32_t)tile_in_wg * FIN_BYTES;
 #pragma unroll
-        for (int i = 0; i < FIN_BYTES / 1024; ++i) {
-            const uint4 v = src[i * 64 + lane];
-            u32x4 t;
-            t.x = v.x; t.y = v.y; t.z = v.z; t.w = v.w;
-            *(lds_u32x4 *)(uintptr_t)(fin_wave + (uint32_t)(i * 64 + lane) * 16u) = t;
-        }
-    }
+    for (int i = 0; i < FIN_PIECES; ++i)
+        if (i < FIN_PIECES / KS) *(lds_u32x4 *)(uintptr_t)(fin_wave + (uint32_t)((fin_first + i) * 64 + lane) * 16u) = finv[i];
+    if (KS > 1) __syncthreads();                   // the other waves' parts
     if (!active) return;
     MF_TRACE(6);
     const __amdgpu_buffer_rsrc_t yres = make_rsrc(p.y, (uint32_t)((size_t)g.N * g.C_out * g.HoWo * 4u));
@@ -567,6 +662,7 @@ struct MfCfg {
 struct MfPlan {
     MfCfg cfg;
     bool pair;        // K <= 32: two input channels per step
+    bool stage;       // the rows of a tile fit the staging slots
     int KS, COP, n_cotiles, npairs;
     long long n_pxtiles, n_tiles, n_wgs;
     size_t lds;
@@ -605,7 +701,18 @@ MfPlan mf_plan(const Geom &g)
     if (ks_env == 1 || ks_env == 2 || ks_env == 4) KS = ks_env;
     pl.KS = KS;
     pl.n_wgs = (pl.n_tiles * KS + MF_WAVES - 1) / MF_WAVES;
-    const size_t lut_bytes = (size_t)512 * mf_lrow(pl.pair);
+    // Rows a tile of pxw consecutive pixels can touch, numbered over the whole batch: a change of
+    // output row moves the first row loaded by at most `stride`, a change of image by one more
+    // (the top row of an image is not preceded by a padding row), and the last pixel loads three.
+    const int64_t row_changes = (g.Wo - 1 + pxw - 1) / g.Wo, image_changes = ((int64_t)g.HoWo - 1 + pxw - 1) / g.HoWo;
+    const int64_t tile_rows = g.stride * row_changes + image_changes + 3;
+    // Staging pays where the memory pipeline is the bound: two channel blocks per wave, i.e. only two
+    // matrix instructions per window (measured; with four blocks the loop is bound by the matrix pipe
+    // and the extra LDS traffic costs a little).  SNN_MFMA_STAGE = 1 / 0 forces it on wherever it fits / off.
+    const int stage_env = env_int("SNN_MFMA_STAGE", -1);
+    pl.stage = g.WW <= 2 && tile_rows * (g.WW == 2 ? 3 : 1) <= MF_STAGE_SLOTS &&
+               (stage_env < 0 ? pl.cfg.CB == 2 : stage_env != 0);
+    const size_t lut_bytes = (size_t)512 * mf_lrow(pl.pair) + (pl.stage ? (size_t)MF_WAVES * MF_STAGE_BYTES : 0);
     const int nblk = pl.cfg.PB * pl.cfg.CB;
     const size_t red_bytes = KS > 1 ? (size_t)(MF_WAVES / KS) * (nblk > 4 ? nblk / 2 : nblk) * (KS - 1) * 4096 : 0;
     const size_t fin_bytes = (size_t)MF_WAVES * 32 * pl.cfg.CB * 16 * 8;
@@ -620,15 +727,15 @@ MfPlan mf_plan(const Geom &g)
     pl.off_fin = o;
     o += align_up((size_t)pl.COP * 16 * sizeof(uint2), 256);
     pl.off_lut = o;
-    o += align_up(lut_bytes, 256);
+    o += align_up((size_t)512 * mf_lrow(pl.pair), 256);
     pl.bytes = o;
     return pl;
 }
 
-template <int PB, int CB, int WM, bool PAIR>
+template <int PB, int CB, int WM, bool PAIR, bool STG>
 int launch_mf_one(const MfPlan &pl, const MfParams &prm, hipStream_t s)
 {
-    auto kern = subbit_mfma_kernel<PB, CB, WM, PAIR>;
+    auto kern = subbit_mfma_kernel<PB, CB, WM, PAIR, STG>;
     if (pl.lds > 64 * 1024 &&
         hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)pl.lds) != hipSuccess)
         return SNN_ERR_LAUNCH;
@@ -636,17 +743,18 @@ int launch_mf_one(const MfPlan &pl, const MfParams &prm, hipStream_t s)
     return check_launch();
 }
 
+template <int PB, int CB, bool PAIR>
+int launch_mf_pair(const MfPlan &pl, const MfParams &prm, hipStream_t s)
+{
+    if (prm.g.WW == 1) return pl.stage ? launch_mf_one<PB, CB, 1, PAIR, true>(pl, prm, s) : launch_mf_one<PB, CB, 1, PAIR, false>(pl, prm, s);
+    if (prm.g.WW == 2) return pl.stage ? launch_mf_one<PB, CB, 2, PAIR, true>(pl, prm, s) : launch_mf_one<PB, CB, 2, PAIR, false>(pl, prm, s);
+    return launch_mf_one<PB, CB, 0, PAIR, false>(pl, prm, s);
+}
+
 template <int PB, int CB>
 int launch_mf(const MfPlan &pl, const MfParams &prm, hipStream_t s)
 {
-    if (pl.pair) {
-        if (prm.g.WW == 1) return launch_mf_one<PB, CB, 1, true>(pl, prm, s);
-        if (prm.g.WW == 2) return launch_mf_one<PB, CB, 2, true>(pl, prm, s);
-        return launch_mf_one<PB, CB, 0, true>(pl, prm, s);
-    }
-    if (prm.g.WW == 1) return launch_mf_one<PB, CB, 1, false>(pl, prm, s);
-    if (prm.g.WW == 2) return launch_mf_one<PB, CB, 2, false>(pl, prm, s);
-    return launch_mf_one<PB, CB, 0, false>(pl, prm, s);
+    return pl.pair ? launch_mf_pair<PB, CB, true>(pl, prm, s) : launch_mf_pair<PB, CB, false>(pl, prm, s);
 }
 
 }  // namespace

@@ -134,18 +134,24 @@ def test_subbit_bin(oracle, case):
 
 @pytest.mark.parametrize("tile", ["4,2", "2,4", "2,2", "1,4", "1,2"])
 @pytest.mark.parametrize("split", [1, 2, 4])
-def test_subbit_bin_matrix_core_kernel_every_tile_and_split(oracle, tile, split, monkeypatch):
+@pytest.mark.parametrize("stage", [1, 0])
+def test_subbit_bin_matrix_core_kernel_every_tile_and_split(oracle, tile, split, stage, monkeypatch):
     """Every instantiated wave tile of the matrix-core kernel and every split of the input
     channels over waves, forced on layers with ragged edges: odd and even C_in, C_out not a
-    multiple of 32, rows of one, two and three packed words, both strides, a pixel tail, and
-    both forms of a step (two channels of K <= 32 members, one channel of K <= 64)."""
+    multiple of 32, rows of one, two and three packed words, both strides, a pixel tail, tiles
+    that run over several small images, and both forms of a step (two channels of K <= 32
+    members, one channel of K <= 64).  stage = 1 lets the kernel stage a tile's rows through LDS
+    wherever they fit (rows of one or two words), stage = 0 makes every lane load its own rows."""
     monkeypatch.setenv("SNN_MFMA_TILE", tile)
     monkeypatch.setenv("SNN_MFMA_KS", str(split))
+    monkeypatch.setenv("SNN_MFMA_STAGE", str(stage))
     for seed, (N, C_in, C_out, H, W, stride, K) in enumerate([(3, 45, 150, 13, 11, 1, 32), (2, 20, 70, 16, 12, 2, 32),
                                                              (2, 34, 40, 9, 40, 1, 20), (1, 8, 33, 5, 70, 1, 32),
                                                              (2, 130, 96, 8, 8, 2, 7), (1, 2, 3, 1, 1, 1, 2),
                                                              (2, 24, 40, 9, 11, 1, 64), (2, 33, 70, 14, 14, 2, 40),
-                                                             (1, 1, 36, 6, 40, 1, 33), (1, 7, 8, 5, 70, 1, 64)]):
+                                                             (1, 1, 36, 6, 40, 1, 33), (1, 7, 8, 5, 70, 1, 64),
+                                                             (9, 6, 40, 5, 5, 1, 32), (2, 6, 40, 12, 56, 1, 32),
+                                                             (1, 4, 33, 6, 64, 1, 32), (7, 5, 8, 3, 7, 2, 48)]):
         _say("subbit_bin matrix-core", tile, split, (N, C_in, C_out, H, W, stride, K))
         x, cb, idx, alpha = _inputs(900 + seed, N, C_in, C_out, H, W, K)
         _, Y = oracle.conv_bin(oracle.sign(x), oracle.expand(cb, idx), alpha, stride)
