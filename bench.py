@@ -5,10 +5,12 @@
 
 One "step" is one pass of the whole path over one batch of synthetic input, i.e. the forward
 lines of Alg. 1 for every 3x3 layer of the workload: project the real-valued kernels onto the
-layer's subset (snn_project_kernels), binarise and pack the activations (snn_pack_activations),
-run the sub-bit convolution (snn_subbit_conv2d: stage 1, stage 2, alpha scaling).  Inputs are
-resident in HBM before the timed region.  The same layers are then run through the library's
-1-bit XNOR/popcount kernel (snn_bnn_conv2d on the decoded kernels) for the speed-up.
+layer's subset, binarise and pack the activations, run the sub-bit convolution (stage 1,
+stage 2, alpha scaling) -- one snn_subbit_forward call per layer.  The same work through the
+three separate entry points (snn_project_kernels, snn_pack_activations, snn_subbit_conv2d) is
+timed next to it.  Inputs are resident in HBM before the timed region.  The same layers are
+then run through the library's 1-bit XNOR/popcount kernel (snn_bnn_conv2d on the decoded
+kernels) for the speed-up.
 
 Prints ONE JSON line (metric of the benchmark spec: GOPS-equivalent of the dense convolution the
 layers equal, plus the speed-up over the 1-bit kernel), with a `roofline` object for the
@@ -148,6 +150,7 @@ def main():
         s["yb"] = torch.empty_like(s["y"])
         s["ws_sub"] = B.alloc_workspace(s["d_sub"], B.SNN_WS_SUBBIT)
         s["ws_bnn"] = B.alloc_workspace(s["d_bnn"], B.SNN_WS_BNN)
+        s["ws_fwd"] = B.alloc_workspace(s["d_sub"], B.SNN_WS_FORWARD)
         st.append(s)
     torch.cuda.synchronize()
 
@@ -168,11 +171,22 @@ def main():
     def conv_bnn(s):
         B.snn_bnn_conv2d(s["d_bnn"], s["xc"], s["w9"], s["alpha"], y=s["yb"], workspace=s["ws_bnn"])
 
-    # One step = every layer's project + pack + conv, back to back on one stream.  (Putting the
-    # small project / pack kernels on side streams, eagerly or as a captured HIP graph, was
+    def forward(s):
+        L = s["L"]
+        B.snn_subbit_forward(s["d_sub"], s["x"], s["w"], s["cb"], s["alpha"], idx_out=s["idx"].view(L.C_out, L.C_in),
+                             y=s["y"], workspace=s["ws_fwd"])
+
+    # One step = every layer's projection + sign/pack + convolution, back to back on one stream:
+    # one snn_subbit_forward call per layer, which runs the small operations in one launch and the
+    # convolution in a second.  step_separate is the same work as three calls (four launches) per
+    # layer.  (Putting the small kernels on side streams, eagerly or as a captured HIP graph, was
     # measured and is slower here: the eager form is bound by the host's launch rate, the graph
     # replay runs the kernels no closer together than the single stream does.)
     def step():
+        for s in st:
+            forward(s)
+
+    def step_separate():
         for s in st:
             project(s)
             pack_rows(s)
@@ -202,6 +216,16 @@ def main():
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
+
+    for _ in range(args.warmup):
+        step_separate()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step_separate()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step_separate = (t1 - t0) * 1e3 / args.steps
 
     for _ in range(args.warmup):
         step_bnn()
@@ -299,6 +323,7 @@ def main():
     print("sum: subbit %.1f us, bnn %.1f us, project %.1f us, pack rows %.1f us, pack channels %.1f us; "
           "step %.1f us, bnn step %.1f us" % (sum(t_sub) * 1e3, sum(t_bnn) * 1e3, sum(t_proj) * 1e3, sum(t_pr) * 1e3,
                                                 sum(t_pc) * 1e3, ms_per_step * 1e3, ms_per_step_bnn * 1e3), file=sys.stderr)
+    print("step as three separate calls per layer: %.1f us" % (ms_per_step_separate * 1e3), file=sys.stderr)
 
     # ---- cpu_baseline: the oracle on a bounded sample of the same workload --------------------------------
     cpu = None
@@ -339,7 +364,10 @@ def main():
         "vs_baseline": None,
         "dtype": "u8",
         "data": "synthetic",
-        "config": {"workload": wname, "step": "per layer: snn_project_kernels + snn_pack_activations + snn_subbit_conv2d"},
+        "config": {"workload": wname,
+                   "step": "per layer: one snn_subbit_forward call (projection + sign/pack + table preparation in one launch, "
+                           "sub-bit convolution in a second)"},
+        "ms_per_step_separate_calls": ms_per_step_separate,
         "conv_only_gops_eq": dense_ops / sub_s / 1e9,
         "bnn_conv_only_gops_eq": dense_ops / (sum(t_bnn) * 1e-3) / 1e9,
         "speedup_vs_bnn_conv": sum(t_bnn) / sum(t_sub),

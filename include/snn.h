@@ -62,6 +62,7 @@ extern "C" {
 /* which entry point a workspace is for */
 #define SNN_WS_SUBBIT 0
 #define SNN_WS_BNN    1
+#define SNN_WS_FORWARD 2
 
 /* One 3x3 layer (Sec. 3 notation: c_in, c_out, H, W of the input). */
 typedef struct snn_conv_desc {
@@ -116,6 +117,29 @@ int snn_project_kernels(const float *w, int64_t n, const uint16_t *codebook, int
 int snn_subbit_conv2d(const snn_conv_desc *desc, const void *x, const uint16_t *codebook,
                       const uint16_t *idx, const float *alpha, float *y_nchw,
                       void *workspace, size_t ws_bytes, void *stream);
+
+/*
+ * Alg. 1 forward of one layer in one call: the projection of the layer's real-valued kernels
+ * (Eq. 2 / Eq. 5), sign(a) of its fp32 input, and the sub-bit convolution (Sec. 4.5 / Fig. 6) of
+ * the two.  idx_out and y_nchw equal, bit for bit, what snn_project_kernels,
+ * snn_pack_activations(SNN_ACT_BIN_ROWS) and snn_subbit_conv2d produce one after the other;
+ * the small operations share one launch, so the call costs two launches instead of four.
+ *   desc      host; act must be SNN_ACT_BIN_ROWS (+-1 activations; the packed rows live in the
+ *             workspace)
+ *   x_nchw    device, float [N][C_in][H][W]
+ *   w         device, float [C_out][C_in][9] (row-major 3x3 kernels)
+ *   codebook  device, uint16 [K] 9-bit codes
+ *   alpha     device, float [C_out]
+ *   idx_out   device, uint16 [C_out][C_in], fully overwritten (the projection, which a backward
+ *             pass needs again)
+ *   y_nchw    device, float [N][C_out][H_out][W_out], fully overwritten
+ *   workspace device, >= snn_workspace_bytes(desc, SNN_WS_FORWARD) bytes, 256-byte aligned
+ * Errors: INVALID_ARG; UNSUPPORTED for any other desc->act and for packed inputs of 2^31 words
+ * or more; WORKSPACE; LAUNCH.
+ */
+int snn_subbit_forward(const snn_conv_desc *desc, const float *x_nchw, const float *w,
+                       const uint16_t *codebook, const float *alpha, uint16_t *idx_out,
+                       float *y_nchw, void *workspace, size_t ws_bytes, void *stream);
 
 /*
  * Sec. 3: the 1-bit layer a = lambda * (w_bar o a_bar), "o" = XNOR + bit count over words of

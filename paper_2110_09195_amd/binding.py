@@ -25,8 +25,9 @@ SNN_ACT_F32 = 2
 
 SNN_WS_SUBBIT = 0
 SNN_WS_BNN = 1
+SNN_WS_FORWARD = 2
 
-EXPORTS = ("snn_pack_activations", "snn_project_kernels", "snn_subbit_conv2d", "snn_bnn_conv2d",
+EXPORTS = ("snn_pack_activations", "snn_project_kernels", "snn_subbit_conv2d", "snn_subbit_forward", "snn_bnn_conv2d",
            "snn_workspace_bytes", "snn_packed_bytes", "snn_status_string")
 
 
@@ -61,6 +62,8 @@ def lib():
         L.snn_project_kernels.restype = i32
         L.snn_subbit_conv2d.argtypes = [dp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.snn_subbit_conv2d.restype = i32
+        L.snn_subbit_forward.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.snn_subbit_forward.restype = i32
         L.snn_bnn_conv2d.argtypes = [dp, vp, vp, vp, vp, vp, sz, vp]
         L.snn_bnn_conv2d.restype = i32
         L.snn_workspace_bytes.argtypes = [dp, i32]
@@ -166,6 +169,28 @@ def snn_subbit_conv2d(desc, x, codebook, idx, alpha, y=None, workspace=None):
     _check(lib().snn_subbit_conv2d(ctypes.byref(desc), _ptr(x), _ptr(codebook), _ptr(idx), _ptr(alpha), _ptr(y),
                                    _ptr(workspace), workspace.numel(), _stream()), "snn_subbit_conv2d")
     return y
+
+
+def snn_subbit_forward(desc, x, w, codebook, alpha, idx_out=None, y=None, workspace=None):
+    """One layer's forward pass: x float32 NCHW, w float32 [C_out][C_in][9] (or [C_out*C_in][9]),
+    codebook int16 [K], alpha float32 [C_out] -> (y float32 [N][C_out][Ho][Wo], idx int16 [C_out][C_in])."""
+    _dev(x, torch.float32, "x")
+    _dev(w, torch.float32, "w")
+    _dev(codebook, torch.int16, "codebook")
+    _dev(alpha, torch.float32, "alpha")
+    if w.numel() != desc.C_out * desc.C_in * 9:
+        raise ValueError("w has the wrong size")
+    if idx_out is None:
+        idx_out = torch.empty((desc.C_out, desc.C_in), dtype=torch.int16, device=x.device)
+    _dev(idx_out, torch.int16, "idx_out")
+    if idx_out.numel() != desc.C_out * desc.C_in:
+        raise ValueError("idx_out has the wrong size")
+    y = _conv_out(desc, y, x.device)
+    if workspace is None:
+        workspace = alloc_workspace(desc, SNN_WS_FORWARD, x.device)
+    _check(lib().snn_subbit_forward(ctypes.byref(desc), _ptr(x), _ptr(w), _ptr(codebook), _ptr(alpha), _ptr(idx_out),
+                                    _ptr(y), _ptr(workspace), workspace.numel(), _stream()), "snn_subbit_forward")
+    return y, idx_out
 
 
 def snn_bnn_conv2d(desc, x, w9, alpha, y=None, workspace=None):

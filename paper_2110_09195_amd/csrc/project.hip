@@ -3,7 +3,7 @@
 // with the inner product accumulated in fp32 from 0 over taps 0..8 in order, adding or
 // subtracting w_t.  fma(w_t, +-1, acc) rounds exactly like acc +- w_t, so the chain below is
 // that sum.  HBM-bound for the subset sizes of the paper (K <= 64): 36 B in, 2 B out per kernel.
-#include "snn_internal.h"
+#include "front_ops.h"
 
 namespace snn {
 
@@ -22,10 +22,7 @@ void project_kernel(const float *__restrict__ w, int64_t n, const uint16_t *__re
     float *wl = lds + K * 12;                // [PROJ_BLOCK][9] staged kernels
     const int tid = threadIdx.x;
 
-    for (int i = tid; i < K * 12; i += PROJ_THREADS) {
-        const int k = i / 12, t = i - 12 * k;
-        coef[i] = (t < 9 && ((codebook[k] >> (8 - t)) & 1)) ? 1.0f : -1.0f;
-    }
+    project_fill_coef(coef, codebook, K, tid, PROJ_THREADS);
 
     const int64_t c0 = (int64_t)blockIdx.x * PROJ_BLOCK;
     const int cnt = (int)min((int64_t)PROJ_BLOCK, n - c0);
@@ -49,34 +46,7 @@ void project_kernel(const float *__restrict__ w, int64_t n, const uint16_t *__re
             wt[q][t] = (q * PROJ_THREADS + tid < cnt) ? wl[(q * PROJ_THREADS + tid) * 9 + t] : 0.0f;
 
     int best[PROJ_PER];
-    float best_score[PROJ_PER];
-#pragma unroll
-    for (int q = 0; q < PROJ_PER; ++q) {
-        best[q] = 0;
-        best_score[q] = 0.0f;
-    }
-    for (int k = 0; k < K; ++k) {
-        const float4 ca = *(const float4 *)(coef + k * 12);          // wave-uniform address: broadcast
-        const float4 cb = *(const float4 *)(coef + k * 12 + 4);
-        const float c8 = coef[k * 12 + 8];
-#pragma unroll
-        for (int q = 0; q < PROJ_PER; ++q) {
-            float acc = 0.0f;
-            acc = __builtin_fmaf(wt[q][0], ca.x, acc);
-            acc = __builtin_fmaf(wt[q][1], ca.y, acc);
-            acc = __builtin_fmaf(wt[q][2], ca.z, acc);
-            acc = __builtin_fmaf(wt[q][3], ca.w, acc);
-            acc = __builtin_fmaf(wt[q][4], cb.x, acc);
-            acc = __builtin_fmaf(wt[q][5], cb.y, acc);
-            acc = __builtin_fmaf(wt[q][6], cb.z, acc);
-            acc = __builtin_fmaf(wt[q][7], cb.w, acc);
-            acc = __builtin_fmaf(wt[q][8], c8, acc);
-            if (k == 0 || acc > best_score[q]) {
-                best[q] = k;
-                best_score[q] = acc;
-            }
-        }
-    }
+    project_argmax<PROJ_PER>(wt, coef, K, best);
 #pragma unroll
     for (int q = 0; q < PROJ_PER; ++q)
         if (q * PROJ_THREADS + tid < cnt) idx_out[c0 + q * PROJ_THREADS + tid] = (uint16_t)best[q];

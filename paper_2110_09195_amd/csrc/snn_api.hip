@@ -61,6 +61,10 @@ size_t snn_workspace_bytes(const snn_conv_desc *desc, int which)
         if (!desc_ok(desc, true) || !subbit_act_supported(desc->act)) return 0;
         return subbit_workspace_bytes(make_geom(*desc), desc->act);
     }
+    if (which == SNN_WS_FORWARD) {
+        if (!desc_ok(desc, true) || desc->act != SNN_ACT_BIN_ROWS) return 0;
+        return subbit_forward_workspace_bytes(make_geom(*desc));
+    }
     if (which == SNN_WS_BNN) {
         if (!desc_ok(desc, false) || !bnn_supported(desc)) return 0;
         return bnn_workspace_bytes(make_geom(*desc), desc->act);
@@ -102,6 +106,18 @@ int snn_subbit_conv2d(const snn_conv_desc *desc, const void *x, const uint16_t *
     const size_t need = subbit_workspace_bytes(g, desc->act);
     if (need > 0 && (!workspace || ws_bytes < need || ((uintptr_t)workspace & 255u))) return SNN_ERR_WORKSPACE;
     return launch_subbit(g, desc->act, x, codebook, idx, alpha, y_nchw, workspace, (hipStream_t)stream);
+}
+
+int snn_subbit_forward(const snn_conv_desc *desc, const float *x_nchw, const float *w, const uint16_t *codebook,
+                       const float *alpha, uint16_t *idx_out, float *y_nchw, void *workspace, size_t ws_bytes,
+                       void *stream)
+{
+    if (!desc_ok(desc, true) || !x_nchw || !w || !codebook || !alpha || !idx_out || !y_nchw) return SNN_ERR_INVALID_ARG;
+    if (desc->act != SNN_ACT_BIN_ROWS) return SNN_ERR_UNSUPPORTED;
+    const Geom g = make_geom(*desc);
+    const size_t need = subbit_forward_workspace_bytes(g);
+    if (!workspace || ws_bytes < need || ((uintptr_t)workspace & 255u)) return SNN_ERR_WORKSPACE;
+    return launch_subbit_forward(g, x_nchw, w, codebook, alpha, idx_out, y_nchw, workspace, (hipStream_t)stream);
 }
 
 int snn_bnn_conv2d(const snn_conv_desc *desc, const void *x, const uint16_t *w9, const float *alpha,

@@ -90,6 +90,14 @@ size_t subbit_mfma_workspace_bytes(const Geom &g);
 int launch_subbit_mfma(const Geom &g, const void *x, const uint16_t *codebook, const uint16_t *idx,
                        const float *alpha, float *y, void *ws, hipStream_t s);
 
+int launch_subbit_forward_mfma(const Geom &g, const float *x, const float *w, const uint16_t *codebook,
+                               const float *alpha, uint16_t *idx_out, float *y, uint32_t *xr, void *ws, hipStream_t s);
+
+// Alg. 1 forward of one layer from fp32 activations and real-valued kernels (binary activations)
+size_t subbit_forward_workspace_bytes(const Geom &g);
+int launch_subbit_forward(const Geom &g, const float *x, const float *w, const uint16_t *codebook,
+                          const float *alpha, uint16_t *idx_out, float *y, void *ws, hipStream_t s);
+
 inline int check_launch()
 {
     return hipGetLastError() == hipSuccess ? SNN_OK : SNN_ERR_LAUNCH;

@@ -328,4 +328,25 @@ int launch_subbit(const Geom &g, int act, const void *x, const uint16_t *codeboo
     return launch_direct<4, 4>(pl, prm, grid, s);
 }
 
+// ---- one layer's forward pass in one call -----------------------------------------------------------
+// Workspace: [the convolution's own workspace][packed rows of sign(x)].
+size_t subbit_forward_workspace_bytes(const Geom &g)
+{
+    return align_up(subbit_workspace_bytes(g, SNN_ACT_BIN_ROWS), 256) +
+           align_up((size_t)g.N * g.C_in * g.H * g.WW * sizeof(uint32_t), 256);
+}
+
+int launch_subbit_forward(const Geom &g, const float *x, const float *w, const uint16_t *codebook,
+                          const float *alpha, uint16_t *idx_out, float *y, void *ws, hipStream_t s)
+{
+    uint32_t *xr = (uint32_t *)((char *)ws + align_up(subbit_workspace_bytes(g, SNN_ACT_BIN_ROWS), 256));
+    if (use_mfma(g)) return launch_subbit_forward_mfma(g, x, w, codebook, alpha, idx_out, y, xr, ws, s);
+    // layers the matrix-core kernel does not take: the three operations one after the other
+    int rc = launch_pack_rows(x, xr, (int64_t)g.N * g.C_in * g.H, g.W, s);
+    if (rc != SNN_OK) return rc;
+    rc = launch_project(w, (int64_t)g.C_out * g.C_in, codebook, g.K, idx_out, s);
+    if (rc != SNN_OK) return rc;
+    return launch_subbit(g, SNN_ACT_BIN_ROWS, xr, codebook, idx_out, alpha, y, ws, s);
+}
+
 }  // namespace snn

@@ -21,7 +21,7 @@
 // A wave owns PB blocks of 32 pixels x CB blocks of 32 output channels and a range of input
 // channel pairs; the KS waves that split the channels of one tile sit in one workgroup and add
 // their partial sums through LDS.
-#include "snn_internal.h"
+#include "front_ops.h"
 
 #include <type_traits>
 
@@ -94,6 +94,57 @@ __host__ __device__ inline uint32_t fp6_of_int(int v)
 //   fin[co][type] = {2 corr + C_in * (valid_taps(type) - 8), alpha[co]} with corr = sum over c_in of the
 //     zero bits of the selected code at the taps that border type `type` puts outside the image
 //   lut[window] = 32 FP6 codes of m_k - 4 (0 for k >= K)
+// one thread per 32-bit word of the table; a row is 6 words of 32 FP6 codes per lane half
+__device__ inline void prep_lut_block(const uint16_t *__restrict__ codebook, int K, int pair, int block, uint32_t *__restrict__ lut)
+{
+    const int wpr = pair ? 6 : 12;
+    const int i = block * 256 + (int)threadIdx.x;
+    if (i < 512 * wpr) {
+        const int win = i / wpr, wh = i - win * wpr;
+        const int half = wh / 6, w = wh - 6 * half;
+        uint32_t word = 0;
+        for (int kl = (32 * w) / 6; kl <= (32 * w + 31) / 6; ++kl) {
+            const int k = 32 * half + kl;
+            if (k >= K) break;
+            const int m = 9 - __popc((uint32_t)win ^ code_to_window_order(codebook[k] & 511u));
+            const int at = 6 * kl - 32 * w;                // position of the code's bit 0 in this word
+            const uint32_t code = fp6_of_int(m - 4);
+            word |= at >= 0 ? code << at : code >> -at;
+        }
+        lut[i] = word;
+    }
+}
+
+// selector word of subset member k (see below)
+__device__ inline uint32_t sel_word(uint32_t k)
+{
+    const uint32_t code = 2u * ((k >> 3) & 3u) + (k & 1u);       // k % 32 inside its lane half
+    const int sh = 8 * ((k >> 1) & 3u);
+    return (MF_SEL_NONE & ~(0xffu << sh)) | (code << sh);
+}
+
+// Stores the selector of (output channel co at position pos of a selector row, input channel ci)
+// where the convolution's step / lane half expects it; k < 0: no member (padding channel).
+__device__ inline void store_sel(uint32_t *__restrict__ sel, int COP, int C_in, int pair, int pos, int ci, int k)
+{
+    const uint32_t s = k >= 0 ? sel_word((uint32_t)k) : MF_SEL_NONE;
+    if (!pair) {
+        // one channel per step; the member's half (k / 32) gets the selector, the other one nothing
+        const int hk = k >= 32 ? 1 : 0;
+        sel[((int64_t)ci * 2 + hk) * COP + pos] = s;
+        sel[((int64_t)ci * 2 + (hk ^ 1)) * COP + pos] = MF_SEL_NONE;
+        return;
+    }
+    // channel ci is half (ci % 2) of step ci / 2, except the last channel of an odd C_in
+    int c = ci >> 1, h = ci & 1;
+    if ((C_in & 1) && ci == C_in - 1) {
+        c = (C_in + 1) / 2 - 1;
+        h = 1;
+        sel[((int64_t)c * 2 + 0) * COP + pos] = MF_SEL_NONE;
+    }
+    sel[((int64_t)c * 2 + h) * COP + pos] = s;
+}
+
 __global__ __launch_bounds__(256)
 void subbit_mfma_prep_kernel(const uint16_t *__restrict__ codebook, const uint16_t *__restrict__ idx, int C_in,
                              int C_out, int COP, int CB, int K, int pair, int sel_blocks, int lut_blocks,
@@ -112,57 +163,20 @@ void subbit_mfma_prep_kernel(const uint16_t *__restrict__ codebook, const uint16
             tile[e / 32][e % 32] = (co < C_out && ci < C_in) ? (uint16_t)min((int)idx[(int64_t)co * C_in + ci], K - 1) : 0xffffu;
         }
         __syncthreads();
-        const int npairs = (C_in + 1) / 2;
         for (int e = tid; e < 1024; e += 256) {
             const int co_l = e % 32, ci_l = e / 32;
             const int ci = ci0 + ci_l;
             if (ci >= C_in) continue;
             const uint32_t k = tile[co_l][ci_l];
-            uint32_t s = MF_SEL_NONE;
-            if (k != 0xffffu) {
-                const uint32_t code = 2u * ((k >> 3) & 3u) + (k & 1u);       // k % 32 inside its lane half
-                const int sh = 8 * ((k >> 1) & 3u);
-                s = (s & ~(0xffu << sh)) | (code << sh);
-            }
             // position inside a row of COP selectors: [wave tile][channel in block][block]
             const int co = co0 + co_l, tilew = 32 * CB;
             const int pos = (co / tilew) * tilew + (co % 32) * CB + (co % tilew) / 32;
-            if (!pair) {
-                // one channel per step; the member's half (k / 32) gets the selector, the other one nothing
-                const int hk = (k != 0xffffu && k >= 32) ? 1 : 0;
-                sel[((int64_t)ci * 2 + hk) * COP + pos] = s;
-                sel[((int64_t)ci * 2 + (hk ^ 1)) * COP + pos] = MF_SEL_NONE;
-                continue;
-            }
-            // channel ci is half (ci % 2) of step ci / 2, except the last channel of an odd C_in
-            int c = ci >> 1, h = ci & 1;
-            if ((C_in & 1) && ci == C_in - 1) {
-                c = npairs - 1;
-                h = 1;
-                sel[((int64_t)c * 2 + 0) * COP + pos] = MF_SEL_NONE;
-            }
-            sel[((int64_t)c * 2 + h) * COP + pos] = s;
+            store_sel(sel, COP, C_in, pair, pos, ci, k == 0xffffu ? -1 : (int)k);
         }
         return;
     }
     if (b >= (int)gridDim.x - lut_blocks) {
-        // one thread per 32-bit word of the table; a row is 6 words of 32 FP6 codes per lane half
-        const int wpr = pair ? 6 : 12;
-        const int i = (b - ((int)gridDim.x - lut_blocks)) * 256 + tid;
-        if (i < 512 * wpr) {
-            const int win = i / wpr, wh = i - win * wpr;
-            const int half = wh / 6, w = wh - 6 * half;
-            uint32_t word = 0;
-            for (int kl = (32 * w) / 6; kl <= (32 * w + 31) / 6; ++kl) {
-                const int k = 32 * half + kl;
-                if (k >= K) break;
-                const int m = 9 - __popc((uint32_t)win ^ code_to_window_order(codebook[k] & 511u));
-                const int at = 6 * kl - 32 * w;                // position of the code's bit 0 in this word
-                const uint32_t code = fp6_of_int(m - 4);
-                word |= at >= 0 ? code << at : code >> -at;
-            }
-            lut[i] = word;
-        }
+        prep_lut_block(codebook, K, pair, b - ((int)gridDim.x - lut_blocks), lut);
         return;
     }
     // one wave per output channel; the zero-bit patterns of the K codes go through LDS so that the
@@ -199,6 +213,95 @@ void subbit_mfma_prep_kernel(const uint16_t *__restrict__ codebook, const uint16
             if ((inv >> t) & 1u) s += zeros[t];
         const float a = co < C_out ? alpha[co] : 0.0f;
         fin[co * 16 + lane] = make_uint2((uint32_t)(2 * s + (border_valid_taps(lane) - 8) * C_in), __float_as_uint(a));
+    }
+}
+
+// ---- fused front kernel of snn_subbit_forward -----------------------------------------------------------
+// Everything the convolution needs, in ONE launch whose blocks play three roles (block index ranges
+// in this order, the long dependent chains first):
+//   [0, COP)            one block per output channel: projection of its C_in real-valued kernels
+//                       (Eq. 2 / Eq. 5) -> idx_out, selector words, finishing table row
+//   [COP, +lut_blocks)  the lookup table
+//   the rest            sign + packing of the activations into packed rows (Alg. 1: sign(a))
+// The few channel blocks ride along with the bandwidth-bound packing blocks instead of costing two
+// launches of their own.
+struct FrontParams {
+    const float *x;           // activations [rows][W]
+    uint32_t *xr;             // packed rows
+    int64_t rows;
+    int W, WW, rows_per_block, vec;
+    const float *w;           // [C_out][C_in][9]
+    const uint16_t *codebook;
+    const float *alpha;
+    uint16_t *idx_out;        // [C_out][C_in]
+    uint32_t *sel;
+    uint2 *fin;
+    uint32_t *lut;
+    int C_in, C_out, COP, CB, K, pair, lut_blocks;
+};
+
+__global__ __launch_bounds__(256)
+void subbit_front_kernel(const FrontParams p)
+{
+    static_assert(PACK_THREADS == 256, "one block size for all roles");
+    // pack role: PACK_LDS_WORDS words; channel role: coef[K][12] floats, zero-bit patterns, per-wave counts
+    __shared__ __align__(16) uint32_t lds[64 * 12 + 64 + 4 * 9];
+    const int tid = threadIdx.x;
+    const int b = blockIdx.x;
+    if (b >= p.COP + p.lut_blocks) {
+        static_assert(PACK_LDS_WORDS <= 64 * 12, "the packing role's bit stream fits");
+        pack_rows_block(p.x, p.xr, p.rows, p.W, p.WW, p.rows_per_block, p.vec, (int64_t)(b - p.COP - p.lut_blocks), lds);
+        return;
+    }
+    if (b >= p.COP) {
+        prep_lut_block(p.codebook, p.K, p.pair, b - p.COP, p.lut);
+        return;
+    }
+    // ---- one output channel ----
+    float *coef = (float *)lds;
+    uint32_t *zbits = lds + 64 * 12;
+    uint32_t *wsum = zbits + 64;
+    const int K = p.K, C_in = p.C_in;
+    project_fill_coef(coef, p.codebook, K, tid, 256);
+    for (int k = tid; k < K; k += 256) zbits[k] = ~code_to_window_order(p.codebook[k] & 511u) & 511u;
+    __syncthreads();
+    const int co = b, lane = tid & 63, wave = tid >> 6;
+    const bool real = co < p.C_out;               // channels past C_out pad the last wave tile: no member, no output
+    const int tilew = 32 * p.CB;
+    const int pos = (co / tilew) * tilew + (co % 32) * p.CB + (co % tilew) / 32;
+    int zeros[9];
+#pragma unroll
+    for (int t = 0; t < 9; ++t) zeros[t] = 0;
+    for (int c0 = 0; c0 < C_in; c0 += 256) {
+        const int ci = c0 + tid;
+        const bool have = real && ci < C_in;
+        float wt[1][9];
+        const float *src = p.w + ((int64_t)co * C_in + ci) * 9;
+#pragma unroll
+        for (int t = 0; t < 9; ++t) wt[0][t] = have ? src[t] : 0.0f;
+        int best[1];
+        project_argmax<1>(wt, coef, K, best);
+        if (ci < C_in) {
+            if (real) p.idx_out[(int64_t)co * C_in + ci] = (uint16_t)best[0];
+            store_sel(p.sel, p.COP, C_in, p.pair, pos, ci, real ? best[0] : -1);
+        }
+        const uint32_t z = have ? zbits[best[0]] : 0u;
+#pragma unroll
+        for (int t = 0; t < 9; ++t) zeros[t] += __popcll(__ballot((z >> t) & 1u));
+    }
+    if (lane == 0) {
+#pragma unroll
+        for (int t = 0; t < 9; ++t) wsum[wave * 9 + t] = (uint32_t)zeros[t];
+    }
+    __syncthreads();
+    if (tid < 16) {
+        const uint32_t inv = border_invalid_window(tid);
+        int sum = 0;
+#pragma unroll
+        for (int t = 0; t < 9; ++t)
+            if ((inv >> t) & 1u) sum += (int)(wsum[t] + wsum[9 + t] + wsum[18 + t] + wsum[27 + t]);
+        const float a = real ? p.alpha[co] : 0.0f;
+        p.fin[co * 16 + tid] = make_uint2((uint32_t)(2 * sum + (border_valid_taps(tid) - 8) * C_in), __float_as_uint(a));
     }
 }
 
@@ -772,12 +875,10 @@ bool subbit_mfma_supported(const Geom &g)
 
 size_t subbit_mfma_workspace_bytes(const Geom &g) { return mf_plan(g).bytes; }
 
-int launch_subbit_mfma(const Geom &g, const void *x, const uint16_t *codebook, const uint16_t *idx,
-                       const float *alpha, float *y, void *ws, hipStream_t s)
-{
-    const MfPlan pl = mf_plan(g);
-    if (pl.n_wgs > 0x7fffffffLL || pl.lds > 160 * 1024) return SNN_ERR_UNSUPPORTED;
+namespace {
 
+MfParams mf_params(const MfPlan &pl, const Geom &g, const void *x, float *y, void *ws)
+{
     MfParams prm;
     prm.x = (const uint32_t *)x;
     prm.sel = (const uint32_t *)((char *)ws + pl.off_sel);
@@ -794,14 +895,11 @@ int launch_subbit_mfma(const Geom &g, const void *x, const uint16_t *codebook, c
 #ifdef SNN_MF_TRACE
     prm.trace = (unsigned long long *)ws;
 #endif
+    return prm;
+}
 
-    const int sel_blocks = (pl.COP / 32) * ((g.C_in + 31) / 32);
-    const int corr_blocks = (pl.COP + 3) / 4;
-    const int lut_blocks = (512 * (pl.pair ? 6 : 12) + 255) / 256;
-    hipLaunchKernelGGL(subbit_mfma_prep_kernel, dim3((unsigned)(sel_blocks + corr_blocks + lut_blocks)), dim3(256), 0, s,
-                       codebook, idx, g.C_in, g.C_out, pl.COP, pl.cfg.CB, g.K, pl.pair ? 1 : 0, sel_blocks, lut_blocks, alpha,
-                       (uint32_t *)prm.sel, (uint2 *)prm.fin, (uint32_t *)prm.lut);
-
+int launch_mf_conv(const MfPlan &pl, const MfParams &prm, hipStream_t s)
+{
     const MfCfg &c = pl.cfg;
     if (c.PB == 4 && c.CB == 2) return launch_mf<4, 2>(pl, prm, s);
     if (c.PB == 2 && c.CB == 4) return launch_mf<2, 4>(pl, prm, s);
@@ -809,6 +907,62 @@ int launch_subbit_mfma(const Geom &g, const void *x, const uint16_t *codebook, c
     if (c.PB == 1 && c.CB == 4) return launch_mf<1, 4>(pl, prm, s);
     if (c.PB == 1 && c.CB == 2) return launch_mf<1, 2>(pl, prm, s);
     return SNN_ERR_UNSUPPORTED;
+}
+
+}  // namespace
+
+int launch_subbit_mfma(const Geom &g, const void *x, const uint16_t *codebook, const uint16_t *idx,
+                       const float *alpha, float *y, void *ws, hipStream_t s)
+{
+    const MfPlan pl = mf_plan(g);
+    if (pl.n_wgs > 0x7fffffffLL || pl.lds > 160 * 1024) return SNN_ERR_UNSUPPORTED;
+    const MfParams prm = mf_params(pl, g, x, y, ws);
+
+    const int sel_blocks = (pl.COP / 32) * ((g.C_in + 31) / 32);
+    const int corr_blocks = (pl.COP + 3) / 4;
+    const int lut_blocks = (512 * (pl.pair ? 6 : 12) + 255) / 256;
+    hipLaunchKernelGGL(subbit_mfma_prep_kernel, dim3((unsigned)(sel_blocks + corr_blocks + lut_blocks)), dim3(256), 0, s,
+                       codebook, idx, g.C_in, g.C_out, pl.COP, pl.cfg.CB, g.K, pl.pair ? 1 : 0, sel_blocks, lut_blocks, alpha,
+                       (uint32_t *)prm.sel, (uint2 *)prm.fin, (uint32_t *)prm.lut);
+    return launch_mf_conv(pl, prm, s);
+}
+
+// Alg. 1 forward of a layer in two launches: the front kernel (projection, selector / finishing /
+// lookup tables, sign + packing into `xr`), then the convolution on `xr`.
+int launch_subbit_forward_mfma(const Geom &g, const float *x, const float *w, const uint16_t *codebook,
+                               const float *alpha, uint16_t *idx_out, float *y, uint32_t *xr, void *ws, hipStream_t s)
+{
+    const MfPlan pl = mf_plan(g);
+    if (pl.n_wgs > 0x7fffffffLL || pl.lds > 160 * 1024) return SNN_ERR_UNSUPPORTED;
+    const MfParams prm = mf_params(pl, g, xr, y, ws);
+
+    FrontParams fp;
+    fp.x = x;
+    fp.xr = xr;
+    fp.rows = (int64_t)g.N * g.C_in * g.H;
+    fp.W = g.W;
+    fp.WW = g.WW;
+    const PackRowsPlan pk = pack_rows_plan(x, fp.rows, g.W);
+    fp.rows_per_block = pk.rows_per_block;
+    fp.vec = pk.vec;
+    fp.w = w;
+    fp.codebook = codebook;
+    fp.alpha = alpha;
+    fp.idx_out = idx_out;
+    fp.sel = (uint32_t *)prm.sel;
+    fp.fin = (uint2 *)prm.fin;
+    fp.lut = (uint32_t *)prm.lut;
+    fp.C_in = g.C_in;
+    fp.C_out = g.C_out;
+    fp.COP = pl.COP;
+    fp.CB = pl.cfg.CB;
+    fp.K = g.K;
+    fp.pair = pl.pair ? 1 : 0;
+    fp.lut_blocks = (512 * (pl.pair ? 6 : 12) + 255) / 256;
+    const int64_t blocks = (int64_t)pl.COP + fp.lut_blocks + pk.blocks;
+    if (blocks > 0x7fffffffLL) return SNN_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL(subbit_front_kernel, dim3((unsigned)blocks), dim3(256), 0, s, fp);
+    return launch_mf_conv(pl, prm, s);
 }
 
 }  // namespace snn

@@ -87,3 +87,12 @@ def assert_f32_close(y, ref_y, ref_S_times_alpha=None, tol=1e-5):
     err = np.abs(y.astype(np.float64) - ref)
     bad = err > bound
     assert not bad.any(), "max err/bound = %g at %s" % ((err / bound).max(), np.argwhere(bad)[:4])
+
+
+def subbit_forward(x, w, codebook, alpha, C_out, stride=1):
+    """One call for the layer's forward pass: returns (y, idx) as numpy arrays."""
+    N, C_in, H, W = x.shape
+    d = B.make_desc(N, C_in, C_out, H, W, stride, int(codebook.size), B.SNN_ACT_BIN_ROWS)
+    y, idx = B.snn_subbit_forward(d, dev(x), dev(w.reshape(-1, 9)), dev(codebook), dev(alpha))
+    torch.cuda.synchronize()
+    return y.cpu().numpy(), host_u16(idx)

@@ -73,6 +73,7 @@ def test_invalid_arguments_are_status_codes_not_crashes(L):
     null = ctypes.c_void_p(0)
     assert L.snn_subbit_conv2d(ctypes.byref(d), null, null, null, null, null, null, 0, null) == binding.SNN_ERR_INVALID_ARG
     assert L.snn_bnn_conv2d(ctypes.byref(d), null, null, null, null, null, 0, null) == binding.SNN_ERR_INVALID_ARG
+    assert L.snn_subbit_forward(ctypes.byref(d), null, null, null, null, null, null, null, 0, null) == binding.SNN_ERR_INVALID_ARG
     assert L.snn_pack_activations(null, null, 1, 1, 1, 1, 0, null) == binding.SNN_ERR_INVALID_ARG
     assert L.snn_project_kernels(null, 4, null, 32, null, null) == binding.SNN_ERR_INVALID_ARG
     assert L.snn_subbit_conv2d(None, null, null, null, null, null, null, 0, null) == binding.SNN_ERR_INVALID_ARG
@@ -90,3 +91,13 @@ def test_invalid_arguments_are_status_codes_not_crashes(L):
     assert L.snn_subbit_conv2d(ctypes.byref(d), one, one, one, one, one, odd, 1 << 30, null) == binding.SNN_ERR_WORKSPACE
     d.act = binding.SNN_ACT_BIN_CHANNELS
     assert L.snn_bnn_conv2d(ctypes.byref(d), one, one, one, one, odd, 1 << 30, null) == binding.SNN_ERR_WORKSPACE
+    # the one-call forward pass: binary activations only, and its own workspace size
+    assert L.snn_subbit_forward(ctypes.byref(d), one, one, one, one, one, one, one, 1 << 30, null) == binding.SNN_ERR_UNSUPPORTED
+    d.act = binding.SNN_ACT_BIN_ROWS
+    assert L.snn_subbit_forward(ctypes.byref(d), one, one, one, one, one, one, one, 16, null) == binding.SNN_ERR_WORKSPACE
+    assert L.snn_subbit_forward(ctypes.byref(d), one, one, one, one, one, one, odd, 1 << 30, null) == binding.SNN_ERR_WORKSPACE
+    ws_conv = binding.snn_workspace_bytes(d, binding.SNN_WS_SUBBIT)
+    ws_fwd = binding.snn_workspace_bytes(d, binding.SNN_WS_FORWARD)
+    assert ws_fwd >= ws_conv + binding.snn_packed_bytes(d.N, d.C_in, d.H, d.W, binding.SNN_ACT_BIN_ROWS)
+    d.act = binding.SNN_ACT_F32
+    assert binding.snn_workspace_bytes(d, binding.SNN_WS_FORWARD) == 0

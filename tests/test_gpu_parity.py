@@ -324,6 +324,70 @@ def test_project_empty():
     assert B.snn_project_kernels(w, cb).numel() == 0
 
 
+# ---- the layer's forward pass in one call ---------------------------------------------------------------------------
+
+FORWARD_CASES = SUBBIT_CASES + [
+    (3, 45, 150, 13, 11, 1, 32, "uniform"), (2, 33, 70, 14, 14, 2, 40, "uniform"), (9, 6, 40, 5, 5, 1, 32, "uniform"),
+    (2, 6, 40, 12, 56, 1, 32, "uniform"), (1, 300, 9, 6, 6, 1, 32, "uniform"), (1, 515, 3, 3, 3, 1, 64, "uniform"),
+]
+
+
+def _latent_kernels(g, cb, C_out, C_in, dist):
+    """Real-valued kernels; for "zipf" they are drawn around skewed subset members so that the
+    projection is skewed too, and a part of them ties (small integers)."""
+    w = synth.real_kernels(g, C_out * C_in)
+    if dist == "zipf":
+        idx0 = synth.indices(g, C_out, C_in, int(cb.size), "zipf").reshape(-1)
+        members = np.array([[1.0 if (int(c) >> (8 - t)) & 1 else -1.0 for t in range(9)] for c in cb], dtype=np.float32)
+        w = (members[idx0] + 0.3 * w).astype(np.float32)
+    w[::5] = np.round(w[::5] * 2)
+    return w.astype(np.float32)
+
+
+@pytest.mark.parametrize("case", FORWARD_CASES)
+@pytest.mark.parametrize("mfma", ["1", "0"])
+def test_subbit_forward(oracle, case, mfma, monkeypatch):
+    """snn_subbit_forward against the oracle's three steps (project, sign, direct convolution with
+    the decoded kernels): indices and outputs bit-exact.  mfma = 0 routes every case through the
+    path that launches the three operations one after the other."""
+    _say("subbit_forward", case, mfma)
+    monkeypatch.setenv("SNN_SUBBIT_MFMA", mfma)
+    N, C_in, C_out, H, W, stride, K, dist = case
+    g = np.random.default_rng(4000 + sum(case[:7]))
+    x = g.standard_normal((N, C_in, H, W), dtype=np.float32)
+    x.flat[::13] = 0.0
+    x.flat[5::17] = -0.0
+    cb = synth.codebook(g, K)
+    alpha = synth.alpha(g, C_out)
+    w = _latent_kernels(g, cb, C_out, C_in, dist)
+    idx_ref, _ = oracle.project(w, cb)
+    idx_ref = idx_ref.reshape(C_out, C_in)
+    _, Y = oracle.conv_bin(oracle.sign(x), oracle.expand(cb, idx_ref), alpha, stride)
+    y, idx = G.subbit_forward(x, w, cb, alpha, C_out, stride)
+    assert (idx.reshape(C_out, C_in) == idx_ref).all()
+    assert y.shape == Y.shape
+    assert (y == Y).all(), np.argwhere(y != Y)[:5]
+
+
+def test_subbit_forward_equals_the_three_calls():
+    """Same device buffers through both routes: the one call and project + pack + conv."""
+    import torch
+    g = np.random.default_rng(99)
+    N, C_in, C_out, H, W, K = 4, 64, 96, 14, 14, 32
+    x = G.dev(g.standard_normal((N, C_in, H, W), dtype=np.float32))
+    w = G.dev(synth.real_kernels(g, C_out * C_in))
+    cb = G.dev(synth.codebook(g, K))
+    alpha = G.dev(synth.alpha(g, C_out))
+    d = B.make_desc(N, C_in, C_out, H, W, 1, K, B.SNN_ACT_BIN_ROWS)
+    y1, idx1 = B.snn_subbit_forward(d, x, w, cb, alpha)
+    idx2 = B.snn_project_kernels(w, cb)
+    xp = B.snn_pack_activations(x, B.SNN_ACT_BIN_ROWS)
+    y2 = B.snn_subbit_conv2d(d, xp, cb, idx2.view(C_out, C_in), alpha)
+    torch.cuda.synchronize()
+    assert torch.equal(idx1.view(-1), idx2.view(-1))
+    assert torch.equal(y1, y2)
+
+
 # ---- error paths that need device pointers -----------------------------------------------------------------------
 
 def test_workspace_too_small_is_reported():
