@@ -127,6 +127,8 @@ __device__ inline void project_argmax(const float (&wt)[Q][9], const float *coef
         best[q] = 0;
         best_score[q] = 0.0f;
     }
+    // unrolled so that the coefficient reads of several members are in flight and their chains interleave
+#pragma unroll 4
     for (int k = 0; k < K; ++k) {
         const float4 ca = *(const float4 *)(coef + k * 12);          // wave-uniform address: broadcast
         const float4 cb = *(const float4 *)(coef + k * 12 + 4);

@@ -1,8 +1,8 @@
 // Nearest-subset-member projection (Eq. 2 / Eq. 5, Alg. 1 forward):
 //   idx[c] = arg max_k <P_k, w_c>   (lowest index among equal scores)
 // with the inner product accumulated in fp32 from 0 over taps 0..8 in order, adding or
-// subtracting w_t.  fma(w_t, +-1, acc) rounds exactly like acc +- w_t, so the chain below is
-// that sum.  HBM-bound for the subset sizes of the paper (K <= 64): 36 B in, 2 B out per kernel.
+// subtracting w_t (project_argmax in front_ops.h: fma(w_t, +-1, acc) rounds exactly like
+// acc +- w_t).  HBM-bound for the subset sizes of the paper (K <= 64): 36 B in, 2 B out per kernel.
 #include "front_ops.h"
 
 namespace snn {

@@ -250,7 +250,9 @@ void subbit_front_kernel(const FrontParams p)
     const int b = blockIdx.x;
     if (b >= p.COP + p.lut_blocks) {
         static_assert(PACK_LDS_WORDS <= 64 * 12, "the packing role's bit stream fits");
+#if !(defined(FRONT_DBG) && (FRONT_DBG & 4))
         pack_rows_block(p.x, p.xr, p.rows, p.W, p.WW, p.rows_per_block, p.vec, (int64_t)(b - p.COP - p.lut_blocks), lds);
+#endif
         return;
     }
     if (b >= p.COP) {
@@ -258,36 +260,64 @@ void subbit_front_kernel(const FrontParams p)
         return;
     }
     // ---- one output channel ----
+    // A thread projects two kernels at a time (input channels tid and tid + 256 of a group of
+    // 512); the kernels of the first group are requested before anything else, those of the next
+    // group before the current one is worked on, so that the block waits for memory once.
+    const int K = p.K, C_in = p.C_in;
+    const int co = b, lane = tid & 63, wave = tid >> 6;
+    const bool real = co < p.C_out;               // channels past C_out pad the last wave tile: no member, no output
+    auto load_kernels = [&](int c0, float (&d)[2][9]) {
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+            const int ci = c0 + 256 * q + tid;
+            const bool have = real && ci < C_in;
+            const float *src = p.w + ((int64_t)co * C_in + ci) * 9;
+#pragma unroll
+            for (int t = 0; t < 9; ++t) d[q][t] = have ? src[t] : 0.0f;
+        }
+    };
+    float wt[2][9];
+    load_kernels(0, wt);
+    const float a = real ? p.alpha[co] : 0.0f;     // needed last, requested first
     float *coef = (float *)lds;
     uint32_t *zbits = lds + 64 * 12;
     uint32_t *wsum = zbits + 64;
-    const int K = p.K, C_in = p.C_in;
     project_fill_coef(coef, p.codebook, K, tid, 256);
     for (int k = tid; k < K; k += 256) zbits[k] = ~code_to_window_order(p.codebook[k] & 511u) & 511u;
     __syncthreads();
-    const int co = b, lane = tid & 63, wave = tid >> 6;
-    const bool real = co < p.C_out;               // channels past C_out pad the last wave tile: no member, no output
     const int tilew = 32 * p.CB;
     const int pos = (co / tilew) * tilew + (co % 32) * p.CB + (co % tilew) / 32;
     int zeros[9];
 #pragma unroll
     for (int t = 0; t < 9; ++t) zeros[t] = 0;
-    for (int c0 = 0; c0 < C_in; c0 += 256) {
-        const int ci = c0 + tid;
-        const bool have = real && ci < C_in;
-        float wt[1][9];
-        const float *src = p.w + ((int64_t)co * C_in + ci) * 9;
+    for (int c0 = 0; c0 < C_in; c0 += 512) {
+        float nx[2][9];
+        if (c0 + 512 < C_in) load_kernels(c0 + 512, nx);
+        int best[2];
+#if defined(FRONT_DBG) && (FRONT_DBG & 2)
+        best[0] = (int)(wt[0][0] > 0.f); best[1] = (int)(wt[1][3] > 0.f);
+#else
+        project_argmax<2>(wt, coef, K, best);
+#endif
 #pragma unroll
-        for (int t = 0; t < 9; ++t) wt[0][t] = have ? src[t] : 0.0f;
-        int best[1];
-        project_argmax<1>(wt, coef, K, best);
-        if (ci < C_in) {
-            if (real) p.idx_out[(int64_t)co * C_in + ci] = (uint16_t)best[0];
-            store_sel(p.sel, p.COP, C_in, p.pair, pos, ci, real ? best[0] : -1);
+        for (int q = 0; q < 2; ++q) {
+            const int ci = c0 + 256 * q + tid;
+            if (ci < C_in) {
+                if (real) p.idx_out[(int64_t)co * C_in + ci] = (uint16_t)best[q];
+#if !(defined(FRONT_DBG) && (FRONT_DBG & 1))
+                store_sel(p.sel, p.COP, C_in, p.pair, pos, ci, real ? best[q] : -1);
+#endif
+            }
+            const uint32_t z = (real && ci < C_in) ? zbits[best[q]] : 0u;
+#pragma unroll
+            for (int t = 0; t < 9; ++t) zeros[t] += __popcll(__ballot((z >> t) & 1u));
         }
-        const uint32_t z = have ? zbits[best[0]] : 0u;
+        if (c0 + 512 < C_in) {
 #pragma unroll
-        for (int t = 0; t < 9; ++t) zeros[t] += __popcll(__ballot((z >> t) & 1u));
+            for (int q = 0; q < 2; ++q)
+#pragma unroll
+                for (int t = 0; t < 9; ++t) wt[q][t] = nx[q][t];
+        }
     }
     if (lane == 0) {
 #pragma unroll
@@ -300,7 +330,6 @@ void subbit_front_kernel(const FrontParams p)
 #pragma unroll
         for (int t = 0; t < 9; ++t)
             if ((inv >> t) & 1u) sum += (int)(wsum[t] + wsum[9 + t] + wsum[18 + t] + wsum[27 + t]);
-        const float a = real ? p.alpha[co] : 0.0f;
         p.fin[co * 16 + tid] = make_uint2((uint32_t)(2 * sum + (border_valid_taps(tid) - 8) * C_in), __float_as_uint(a));
     }
 }
