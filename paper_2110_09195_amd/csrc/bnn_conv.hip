@@ -109,7 +109,7 @@ void bnn_regs_kernel(const uint32_t *__restrict__ x, const uint32_t *__restrict_
                 mm += __popc(xr[t][cw] ^ wp[t * CWT + cw]);
         const int S = base - 2 * (mm - corr[co * 16 + type]);
         if (active)
-            yp[(int64_t)co * g.HoWo] = (float)S * alpha[co];
+            store_output(yp + (int64_t)co * g.HoWo, (float)S * alpha[co]);
     }
 }
 
@@ -176,7 +176,7 @@ void bnn_bin_kernel(const uint32_t *__restrict__ x, const uint32_t *__restrict__
         for (int q = 0; q < PXL; ++q) {
             const int cr = type[q] ? corr[co * 16 + type[q]] : 0;
             const int S = base[q] - 2 * (mm[q][c] - cr);
-            if (active[q]) y[((int64_t)nn[q] * g.C_out + co) * g.HoWo + rr[q]] = (float)S * a;
+            if (active[q]) store_output(y + ((int64_t)nn[q] * g.C_out + co) * g.HoWo + rr[q], (float)S * a);
         }
     }
 }
@@ -237,7 +237,7 @@ void bnn_f32_kernel(const float *__restrict__ x, const uint32_t *__restrict__ fl
 #pragma unroll
         for (int j = 0; j < F32_CO; ++j)
             if (co0 + j < g.C_out)
-                y[((int64_t)n * g.C_out + co0 + j) * g.HoWo + r] = alpha[co0 + j] * acc[j];
+                store_output(y + ((int64_t)n * g.C_out + co0 + j) * g.HoWo + r, alpha[co0 + j] * acc[j]);
     }
 }
 

@@ -198,7 +198,7 @@ void subbit_direct_kernel(const SbParams p, int CIC)
                     const uint32_t pair = (b & 1) ? wide_o[j][w] : wide_e[j][w];
                     const int M = (int)((pair >> (16 * (b >> 1))) & 0xffffu);
                     const int S = 2 * (M - p.corr[co * 16 + type]) - base;
-                    p.y[((int64_t)n * g.C_out + co) * g.HoWo + r] = (float)S * p.alpha[co];
+                    store_output(p.y + ((int64_t)n * g.C_out + co) * g.HoWo + r, (float)S * p.alpha[co]);
                 }
             }
             if (++wo == g.Wo) {

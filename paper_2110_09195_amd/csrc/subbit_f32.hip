@@ -117,7 +117,7 @@ void subbit_f32_kernel(const float *__restrict__ x, const uint32_t *__restrict__
 #pragma unroll
         for (int j = 0; j < J; ++j)
             if (lane_co + j < g.C_out)
-                y[((int64_t)n * g.C_out + lane_co + j) * g.HoWo + r] = alpha[lane_co + j] * acc[j][b];
+                store_output(y + ((int64_t)n * g.C_out + lane_co + j) * g.HoWo + r, alpha[lane_co + j] * acc[j][b]);
     }
 }
 

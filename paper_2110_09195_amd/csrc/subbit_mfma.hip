@@ -250,9 +250,7 @@ void subbit_front_kernel(const FrontParams p)
     const int b = blockIdx.x;
     if (b >= p.COP + p.lut_blocks) {
         static_assert(PACK_LDS_WORDS <= 64 * 12, "the packing role's bit stream fits");
-#if !(defined(FRONT_DBG) && (FRONT_DBG & 4))
         pack_rows_block(p.x, p.xr, p.rows, p.W, p.WW, p.rows_per_block, p.vec, (int64_t)(b - p.COP - p.lut_blocks), lds);
-#endif
         return;
     }
     if (b >= p.COP) {
@@ -294,19 +292,13 @@ void subbit_front_kernel(const FrontParams p)
         float nx[2][9];
         if (c0 + 512 < C_in) load_kernels(c0 + 512, nx);
         int best[2];
-#if defined(FRONT_DBG) && (FRONT_DBG & 2)
-        best[0] = (int)(wt[0][0] > 0.f); best[1] = (int)(wt[1][3] > 0.f);
-#else
         project_argmax<2>(wt, coef, K, best);
-#endif
 #pragma unroll
         for (int q = 0; q < 2; ++q) {
             const int ci = c0 + 256 * q + tid;
             if (ci < C_in) {
                 if (real) p.idx_out[(int64_t)co * C_in + ci] = (uint16_t)best[q];
-#if !(defined(FRONT_DBG) && (FRONT_DBG & 1))
                 store_sel(p.sel, p.COP, C_in, p.pair, pos, ci, real ? best[q] : -1);
-#endif
             }
             const uint32_t z = (real && ci < C_in) ? zbits[best[q]] : 0u;
 #pragma unroll
@@ -344,7 +336,9 @@ __device__ inline __amdgpu_buffer_rsrc_t make_rsrc(const void *base, uint32_t by
 }
 __device__ inline void buf_store(__amdgpu_buffer_rsrc_t r, float v, uint32_t lane_off, uint32_t uniform_off)
 {
-    __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(v), r, (int)lane_off, (int)uniform_off, 0);
+    // non-temporal: the output is written once and not read again by this kernel; marked so, it drains to
+    // memory while the kernel runs instead of sitting in L2 until the write-back at the kernel's end
+    __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(v), r, (int)lane_off, (int)uniform_off, 2 /* nt */);
 }
 typedef uint32_t u32x3 __attribute__((ext_vector_type(3)));
 __device__ inline uint32_t buf_load1(__amdgpu_buffer_rsrc_t r, uint32_t lane_off, uint32_t uniform_off)
