@@ -31,7 +31,7 @@ void pack_channels_kernel(const float *__restrict__ x, uint32_t *__restrict__ ou
     uint32_t word = 0;
 #pragma unroll 8
     for (int c = 0; c < nc; ++c)
-        word |= (uint32_t)(src[(int64_t)c * HW] >= 0.0f) << c;
+        word |= (uint32_t)(load_once(src + (int64_t)c * HW) >= 0.0f) << c;
     out[pix * CW + cw] = word;
 }
 
