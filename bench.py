@@ -67,6 +67,10 @@ def _measured_traffic(args):
         return None
 
 
+def dense_ops_of(layers):
+    return sum(L.dense_ops for L in layers)
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -237,6 +241,42 @@ def main():
     t1 = time.perf_counter()
     ms_per_step_bnn = (t1 - t0) * 1e3 / args.steps
 
+    # ---- the same stack as a chain of 1-bit activations (resnet18 workload only) ---------------------------
+    # Layer i's convolution ends in the next layer's binarisation (snn_subbit_forward_sign): the packed
+    # output of one layer is the packed input of the next, no fp32 activations are written and nothing
+    # is packed in between.  Reported next to the headline, not as it: the headline's layers each take
+    # their own fp32 input, as the workload is defined.
+    chained = None
+    chain_ok = args.workload == "resnet18" and not args.layer and all(
+        a.C_out == b.C_in and a.H_out == b.H and a.W_out == b.W for a, b in zip(layers, layers[1:]))
+    if chain_ok:
+        for i, s in enumerate(st):
+            L = s["L"]
+            s["beta"] = dev((0.25 * synth.rng(cfg_no, 200 + i).standard_normal(L.C_out)).astype(np.float32))
+            words = L.N * L.C_out * L.H_out * ((L.W_out + 31) // 32)
+            s["out_bits"] = torch.empty(words, dtype=torch.int32, device="cuda")
+
+        def step_chained():
+            xin = B.snn_pack_activations(st[0]["x"], B.SNN_ACT_BIN_ROWS, out=st[0]["xr"])
+            for s in st:
+                L = s["L"]
+                B.snn_subbit_forward_sign(s["d_sub"], xin, s["w"], s["cb"], s["alpha"], s["beta"],
+                                          idx_out=s["idx"].view(L.C_out, L.C_in), out=s["out_bits"], workspace=s["ws_sub"])
+                xin = s["out_bits"]
+
+        for _ in range(args.warmup):
+            step_chained()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            step_chained()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        ms_chained = (t1 - t0) * 1e3 / args.steps
+        chained = {"ms_per_step": ms_chained, "gops_eq": dense_ops_of(layers) / (ms_chained * 1e-3) / 1e9,
+                   "step": "pack the first input once, then one snn_subbit_forward_sign per layer (projection + tables, "
+                           "convolution ending in the next layer's sign): 1-bit activations from layer to layer"}
+
     # the two kernels must agree (same decoded weights): a cheap end-to-end sanity check
     for s in st:
         assert torch.equal(s["y"], s["yb"]), "sub-bit and 1-bit kernels disagree on " + s["L"].name
@@ -324,6 +364,8 @@ def main():
           "step %.1f us, bnn step %.1f us" % (sum(t_sub) * 1e3, sum(t_bnn) * 1e3, sum(t_proj) * 1e3, sum(t_pr) * 1e3,
                                                 sum(t_pc) * 1e3, ms_per_step * 1e3, ms_per_step_bnn * 1e3), file=sys.stderr)
     print("step as three separate calls per layer: %.1f us" % (ms_per_step_separate * 1e3), file=sys.stderr)
+    if chained is not None:
+        print("chained 1-bit stack (forward_sign per layer): %.1f us" % (chained["ms_per_step"] * 1e3), file=sys.stderr)
 
     # ---- cpu_baseline: the oracle on a bounded sample of the same workload --------------------------------
     cpu = None
@@ -346,6 +388,18 @@ def main():
             t_cpu += time.perf_counter() - c0
             ops_cpu += L.dense_ops // L.N * x.shape[0]
             assert (s["y"][:n_img].cpu().numpy() == Y).all(), "GPU result differs from the oracle on " + L.name
+        if chained is not None:
+            # the chain, first two images, layer by layer against the oracle (images are independent)
+            xs = oracle.sign(st[0]["x"][:2].cpu().numpy())
+            for s in st:
+                L = s["L"]
+                idx, _ = oracle.project(s["w"].cpu().numpy(), s["cb"].cpu().numpy().view(np.uint16))
+                codes = oracle.expand(s["cb"].cpu().numpy().view(np.uint16), idx.reshape(L.C_out, L.C_in))
+                want, xs = oracle.conv_sign(xs, codes, s["alpha"].cpu().numpy(), s["beta"].cpu().numpy(), L.stride)
+                per_img = L.C_out * L.H_out * ((L.W_out + 31) // 32)
+                got = s["out_bits"][:2 * per_img].cpu().numpy().view(np.uint32).reshape(want.shape)
+                assert (got == want).all(), "chained GPU result differs from the oracle on " + L.name
+            chained["checked"] = "first 2 images of every layer's packed output equal the oracle's chain"
         cpu = {"value": ops_cpu / t_cpu / 1e9, "unit": "GOPS-equivalent", "cores": oracle.threads(), "kind": "oracle",
                "sample": "same %d layers, first %d images of the batch (project + sign + direct conv), %.1f s" % (
                    len(layers), min(n_img, layers[0].N), t_cpu)}
@@ -375,6 +429,7 @@ def main():
         "bnn_ms_per_step": ms_per_step_bnn,
         "breakdown_us": {"subbit_conv": sum(t_sub) * 1e3, "bnn_conv": sum(t_bnn) * 1e3, "project": sum(t_proj) * 1e3,
                          "pack_rows": sum(t_pr) * 1e3, "pack_channels": sum(t_pc) * 1e3},
+        "chained_1bit_stack": chained,
         "roofline": roofline,
         "cpu_baseline": cpu,
     }

@@ -142,6 +142,39 @@ int snn_subbit_forward(const snn_conv_desc *desc, const float *x_nchw, const flo
                        float *y_nchw, void *workspace, size_t ws_bytes, void *stream);
 
 /*
+ * The sub-bit convolution (Sec. 4.5) followed by the next layer's binarisation (Alg. 1 forward:
+ * sign(a^i), after the channel-wise affine that batch normalisation folds into alpha and beta):
+ *   bit[n][co][ho][wo] = ( fl(fl((float)S * alpha[co]) + beta[co]) >= 0 )
+ * with S the integer convolution sum and fl() rounding to fp32 (no fused multiply-add), written
+ * as packed rows, the layout snn_subbit_conv2d consumes: a stack of layers passes 1-bit
+ * activations from layer to layer and never writes fp32 activations.
+ *   desc       host; act must be SNN_ACT_BIN_ROWS
+ *   x_packed   device, uint32 [N][C_in][H][ceil(W/32)]
+ *   codebook, idx, alpha: as for snn_subbit_conv2d;  beta  device, float [C_out]
+ *   out_packed device, uint32 [N][C_out][H_out][ceil(W_out/32)], fully overwritten (unused high
+ *              bits of a last word 0)
+ *   workspace  device, >= snn_workspace_bytes(desc, SNN_WS_SUBBIT) bytes, 256-byte aligned
+ * Errors: INVALID_ARG; UNSUPPORTED for any other desc->act and for layers outside the
+ * matrix-core kernel (K > 64, or C_in = 1 with K <= 32, or tensors of 2^30 words or more);
+ * WORKSPACE; LAUNCH.
+ */
+int snn_subbit_conv2d_sign(const snn_conv_desc *desc, const void *x_packed, const uint16_t *codebook,
+                           const uint16_t *idx, const float *alpha, const float *beta,
+                           void *out_packed, void *workspace, size_t ws_bytes, void *stream);
+
+/*
+ * The same with the projection of the layer's real-valued kernels in front (Alg. 1 forward of a
+ * layer inside a stack): idx_out = project(w) as snn_project_kernels computes it, then
+ * snn_subbit_conv2d_sign with it; two launches.
+ *   w        device, float [C_out][C_in][9];  idx_out  device, uint16 [C_out][C_in], fully overwritten
+ *   the rest as for snn_subbit_conv2d_sign (workspace: SNN_WS_SUBBIT).
+ */
+int snn_subbit_forward_sign(const snn_conv_desc *desc, const void *x_packed, const float *w,
+                            const uint16_t *codebook, const float *alpha, const float *beta,
+                            uint16_t *idx_out, void *out_packed, void *workspace, size_t ws_bytes,
+                            void *stream);
+
+/*
  * Sec. 3: the 1-bit layer a = lambda * (w_bar o a_bar), "o" = XNOR + bit count over words of
  * 32 input channels.  The baseline every sub-bit number is compared with.
  *   desc      host; act = SNN_ACT_BIN_CHANNELS (+-1 activations) or SNN_ACT_F32; K ignored

@@ -14,6 +14,7 @@ from .oracle import (  # noqa: F401
     pack_channels,
     expand,
     conv_bin,
+    conv_sign,
     conv_f32,
     two_stage_bin,
     two_stage_f32,

@@ -116,6 +116,17 @@ def conv_bin(xs, codes, alpha, stride=1):
     return S, Y
 
 
+def conv_sign(xs, codes, alpha, beta, stride=1):
+    """The convolution followed by the next layer's binarisation (Alg. 1 forward, sign(a^i), after
+    the channel-wise affine alpha, beta): bit = (fl(fl(S * alpha) + beta) >= 0) in fp32, as packed
+    rows uint32 [N][C_out][Ho][ceil(Wo/32)] and as the +-1 tensor the next conv_bin takes."""
+    _, Y = conv_bin(xs, codes, alpha, stride)
+    beta = _c(beta, np.float32)
+    assert beta.shape == (Y.shape[1],)
+    t = (Y + beta[None, :, None, None]).astype(np.float32)        # one fp32 rounding: Y and beta are fp32
+    return pack_rows(t), sign(t)
+
+
 def conv_f32(x, codes, alpha, stride=1):
     """Direct convolution, fp32 activations, float64 accumulation.
     Returns (S float64, Y float32)."""

@@ -27,7 +27,8 @@ SNN_WS_SUBBIT = 0
 SNN_WS_BNN = 1
 SNN_WS_FORWARD = 2
 
-EXPORTS = ("snn_pack_activations", "snn_project_kernels", "snn_subbit_conv2d", "snn_subbit_forward", "snn_bnn_conv2d",
+EXPORTS = ("snn_pack_activations", "snn_project_kernels", "snn_subbit_conv2d", "snn_subbit_forward",
+           "snn_subbit_conv2d_sign", "snn_subbit_forward_sign", "snn_bnn_conv2d",
            "snn_workspace_bytes", "snn_packed_bytes", "snn_status_string")
 
 
@@ -64,6 +65,10 @@ def lib():
         L.snn_subbit_conv2d.restype = i32
         L.snn_subbit_forward.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.snn_subbit_forward.restype = i32
+        L.snn_subbit_conv2d_sign.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.snn_subbit_conv2d_sign.restype = i32
+        L.snn_subbit_forward_sign.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.snn_subbit_forward_sign.restype = i32
         L.snn_bnn_conv2d.argtypes = [dp, vp, vp, vp, vp, vp, sz, vp]
         L.snn_bnn_conv2d.restype = i32
         L.snn_workspace_bytes.argtypes = [dp, i32]
@@ -191,6 +196,53 @@ def snn_subbit_forward(desc, x, w, codebook, alpha, idx_out=None, y=None, worksp
     _check(lib().snn_subbit_forward(ctypes.byref(desc), _ptr(x), _ptr(w), _ptr(codebook), _ptr(alpha), _ptr(idx_out),
                                     _ptr(y), _ptr(workspace), workspace.numel(), _stream()), "snn_subbit_forward")
     return y, idx_out
+
+
+def _sign_out(desc, out, device):
+    Ho, Wo = out_hw(desc)
+    words = desc.N * desc.C_out * Ho * ((Wo + 31) // 32)
+    if out is None:
+        out = torch.empty(words, dtype=torch.int32, device=device)
+    _dev(out, torch.int32, "out")
+    if out.numel() < words:
+        raise ValueError("packed output too small")
+    return out
+
+
+def snn_subbit_conv2d_sign(desc, x, codebook, idx, alpha, beta, out=None, workspace=None):
+    """x: packed int32 rows; -> packed int32 rows [N][C_out][Ho][ceil(Wo/32)] of (S*alpha + beta >= 0)."""
+    _dev(x, torch.int32, "x")
+    _dev(codebook, torch.int16, "codebook")
+    _dev(idx, torch.int16, "idx")
+    _dev(alpha, torch.float32, "alpha")
+    _dev(beta, torch.float32, "beta")
+    out = _sign_out(desc, out, x.device)
+    if workspace is None:
+        workspace = alloc_workspace(desc, SNN_WS_SUBBIT, x.device)
+    _check(lib().snn_subbit_conv2d_sign(ctypes.byref(desc), _ptr(x), _ptr(codebook), _ptr(idx), _ptr(alpha), _ptr(beta),
+                                        _ptr(out), _ptr(workspace), workspace.numel(), _stream()), "snn_subbit_conv2d_sign")
+    return out
+
+
+def snn_subbit_forward_sign(desc, x, w, codebook, alpha, beta, idx_out=None, out=None, workspace=None):
+    """x: packed int32 rows, w float32 [C_out*C_in][9] -> (packed int32 rows of the output signs, idx int16)."""
+    _dev(x, torch.int32, "x")
+    _dev(w, torch.float32, "w")
+    _dev(codebook, torch.int16, "codebook")
+    _dev(alpha, torch.float32, "alpha")
+    _dev(beta, torch.float32, "beta")
+    if w.numel() != desc.C_out * desc.C_in * 9:
+        raise ValueError("w has the wrong size")
+    if idx_out is None:
+        idx_out = torch.empty((desc.C_out, desc.C_in), dtype=torch.int16, device=x.device)
+    _dev(idx_out, torch.int16, "idx_out")
+    out = _sign_out(desc, out, x.device)
+    if workspace is None:
+        workspace = alloc_workspace(desc, SNN_WS_SUBBIT, x.device)
+    _check(lib().snn_subbit_forward_sign(ctypes.byref(desc), _ptr(x), _ptr(w), _ptr(codebook), _ptr(alpha), _ptr(beta),
+                                         _ptr(idx_out), _ptr(out), _ptr(workspace), workspace.numel(), _stream()),
+           "snn_subbit_forward_sign")
+    return out, idx_out
 
 
 def snn_bnn_conv2d(desc, x, w9, alpha, y=None, workspace=None):

@@ -120,6 +120,32 @@ int snn_subbit_forward(const snn_conv_desc *desc, const float *x_nchw, const flo
     return launch_subbit_forward(g, x_nchw, w, codebook, alpha, idx_out, y_nchw, workspace, (hipStream_t)stream);
 }
 
+int snn_subbit_conv2d_sign(const snn_conv_desc *desc, const void *x_packed, const uint16_t *codebook,
+                           const uint16_t *idx, const float *alpha, const float *beta, void *out_packed,
+                           void *workspace, size_t ws_bytes, void *stream)
+{
+    if (!desc_ok(desc, true) || !x_packed || !codebook || !idx || !alpha || !beta || !out_packed) return SNN_ERR_INVALID_ARG;
+    if (desc->act != SNN_ACT_BIN_ROWS) return SNN_ERR_UNSUPPORTED;
+    const Geom g = make_geom(*desc);
+    const size_t need = subbit_workspace_bytes(g, desc->act);
+    if (!workspace || ws_bytes < need || ((uintptr_t)workspace & 255u)) return SNN_ERR_WORKSPACE;
+    return launch_subbit_sign(g, x_packed, codebook, idx, alpha, beta, (uint32_t *)out_packed, workspace, (hipStream_t)stream);
+}
+
+int snn_subbit_forward_sign(const snn_conv_desc *desc, const void *x_packed, const float *w, const uint16_t *codebook,
+                            const float *alpha, const float *beta, uint16_t *idx_out, void *out_packed,
+                            void *workspace, size_t ws_bytes, void *stream)
+{
+    if (!desc_ok(desc, true) || !x_packed || !w || !codebook || !alpha || !beta || !idx_out || !out_packed)
+        return SNN_ERR_INVALID_ARG;
+    if (desc->act != SNN_ACT_BIN_ROWS) return SNN_ERR_UNSUPPORTED;
+    const Geom g = make_geom(*desc);
+    const size_t need = subbit_workspace_bytes(g, desc->act);
+    if (!workspace || ws_bytes < need || ((uintptr_t)workspace & 255u)) return SNN_ERR_WORKSPACE;
+    return launch_subbit_forward_sign(g, x_packed, w, codebook, alpha, beta, idx_out, (uint32_t *)out_packed, workspace,
+                                      (hipStream_t)stream);
+}
+
 int snn_bnn_conv2d(const snn_conv_desc *desc, const void *x, const uint16_t *w9, const float *alpha,
                    float *y_nchw, void *workspace, size_t ws_bytes, void *stream)
 {

@@ -84,14 +84,30 @@ size_t subbit_workspace_bytes(const Geom &g, int act);
 int launch_subbit(const Geom &g, int act, const void *x, const uint16_t *codebook,
                   const uint16_t *idx, const float *alpha, float *y, void *ws, hipStream_t s);
 
+// Optional ending of the sub-bit convolution: instead of y, the next layer's packed rows
+// bit = ((float)S * alpha[co] + beta[co] >= 0), uint32 [N][C_out][H_out][ceil(W_out / 32)].
+struct SignEpilogue {
+    const float *beta;
+    uint32_t *out;
+};
+
 // matrix-core variant of the sub-bit convolution (+-1 activations, K <= 64)
 bool subbit_mfma_supported(const Geom &g);
 size_t subbit_mfma_workspace_bytes(const Geom &g);
 int launch_subbit_mfma(const Geom &g, const void *x, const uint16_t *codebook, const uint16_t *idx,
-                       const float *alpha, float *y, void *ws, hipStream_t s);
+                       const float *alpha, float *y, void *ws, hipStream_t s, const SignEpilogue *sign = nullptr);
 
 int launch_subbit_forward_mfma(const Geom &g, const float *x, const float *w, const uint16_t *codebook,
-                               const float *alpha, uint16_t *idx_out, float *y, uint32_t *xr, void *ws, hipStream_t s);
+                               const float *alpha, uint16_t *idx_out, float *y, uint32_t *xr, void *ws, hipStream_t s,
+                               const SignEpilogue *sign = nullptr);
+
+// the two calls that end in the sign epilogue (packed rows in, packed rows out); UNSUPPORTED where
+// the matrix-core kernel does not apply
+int launch_subbit_sign(const Geom &g, const void *x_packed, const uint16_t *codebook, const uint16_t *idx,
+                       const float *alpha, const float *beta, uint32_t *out_packed, void *ws, hipStream_t s);
+int launch_subbit_forward_sign(const Geom &g, const void *x_packed, const float *w, const uint16_t *codebook,
+                               const float *alpha, const float *beta, uint16_t *idx_out, uint32_t *out_packed, void *ws,
+                               hipStream_t s);
 
 // Alg. 1 forward of one layer from fp32 activations and real-valued kernels (binary activations)
 size_t subbit_forward_workspace_bytes(const Geom &g);

@@ -349,4 +349,22 @@ int launch_subbit_forward(const Geom &g, const float *x, const float *w, const u
     return launch_subbit(g, SNN_ACT_BIN_ROWS, xr, codebook, idx_out, alpha, y, ws, s);
 }
 
+// ---- convolution + the next layer's binarisation --------------------------------------------------------
+int launch_subbit_sign(const Geom &g, const void *x_packed, const uint16_t *codebook, const uint16_t *idx,
+                       const float *alpha, const float *beta, uint32_t *out_packed, void *ws, hipStream_t s)
+{
+    if (!use_mfma(g)) return SNN_ERR_UNSUPPORTED;
+    const SignEpilogue sign = {beta, out_packed};
+    return launch_subbit_mfma(g, x_packed, codebook, idx, alpha, nullptr, ws, s, &sign);
+}
+
+int launch_subbit_forward_sign(const Geom &g, const void *x_packed, const float *w, const uint16_t *codebook,
+                               const float *alpha, const float *beta, uint16_t *idx_out, uint32_t *out_packed, void *ws,
+                               hipStream_t s)
+{
+    if (!use_mfma(g)) return SNN_ERR_UNSUPPORTED;
+    const SignEpilogue sign = {beta, out_packed};
+    return launch_subbit_forward_mfma(g, nullptr, w, codebook, alpha, idx_out, nullptr, (uint32_t *)x_packed, ws, s, &sign);
+}
+
 }  // namespace snn

@@ -53,6 +53,11 @@ struct MfParams {
     const uint32_t *sel;      // [steps][2][COP] selector words for the one-hot operand
     const uint2 *fin;         // [COP][16] per (output channel, border type): {2 corr + C_in (valid_taps - 8), alpha bits}
     float *y;
+    // binarised output (sign epilogue) instead of y when sign_out != nullptr:
+    // bit = ((float)S * alpha[co] + beta[co] >= 0), packed rows [N][C_out][H_out][ceil(W_out / 32)];
+    // `fin` then holds thresholds (fin_entry)
+    uint32_t *sign_out;
+    int n_pxblocks;           // blocks of up to 32 pixels (see PixelMap)
     Geom g;
     int COP;                  // C_out padded to whole wave tiles
     int KS;                   // waves that split the channel pairs of one tile: 1, 2 or 4
@@ -115,6 +120,54 @@ __device__ inline void prep_lut_block(const uint16_t *__restrict__ codebook, int
     }
 }
 
+// fl(fl(a * b) + c): two fp32 roundings, never contracted into a fused multiply-add (the sign epilogue's
+// definition; a threshold that sits exactly on an attained value must compare equal)
+__device__ inline float mul_then_add(float a, float b, float c)
+{
+#pragma clang fp contract(off)
+    const float prod = a * b;
+    return prod + c;
+}
+
+// One entry of the finishing table, for output channel co and border type `type`:
+//   corr_term = 2 corr + C_in (valid_taps(type) - 8), so that S = 2 acc - corr_term for the accumulator acc.
+// fp32 output (beta == nullptr): {corr_term, alpha}; the epilogue computes y = float(S) * alpha.
+// Sign epilogue: the bit (fl(fl(S * alpha) + beta) >= 0) is monotone in the integer S, so it equals
+// S >= T (alpha > 0) or S <= T (alpha < 0) for a threshold T found here by bisection over all sums
+// the layer can produce, with the very fp32 expression that defines the bit; folded with corr_term
+// the entry is {mult, thr} (two floats) and the epilogue's test is acc * mult >= thr, exact
+// because acc, mult and thr are small integers.  alpha = 0 or NaN: the bit does not depend on S (mult = 0).
+__device__ inline uint2 fin_entry(int corr_term, float a, const float *beta, int co, bool real, int C_in)
+{
+    if (!beta) return make_uint2((uint32_t)corr_term, __float_as_uint(a));
+    const float b = real ? beta[co] : 0.0f;
+    const int smax = 9 * C_in;
+    auto pred = [&](int S) { return mul_then_add((float)S, a, b) >= 0.0f; };
+    float mult, thr;
+    if (a > 0.0f || a < 0.0f) {
+        // first S in [-smax, smax + 1] from which on the bit is 1 (a > 0) / 0 (a < 0)
+        int lo = -smax, hi = smax + 1;
+        while (lo < hi) {
+            const int mid = (lo + hi) >> 1;
+            if (pred(mid) == (a > 0.0f)) hi = mid;
+            else lo = mid + 1;
+        }
+        if (a > 0.0f) {
+            const int t = lo + corr_term;                       // 2 acc >= T + corr_term
+            mult = 1.0f;
+            thr = (float)((t + 1) >> 1);                        // ceil(t / 2)
+        } else {
+            const int t = (lo - 1) + corr_term;                 // 2 acc <= T + corr_term, T = lo - 1 the last S with bit 1
+            mult = -1.0f;
+            thr = -(float)(t >> 1);                             // -floor(t / 2)
+        }
+    } else {
+        mult = 0.0f;
+        thr = pred(0) ? -1.0f : 1.0f;
+    }
+    return make_uint2(__float_as_uint(mult), __float_as_uint(thr));
+}
+
 // selector word of subset member k (see below)
 __device__ inline uint32_t sel_word(uint32_t k)
 {
@@ -149,7 +202,7 @@ __global__ __launch_bounds__(256)
 void subbit_mfma_prep_kernel(const uint16_t *__restrict__ codebook, const uint16_t *__restrict__ idx, int C_in,
                              int C_out, int COP, int CB, int K, int pair, int sel_blocks, int lut_blocks,
                              const float *__restrict__ alpha, uint32_t *__restrict__ sel, uint2 *__restrict__ fin,
-                             uint32_t *__restrict__ lut)
+                             uint32_t *__restrict__ lut, const float *__restrict__ beta)
 {
     const int tid = threadIdx.x;
     const int b = blockIdx.x;
@@ -212,7 +265,7 @@ void subbit_mfma_prep_kernel(const uint16_t *__restrict__ codebook, const uint16
         for (int t = 0; t < 9; ++t)
             if ((inv >> t) & 1u) s += zeros[t];
         const float a = co < C_out ? alpha[co] : 0.0f;
-        fin[co * 16 + lane] = make_uint2((uint32_t)(2 * s + (border_valid_taps(lane) - 8) * C_in), __float_as_uint(a));
+        fin[co * 16 + lane] = fin_entry(2 * s + (border_valid_taps(lane) - 8) * C_in, a, beta, co, co < C_out, C_in);
     }
 }
 
@@ -222,7 +275,8 @@ void subbit_mfma_prep_kernel(const uint16_t *__restrict__ codebook, const uint16
 //   [0, COP)            one block per output channel: projection of its C_in real-valued kernels
 //                       (Eq. 2 / Eq. 5) -> idx_out, selector words, finishing table row
 //   [COP, +lut_blocks)  the lookup table
-//   the rest            sign + packing of the activations into packed rows (Alg. 1: sign(a))
+//   the rest            sign + packing of the activations into packed rows (Alg. 1: sign(a)); none when the
+//                       input is packed already
 // The few channel blocks ride along with the bandwidth-bound packing blocks instead of costing two
 // launches of their own.
 struct FrontParams {
@@ -238,6 +292,8 @@ struct FrontParams {
     uint2 *fin;
     uint32_t *lut;
     int C_in, C_out, COP, CB, K, pair, lut_blocks;
+    const float *beta;        // sign epilogue: the finishing table holds thresholds (see fin_entry); else nullptr
+    int64_t pack_blocks;      // 0: the activations are packed already
 };
 
 __global__ __launch_bounds__(256)
@@ -322,7 +378,7 @@ void subbit_front_kernel(const FrontParams p)
 #pragma unroll
         for (int t = 0; t < 9; ++t)
             if ((inv >> t) & 1u) sum += (int)(wsum[t] + wsum[9 + t] + wsum[18 + t] + wsum[27 + t]);
-        p.fin[co * 16 + tid] = make_uint2((uint32_t)(2 * sum + (border_valid_taps(tid) - 8) * C_in), __float_as_uint(a));
+        p.fin[co * 16 + tid] = fin_entry(2 * sum + (border_valid_taps(tid) - 8) * C_in, a, p.beta, co, real, C_in);
     }
 }
 
@@ -392,8 +448,58 @@ void subbit_mfma_kernel(const MfParams p)
     const bool active = tile < p.n_tiles;                       // wave-uniform
     const long long tl = active ? tile : p.n_tiles - 1;
     const int co_tile = (int)(tl % p.n_cotiles);
-    const long long p_tile = (tl / p.n_cotiles) * (32 * PB);
+    const int blk0 = (int)(tl / p.n_cotiles) * PB;              // first pixel block of the tile
     const int co0 = co_tile * (32 * CB);
+
+    // Pixel blocks.  For the fp32 output, block B is pixels 32 B .. 32 B + 31 of the flattened
+    // (n, ho, wo) order.  For the sign epilogue a block is made of whole output words instead, so
+    // that the wave that owns a block owns the words it writes: whole rows while they fit 32 pixels
+    // (W_out <= 32: floor(32 / W_out) rows per block), else one 32-pixel word of a row; the lanes
+    // left over are idle (12.5 % for rows of 7, 14, 28 or 56 pixels).  Either way the pixels of a tile
+    // lie within 32 PB consecutive pixels of the flattened order.  Idle lanes and blocks past the end
+    // work on the first pixel of their (or the last) block and are not written.
+    const int P32 = (int)g.P;
+    const bool aligned = p.sign_out != nullptr;
+    const int rows_pb = g.Wo <= 32 ? 32 / g.Wo : 1;             // aligned, short rows: rows per block
+    const int bpi = (g.Ho + rows_pb - 1) / rows_pb;             //   blocks per image
+    const int wpr = (g.Wo + 31) / 32;                           // aligned, long rows: blocks (words) per row
+    auto pixel_of = [&](int pb, int lane_px, int &n, int &ho, int &wo) -> bool {
+        int B = blk0 + pb;
+        bool ok = B < p.n_pxblocks;
+        if (!ok) B = p.n_pxblocks - 1;
+        if (!aligned) {
+            int pp = B * 32 + lane_px;
+            if (pp >= P32) {
+                ok = false;
+                pp = P32 - 1;
+            }
+            n = pp / g.HoWo;
+            const int r = pp - n * g.HoWo;
+            ho = r / g.Wo;
+            wo = r - ho * g.Wo;
+        } else if (g.Wo <= 32) {
+            n = B / bpi;
+            const int rb = B - n * bpi;
+            int rl = lane_px / g.Wo;
+            wo = lane_px - rl * g.Wo;
+            if (rl >= rows_pb || rb * rows_pb + rl >= g.Ho) {
+                ok = false;
+                rl = 0;
+                wo = 0;
+            }
+            ho = rb * rows_pb + rl;
+        } else {
+            const int R = B / wpr, j = B - R * wpr;
+            n = R / g.Ho;
+            ho = R - n * g.Ho;
+            wo = 32 * j + lane_px;
+            if (wo >= g.Wo) {
+                ok = false;
+                wo = 32 * j;
+            }
+        }
+        return ok;
+    };
 
     MF_TRACE(0);
 
@@ -420,7 +526,6 @@ void subbit_mfma_kernel(const MfParams p)
     uint32_t sh[PB], m7[PB], lsh[PB], vm[PB];
     uint32_t yoff[PB];                             // byte offset of y[n][4 h][pixel], out of range for pixels past the end
     int ptype[PB];                                 // border type
-    const int P32 = (int)g.P;
     // Staging (STG): rows are numbered R = n * H + h over the whole batch; the wave stages words
     // [0, MF_STAGE_SLOTS) of the run of rows that starts at R_first, the first row the tile's
     // first pixel loads.  A pixel's three rows start (R - R_first) * WM + jlo words into the run.
@@ -431,9 +536,8 @@ void subbit_mfma_kernel(const MfParams p)
     uint32_t gshift = 0;                           // two-word rows: the piece is bits [gshift, gshift + 32) of the two words loaded
     uint32_t loff[PB];                             // LDS address of the pixel's piece of its first row
     if constexpr (STG) {
-        const int pt = (int)p_tile;
-        const int n0 = pt / g.HoWo;
-        const int ho0 = (pt - n0 * g.HoWo) / g.Wo;
+        int n0, ho0, wo0;
+        pixel_of(0, 0, n0, ho0, wo0);              // the tile's first pixel (wave-uniform)
         const int hc0 = ho0 * g.stride;
         R_first = n0 * g.H + (hc0 == 0 ? 0 : hc0 - 1);
         const int R = R_first + n_l / SW, piece = n_l % SW;
@@ -444,13 +548,9 @@ void subbit_mfma_kernel(const MfParams p)
     }
 #pragma unroll
     for (int pb = 0; pb < PB; ++pb) {
-        int pp = (int)p_tile + pb * 32 + n_l;
-        const bool ok = pp < P32;
-        if (!ok) pp = P32 - 1;
-        const int n = pp / g.HoWo;
-        const int r = pp - n * g.HoWo;
-        const int ho = r / g.Wo, wo = r - ho * g.Wo;
-        yoff[pb] = ok ? (uint32_t)((n * g.C_out + 4 * h) * g.HoWo + r) * 4u : 0xffffffffu;
+        int n, ho, wo;
+        const bool ok = pixel_of(pb, n_l, n, ho, wo);
+        yoff[pb] = ok ? (uint32_t)((n * g.C_out + 4 * h) * g.HoWo + ho * g.Wo + wo) * 4u : 0xffffffffu;
         ptype[pb] = border_type(ho, wo, g.H, g.W, g.stride);
         vm[pb] = ~border_invalid_window(ptype[pb]) & 0x1ffu;
         const int hc = ho * g.stride, first = wo * g.stride - 1;
@@ -759,6 +859,90 @@ void subbit_mfma_kernel(const MfParams p)
     if (KS > 1) __syncthreads();                   // the other waves' parts
     if (!active) return;
     MF_TRACE(6);
+    if (p.sign_out) {
+        // ---- sign epilogue: bit = ((float)S * alpha + beta >= 0) = (acc * mult >= thr), the next layer's packed rows
+        // The 32 lanes of a half hold the pixels of one block of one channel: a ballot turns their signs
+        // into a bit string that holds the block's words of that channel (a block is made of whole words,
+        // so nobody else writes them and every word gets written).  Lane (c, half) collects word
+        // 2 G + half of channel c of the block while the 16 accumulator registers go by (register r is
+        // channels cl and cl + 4, in the low and the high half of the ballot), so that a block of 32
+        // channels costs one store instruction per pair of words instead of sixteen.
+        const int WWo = (g.Wo + 31) / 32;
+        const uint32_t oplane = (uint32_t)(g.Ho * WWo);            // words per output channel plane
+        const bool short_rows = g.Wo <= 32;
+        const int wpb = short_rows ? rows_pb : 1;                  // words of one channel in a block
+        const int NG = (wpb + 1) / 2;
+        const uint32_t wmask = g.Wo < 32 ? (1u << g.Wo) - 1u : 0xffffffffu;
+        const bool takes_hi = (n_l & 4) != 0;
+#pragma unroll
+        for (int pb = 0; pb < PB; ++pb) {
+            int n, ho, wo;
+            const bool ok = pixel_of(pb, n_l, n, ho, wo);
+            // the block's image, its first word inside a channel plane and how many of its words exist (wave-uniform)
+            int B = blk0 + pb;
+            const bool bvalid = B < p.n_pxblocks;
+            if (!bvalid) B = p.n_pxblocks - 1;
+            int bn, bword, bwords;
+            if (short_rows) {
+                bn = B / bpi;
+                bword = (B - bn * bpi) * rows_pb;
+                bwords = min(rows_pb, g.Ho - bword);
+            } else {
+                const int R = B / wpr;
+                bn = R / g.Ho;
+                bword = (R - bn * g.Ho) * WWo + (B - R * wpr);
+                bwords = 1;
+            }
+            if (!bvalid) bwords = 0;
+            const unsigned long long okm = __ballot(ok);
+#pragma unroll
+            for (int cb = 0; cb < CB; ++cb) {
+                const int q = cb * PB + pb;
+                if (KS > 1 && (q & (KS - 1)) != split) continue;
+                const uint32_t fin_lane = fin_wave + (uint32_t)(((cb * 32 + 4 * h) * 16 + ptype[pb]) * 8);
+                const int co = co0 + cb * 32 + n_l;                // the channel whose words this lane collects
+                if (wpb == 1) {
+                    // one word per channel and block (rows longer than 16 pixels): the two halves of the
+                    // ballot are the words of channels cl and cl + 4; they go straight into the lanes of
+                    // those channels
+                    u32x2 f[16];
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) f[r] = *(lds_cu32x2 *)(uintptr_t)(fin_lane + (uint32_t)((8 * (r / 4) + (r % 4)) * 128));
+                    uint32_t outw = 0;
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const int cl = 8 * (r / 4) + (r % 4);
+                        const unsigned long long m =
+                            __ballot(acc[cb][pb][r] * __uint_as_float(f[r].x) >= __uint_as_float(f[r].y)) & okm;
+                        const uint32_t m_lo = (uint32_t)m, m_hi = (uint32_t)(m >> 32);     // wave-uniform
+                        asm("v_writelane_b32 %0, %1, %2" : "+v"(outw) : "s"(m_lo), "n"(cl));
+                        asm("v_writelane_b32 %0, %1, %2" : "+v"(outw) : "s"(m_hi), "n"(cl + 4));
+                    }
+                    if (h == 0 && bwords > 0 && co < g.C_out) p.sign_out[(uint32_t)(bn * g.C_out + co) * oplane + (uint32_t)bword] = outw;
+                    continue;
+                }
+                for (int G = 0; G < NG; ++G) {
+                    const int j = 2 * G + h;
+                    const uint32_t lshift = short_rows ? (uint32_t)(j * g.Wo) & 31u : 0u;
+                    uint32_t outw = 0;
+                    u32x2 f[16];                                                   // {mult, thr} of the lane's 16 channels
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) f[r] = *(lds_cu32x2 *)(uintptr_t)(fin_lane + (uint32_t)((8 * (r / 4) + (r % 4)) * 128));
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const int cl = 8 * (r / 4) + (r % 4);                      // channel inside the block, lane half 0
+                        const unsigned long long m =
+                            __ballot(acc[cb][pb][r] * __uint_as_float(f[r].x) >= __uint_as_float(f[r].y)) & okm;
+                        const uint32_t src = takes_hi ? (uint32_t)(m >> 32) : (uint32_t)m;
+                        if ((n_l & ~4) == cl) outw = (src >> lshift) & wmask;
+                    }
+                    if (j < bwords && co < g.C_out) p.sign_out[(uint32_t)(bn * g.C_out + co) * oplane + (uint32_t)(bword + j)] = outw;
+                }
+            }
+        }
+        MF_TRACE(7);
+        return;
+    }
     const __amdgpu_buffer_rsrc_t yres = make_rsrc(p.y, (uint32_t)((size_t)g.N * g.C_out * g.HoWo * 4u));
     const uint32_t chan_bytes = (uint32_t)g.HoWo * 4u;
 #pragma unroll
@@ -790,7 +974,7 @@ struct MfPlan {
     bool pair;        // K <= 32: two input channels per step
     bool stage;       // the rows of a tile fit the staging slots
     int KS, COP, n_cotiles, npairs;
-    long long n_pxtiles, n_tiles, n_wgs;
+    long long n_pxblocks, n_pxtiles, n_tiles, n_wgs;
     size_t lds;
     size_t off_sel, off_fin, off_lut, bytes;
 };
@@ -801,7 +985,18 @@ int env_int(const char *name, int dflt)
     return e ? atoi(e) : dflt;
 }
 
-MfPlan mf_plan(const Geom &g)
+// blocks of up to 32 pixels: 32 consecutive pixels each, or (sign epilogue) whole output words
+int64_t mf_pxblocks(const Geom &g, bool aligned)
+{
+    if (!aligned) return (g.P + 31) / 32;
+    if (g.Wo <= 32) {
+        const int rows_pb = 32 / g.Wo;
+        return (int64_t)g.N * ((g.Ho + rows_pb - 1) / rows_pb);
+    }
+    return (int64_t)g.N * g.Ho * ((g.Wo + 31) / 32);
+}
+
+MfPlan mf_plan(const Geom &g, bool aligned = false)
 {
     MfPlan pl;
     // tile of a wave: 128 accumulator registers (PB x CB = 8); few channels -> more pixels per wave
@@ -816,7 +1011,8 @@ MfPlan mf_plan(const Geom &g)
     const int cow = 32 * pl.cfg.CB, pxw = 32 * pl.cfg.PB;
     pl.COP = (g.C_out + cow - 1) / cow * cow;
     pl.n_cotiles = pl.COP / cow;
-    pl.n_pxtiles = (g.P + pxw - 1) / pxw;
+    pl.n_pxblocks = mf_pxblocks(g, aligned);
+    pl.n_pxtiles = (pl.n_pxblocks + pl.cfg.PB - 1) / pl.cfg.PB;
     pl.n_tiles = pl.n_pxtiles * pl.n_cotiles;
     pl.pair = g.K <= 32;
     pl.npairs = pl.pair ? (g.C_in + 1) / 2 : g.C_in;
@@ -900,7 +1096,7 @@ size_t subbit_mfma_workspace_bytes(const Geom &g) { return mf_plan(g).bytes; }
 
 namespace {
 
-MfParams mf_params(const MfPlan &pl, const Geom &g, const void *x, float *y, void *ws)
+MfParams mf_params(const MfPlan &pl, const Geom &g, const void *x, float *y, void *ws, const SignEpilogue *sign)
 {
     MfParams prm;
     prm.x = (const uint32_t *)x;
@@ -908,6 +1104,7 @@ MfParams mf_params(const MfPlan &pl, const Geom &g, const void *x, float *y, voi
     prm.fin = (const uint2 *)((char *)ws + pl.off_fin);
     prm.lut = (const uint32_t *)((char *)ws + pl.off_lut);
     prm.y = y;
+    prm.sign_out = sign ? sign->out : nullptr;
     prm.g = g;
     prm.COP = pl.COP;
     prm.KS = pl.KS;
@@ -915,6 +1112,7 @@ MfParams mf_params(const MfPlan &pl, const Geom &g, const void *x, float *y, voi
     prm.pairs_per_split = (pl.npairs + pl.KS - 1) / pl.KS;
     prm.n_cotiles = pl.n_cotiles;
     prm.n_tiles = pl.n_tiles;
+    prm.n_pxblocks = (int)pl.n_pxblocks;
 #ifdef SNN_MF_TRACE
     prm.trace = (unsigned long long *)ws;
 #endif
@@ -935,29 +1133,31 @@ int launch_mf_conv(const MfPlan &pl, const MfParams &prm, hipStream_t s)
 }  // namespace
 
 int launch_subbit_mfma(const Geom &g, const void *x, const uint16_t *codebook, const uint16_t *idx,
-                       const float *alpha, float *y, void *ws, hipStream_t s)
+                       const float *alpha, float *y, void *ws, hipStream_t s, const SignEpilogue *sign)
 {
-    const MfPlan pl = mf_plan(g);
-    if (pl.n_wgs > 0x7fffffffLL || pl.lds > 160 * 1024) return SNN_ERR_UNSUPPORTED;
-    const MfParams prm = mf_params(pl, g, x, y, ws);
+    const MfPlan pl = mf_plan(g, sign != nullptr);
+    if (pl.n_wgs > 0x7fffffffLL || pl.lds > 160 * 1024 || pl.n_pxblocks > 0x7fffffffLL) return SNN_ERR_UNSUPPORTED;
+    const MfParams prm = mf_params(pl, g, x, y, ws, sign);
 
     const int sel_blocks = (pl.COP / 32) * ((g.C_in + 31) / 32);
     const int corr_blocks = (pl.COP + 3) / 4;
     const int lut_blocks = (512 * (pl.pair ? 6 : 12) + 255) / 256;
     hipLaunchKernelGGL(subbit_mfma_prep_kernel, dim3((unsigned)(sel_blocks + corr_blocks + lut_blocks)), dim3(256), 0, s,
                        codebook, idx, g.C_in, g.C_out, pl.COP, pl.cfg.CB, g.K, pl.pair ? 1 : 0, sel_blocks, lut_blocks, alpha,
-                       (uint32_t *)prm.sel, (uint2 *)prm.fin, (uint32_t *)prm.lut);
+                       (uint32_t *)prm.sel, (uint2 *)prm.fin, (uint32_t *)prm.lut, sign ? sign->beta : nullptr);
     return launch_mf_conv(pl, prm, s);
 }
 
 // Alg. 1 forward of a layer in two launches: the front kernel (projection, selector / finishing /
-// lookup tables, sign + packing into `xr`), then the convolution on `xr`.
+// lookup tables, and sign + packing of x into `xr` unless x is null: then `xr` holds the packed
+// input already), then the convolution on `xr`, ending in y or in the sign epilogue.
 int launch_subbit_forward_mfma(const Geom &g, const float *x, const float *w, const uint16_t *codebook,
-                               const float *alpha, uint16_t *idx_out, float *y, uint32_t *xr, void *ws, hipStream_t s)
+                               const float *alpha, uint16_t *idx_out, float *y, uint32_t *xr, void *ws, hipStream_t s,
+                               const SignEpilogue *sign)
 {
-    const MfPlan pl = mf_plan(g);
-    if (pl.n_wgs > 0x7fffffffLL || pl.lds > 160 * 1024) return SNN_ERR_UNSUPPORTED;
-    const MfParams prm = mf_params(pl, g, xr, y, ws);
+    const MfPlan pl = mf_plan(g, sign != nullptr);
+    if (pl.n_wgs > 0x7fffffffLL || pl.lds > 160 * 1024 || pl.n_pxblocks > 0x7fffffffLL) return SNN_ERR_UNSUPPORTED;
+    const MfParams prm = mf_params(pl, g, xr, y, ws, sign);
 
     FrontParams fp;
     fp.x = x;
@@ -968,6 +1168,7 @@ int launch_subbit_forward_mfma(const Geom &g, const float *x, const float *w, co
     const PackRowsPlan pk = pack_rows_plan(x, fp.rows, g.W);
     fp.rows_per_block = pk.rows_per_block;
     fp.vec = pk.vec;
+    fp.pack_blocks = x ? pk.blocks : 0;
     fp.w = w;
     fp.codebook = codebook;
     fp.alpha = alpha;
@@ -982,7 +1183,8 @@ int launch_subbit_forward_mfma(const Geom &g, const float *x, const float *w, co
     fp.K = g.K;
     fp.pair = pl.pair ? 1 : 0;
     fp.lut_blocks = (512 * (pl.pair ? 6 : 12) + 255) / 256;
-    const int64_t blocks = (int64_t)pl.COP + fp.lut_blocks + pk.blocks;
+    fp.beta = sign ? sign->beta : nullptr;
+    const int64_t blocks = (int64_t)pl.COP + fp.lut_blocks + fp.pack_blocks;
     if (blocks > 0x7fffffffLL) return SNN_ERR_UNSUPPORTED;
     hipLaunchKernelGGL(subbit_front_kernel, dim3((unsigned)blocks), dim3(256), 0, s, fp);
     return launch_mf_conv(pl, prm, s);

@@ -96,3 +96,23 @@ def subbit_forward(x, w, codebook, alpha, C_out, stride=1):
     y, idx = B.snn_subbit_forward(d, dev(x), dev(w.reshape(-1, 9)), dev(codebook), dev(alpha))
     torch.cuda.synchronize()
     return y.cpu().numpy(), host_u16(idx)
+
+
+def subbit_sign(xp, shape, codebook, idx, alpha, beta, stride=1):
+    """xp: packed rows (uint32 numpy) of an input of `shape` = (N, C_in, H, W) -> packed rows of the output signs."""
+    N, C_in, H, W = shape
+    C_out = idx.shape[0]
+    d = B.make_desc(N, C_in, C_out, H, W, stride, int(codebook.size), B.SNN_ACT_BIN_ROWS)
+    out = B.snn_subbit_conv2d_sign(d, dev(xp.reshape(-1)), dev(codebook), dev(idx), dev(alpha), dev(beta))
+    torch.cuda.synchronize()
+    Ho, Wo = B.out_hw(d)
+    return host_u32(out).reshape(N, C_out, Ho, (Wo + 31) // 32)
+
+
+def subbit_forward_sign(xp, shape, w, codebook, alpha, beta, C_out, stride=1):
+    N, C_in, H, W = shape
+    d = B.make_desc(N, C_in, C_out, H, W, stride, int(codebook.size), B.SNN_ACT_BIN_ROWS)
+    out, idx = B.snn_subbit_forward_sign(d, dev(xp.reshape(-1)), dev(w.reshape(-1, 9)), dev(codebook), dev(alpha), dev(beta))
+    torch.cuda.synchronize()
+    Ho, Wo = B.out_hw(d)
+    return host_u32(out).reshape(N, C_out, Ho, (Wo + 31) // 32), host_u16(idx)

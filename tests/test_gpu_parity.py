@@ -388,6 +388,92 @@ def test_subbit_forward_equals_the_three_calls():
     assert torch.equal(y1, y2)
 
 
+# ---- convolution + the next layer's sign ------------------------------------------------------------------------------
+
+def _matrix_core_layer(case):
+    N, C_in, C_out, H, W, stride, K = case[:7]
+    return K <= 64 and (K > 32 or C_in >= 2)
+
+
+def _beta_near_outputs(g, Y, C_out):
+    """Thresholds inside the range of each channel's outputs, a third of them exactly on an attained
+    value (so that the >= edge is exercised)."""
+    beta = np.empty(C_out, dtype=np.float32)
+    for co in range(C_out):
+        vals = Y[:, co].reshape(-1)
+        pick = vals[g.integers(0, vals.size)]
+        beta[co] = -pick if co % 3 == 0 else -(pick + np.float32(g.standard_normal()) * np.float32(0.5))
+    return beta
+
+
+@pytest.mark.parametrize("case", FORWARD_CASES)
+def test_subbit_conv2d_sign(oracle, case):
+    _say("subbit_conv2d_sign", case)
+    N, C_in, C_out, H, W, stride, K, dist = case
+    x, cb, idx, alpha = _inputs(7000 + sum(case[:7]), N, C_in, C_out, H, W, K, dist)
+    g = np.random.default_rng(7001 + sum(case[:7]))
+    alpha[::4] *= -1.0                                   # a folded batch-norm scale may be negative
+    xs = oracle.sign(x)
+    codes = oracle.expand(cb, idx)
+    _, Y = oracle.conv_bin(xs, codes, alpha, stride)
+    beta = _beta_near_outputs(g, Y, C_out)
+    if not _matrix_core_layer(case):
+        with pytest.raises(B.SnnError) as e:
+            G.subbit_sign(oracle.pack_rows(x), x.shape, cb, idx, alpha, beta, stride)
+        assert e.value.status == B.SNN_ERR_UNSUPPORTED
+        return
+    want, _ = oracle.conv_sign(xs, codes, alpha, beta, stride)
+    got = G.subbit_sign(oracle.pack_rows(x), x.shape, cb, idx, alpha, beta, stride)
+    assert got.shape == want.shape
+    assert (got == want).all(), np.argwhere(got != want)[:5]
+
+
+@pytest.mark.parametrize("tile", ["4,2", "2,4", "2,2", "1,4", "1,2"])
+@pytest.mark.parametrize("split", [1, 2, 4])
+def test_subbit_conv2d_sign_every_tile_and_split(oracle, tile, split, monkeypatch):
+    monkeypatch.setenv("SNN_MFMA_TILE", tile)
+    monkeypatch.setenv("SNN_MFMA_KS", str(split))
+    for seed, (N, C_in, C_out, H, W, stride, K) in enumerate([(3, 45, 150, 13, 11, 1, 32), (2, 20, 70, 16, 12, 2, 32),
+                                                             (2, 34, 40, 9, 40, 1, 20), (1, 8, 33, 5, 70, 1, 32),
+                                                             (9, 6, 40, 5, 5, 1, 32), (2, 6, 40, 12, 56, 1, 32),
+                                                             (1, 7, 8, 5, 70, 1, 64), (2, 16, 36, 3, 130, 2, 32)]):
+        _say("subbit_conv2d_sign", tile, split, (N, C_in, C_out, H, W, stride, K))
+        x, cb, idx, alpha = _inputs(7100 + seed, N, C_in, C_out, H, W, K)
+        g = np.random.default_rng(7200 + seed)
+        xs, codes = oracle.sign(x), oracle.expand(cb, idx)
+        _, Y = oracle.conv_bin(xs, codes, alpha, stride)
+        beta = _beta_near_outputs(g, Y, C_out)
+        want, _ = oracle.conv_sign(xs, codes, alpha, beta, stride)
+        got = G.subbit_sign(oracle.pack_rows(x), x.shape, cb, idx, alpha, beta, stride)
+        assert (got == want).all(), np.argwhere(got != want)[:5]
+
+
+def test_subbit_forward_sign_chain(oracle):
+    """A stack of layers passing 1-bit activations: every layer's packed output is the next layer's
+    input, on the GPU and in the oracle; compared after every layer."""
+    g = np.random.default_rng(4242)
+    N, H, W = 3, 20, 20
+    chain = [(24, 40, 1, 32), (40, 40, 1, 32), (40, 72, 2, 16), (72, 72, 1, 64), (72, 130, 2, 32), (130, 96, 1, 32)]
+    x = g.standard_normal((N, chain[0][0], H, W), dtype=np.float32)
+    xs = oracle.sign(x)
+    xp = oracle.pack_rows(x)
+    shape = x.shape
+    for li, (C_in, C_out, stride, K) in enumerate(chain):
+        _say("chain layer", li, (C_in, C_out, stride, K))
+        cb = synth.codebook(g, K)
+        w = synth.real_kernels(g, C_out * C_in)
+        alpha = synth.alpha(g, C_out)
+        idx_ref, _ = oracle.project(w, cb)
+        codes = oracle.expand(cb, idx_ref.reshape(C_out, C_in))
+        _, Y = oracle.conv_bin(xs, codes, alpha, stride)
+        beta = _beta_near_outputs(g, Y, C_out)
+        want, xs = oracle.conv_sign(xs, codes, alpha, beta, stride)
+        xp, idx = G.subbit_forward_sign(xp, shape, w, cb, alpha, beta, C_out, stride)     # GPU output feeds the GPU's next layer
+        assert (idx.reshape(-1) == idx_ref.reshape(-1)).all(), li
+        assert (xp == want).all(), (li, np.argwhere(xp != want)[:5])
+        shape = (N, C_out, want.shape[2], xs.shape[3])
+
+
 # ---- error paths that need device pointers -----------------------------------------------------------------------
 
 def test_workspace_too_small_is_reported():

@@ -285,3 +285,53 @@ def test_pack_channels_matches_packbits(oracle, C):
     bits[..., :C] = (x >= 0).transpose(0, 2, 3, 1)
     ref = np.packbits(bits, axis=-1, bitorder="little").view(np.uint32).reshape(2, 3, 5, CW)
     assert (got == ref).all()
+
+
+# ---- convolution + the next layer's sign (Alg. 1 forward, chained layers) ---------------------------
+
+@pytest.mark.parametrize("stride,W", [(1, 9), (2, 37), (1, 33)])
+def test_conv_sign_against_brute_force_threshold(oracle, stride, W):
+    """bit = (S * alpha + beta >= 0): with alpha a power of two the fp32 product is exact, so the bit
+    equals the integer comparison S * alpha >= -beta done in exact arithmetic (pure Python), for
+    thresholds that sit exactly on attained values (the >= edge), between them, and for negative alpha
+    (the comparison flips)."""
+    from fractions import Fraction
+    g = np.random.default_rng(300 + W)
+    N, C_in, C_out, H = 2, 5, 6, 7
+    xs = _rand_pm1(g, (N, C_in, H, W))
+    codes = g.integers(0, 512, size=(C_out, C_in)).astype(np.uint16)
+    alpha = np.array([0.5, -0.25, 2.0, 1.0, -1.0, 0.125], dtype=np.float32)
+    beta = np.array([1.5, -0.75, 0.0, -3.0, 5.0, 0.0625], dtype=np.float32)       # exact in fp32, sums exact too
+    S = naive.conv3x3(xs.astype(np.int64), _weights_from_codes(codes), stride)
+    packed, pm1 = oracle.conv_sign(xs, codes, alpha, beta, stride)
+    Ho, Wo = S.shape[2:]
+    assert packed.shape == (N, C_out, Ho, (Wo + 31) // 32) and pm1.shape == S.shape
+    for n in range(N):
+        for co in range(C_out):
+            for ho in range(Ho):
+                for wo in range(Wo):
+                    want = Fraction(int(S[n, co, ho, wo])) * Fraction(float(alpha[co])) + Fraction(float(beta[co])) >= 0
+                    assert (int(packed[n, co, ho, wo // 32]) >> (wo % 32)) & 1 == int(want)
+                    assert pm1[n, co, ho, wo] == (1 if want else -1)
+    # unused high bits of a last word are zero
+    if Wo % 32:
+        assert (packed[..., -1] >> (Wo % 32) == 0).all()
+
+
+def test_conv_sign_rounds_product_then_sum(oracle):
+    """The product is rounded to fp32 before beta is added (no fused multiply-add).  Near 3 the fp32
+    spacing is 2^-22; with alpha = 1 + 2^-23 and S = 3 the exact product 3 + 1.5 * 2^-22 is a tie and
+    rounds to even, 3 + 2 * 2^-22.  beta = -(3 + 2 * 2^-22) then gives exactly 0 -> bit 1, where a
+    fused multiply-add would see -0.5 * 2^-22 -> bit 0."""
+    xs = np.ones((1, 1, 3, 3), dtype=np.int8)
+    xs[0, 0, 0, :] = -1                                      # centre pixel: 6 - 3 with the all-ones kernel
+    codes = np.array([[511]], dtype=np.uint16)
+    alpha = np.array([1.0 + 2.0 ** -23], dtype=np.float32)
+    assert float(alpha[0]) == 1.0 + 2.0 ** -23
+    S, Y = oracle.conv_bin(xs, codes, alpha, 1)
+    assert S[0, 0, 1, 1] == 3
+    assert float(Y[0, 0, 1, 1]) == 3.0 + 2.0 ** -21
+    beta = np.array([-(3.0 + 2.0 ** -21)], dtype=np.float32)
+    assert float(beta[0]) == -(3.0 + 2.0 ** -21)
+    packed, pm1 = oracle.conv_sign(xs, codes, alpha, beta, 1)
+    assert pm1[0, 0, 1, 1] == 1 and (int(packed[0, 0, 1, 0]) >> 1) & 1 == 1
