@@ -306,6 +306,29 @@ def main():
     t_pr = event_time(pack_rows, reps)
     t_pc = event_time(pack_channels, reps)
 
+    # training-side lines of Alg. 1 (not part of the step, which is the forward pass): the straight-through
+    # estimator + gradient of the subset tensor, and the sign-memory update with the repeated-member check
+    for i, s in enumerate(st):
+        L = s["L"]
+        gq = synth.rng(cfg_no, 300 + i)
+        s["g_wbar"] = dev(gq.standard_normal((L.C_out * L.C_in, 9)).astype(np.float32))
+        s["g_w"] = torch.empty_like(s["g_wbar"])
+        s["g_p"] = torch.empty((L.K, 9), dtype=torch.float32, device="cuda")
+        s["p"] = dev((0.01 * gq.standard_normal((L.K, 9))).astype(np.float32))
+        s["m"] = torch.ones((L.K, 9), dtype=torch.int8, device="cuda")
+        s["ws_bwd"] = torch.empty(max(int(B.lib().snn_project_backward_workspace_bytes(L.C_out * L.C_in, L.K)), 256),
+                                  dtype=torch.uint8, device="cuda")
+
+    def project_backward(s):
+        B.snn_project_backward(s["w"], s["g_wbar"], s["idx"], s["L"].K, g_w=s["g_w"], g_p=s["g_p"], workspace=s["ws_bwd"])
+
+    def subset_update(s):
+        B.snn_subset_update(s["p"], s["m"], 1e-3)
+
+    t_pb = event_time(project_backward, reps)
+    t_su = event_time(subset_update, reps)
+    bwd_bytes = sum(L.C_out * L.C_in * (36 + 36 + 2 + 36) for L in layers)
+
     dense_ops = sum(L.dense_ops for L in layers)
     gather_adds = sum(accounting.stage2_gather_adds(L) for L in layers)
     responses = sum(accounting.stage1_responses(L) for L in layers)
@@ -429,6 +452,10 @@ def main():
         "bnn_ms_per_step": ms_per_step_bnn,
         "breakdown_us": {"subbit_conv": sum(t_sub) * 1e3, "bnn_conv": sum(t_bnn) * 1e3, "project": sum(t_proj) * 1e3,
                          "pack_rows": sum(t_pr) * 1e3, "pack_channels": sum(t_pc) * 1e3},
+        "training_side_us": {"project_backward": sum(t_pb) * 1e3, "subset_update": sum(t_su) * 1e3,
+                             "project_backward_GBps": bwd_bytes / (sum(t_pb) * 1e-3) / 1e9,
+                             "note": "per-call HIP-event times summed over the layers (each includes ~8 us of event and "
+                                     "launch overhead); Alg. 1 backward lines, outside the step"},
         "chained_1bit_stack": chained,
         "roofline": roofline,
         "cpu_baseline": cpu,

@@ -175,6 +175,36 @@ int snn_subbit_forward_sign(const snn_conv_desc *desc, const void *x_packed, con
                             void *stream);
 
 /*
+ * Alg. 1 backward, the two lines that touch the kernels of a layer.  Given the gradient w.r.t. the
+ * binarised kernels w_bar (from the convolution's backward pass, which is not part of this library):
+ *   g_w[c][t] = g_wbar[c][t] if -1 < w[c][t] < 1 else 0       (Eq. 3, straight-through estimator, per element)
+ *   g_p[k][t] = sum over the kernels c with idx[c] == k of g_wbar[c][t]
+ *               (the gradient of the subset tensor p, taken as that of its sign memory m:
+ *                backward of Eq. 5 / the p-update of Alg. 1); summed in fp32, per block of 512
+ *                kernels in unspecified order, the block sums then in a fixed order
+ *   w, g_wbar  device, float [n][9];  idx  device, uint16 [n], values < K (as snn_project_kernels wrote them)
+ *   g_w        device, float [n][9], fully overwritten;  g_p  device, float [K][9], fully overwritten
+ *   workspace  device, >= snn_project_backward_workspace_bytes(n, K) bytes, 256-byte aligned
+ * n = 0 is allowed (g_p = 0).  Errors: INVALID_ARG; WORKSPACE; LAUNCH.
+ */
+int snn_project_backward(const float *w, const float *g_wbar, const uint16_t *idx, int64_t n, int K,
+                         float *g_w, float *g_p, void *workspace, size_t ws_bytes, void *stream);
+size_t snn_project_backward_workspace_bytes(int64_t n, int K);
+
+/*
+ * Eq. 4 and the repeated-member check of Sec. 4.3, for one layer's subset:
+ *   m[k][t]     <- sign(p[k][t]) where |p[k][t]| > theta, unchanged elsewhere      (m in {+1, -1})
+ *   codebook[k]  = the 9-bit code of m[k] (tap t at bit 8 - t, +1 -> 1): the subset the next forward pass uses
+ *   dup[k]       = 1 if some j < k has the same code (the caller replaces such members by freshly
+ *                  sampled kernels; the random draw is the caller's), else 0
+ *   p  device, float [K][9];  m  device, int8 [K][9], updated in place;  theta >= 0
+ *   codebook_out  device, uint16 [K];  dup_out  device, uint8 [K]
+ * Errors: INVALID_ARG (null pointers, K outside 1..512, theta negative or NaN); LAUNCH.
+ */
+int snn_subset_update(const float *p, int8_t *m, float theta, int K, uint16_t *codebook_out,
+                      uint8_t *dup_out, void *stream);
+
+/*
  * Sec. 3: the 1-bit layer a = lambda * (w_bar o a_bar), "o" = XNOR + bit count over words of
  * 32 input channels.  The baseline every sub-bit number is compared with.
  *   desc      host; act = SNN_ACT_BIN_CHANNELS (+-1 activations) or SNN_ACT_F32; K ignored

@@ -15,6 +15,8 @@ from .oracle import (  # noqa: F401
     expand,
     conv_bin,
     conv_sign,
+    project_backward,
+    subset_update,
     conv_f32,
     two_stage_bin,
     two_stage_f32,

@@ -186,3 +186,45 @@ def project(w, codebook):
     score = np.empty(n, dtype=np.float32)
     _load().snn_oracle_project(_p(w), ctypes.c_int64(n), _p(codebook), int(codebook.size), _p(idx), _p(score))
     return idx, score
+
+
+# ---- training side (Alg. 1 backward lines); plain numpy, float64 sums ---------------------------------
+
+def project_backward(w, g_wbar, idx, K):
+    """Eq. 3: the straight-through estimator, element by element: the gradient of the binarised kernel
+    passes where -1 < w < 1 and is 0 elsewhere.  Backward of Eq. 5 (Alg. 1, update of p): the gradient
+    of subset member k is the sum of the gradients of the binarised kernels that were assigned to it.
+    w, g_wbar: [n][9] float32; idx: [n].  Returns (g_w float32 [n][9], g_p float64 [K][9])."""
+    w = _c(w, np.float32).reshape(-1, 9)
+    g = _c(g_wbar, np.float32).reshape(-1, 9)
+    idx = np.asarray(idx).reshape(-1).astype(np.int64)
+    assert w.shape == g.shape and idx.shape[0] == w.shape[0]
+    assert idx.size == 0 or (0 <= idx.min() and idx.max() < K)
+    inside = (w > np.float32(-1.0)) & (w < np.float32(1.0))
+    g_w = np.where(inside, g, np.float32(0.0)).astype(np.float32)
+    g_p = np.zeros((K, 9), dtype=np.float64)
+    np.add.at(g_p, idx, g.astype(np.float64))
+    return g_w, g_p
+
+
+def subset_update(p, m, theta):
+    """Eq. 4: m follows sign(p) where |p| > theta and keeps its value elsewhere; then the 9-bit code of
+    every member (tap t at bit 8 - t, +1 -> 1) and, per member, whether an earlier member has the same
+    code (Sec. 4.3: repeated members are to be replaced).  p: [K][9] float32, m: [K][9] in {+1, -1}.
+    Returns (m' int8 [K][9], codes uint16 [K], dup uint8 [K])."""
+    p = _c(p, np.float32).reshape(-1, 9)
+    m = np.asarray(m, dtype=np.int8).reshape(-1, 9)
+    assert p.shape == m.shape and theta >= 0
+    follow = np.abs(p) > np.float32(theta)
+    m2 = np.where(follow, np.where(p > 0, 1, -1), m).astype(np.int8)
+    codes = np.zeros(p.shape[0], dtype=np.uint16)
+    for k in range(p.shape[0]):
+        for t in range(9):
+            if m2[k, t] > 0:
+                codes[k] |= np.uint16(1 << (8 - t))
+    dup = np.zeros(p.shape[0], dtype=np.uint8)
+    seen = set()
+    for k in range(p.shape[0]):
+        dup[k] = 1 if int(codes[k]) in seen else 0
+        seen.add(int(codes[k]))
+    return m2, codes, dup

@@ -28,7 +28,8 @@ SNN_WS_BNN = 1
 SNN_WS_FORWARD = 2
 
 EXPORTS = ("snn_pack_activations", "snn_project_kernels", "snn_subbit_conv2d", "snn_subbit_forward",
-           "snn_subbit_conv2d_sign", "snn_subbit_forward_sign", "snn_bnn_conv2d",
+           "snn_subbit_conv2d_sign", "snn_subbit_forward_sign", "snn_project_backward",
+           "snn_project_backward_workspace_bytes", "snn_subset_update", "snn_bnn_conv2d",
            "snn_workspace_bytes", "snn_packed_bytes", "snn_status_string")
 
 
@@ -69,6 +70,12 @@ def lib():
         L.snn_subbit_conv2d_sign.restype = i32
         L.snn_subbit_forward_sign.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.snn_subbit_forward_sign.restype = i32
+        L.snn_project_backward.argtypes = [vp, vp, vp, i64, i32, vp, vp, vp, sz, vp]
+        L.snn_project_backward.restype = i32
+        L.snn_project_backward_workspace_bytes.argtypes = [i64, i32]
+        L.snn_project_backward_workspace_bytes.restype = sz
+        L.snn_subset_update.argtypes = [vp, vp, ctypes.c_float, i32, vp, vp, vp]
+        L.snn_subset_update.restype = i32
         L.snn_bnn_conv2d.argtypes = [dp, vp, vp, vp, vp, vp, sz, vp]
         L.snn_bnn_conv2d.restype = i32
         L.snn_workspace_bytes.argtypes = [dp, i32]
@@ -243,6 +250,40 @@ def snn_subbit_forward_sign(desc, x, w, codebook, alpha, beta, idx_out=None, out
                                          _ptr(idx_out), _ptr(out), _ptr(workspace), workspace.numel(), _stream()),
            "snn_subbit_forward_sign")
     return out, idx_out
+
+
+def snn_project_backward(w, g_wbar, idx, K, g_w=None, g_p=None, workspace=None):
+    """w, g_wbar float32 [n][9], idx int16 [n] -> (g_w float32 [n][9], g_p float32 [K][9])."""
+    _dev(w, torch.float32, "w")
+    _dev(g_wbar, torch.float32, "g_wbar")
+    _dev(idx, torch.int16, "idx")
+    n = w.numel() // 9
+    if g_wbar.numel() != n * 9 or idx.numel() != n:
+        raise ValueError("w, g_wbar and idx disagree on the number of kernels")
+    if g_w is None:
+        g_w = torch.empty((n, 9), dtype=torch.float32, device=w.device)
+    if g_p is None:
+        g_p = torch.empty((K, 9), dtype=torch.float32, device=w.device)
+    _dev(g_w, torch.float32, "g_w")
+    _dev(g_p, torch.float32, "g_p")
+    if workspace is None:
+        workspace = torch.empty(max(int(lib().snn_project_backward_workspace_bytes(n, K)), 256), dtype=torch.uint8, device=w.device)
+    _check(lib().snn_project_backward(_ptr(w), _ptr(g_wbar), _ptr(idx), n, K, _ptr(g_w), _ptr(g_p), _ptr(workspace),
+                                      workspace.numel(), _stream()), "snn_project_backward")
+    return g_w, g_p
+
+
+def snn_subset_update(p, m, theta):
+    """p float32 [K][9], m int8 [K][9] (updated in place) -> (codebook int16 [K], dup uint8 [K])."""
+    _dev(p, torch.float32, "p")
+    _dev(m, torch.int8, "m")
+    K = p.numel() // 9
+    if m.numel() != K * 9:
+        raise ValueError("p and m disagree on K")
+    cb = torch.empty(K, dtype=torch.int16, device=p.device)
+    dup = torch.empty(K, dtype=torch.uint8, device=p.device)
+    _check(lib().snn_subset_update(_ptr(p), _ptr(m), float(theta), K, _ptr(cb), _ptr(dup), _stream()), "snn_subset_update")
+    return cb, dup
 
 
 def snn_bnn_conv2d(desc, x, w9, alpha, y=None, workspace=None):

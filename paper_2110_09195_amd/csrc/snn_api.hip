@@ -146,6 +146,28 @@ int snn_subbit_forward_sign(const snn_conv_desc *desc, const void *x_packed, con
                                       (hipStream_t)stream);
 }
 
+size_t snn_project_backward_workspace_bytes(int64_t n, int K)
+{
+    if (n < 0 || n >= ((int64_t)1 << 40) || K < 1 || K > 512) return 0;
+    return project_backward_workspace_bytes(n, K);
+}
+
+int snn_project_backward(const float *w, const float *g_wbar, const uint16_t *idx, int64_t n, int K, float *g_w,
+                         float *g_p, void *workspace, size_t ws_bytes, void *stream)
+{
+    if (n < 0 || n >= ((int64_t)1 << 40) || K < 1 || K > 512 || !g_p) return SNN_ERR_INVALID_ARG;
+    if (n > 0 && (!w || !g_wbar || !idx || !g_w)) return SNN_ERR_INVALID_ARG;
+    if (!workspace || ws_bytes < project_backward_workspace_bytes(n, K) || ((uintptr_t)workspace & 255u)) return SNN_ERR_WORKSPACE;
+    return launch_project_backward(w, g_wbar, idx, n, K, g_w, g_p, workspace, (hipStream_t)stream);
+}
+
+int snn_subset_update(const float *p, int8_t *m, float theta, int K, uint16_t *codebook_out, uint8_t *dup_out,
+                      void *stream)
+{
+    if (!p || !m || !codebook_out || !dup_out || K < 1 || K > 512 || !(theta >= 0.0f)) return SNN_ERR_INVALID_ARG;
+    return launch_subset_update(p, m, theta, K, codebook_out, dup_out, (hipStream_t)stream);
+}
+
 int snn_bnn_conv2d(const snn_conv_desc *desc, const void *x, const uint16_t *w9, const float *alpha,
                    float *y_nchw, void *workspace, size_t ws_bytes, void *stream)
 {

@@ -119,6 +119,12 @@ int launch_subbit_forward(const Geom &g, const float *x, const float *w, const u
 // the write-back at the kernel's end (measured: the kernels that follow run faster).
 __device__ inline void store_output(float *p, float v) { __builtin_nontemporal_store(v, p); }
 
+// training side (Alg. 1 backward lines)
+size_t project_backward_workspace_bytes(int64_t n, int K);
+int launch_project_backward(const float *w, const float *g_wbar, const uint16_t *idx, int64_t n, int K, float *g_w,
+                            float *g_p, void *ws, hipStream_t s);
+int launch_subset_update(const float *p, int8_t *m, float theta, int K, uint16_t *codebook, uint8_t *dup, hipStream_t s);
+
 inline int check_launch()
 {
     return hipGetLastError() == hipSuccess ? SNN_OK : SNN_ERR_LAUNCH;

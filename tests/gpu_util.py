@@ -116,3 +116,16 @@ def subbit_forward_sign(xp, shape, w, codebook, alpha, beta, C_out, stride=1):
     torch.cuda.synchronize()
     Ho, Wo = B.out_hw(d)
     return host_u32(out).reshape(N, C_out, Ho, (Wo + 31) // 32), host_u16(idx)
+
+
+def project_backward(w, g_wbar, idx, K):
+    g_w, g_p = B.snn_project_backward(dev(w.reshape(-1, 9)), dev(g_wbar.reshape(-1, 9)), dev(idx.astype(np.uint16)), K)
+    torch.cuda.synchronize()
+    return g_w.cpu().numpy(), g_p.cpu().numpy()
+
+
+def subset_update(p, m, theta):
+    md = torch.from_numpy(np.ascontiguousarray(m.astype(np.int8))).cuda()
+    cb, dup = B.snn_subset_update(dev(p.astype(np.float32)), md, theta)
+    torch.cuda.synchronize()
+    return md.cpu().numpy(), host_u16(cb), dup.cpu().numpy()

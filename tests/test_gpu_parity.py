@@ -474,6 +474,64 @@ def test_subbit_forward_sign_chain(oracle):
         shape = (N, C_out, want.shape[2], xs.shape[3])
 
 
+# ---- training side: Alg. 1 backward lines ------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("n,K", [(1, 1), (7, 4), (512, 32), (513, 32), (5000, 16), (4096, 512), (64 * 64, 32), (512 * 512, 32),
+                                 (100000, 5)])
+def test_project_backward(oracle, n, K):
+    """g_w bit-exact (a select); g_p within the bound of fp32 summation: blocks of 512 kernels are summed
+    in any order, the block sums by 64 lanes and a butterfly, so |error| <= (512 + blocks) * 2^-24 *
+    sum |terms| per entry holds with room to spare."""
+    _say("project_backward", n, K)
+    g = np.random.default_rng(n * 7 + K)
+    w = (1.2 * g.standard_normal((n, 9))).astype(np.float32)
+    w[::17, 3] = 1.0
+    w[5::19, 0] = -1.0
+    gw = g.standard_normal((n, 9)).astype(np.float32)
+    idx = g.integers(0, K, size=n)
+    if n >= 1000:
+        idx[: n // 2] = 0                                   # one heavily used member
+    ref_w, ref_p = oracle.project_backward(w, gw, idx, K)
+    got_w, got_p = G.project_backward(w, gw, idx, K)
+    assert (got_w == ref_w).all()
+    sum_abs = np.zeros((K, 9))
+    np.add.at(sum_abs, idx, np.abs(gw).astype(np.float64))
+    blocks = (n + 511) // 512
+    tol = (512 + blocks) * 2.0 ** -24 * sum_abs + 1e-30
+    assert (np.abs(got_p.astype(np.float64) - ref_p) <= tol).all(), np.abs(got_p - ref_p).max()
+
+
+def test_project_backward_empty():
+    import torch
+    e = torch.empty((0, 9), dtype=torch.float32, device="cuda")
+    g_w, g_p = B.snn_project_backward(e, e, torch.empty(0, dtype=torch.int16, device="cuda"), 8)
+    torch.cuda.synchronize()
+    assert g_w.numel() == 0 and (g_p == 0).all()
+
+
+@pytest.mark.parametrize("K", [1, 2, 16, 32, 64, 300, 512])
+def test_subset_update(oracle, K):
+    _say("subset_update", K)
+    g = np.random.default_rng(60 + K)
+    theta = 1e-3
+    p = (g.standard_normal((K, 9)) * 0.01).astype(np.float32)
+    p[g.random((K, 9)) < 0.3] *= 0.05                      # many weights inside the band
+    p.flat[::7] = theta                                      # exactly on the threshold
+    p.flat[3::11] = -theta
+    p.flat[5::13] = 0.0
+    m = np.where(g.random((K, 9)) < 0.5, 1, -1).astype(np.int8)
+    if K >= 4:                                               # force repeated members
+        p[K - 1] = p[0]
+        m[K - 1] = m[0]
+        p[K // 2] = p[1]
+        m[K // 2] = m[1]
+    ref_m, ref_codes, ref_dup = oracle.subset_update(p, m, theta)
+    got_m, got_codes, got_dup = G.subset_update(p, m, theta)
+    assert (got_m == ref_m).all() and (got_codes == ref_codes).all() and (got_dup == ref_dup).all()
+    if K >= 4:
+        assert ref_dup.sum() >= 2
+
+
 # ---- error paths that need device pointers -----------------------------------------------------------------------
 
 def test_workspace_too_small_is_reported():
