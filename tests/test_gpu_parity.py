@@ -474,6 +474,53 @@ def test_subbit_forward_sign_chain(oracle):
         shape = (N, C_out, want.shape[2], xs.shape[3])
 
 
+# ---- seeded random layers -------------------------------------------------------------------------------------------------
+
+def _random_layers(seed, count):
+    g = np.random.default_rng(seed)
+    out = []
+    while len(out) < count:
+        N = int(g.integers(1, 6))
+        C_in = int(g.choice([1, 2, 3, 7, 16, 33, 64, 100]))
+        C_out = int(g.choice([1, 5, 32, 33, 64, 96, 130, 260]))
+        H = int(g.integers(1, 24))
+        W = int(g.choice([1, 2, 3, 5, 7, 8, 14, 16, 17, 28, 31, 32, 33, 40, 56, 63, 64, 65, 90]))
+        stride = int(g.integers(1, 3))
+        K = int(g.choice([1, 2, 7, 16, 32, 33, 64]))
+        if N * C_in * H * W > 400000 or N * C_out * H * W > 400000:
+            continue
+        out.append((N, C_in, C_out, H, W, stride, K))
+    return out
+
+
+@pytest.mark.parametrize("chunk", range(6))
+def test_random_layers_all_entry_points(oracle, chunk):
+    """Seeded random shapes (tiny images, rows around the word boundaries, odd channel counts, both
+    strides, subsets up to 64) through the plain convolution, the one-call forward and the sign
+    epilogue, each bit-exact against the oracle."""
+    for case in _random_layers(9000 + chunk, 12):
+        N, C_in, C_out, H, W, stride, K = case
+        _say("random layer", case)
+        g = np.random.default_rng(hash(case) % 2**32)
+        x = g.standard_normal((N, C_in, H, W), dtype=np.float32)
+        cb = synth.codebook(g, K)
+        alpha = synth.alpha(g, C_out)
+        w = synth.real_kernels(g, C_out * C_in)
+        idx_ref, _ = oracle.project(w, cb)
+        idx_ref = idx_ref.reshape(C_out, C_in)
+        xs, codes = oracle.sign(x), oracle.expand(cb, idx_ref)
+        _, Y = oracle.conv_bin(xs, codes, alpha, stride)
+        y = G.subbit_bin(x, cb, idx_ref, alpha, stride)
+        assert (y == Y).all(), (case, np.argwhere(y != Y)[:3])
+        y1, idx1 = G.subbit_forward(x, w, cb, alpha, C_out, stride)
+        assert (idx1.reshape(C_out, C_in) == idx_ref).all() and (y1 == Y).all(), case
+        if _matrix_core_layer(case):
+            beta = _beta_near_outputs(g, Y, C_out)
+            want, _ = oracle.conv_sign(xs, codes, alpha, beta, stride)
+            got = G.subbit_sign(oracle.pack_rows(x), x.shape, cb, idx_ref, alpha, beta, stride)
+            assert (got == want).all(), (case, np.argwhere(got != want)[:3])
+
+
 # ---- training side: Alg. 1 backward lines ------------------------------------------------------------------------------
 
 @pytest.mark.parametrize("n,K", [(1, 1), (7, 4), (512, 32), (513, 32), (5000, 16), (4096, 512), (64 * 64, 32), (512 * 512, 32),
