@@ -119,6 +119,23 @@ int snn_subbit_conv2d(const snn_conv_desc *desc, const void *x, const uint16_t *
                       void *workspace, size_t ws_bytes, void *stream);
 
 /*
+ * snn_subbit_conv2d in two halves, for weights that stay fixed over many calls (inference):
+ * snn_subbit_prepare turns codebook, idx and alpha into the tables the convolution reads (one small
+ * launch; to be repeated whenever one of them changes), snn_subbit_conv2d_prepared is the
+ * convolution alone (one launch).  prepare followed by conv2d_prepared on the same stream equals
+ * snn_subbit_conv2d bit for bit.  The environment overrides that select kernels must not change
+ * between the two calls.
+ *   workspace  the same buffer in both calls (>= snn_workspace_bytes(desc, SNN_WS_SUBBIT) bytes,
+ *              256-byte aligned); its contents belong to the library until the weights change
+ *   alpha      the same values in both calls (some kernels read alpha at convolution time)
+ *   everything else as for snn_subbit_conv2d, same errors.
+ */
+int snn_subbit_prepare(const snn_conv_desc *desc, const uint16_t *codebook, const uint16_t *idx,
+                       const float *alpha, void *workspace, size_t ws_bytes, void *stream);
+int snn_subbit_conv2d_prepared(const snn_conv_desc *desc, const void *x, const float *alpha,
+                               float *y_nchw, void *workspace, size_t ws_bytes, void *stream);
+
+/*
  * Alg. 1 forward of one layer in one call: the projection of the layer's real-valued kernels
  * (Eq. 2 / Eq. 5), sign(a) of its fp32 input, and the sub-bit convolution (Sec. 4.5 / Fig. 6) of
  * the two.  idx_out and y_nchw equal, bit for bit, what snn_project_kernels,

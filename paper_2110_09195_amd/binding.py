@@ -28,6 +28,7 @@ SNN_WS_BNN = 1
 SNN_WS_FORWARD = 2
 
 EXPORTS = ("snn_pack_activations", "snn_project_kernels", "snn_subbit_conv2d", "snn_subbit_forward",
+           "snn_subbit_prepare", "snn_subbit_conv2d_prepared",
            "snn_subbit_conv2d_sign", "snn_subbit_forward_sign", "snn_project_backward",
            "snn_project_backward_workspace_bytes", "snn_subset_update", "snn_bnn_conv2d",
            "snn_workspace_bytes", "snn_packed_bytes", "snn_status_string")
@@ -64,6 +65,10 @@ def lib():
         L.snn_project_kernels.restype = i32
         L.snn_subbit_conv2d.argtypes = [dp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.snn_subbit_conv2d.restype = i32
+        L.snn_subbit_prepare.argtypes = [dp, vp, vp, vp, vp, sz, vp]
+        L.snn_subbit_prepare.restype = i32
+        L.snn_subbit_conv2d_prepared.argtypes = [dp, vp, vp, vp, vp, sz, vp]
+        L.snn_subbit_conv2d_prepared.restype = i32
         L.snn_subbit_forward.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.snn_subbit_forward.restype = i32
         L.snn_subbit_conv2d_sign.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
@@ -180,6 +185,26 @@ def snn_subbit_conv2d(desc, x, codebook, idx, alpha, y=None, workspace=None):
         workspace = alloc_workspace(desc, SNN_WS_SUBBIT, x.device)
     _check(lib().snn_subbit_conv2d(ctypes.byref(desc), _ptr(x), _ptr(codebook), _ptr(idx), _ptr(alpha), _ptr(y),
                                    _ptr(workspace), workspace.numel(), _stream()), "snn_subbit_conv2d")
+    return y
+
+
+def snn_subbit_prepare(desc, codebook, idx, alpha, workspace=None):
+    """Weights -> tables in `workspace` (returned); then any number of snn_subbit_conv2d_prepared calls."""
+    _dev(codebook, torch.int16, "codebook")
+    _dev(idx, torch.int16, "idx")
+    _dev(alpha, torch.float32, "alpha")
+    if workspace is None:
+        workspace = alloc_workspace(desc, SNN_WS_SUBBIT, codebook.device)
+    _check(lib().snn_subbit_prepare(ctypes.byref(desc), _ptr(codebook), _ptr(idx), _ptr(alpha), _ptr(workspace),
+                                    workspace.numel(), _stream()), "snn_subbit_prepare")
+    return workspace
+
+
+def snn_subbit_conv2d_prepared(desc, x, alpha, workspace, y=None):
+    _dev(alpha, torch.float32, "alpha")
+    y = _conv_out(desc, y, x.device)
+    _check(lib().snn_subbit_conv2d_prepared(ctypes.byref(desc), _ptr(x), _ptr(alpha), _ptr(y), _ptr(workspace),
+                                            workspace.numel(), _stream()), "snn_subbit_conv2d_prepared")
     return y
 
 

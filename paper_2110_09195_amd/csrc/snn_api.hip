@@ -108,6 +108,28 @@ int snn_subbit_conv2d(const snn_conv_desc *desc, const void *x, const uint16_t *
     return launch_subbit(g, desc->act, x, codebook, idx, alpha, y_nchw, workspace, (hipStream_t)stream);
 }
 
+int snn_subbit_prepare(const snn_conv_desc *desc, const uint16_t *codebook, const uint16_t *idx, const float *alpha,
+                       void *workspace, size_t ws_bytes, void *stream)
+{
+    if (!desc_ok(desc, true) || !codebook || !idx || !alpha) return SNN_ERR_INVALID_ARG;
+    if (!subbit_act_supported(desc->act)) return SNN_ERR_UNSUPPORTED;
+    const Geom g = make_geom(*desc);
+    const size_t need = subbit_workspace_bytes(g, desc->act);
+    if (need > 0 && (!workspace || ws_bytes < need || ((uintptr_t)workspace & 255u))) return SNN_ERR_WORKSPACE;
+    return launch_subbit(g, desc->act, nullptr, codebook, idx, alpha, nullptr, workspace, (hipStream_t)stream, SNN_PHASE_PREPARE);
+}
+
+int snn_subbit_conv2d_prepared(const snn_conv_desc *desc, const void *x, const float *alpha, float *y_nchw,
+                               void *workspace, size_t ws_bytes, void *stream)
+{
+    if (!desc_ok(desc, true) || !x || !alpha || !y_nchw) return SNN_ERR_INVALID_ARG;
+    if (!subbit_act_supported(desc->act)) return SNN_ERR_UNSUPPORTED;
+    const Geom g = make_geom(*desc);
+    const size_t need = subbit_workspace_bytes(g, desc->act);
+    if (need > 0 && (!workspace || ws_bytes < need || ((uintptr_t)workspace & 255u))) return SNN_ERR_WORKSPACE;
+    return launch_subbit(g, desc->act, x, nullptr, nullptr, alpha, y_nchw, workspace, (hipStream_t)stream, SNN_PHASE_CONVOLVE);
+}
+
 int snn_subbit_forward(const snn_conv_desc *desc, const float *x_nchw, const float *w, const uint16_t *codebook,
                        const float *alpha, uint16_t *idx_out, float *y_nchw, void *workspace, size_t ws_bytes,
                        void *stream)

@@ -80,9 +80,14 @@ size_t bnn_workspace_bytes(const Geom &g, int act);
 int launch_bnn(const Geom &g, int act, const void *x, const uint16_t *w9, const float *alpha,
                float *y, void *ws, hipStream_t s);
 
+// A sub-bit convolution is a small preparation kernel (weights -> tables in the workspace) and the
+// convolution proper; callers whose weights stay fixed run the two separately.
+enum : int { SNN_PHASE_PREPARE = 1, SNN_PHASE_CONVOLVE = 2, SNN_PHASE_BOTH = 3 };
+
 size_t subbit_workspace_bytes(const Geom &g, int act);
 int launch_subbit(const Geom &g, int act, const void *x, const uint16_t *codebook,
-                  const uint16_t *idx, const float *alpha, float *y, void *ws, hipStream_t s);
+                  const uint16_t *idx, const float *alpha, float *y, void *ws, hipStream_t s,
+                  int phases = SNN_PHASE_BOTH);
 
 // Optional ending of the sub-bit convolution: instead of y, the next layer's packed rows
 // bit = ((float)S * alpha[co] + beta[co] >= 0), uint32 [N][C_out][H_out][ceil(W_out / 32)].
@@ -95,7 +100,8 @@ struct SignEpilogue {
 bool subbit_mfma_supported(const Geom &g);
 size_t subbit_mfma_workspace_bytes(const Geom &g);
 int launch_subbit_mfma(const Geom &g, const void *x, const uint16_t *codebook, const uint16_t *idx,
-                       const float *alpha, float *y, void *ws, hipStream_t s, const SignEpilogue *sign = nullptr);
+                       const float *alpha, float *y, void *ws, hipStream_t s, const SignEpilogue *sign = nullptr,
+                       int phases = SNN_PHASE_BOTH);
 
 int launch_subbit_forward_mfma(const Geom &g, const float *x, const float *w, const uint16_t *codebook,
                                const float *alpha, uint16_t *idx_out, float *y, uint32_t *xr, void *ws, hipStream_t s,

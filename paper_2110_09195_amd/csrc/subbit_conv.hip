@@ -277,7 +277,7 @@ bool use_mfma(const Geom &g)
 }  // namespace
 
 int launch_subbit_f32(const Geom &g, const void *x, const uint16_t *codebook, const uint16_t *idx,
-                      const float *alpha, float *y, void *ws, hipStream_t s);
+                      const float *alpha, float *y, void *ws, hipStream_t s, int phases);
 size_t subbit_f32_workspace_bytes(const Geom &g);
 
 size_t subbit_workspace_bytes(const Geom &g, int act)
@@ -290,10 +290,10 @@ size_t subbit_workspace_bytes(const Geom &g, int act)
 }
 
 int launch_subbit(const Geom &g, int act, const void *x, const uint16_t *codebook, const uint16_t *idx,
-                  const float *alpha, float *y, void *ws, hipStream_t s)
+                  const float *alpha, float *y, void *ws, hipStream_t s, int phases)
 {
-    if (act == SNN_ACT_F32) return launch_subbit_f32(g, x, codebook, idx, alpha, y, ws, s);
-    if (use_mfma(g)) return launch_subbit_mfma(g, x, codebook, idx, alpha, y, ws, s);
+    if (act == SNN_ACT_F32) return launch_subbit_f32(g, x, codebook, idx, alpha, y, ws, s, phases);
+    if (use_mfma(g)) return launch_subbit_mfma(g, x, codebook, idx, alpha, y, ws, s, nullptr, phases);
 
     const SbPlan pl = make_plan(g);
     const SbCfg &c = pl.cfg;
@@ -316,9 +316,11 @@ int launch_subbit(const Geom &g, int act, const void *x, const uint16_t *codeboo
     const int64_t n_offs = (int64_t)pl.nchunks * pl.COP * 8;
     const int offs_blocks = (int)((n_offs + 255) / 256);
     const int corr_blocks = (pl.COP + 3) / 4;
-    hipLaunchKernelGGL(subbit_prep_kernel, dim3((unsigned)(offs_blocks + corr_blocks)), dim3(256), 0, s, codebook, idx,
-                       g.C_in, g.C_out, pl.COP, g.K, pl.nchunks, offs_blocks, (uint32_t *)prm.codes,
-                       (uint16_t *)prm.offs, (int32_t *)prm.corr);
+    if (phases & SNN_PHASE_PREPARE)
+        hipLaunchKernelGGL(subbit_prep_kernel, dim3((unsigned)(offs_blocks + corr_blocks)), dim3(256), 0, s, codebook, idx,
+                           g.C_in, g.C_out, pl.COP, g.K, pl.nchunks, offs_blocks, (uint32_t *)prm.codes,
+                           (uint16_t *)prm.offs, (int32_t *)prm.corr);
+    if (!(phases & SNN_PHASE_CONVOLVE)) return check_launch();
 
     const dim3 grid((unsigned)tiles, (unsigned)cblocks);
     if (c.J == 1 && c.NW == 1) return launch_direct<1, 1>(pl, prm, grid, s);

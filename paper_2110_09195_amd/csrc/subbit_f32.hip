@@ -158,7 +158,7 @@ size_t subbit_f32_workspace_bytes(const Geom &g)
 }
 
 int launch_subbit_f32(const Geom &g, const void *x, const uint16_t *codebook, const uint16_t *idx,
-                      const float *alpha, float *y, void *ws, hipStream_t s)
+                      const float *alpha, float *y, void *ws, hipStream_t s, int phases)
 {
     const F32Cfg c = pick_f32_cfg(g.C_out);
     const int COP = (g.C_out + c.COB - 1) / c.COB * c.COB;
@@ -172,8 +172,10 @@ int launch_subbit_f32(const Geom &g, const void *x, const uint16_t *codebook, co
     const size_t lds = (size_t)CIC * g.K * SF_TP * sizeof(float) + (size_t)g.K * 9 * sizeof(float);
     if (lds > 160 * 1024) return SNN_ERR_UNSUPPORTED;
     const int64_t nprep = (int64_t)g.C_in * COP + 512;
-    hipLaunchKernelGGL(subbit_f32_prep_kernel, dim3((unsigned)((nprep + 255) / 256)), dim3(256), 0, s, codebook, idx,
-                       g.C_in, g.C_out, COP, g.K, codes, offs);
+    if (phases & SNN_PHASE_PREPARE)
+        hipLaunchKernelGGL(subbit_f32_prep_kernel, dim3((unsigned)((nprep + 255) / 256)), dim3(256), 0, s, codebook, idx,
+                           g.C_in, g.C_out, COP, g.K, codes, offs);
+    if (!(phases & SNN_PHASE_CONVOLVE)) return check_launch();
     const dim3 grid((unsigned)tiles, (unsigned)cblocks);
 #define SNN_F32_CASE(J_)                                                                                       \
     case J_: {                                                                                                 \

@@ -1133,7 +1133,7 @@ int launch_mf_conv(const MfPlan &pl, const MfParams &prm, hipStream_t s)
 }  // namespace
 
 int launch_subbit_mfma(const Geom &g, const void *x, const uint16_t *codebook, const uint16_t *idx,
-                       const float *alpha, float *y, void *ws, hipStream_t s, const SignEpilogue *sign)
+                       const float *alpha, float *y, void *ws, hipStream_t s, const SignEpilogue *sign, int phases)
 {
     const MfPlan pl = mf_plan(g, sign != nullptr);
     if (pl.n_wgs > 0x7fffffffLL || pl.lds > 160 * 1024 || pl.n_pxblocks > 0x7fffffffLL) return SNN_ERR_UNSUPPORTED;
@@ -1142,9 +1142,11 @@ int launch_subbit_mfma(const Geom &g, const void *x, const uint16_t *codebook, c
     const int sel_blocks = (pl.COP / 32) * ((g.C_in + 31) / 32);
     const int corr_blocks = (pl.COP + 3) / 4;
     const int lut_blocks = (512 * (pl.pair ? 6 : 12) + 255) / 256;
-    hipLaunchKernelGGL(subbit_mfma_prep_kernel, dim3((unsigned)(sel_blocks + corr_blocks + lut_blocks)), dim3(256), 0, s,
-                       codebook, idx, g.C_in, g.C_out, pl.COP, pl.cfg.CB, g.K, pl.pair ? 1 : 0, sel_blocks, lut_blocks, alpha,
-                       (uint32_t *)prm.sel, (uint2 *)prm.fin, (uint32_t *)prm.lut, sign ? sign->beta : nullptr);
+    if (phases & SNN_PHASE_PREPARE)
+        hipLaunchKernelGGL(subbit_mfma_prep_kernel, dim3((unsigned)(sel_blocks + corr_blocks + lut_blocks)), dim3(256), 0, s,
+                           codebook, idx, g.C_in, g.C_out, pl.COP, pl.cfg.CB, g.K, pl.pair ? 1 : 0, sel_blocks, lut_blocks, alpha,
+                           (uint32_t *)prm.sel, (uint2 *)prm.fin, (uint32_t *)prm.lut, sign ? sign->beta : nullptr);
+    if (!(phases & SNN_PHASE_CONVOLVE)) return check_launch();
     return launch_mf_conv(pl, prm, s);
 }
 

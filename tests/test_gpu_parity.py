@@ -474,6 +474,33 @@ def test_subbit_forward_sign_chain(oracle):
         shape = (N, C_out, want.shape[2], xs.shape[3])
 
 
+# ---- the convolution in two halves (fixed weights) ----------------------------------------------------------------------
+
+@pytest.mark.parametrize("case", [SUBBIT_CASES[1], SUBBIT_CASES[2], SUBBIT_CASES[9], SUBBIT_CASES[13], SUBBIT_CASES[16]])
+@pytest.mark.parametrize("act", ["bin", "f32"])
+def test_prepare_then_convolve_equals_the_single_call(oracle, case, act):
+    """snn_subbit_prepare once, snn_subbit_conv2d_prepared on two different inputs: each equals
+    snn_subbit_conv2d on that input bit for bit (matrix-core, fallback (K = 100) and fp32 kernels)."""
+    import torch
+    _say("prepare + convolve", case, act)
+    N, C_in, C_out, H, W, stride, K, dist = case
+    x, cb, idx, alpha = _inputs(8000 + sum(case[:7]), N, C_in, C_out, H, W, K, dist)
+    x2 = np.random.default_rng(8001).standard_normal(x.shape, dtype=np.float32)
+    layout = B.SNN_ACT_BIN_ROWS if act == "bin" else B.SNN_ACT_F32
+    d = B.make_desc(N, C_in, C_out, H, W, stride, K, layout)
+    cbd, idxd, ald = G.dev(cb), G.dev(idx), G.dev(alpha)
+    ws = B.snn_subbit_prepare(d, cbd, idxd, ald)
+    for xi in (x, x2):
+        xin = B.snn_pack_activations(G.dev(xi), B.SNN_ACT_BIN_ROWS) if act == "bin" else G.dev(xi)
+        y_two = B.snn_subbit_conv2d_prepared(d, xin, ald, ws)
+        y_one = B.snn_subbit_conv2d(d, xin, cbd, idxd, ald)
+        torch.cuda.synchronize()
+        assert torch.equal(y_two, y_one)
+    if act == "bin":
+        _, Y = oracle.conv_bin(oracle.sign(x2), oracle.expand(cb, idx), alpha, stride)
+        assert (y_two.cpu().numpy() == Y).all()
+
+
 # ---- seeded random layers -------------------------------------------------------------------------------------------------
 
 def _random_layers(seed, count):
