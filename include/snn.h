@@ -180,6 +180,19 @@ int snn_subbit_conv2d_sign(const snn_conv_desc *desc, const void *x_packed, cons
                            void *out_packed, void *workspace, size_t ws_bytes, void *stream);
 
 /*
+ * snn_subbit_conv2d_sign in two halves for fixed weights, like snn_subbit_prepare /
+ * snn_subbit_conv2d_prepared: the tables (thresholds included) once, then one launch per call.
+ * A stack of prepared layers runs with one launch per layer and 1-bit activations throughout.
+ * The workspace of snn_subbit_prepare_sign serves only snn_subbit_conv2d_sign_prepared (and
+ * that of snn_subbit_prepare only snn_subbit_conv2d_prepared).
+ */
+int snn_subbit_prepare_sign(const snn_conv_desc *desc, const uint16_t *codebook, const uint16_t *idx,
+                            const float *alpha, const float *beta, void *workspace, size_t ws_bytes,
+                            void *stream);
+int snn_subbit_conv2d_sign_prepared(const snn_conv_desc *desc, const void *x_packed, void *out_packed,
+                                    void *workspace, size_t ws_bytes, void *stream);
+
+/*
  * The same with the projection of the layer's real-valued kernels in front (Alg. 1 forward of a
  * layer inside a stack): idx_out = project(w) as snn_project_kernels computes it, then
  * snn_subbit_conv2d_sign with it; two launches.

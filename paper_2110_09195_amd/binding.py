@@ -29,7 +29,8 @@ SNN_WS_FORWARD = 2
 
 EXPORTS = ("snn_pack_activations", "snn_project_kernels", "snn_subbit_conv2d", "snn_subbit_forward",
            "snn_subbit_prepare", "snn_subbit_conv2d_prepared",
-           "snn_subbit_conv2d_sign", "snn_subbit_forward_sign", "snn_project_backward",
+           "snn_subbit_conv2d_sign", "snn_subbit_forward_sign", "snn_subbit_prepare_sign",
+           "snn_subbit_conv2d_sign_prepared", "snn_project_backward",
            "snn_project_backward_workspace_bytes", "snn_subset_update", "snn_bnn_conv2d",
            "snn_workspace_bytes", "snn_packed_bytes", "snn_status_string")
 
@@ -73,6 +74,10 @@ def lib():
         L.snn_subbit_forward.restype = i32
         L.snn_subbit_conv2d_sign.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.snn_subbit_conv2d_sign.restype = i32
+        L.snn_subbit_prepare_sign.argtypes = [dp, vp, vp, vp, vp, vp, sz, vp]
+        L.snn_subbit_prepare_sign.restype = i32
+        L.snn_subbit_conv2d_sign_prepared.argtypes = [dp, vp, vp, vp, sz, vp]
+        L.snn_subbit_conv2d_sign_prepared.restype = i32
         L.snn_subbit_forward_sign.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.snn_subbit_forward_sign.restype = i32
         L.snn_project_backward.argtypes = [vp, vp, vp, i64, i32, vp, vp, vp, sz, vp]
@@ -253,6 +258,26 @@ def snn_subbit_conv2d_sign(desc, x, codebook, idx, alpha, beta, out=None, worksp
         workspace = alloc_workspace(desc, SNN_WS_SUBBIT, x.device)
     _check(lib().snn_subbit_conv2d_sign(ctypes.byref(desc), _ptr(x), _ptr(codebook), _ptr(idx), _ptr(alpha), _ptr(beta),
                                         _ptr(out), _ptr(workspace), workspace.numel(), _stream()), "snn_subbit_conv2d_sign")
+    return out
+
+
+def snn_subbit_prepare_sign(desc, codebook, idx, alpha, beta, workspace=None):
+    _dev(codebook, torch.int16, "codebook")
+    _dev(idx, torch.int16, "idx")
+    _dev(alpha, torch.float32, "alpha")
+    _dev(beta, torch.float32, "beta")
+    if workspace is None:
+        workspace = alloc_workspace(desc, SNN_WS_SUBBIT, codebook.device)
+    _check(lib().snn_subbit_prepare_sign(ctypes.byref(desc), _ptr(codebook), _ptr(idx), _ptr(alpha), _ptr(beta),
+                                         _ptr(workspace), workspace.numel(), _stream()), "snn_subbit_prepare_sign")
+    return workspace
+
+
+def snn_subbit_conv2d_sign_prepared(desc, x, workspace, out=None):
+    _dev(x, torch.int32, "x")
+    out = _sign_out(desc, out, x.device)
+    _check(lib().snn_subbit_conv2d_sign_prepared(ctypes.byref(desc), _ptr(x), _ptr(out), _ptr(workspace),
+                                                 workspace.numel(), _stream()), "snn_subbit_conv2d_sign_prepared")
     return out
 
 

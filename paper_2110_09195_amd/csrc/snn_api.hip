@@ -154,6 +154,29 @@ int snn_subbit_conv2d_sign(const snn_conv_desc *desc, const void *x_packed, cons
     return launch_subbit_sign(g, x_packed, codebook, idx, alpha, beta, (uint32_t *)out_packed, workspace, (hipStream_t)stream);
 }
 
+int snn_subbit_prepare_sign(const snn_conv_desc *desc, const uint16_t *codebook, const uint16_t *idx,
+                            const float *alpha, const float *beta, void *workspace, size_t ws_bytes, void *stream)
+{
+    if (!desc_ok(desc, true) || !codebook || !idx || !alpha || !beta) return SNN_ERR_INVALID_ARG;
+    if (desc->act != SNN_ACT_BIN_ROWS) return SNN_ERR_UNSUPPORTED;
+    const Geom g = make_geom(*desc);
+    const size_t need = subbit_workspace_bytes(g, desc->act);
+    if (!workspace || ws_bytes < need || ((uintptr_t)workspace & 255u)) return SNN_ERR_WORKSPACE;
+    return launch_subbit_sign(g, nullptr, codebook, idx, alpha, beta, nullptr, workspace, (hipStream_t)stream, SNN_PHASE_PREPARE);
+}
+
+int snn_subbit_conv2d_sign_prepared(const snn_conv_desc *desc, const void *x_packed, void *out_packed, void *workspace,
+                                    size_t ws_bytes, void *stream)
+{
+    if (!desc_ok(desc, true) || !x_packed || !out_packed) return SNN_ERR_INVALID_ARG;
+    if (desc->act != SNN_ACT_BIN_ROWS) return SNN_ERR_UNSUPPORTED;
+    const Geom g = make_geom(*desc);
+    const size_t need = subbit_workspace_bytes(g, desc->act);
+    if (!workspace || ws_bytes < need || ((uintptr_t)workspace & 255u)) return SNN_ERR_WORKSPACE;
+    return launch_subbit_sign(g, x_packed, nullptr, nullptr, nullptr, nullptr, (uint32_t *)out_packed, workspace,
+                              (hipStream_t)stream, SNN_PHASE_CONVOLVE);
+}
+
 int snn_subbit_forward_sign(const snn_conv_desc *desc, const void *x_packed, const float *w, const uint16_t *codebook,
                             const float *alpha, const float *beta, uint16_t *idx_out, void *out_packed,
                             void *workspace, size_t ws_bytes, void *stream)

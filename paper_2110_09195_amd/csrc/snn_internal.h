@@ -110,7 +110,8 @@ int launch_subbit_forward_mfma(const Geom &g, const float *x, const float *w, co
 // the two calls that end in the sign epilogue (packed rows in, packed rows out); UNSUPPORTED where
 // the matrix-core kernel does not apply
 int launch_subbit_sign(const Geom &g, const void *x_packed, const uint16_t *codebook, const uint16_t *idx,
-                       const float *alpha, const float *beta, uint32_t *out_packed, void *ws, hipStream_t s);
+                       const float *alpha, const float *beta, uint32_t *out_packed, void *ws, hipStream_t s,
+                       int phases = SNN_PHASE_BOTH);
 int launch_subbit_forward_sign(const Geom &g, const void *x_packed, const float *w, const uint16_t *codebook,
                                const float *alpha, const float *beta, uint16_t *idx_out, uint32_t *out_packed, void *ws,
                                hipStream_t s);

@@ -353,11 +353,12 @@ int launch_subbit_forward(const Geom &g, const float *x, const float *w, const u
 
 // ---- convolution + the next layer's binarisation --------------------------------------------------------
 int launch_subbit_sign(const Geom &g, const void *x_packed, const uint16_t *codebook, const uint16_t *idx,
-                       const float *alpha, const float *beta, uint32_t *out_packed, void *ws, hipStream_t s)
+                       const float *alpha, const float *beta, uint32_t *out_packed, void *ws, hipStream_t s, int phases)
 {
     if (!use_mfma(g)) return SNN_ERR_UNSUPPORTED;
+    // the convolution alone needs only the output pointer; a non-null epilogue selects the sign form either way
     const SignEpilogue sign = {beta, out_packed};
-    return launch_subbit_mfma(g, x_packed, codebook, idx, alpha, nullptr, ws, s, &sign);
+    return launch_subbit_mfma(g, x_packed, codebook, idx, alpha, nullptr, ws, s, &sign, phases);
 }
 
 int launch_subbit_forward_sign(const Geom &g, const void *x_packed, const float *w, const uint16_t *codebook,

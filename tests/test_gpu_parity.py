@@ -448,6 +448,36 @@ def test_subbit_conv2d_sign_every_tile_and_split(oracle, tile, split, monkeypatc
         assert (got == want).all(), np.argwhere(got != want)[:5]
 
 
+def test_prepared_sign_stack_equals_the_single_calls(oracle):
+    """Weights of a small stack prepared once, then two different inputs through
+    snn_subbit_conv2d_sign_prepared layer by layer: each layer's output equals the oracle's chain."""
+    import torch
+    g = np.random.default_rng(515)
+    N, H, W = 2, 12, 18
+    chain = [(16, 40, 1, 32), (40, 64, 2, 32), (64, 33, 1, 64)]
+    prepared = []
+    for (C_in, C_out, stride, K) in chain:
+        cb, idx, alpha = synth.codebook(g, K), synth.indices(g, C_out, C_in, K, "uniform"), synth.alpha(g, C_out)
+        beta = (0.5 * g.standard_normal(C_out)).astype(np.float32)
+        prepared.append((cb, idx, alpha, beta))
+    descs, wss = [], []
+    h, w_ = H, W
+    for (C_in, C_out, stride, K), (cb, idx, alpha, beta) in zip(chain, prepared):
+        d = B.make_desc(N, C_in, C_out, h, w_, stride, K, B.SNN_ACT_BIN_ROWS)
+        wss.append(B.snn_subbit_prepare_sign(d, G.dev(cb), G.dev(idx), G.dev(alpha), G.dev(beta)))
+        descs.append(d)
+        h, w_ = B.out_hw(d)
+    for rep in range(2):
+        x = g.standard_normal((N, chain[0][0], H, W), dtype=np.float32)
+        xs = oracle.sign(x)
+        xp = G.dev(oracle.pack_rows(x).reshape(-1))
+        for li, ((C_in, C_out, stride, K), (cb, idx, alpha, beta)) in enumerate(zip(chain, prepared)):
+            want, xs = oracle.conv_sign(xs, oracle.expand(cb, idx), alpha, beta, stride)
+            xp = B.snn_subbit_conv2d_sign_prepared(descs[li], xp, wss[li])
+            torch.cuda.synchronize()
+            assert (G.host_u32(xp).reshape(want.shape) == want).all(), (rep, li)
+
+
 def test_subbit_forward_sign_chain(oracle):
     """A stack of layers passing 1-bit activations: every layer's packed output is the next layer's
     input, on the GPU and in the oracle; compared after every layer."""
