@@ -279,6 +279,31 @@ def test_config5_layers_sampled(oracle, layer_no):
     _sampled_images(oracle, L, 5, layer_no, [0, 63])
 
 
+@pytest.mark.parametrize("layer_no", [0, 4, 5, 9, 12, 15])
+def test_config5_forward_and_sign_sampled(oracle, layer_no):
+    """The calls bench.py's steps are made of, at the full size of the ResNet-18 stack (batch 64): the
+    one-call forward (fp32 output) and the forward ending in the next layer's sign, oracle on two images."""
+    import torch
+    L = synth.resnet18_stack(N=64)[layer_no]
+    g = synth.rng(5, 500 + layer_no)
+    x = synth.activations(g, L.N, L.C_in, L.H, L.W)
+    cb = synth.codebook(g, L.K)
+    w = synth.real_kernels(g, L.C_out * L.C_in)
+    alpha = synth.alpha(g, L.C_out)
+    beta = (0.25 * g.standard_normal(L.C_out)).astype(np.float32)
+    images = [0, 63]
+    idx_ref, _ = oracle.project(w, cb)
+    codes = oracle.expand(cb, idx_ref.reshape(L.C_out, L.C_in))
+    xs = oracle.sign(x[images])
+    _, Y = oracle.conv_bin(xs, codes, alpha, L.stride)
+    want, _ = oracle.conv_sign(xs, codes, alpha, beta, L.stride)
+    y, idx = G.subbit_forward(x, w, cb, alpha, L.C_out, L.stride)
+    assert (idx.reshape(-1) == idx_ref.reshape(-1)).all()
+    assert (y[images] == Y).all()
+    bits, _ = G.subbit_forward_sign(oracle.pack_rows(x), x.shape, w, cb, alpha, beta, L.C_out, L.stride)
+    assert (bits[images] == want).all()
+
+
 # ---- projection ------------------------------------------------------------------------------------------------
 
 @pytest.mark.parametrize("n,K", [(1, 32), (255, 32), (256, 16), (257, 64), (5000, 1), (3000, 512), (70000, 32)])
