@@ -136,6 +136,22 @@ int snn_subbit_conv2d_prepared(const snn_conv_desc *desc, const void *x, const f
                                float *y_nchw, void *workspace, size_t ws_bytes, void *stream);
 
 /*
+ * Sec. 4.4 / Fig. 5: the storage format of a sub-bit layer, tau bits per kernel (tau / 9 bit per
+ * weight).  Index i occupies bits [i * tau, (i + 1) * tau) of a little-endian bit stream of 32-bit
+ * words (bit b of the stream is bit b % 32 of word b / 32); unused high bits of the last word are 0.
+ *   snn_packed_index_bytes(n, tau)   bytes of the stream for n indices (0 for invalid arguments); host-only
+ *   snn_pack_indices                 idx uint16 [n] (values < 2^tau) -> packed, tau in 1..9
+ *   snn_subbit_prepare_packed        snn_subbit_prepare reading the stream directly (the indices are
+ *                                    unpacked inside the preparation kernel); follow with
+ *                                    snn_subbit_conv2d_prepared.  desc->K <= 2^tau; +-1 activations and the
+ *                                    matrix-core kernel only (K <= 64), else UNSUPPORTED.
+ */
+size_t snn_packed_index_bytes(int64_t n, int tau);
+int snn_pack_indices(const uint16_t *idx, int64_t n, int tau, void *packed, void *stream);
+int snn_subbit_prepare_packed(const snn_conv_desc *desc, const uint16_t *codebook, const void *idx_packed,
+                              int tau, const float *alpha, void *workspace, size_t ws_bytes, void *stream);
+
+/*
  * Alg. 1 forward of one layer in one call: the projection of the layer's real-valued kernels
  * (Eq. 2 / Eq. 5), sign(a) of its fp32 input, and the sub-bit convolution (Sec. 4.5 / Fig. 6) of
  * the two.  idx_out and y_nchw equal, bit for bit, what snn_project_kernels,

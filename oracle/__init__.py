@@ -17,6 +17,7 @@ from .oracle import (  # noqa: F401
     conv_sign,
     project_backward,
     subset_update,
+    pack_indices,
     conv_f32,
     two_stage_bin,
     two_stage_f32,

@@ -228,3 +228,15 @@ def subset_update(p, m, theta):
         dup[k] = 1 if int(codes[k]) in seen else 0
         seen.add(int(codes[k]))
     return m2, codes, dup
+
+
+def pack_indices(idx, tau):
+    """Sec. 4.4 / Fig. 5: tau bits per kernel index.  Index i occupies bits [i * tau, (i + 1) * tau)
+    of a little-endian bit stream of 32-bit words.  Returns uint32 [ceil(n * tau / 32)]."""
+    idx = np.asarray(idx).reshape(-1).astype(np.uint32)
+    assert 1 <= tau <= 9 and (idx.size == 0 or int(idx.max()) < (1 << tau))
+    bits = ((idx[:, None] >> np.arange(tau, dtype=np.uint32)[None, :]) & 1).astype(np.uint8).reshape(-1)
+    words = (bits.size + 31) // 32
+    padded = np.zeros(words * 32, dtype=np.uint8)
+    padded[:bits.size] = bits
+    return np.packbits(padded, bitorder="little").view(np.uint32)

@@ -28,7 +28,8 @@ SNN_WS_BNN = 1
 SNN_WS_FORWARD = 2
 
 EXPORTS = ("snn_pack_activations", "snn_project_kernels", "snn_subbit_conv2d", "snn_subbit_forward",
-           "snn_subbit_prepare", "snn_subbit_conv2d_prepared",
+           "snn_subbit_prepare", "snn_subbit_conv2d_prepared", "snn_packed_index_bytes", "snn_pack_indices",
+           "snn_subbit_prepare_packed",
            "snn_subbit_conv2d_sign", "snn_subbit_forward_sign", "snn_subbit_prepare_sign",
            "snn_subbit_conv2d_sign_prepared", "snn_project_backward",
            "snn_project_backward_workspace_bytes", "snn_subset_update", "snn_bnn_conv2d",
@@ -70,6 +71,12 @@ def lib():
         L.snn_subbit_prepare.restype = i32
         L.snn_subbit_conv2d_prepared.argtypes = [dp, vp, vp, vp, vp, sz, vp]
         L.snn_subbit_conv2d_prepared.restype = i32
+        L.snn_packed_index_bytes.argtypes = [i64, i32]
+        L.snn_packed_index_bytes.restype = sz
+        L.snn_pack_indices.argtypes = [vp, i64, i32, vp, vp]
+        L.snn_pack_indices.restype = i32
+        L.snn_subbit_prepare_packed.argtypes = [dp, vp, vp, i32, vp, vp, sz, vp]
+        L.snn_subbit_prepare_packed.restype = i32
         L.snn_subbit_forward.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.snn_subbit_forward.restype = i32
         L.snn_subbit_conv2d_sign.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
@@ -202,6 +209,26 @@ def snn_subbit_prepare(desc, codebook, idx, alpha, workspace=None):
         workspace = alloc_workspace(desc, SNN_WS_SUBBIT, codebook.device)
     _check(lib().snn_subbit_prepare(ctypes.byref(desc), _ptr(codebook), _ptr(idx), _ptr(alpha), _ptr(workspace),
                                     workspace.numel(), _stream()), "snn_subbit_prepare")
+    return workspace
+
+
+def snn_pack_indices(idx, tau):
+    """idx int16 [n] -> int32 words holding tau bits per index."""
+    _dev(idx, torch.int16, "idx")
+    n = idx.numel()
+    out = torch.empty(max(int(lib().snn_packed_index_bytes(n, tau)) // 4, 1), dtype=torch.int32, device=idx.device)
+    _check(lib().snn_pack_indices(_ptr(idx), n, tau, _ptr(out), _stream()), "snn_pack_indices")
+    return out
+
+
+def snn_subbit_prepare_packed(desc, codebook, idx_packed, tau, alpha, workspace=None):
+    _dev(codebook, torch.int16, "codebook")
+    _dev(idx_packed, torch.int32, "idx_packed")
+    _dev(alpha, torch.float32, "alpha")
+    if workspace is None:
+        workspace = alloc_workspace(desc, SNN_WS_SUBBIT, codebook.device)
+    _check(lib().snn_subbit_prepare_packed(ctypes.byref(desc), _ptr(codebook), _ptr(idx_packed), tau, _ptr(alpha),
+                                           _ptr(workspace), workspace.numel(), _stream()), "snn_subbit_prepare_packed")
     return workspace
 
 

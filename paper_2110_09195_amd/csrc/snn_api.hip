@@ -119,6 +119,34 @@ int snn_subbit_prepare(const snn_conv_desc *desc, const uint16_t *codebook, cons
     return launch_subbit(g, desc->act, nullptr, codebook, idx, alpha, nullptr, workspace, (hipStream_t)stream, SNN_PHASE_PREPARE);
 }
 
+size_t snn_packed_index_bytes(int64_t n, int tau)
+{
+    if (n < 0 || n >= ((int64_t)1 << 40) || tau < 1 || tau > 9) return 0;
+    return (size_t)((n * tau + 31) / 32) * sizeof(uint32_t);
+}
+
+int snn_pack_indices(const uint16_t *idx, int64_t n, int tau, void *packed, void *stream)
+{
+    if (n < 0 || n >= ((int64_t)1 << 40) || tau < 1 || tau > 9) return SNN_ERR_INVALID_ARG;
+    if (n == 0) return SNN_OK;
+    if (!idx || !packed) return SNN_ERR_INVALID_ARG;
+    return launch_pack_indices(idx, n, tau, (uint32_t *)packed, (hipStream_t)stream);
+}
+
+int snn_subbit_prepare_packed(const snn_conv_desc *desc, const uint16_t *codebook, const void *idx_packed, int tau,
+                              const float *alpha, void *workspace, size_t ws_bytes, void *stream)
+{
+    if (!desc_ok(desc, true) || !codebook || !idx_packed || !alpha || tau < 1 || tau > 9) return SNN_ERR_INVALID_ARG;
+    if (desc->K > (1 << tau)) return SNN_ERR_INVALID_ARG;
+    if (desc->act != SNN_ACT_BIN_ROWS) return SNN_ERR_UNSUPPORTED;
+    const Geom g = make_geom(*desc);
+    if (!subbit_mfma_supported(g)) return SNN_ERR_UNSUPPORTED;
+    const size_t need = subbit_workspace_bytes(g, desc->act);
+    if (!workspace || ws_bytes < need || ((uintptr_t)workspace & 255u)) return SNN_ERR_WORKSPACE;
+    return launch_subbit_mfma(g, nullptr, codebook, (const uint16_t *)idx_packed, alpha, nullptr, workspace,
+                              (hipStream_t)stream, nullptr, SNN_PHASE_PREPARE, tau);
+}
+
 int snn_subbit_conv2d_prepared(const snn_conv_desc *desc, const void *x, const float *alpha, float *y_nchw,
                                void *workspace, size_t ws_bytes, void *stream)
 {

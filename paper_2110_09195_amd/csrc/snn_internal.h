@@ -101,7 +101,9 @@ bool subbit_mfma_supported(const Geom &g);
 size_t subbit_mfma_workspace_bytes(const Geom &g);
 int launch_subbit_mfma(const Geom &g, const void *x, const uint16_t *codebook, const uint16_t *idx,
                        const float *alpha, float *y, void *ws, hipStream_t s, const SignEpilogue *sign = nullptr,
-                       int phases = SNN_PHASE_BOTH);
+                       int phases = SNN_PHASE_BOTH, int tau = 0);
+// tau > 0: `idx` is a stream of tau-bit indices (see snn_pack_indices) instead of uint16
+int launch_pack_indices(const uint16_t *idx, int64_t n, int tau, uint32_t *out, hipStream_t s);
 
 int launch_subbit_forward_mfma(const Geom &g, const float *x, const float *w, const uint16_t *codebook,
                                const float *alpha, uint16_t *idx_out, float *y, uint32_t *xr, void *ws, hipStream_t s,

@@ -168,6 +168,20 @@ __device__ inline uint2 fin_entry(int corr_term, float a, const float *beta, int
     return make_uint2(__float_as_uint(mult), __float_as_uint(thr));
 }
 
+// Index i of an index tensor: plain uint16 (tau = 0), or tau bits at bit i * tau of a little-endian bit
+// stream of 32-bit words (the storage format of Sec. 4.4 / Fig. 5: tau bits per kernel, tau / 9 per weight).
+__device__ inline uint32_t index_at(const void *__restrict__ idx, int64_t i, int tau)
+{
+    if (tau == 0) return ((const uint16_t *)idx)[i];
+    const uint32_t *w = (const uint32_t *)idx;
+    const int64_t bit = i * tau;
+    const int64_t word = bit >> 5;
+    const int sh = (int)(bit & 31);
+    uint32_t v = w[word] >> sh;
+    if (sh + tau > 32) v |= w[word + 1] << (32 - sh);
+    return v & ((1u << tau) - 1u);
+}
+
 // selector word of subset member k (see below)
 __device__ inline uint32_t sel_word(uint32_t k)
 {
@@ -199,7 +213,7 @@ __device__ inline void store_sel(uint32_t *__restrict__ sel, int COP, int C_in, 
 }
 
 __global__ __launch_bounds__(256)
-void subbit_mfma_prep_kernel(const uint16_t *__restrict__ codebook, const uint16_t *__restrict__ idx, int C_in,
+void subbit_mfma_prep_kernel(const uint16_t *__restrict__ codebook, const void *__restrict__ idx, int tau, int C_in,
                              int C_out, int COP, int CB, int K, int pair, int sel_blocks, int lut_blocks,
                              const float *__restrict__ alpha, uint32_t *__restrict__ sel, uint2 *__restrict__ fin,
                              uint32_t *__restrict__ lut, const float *__restrict__ beta)
@@ -213,7 +227,7 @@ void subbit_mfma_prep_kernel(const uint16_t *__restrict__ codebook, const uint16
         const int co0 = (b % cot) * 32, ci0 = (b / cot) * 32;
         for (int e = tid; e < 1024; e += 256) {
             const int co = co0 + e / 32, ci = ci0 + e % 32;
-            tile[e / 32][e % 32] = (co < C_out && ci < C_in) ? (uint16_t)min((int)idx[(int64_t)co * C_in + ci], K - 1) : 0xffffu;
+            tile[e / 32][e % 32] = (co < C_out && ci < C_in) ? (uint16_t)min((int)index_at(idx, (int64_t)co * C_in + ci, tau), K - 1) : 0xffffu;
         }
         __syncthreads();
         for (int e = tid; e < 1024; e += 256) {
@@ -249,7 +263,7 @@ void subbit_mfma_prep_kernel(const uint16_t *__restrict__ codebook, const uint16
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
                 const int ci = c0 + 64 * u + lane;
-                kk[u] = ci < C_in ? min((int)idx[(int64_t)co * C_in + ci], K - 1) : -1;
+                kk[u] = ci < C_in ? min((int)index_at(idx, (int64_t)co * C_in + ci, tau), K - 1) : -1;
             }
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
@@ -1133,7 +1147,7 @@ int launch_mf_conv(const MfPlan &pl, const MfParams &prm, hipStream_t s)
 }  // namespace
 
 int launch_subbit_mfma(const Geom &g, const void *x, const uint16_t *codebook, const uint16_t *idx,
-                       const float *alpha, float *y, void *ws, hipStream_t s, const SignEpilogue *sign, int phases)
+                       const float *alpha, float *y, void *ws, hipStream_t s, const SignEpilogue *sign, int phases, int tau)
 {
     const MfPlan pl = mf_plan(g, sign != nullptr);
     if (pl.n_wgs > 0x7fffffffLL || pl.lds > 160 * 1024 || pl.n_pxblocks > 0x7fffffffLL) return SNN_ERR_UNSUPPORTED;
@@ -1144,7 +1158,7 @@ int launch_subbit_mfma(const Geom &g, const void *x, const uint16_t *codebook, c
     const int lut_blocks = (512 * (pl.pair ? 6 : 12) + 255) / 256;
     if (phases & SNN_PHASE_PREPARE)
         hipLaunchKernelGGL(subbit_mfma_prep_kernel, dim3((unsigned)(sel_blocks + corr_blocks + lut_blocks)), dim3(256), 0, s,
-                           codebook, idx, g.C_in, g.C_out, pl.COP, pl.cfg.CB, g.K, pl.pair ? 1 : 0, sel_blocks, lut_blocks, alpha,
+                           codebook, (const void *)idx, tau, g.C_in, g.C_out, pl.COP, pl.cfg.CB, g.K, pl.pair ? 1 : 0, sel_blocks, lut_blocks, alpha,
                            (uint32_t *)prm.sel, (uint2 *)prm.fin, (uint32_t *)prm.lut, sign ? sign->beta : nullptr);
     if (!(phases & SNN_PHASE_CONVOLVE)) return check_launch();
     return launch_mf_conv(pl, prm, s);
@@ -1190,6 +1204,36 @@ int launch_subbit_forward_mfma(const Geom &g, const float *x, const float *w, co
     if (blocks > 0x7fffffffLL) return SNN_ERR_UNSUPPORTED;
     hipLaunchKernelGGL(subbit_front_kernel, dim3((unsigned)blocks), dim3(256), 0, s, fp);
     return launch_mf_conv(pl, prm, s);
+}
+
+// ---- tau-bit index storage (Sec. 4.4 / Fig. 5) ---------------------------------------------------------------
+namespace {
+
+// one thread per 32-bit word of the bit stream: it collects the indices that overlap its word
+__global__ __launch_bounds__(256)
+void pack_indices_kernel(const uint16_t *__restrict__ idx, int64_t n, int tau, uint32_t *__restrict__ out, int64_t words)
+{
+    const int64_t wd = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (wd >= words) return;
+    const int64_t bit0 = wd * 32;
+    uint32_t v = 0;
+    for (int64_t i = bit0 / tau; i < n && i * tau < bit0 + 32; ++i) {
+        const int64_t at = i * tau - bit0;               // position of the index's bit 0 in this word
+        const uint32_t k = (uint32_t)idx[i] & ((1u << tau) - 1u);
+        v |= at >= 0 ? k << at : k >> -at;
+    }
+    out[wd] = v;
+}
+
+}  // namespace
+
+int launch_pack_indices(const uint16_t *idx, int64_t n, int tau, uint32_t *out, hipStream_t s)
+{
+    const int64_t words = (n * tau + 31) / 32;
+    const int64_t blocks = (words + 255) / 256;
+    if (blocks > 0x7fffffffLL) return SNN_ERR_INVALID_ARG;
+    if (blocks > 0) hipLaunchKernelGGL(pack_indices_kernel, dim3((unsigned)blocks), dim3(256), 0, s, idx, n, tau, out, words);
+    return check_launch();
 }
 
 }  // namespace snn

@@ -556,6 +556,40 @@ def test_prepare_then_convolve_equals_the_single_call(oracle, case, act):
         assert (y_two.cpu().numpy() == Y).all()
 
 
+# ---- tau-bit index storage ---------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("tau", [1, 4, 5, 6, 9])
+@pytest.mark.parametrize("n", [1, 31, 32, 33, 1000, 64 * 64, 300 * 77])
+def test_pack_indices(oracle, tau, n):
+    import torch
+    g = np.random.default_rng(tau * 1000 + n)
+    idx = g.integers(0, 1 << tau, size=n).astype(np.uint16)
+    got = B.snn_pack_indices(G.dev(idx), tau)
+    torch.cuda.synchronize()
+    want = oracle.pack_indices(idx, tau)
+    assert (G.host_u32(got)[: want.size] == want).all()
+
+
+@pytest.mark.parametrize("case", [(2, 64, 64, 14, 14, 1, 32, 5), (3, 45, 150, 13, 11, 1, 32, 5), (2, 20, 70, 16, 12, 2, 16, 4),
+                                  (2, 24, 40, 9, 11, 1, 64, 6), (1, 7, 8, 5, 70, 1, 40, 6), (2, 33, 70, 14, 14, 2, 7, 3),
+                                  (2, 30, 33, 9, 9, 1, 2, 1)])
+def test_prepare_from_packed_indices(oracle, case):
+    """The preparation kernel reading the tau-bit stream (packed by the oracle) gives the same
+    convolution as the uint16 indices, and that is the oracle's."""
+    import torch
+    _say("prepare from packed indices", case)
+    N, C_in, C_out, H, W, stride, K, tau = case
+    x, cb, idx, alpha = _inputs(8800 + sum(case), N, C_in, C_out, H, W, K)
+    d = B.make_desc(N, C_in, C_out, H, W, stride, K, B.SNN_ACT_BIN_ROWS)
+    packed = oracle.pack_indices(idx, tau)
+    ws = B.snn_subbit_prepare_packed(d, G.dev(cb), G.dev(packed), tau, G.dev(alpha))
+    xin = B.snn_pack_activations(G.dev(x), B.SNN_ACT_BIN_ROWS)
+    y = B.snn_subbit_conv2d_prepared(d, xin, G.dev(alpha), ws)
+    torch.cuda.synchronize()
+    _, Y = oracle.conv_bin(oracle.sign(x), oracle.expand(cb, idx), alpha, stride)
+    assert (y.cpu().numpy() == Y).all()
+
+
 # ---- seeded random layers -------------------------------------------------------------------------------------------------
 
 def _random_layers(seed, count):

@@ -57,3 +57,26 @@ def test_subset_update_hysteresis_codes_and_repeats(oracle):
     m3, _, _ = oracle.subset_update(np.array([[0.0, -0.0, 1e-30, -1e-30, 1, -1, 0, 0, 0]], dtype=np.float32),
                                     -np.ones((1, 9), dtype=np.int8), 0.0)
     assert m3.tolist() == [[-1, -1, 1, -1, 1, -1, -1, -1, -1]]
+
+
+def test_pack_indices_layout_and_ratio(oracle):
+    """Sec. 4.4: tau bits per kernel, i.e. tau / 9 bit per weight.  A hand-written stream, the round
+    trip through plain integer arithmetic, and the size."""
+    # tau = 5: indices 1, 31, 0, 17, 8, 3, 30 -> bits 00001 11111 00000 10001 01000 00011 11110 (LSB first per index)
+    idx = np.array([1, 31, 0, 17, 8, 3, 30], dtype=np.uint16)
+    stream = sum(int(k) << (5 * i) for i, k in enumerate(idx))          # arbitrary-precision integer = the bit stream
+    got = oracle.pack_indices(idx, 5)
+    assert got.size == 2 and int(got[0]) == stream & 0xffffffff and int(got[1]) == stream >> 32
+    g = np.random.default_rng(3)
+    for tau in range(1, 10):
+        n = int(g.integers(1, 400))
+        idx = g.integers(0, 1 << tau, size=n).astype(np.uint16)
+        packed = oracle.pack_indices(idx, tau)
+        big = sum(int(w) << (32 * j) for j, w in enumerate(packed))
+        assert [(big >> (tau * i)) & ((1 << tau) - 1) for i in range(n)] == idx.tolist()
+        assert big >> (tau * n) == 0                                    # unused high bits are zero
+        assert packed.size == (n * tau + 31) // 32
+    # 512 x 512 kernels at tau = 5: 5 / 9 bit per weight against 1 bit for the 1-bit layer
+    n = 512 * 512
+    assert oracle.pack_indices(np.zeros(n, dtype=np.uint16), 5).size * 32 == n * 5
+    assert abs(n * 5 / (n * 9) - 0.556) < 1e-3
