@@ -46,6 +46,9 @@ def parse():
     ap.add_argument("--K", type=int, default=32)
     ap.add_argument("--layer", default=None, help="one custom layer instead of a workload: N,C_in,C_out,H,W,stride")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--headline-only", action="store_true",
+                    help="skip the chained 1-bit stack and the training-side timings (profiling runs: every launch of a "
+                         "kernel then belongs to the headline path or to the 1-bit baseline)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 256 MiB elementwise copy kernel once (reference for the HBM byte counters)")
     return ap.parse_args()
@@ -247,7 +250,7 @@ def main():
     # is packed in between.  Reported next to the headline, not as it: the headline's layers each take
     # their own fp32 input, as the workload is defined.
     chained = None
-    chain_ok = args.workload == "resnet18" and not args.layer and all(
+    chain_ok = not args.headline_only and args.workload == "resnet18" and not args.layer and all(
         a.C_out == b.C_in and a.H_out == b.H and a.W_out == b.W for a, b in zip(layers, layers[1:]))
     if chain_ok:
         for i, s in enumerate(st):
@@ -384,8 +387,8 @@ def main():
     def subset_update(s):
         B.snn_subset_update(s["p"], s["m"], 1e-3)
 
-    t_pb = event_time(project_backward, reps)
-    t_su = event_time(subset_update, reps)
+    t_pb = event_time(project_backward, reps) if not args.headline_only else [0.0] * len(st)
+    t_su = event_time(subset_update, reps) if not args.headline_only else [0.0] * len(st)
     bwd_bytes = sum(L.C_out * L.C_in * (36 + 36 + 2 + 36) for L in layers)
 
     dense_ops = sum(L.dense_ops for L in layers)
@@ -519,7 +522,7 @@ def main():
         "breakdown_us": {"subbit_conv": sum(t_sub) * 1e3, "bnn_conv": sum(t_bnn) * 1e3, "project": sum(t_proj) * 1e3,
                          "pack_rows": sum(t_pr) * 1e3, "pack_channels": sum(t_pc) * 1e3},
         "training_side_us": {"project_backward": sum(t_pb) * 1e3, "subset_update": sum(t_su) * 1e3,
-                             "project_backward_GBps": bwd_bytes / (sum(t_pb) * 1e-3) / 1e9,
+                             "project_backward_GBps": bwd_bytes / (sum(t_pb) * 1e-3) / 1e9 if sum(t_pb) > 0 else None,
                              "note": "per-call HIP-event times summed over the layers (each includes ~8 us of event and "
                                      "launch overhead); Alg. 1 backward lines, outside the step"},
         "chained_1bit_stack": chained,
