@@ -5,10 +5,11 @@
 
 One "step" is one pass of the whole path over one batch of synthetic input, i.e. the forward
 lines of Alg. 1 for every 3x3 layer of the workload: project the real-valued kernels onto the
-layer's subset, binarise and pack the activations, run the sub-bit convolution (stage 1,
-stage 2, alpha scaling) -- one snn_subbit_forward call per layer.  The same work through the
-three separate entry points (snn_project_kernels, snn_pack_activations, snn_subbit_conv2d) is
-timed next to it.  Inputs are resident in HBM before the timed region.  The same layers are
+layer's subset (all layers in one launch, snn_subbit_project_prepare_many), then per layer
+binarise and pack the activations and run the sub-bit convolution (stage 1, stage 2, alpha
+scaling).  The same work as one snn_subbit_forward call per layer and through the three
+separate entry points (snn_project_kernels, snn_pack_activations, snn_subbit_conv2d) is timed
+next to it.  Inputs are resident in HBM before the timed region.  The same layers are
 then run through the library's 1-bit XNOR/popcount kernel (snn_bnn_conv2d on the decoded
 kernels) for the speed-up.
 
@@ -189,9 +190,20 @@ def main():
     # layer.  (Putting the small kernels on side streams, eagerly or as a captured HIP graph, was
     # measured and is slower here: the eager form is bound by the host's launch rate, the graph
     # replay runs the kernels no closer together than the single stream does.)
-    def step():
+    def step_forward_calls():
         for s in st:
             forward(s)
+
+    # the headline step: the weights-side work of all layers in ONE launch (projection + tables:
+    # snn_subbit_project_prepare_many), then per layer sign/pack + convolution (two launches)
+    prep_arr = B.layer_weights_array([{"desc": s["d_sub"], "w": s["w"], "codebook": s["cb"], "alpha": s["alpha"],
+                                       "idx_out": s["idx"], "workspace": s["ws_sub"]} for s in st])
+
+    def step():
+        B.snn_subbit_project_prepare_many(prep_arr)
+        for s in st:
+            pack_rows(s)
+            B.snn_subbit_conv2d_prepared(s["d_sub"], s["xr"], s["alpha"], s["ws_sub"], y=s["y"])
 
     def step_separate():
         for s in st:
@@ -223,6 +235,16 @@ def main():
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
+
+    for _ in range(args.warmup):
+        step_forward_calls()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step_forward_calls()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step_forward_calls = (t1 - t0) * 1e3 / args.steps
 
     for _ in range(args.warmup):
         step_separate()
@@ -259,12 +281,16 @@ def main():
             words = L.N * L.C_out * L.H_out * ((L.W_out + 31) // 32)
             s["out_bits"] = torch.empty(words, dtype=torch.int32, device="cuda")
 
+        for s in st:
+            s["ws_chain"] = B.alloc_workspace(s["d_sub"], B.SNN_WS_SUBBIT)
+        chain_arr = B.layer_weights_array([{"desc": s["d_sub"], "w": s["w"], "codebook": s["cb"], "alpha": s["alpha"],
+                                            "beta": s["beta"], "idx_out": s["idx"], "workspace": s["ws_chain"]} for s in st])
+
         def step_chained():
+            B.snn_subbit_project_prepare_many(chain_arr)
             xin = B.snn_pack_activations(st[0]["x"], B.SNN_ACT_BIN_ROWS, out=st[0]["xr"])
             for s in st:
-                L = s["L"]
-                B.snn_subbit_forward_sign(s["d_sub"], xin, s["w"], s["cb"], s["alpha"], s["beta"],
-                                          idx_out=s["idx"].view(L.C_out, L.C_in), out=s["out_bits"], workspace=s["ws_sub"])
+                B.snn_subbit_conv2d_sign_prepared(s["d_sub"], xin, s["ws_chain"], out=s["out_bits"])
                 xin = s["out_bits"]
 
         for _ in range(args.warmup):
@@ -300,8 +326,8 @@ def main():
                    "ms_per_step_inference": ms_chained_inf,
                    "inference_step": "weights prepared once (snn_subbit_prepare_sign); pack the first input, then one "
                                      "snn_subbit_conv2d_sign_prepared launch per layer",
-                   "step": "pack the first input once, then one snn_subbit_forward_sign per layer (projection + tables, "
-                           "convolution ending in the next layer's sign): 1-bit activations from layer to layer"}
+                   "step": "snn_subbit_project_prepare_many (projection + thresholds + tables of all layers), pack the first "
+                           "input, then one snn_subbit_conv2d_sign_prepared per layer: 1-bit activations from layer to layer"}
 
     # the two kernels must agree (same decoded weights): a cheap end-to-end sanity check
     for s in st:
@@ -449,11 +475,12 @@ def main():
     print("sum: subbit %.1f us, bnn %.1f us, project %.1f us, pack rows %.1f us, pack channels %.1f us; "
           "step %.1f us, bnn step %.1f us" % (sum(t_sub) * 1e3, sum(t_bnn) * 1e3, sum(t_proj) * 1e3, sum(t_pr) * 1e3,
                                                 sum(t_pc) * 1e3, ms_per_step * 1e3, ms_per_step_bnn * 1e3), file=sys.stderr)
+    print("step as one snn_subbit_forward per layer: %.1f us" % (ms_per_step_forward_calls * 1e3), file=sys.stderr)
     print("step as three separate calls per layer: %.1f us" % (ms_per_step_separate * 1e3), file=sys.stderr)
     print("inference step (weights prepared once; pack + conv per layer): %.1f us; conv kernels alone: %.1f us" % (
         ms_per_step_inference * 1e3, sum(t_kern) * 1e3), file=sys.stderr)
     if chained is not None:
-        print("chained 1-bit stack (forward_sign per layer): %.1f us; with prepared weights: %.1f us" % (
+        print("chained 1-bit stack (prepare_many + conv_sign per layer): %.1f us; with prepared weights: %.1f us" % (
             chained["ms_per_step"] * 1e3, chained["ms_per_step_inference"] * 1e3), file=sys.stderr)
 
     # ---- cpu_baseline: the oracle on a bounded sample of the same workload --------------------------------
@@ -508,8 +535,10 @@ def main():
         "dtype": "u8",
         "data": "synthetic",
         "config": {"workload": wname,
-                   "step": "per layer: one snn_subbit_forward call (projection + sign/pack + table preparation in one launch, "
-                           "sub-bit convolution in a second)"},
+                   "step": "snn_subbit_project_prepare_many (projection + tables of all layers, one launch), then per layer "
+                           "snn_pack_activations + snn_subbit_conv2d_prepared"},
+        "ms_per_step_forward_calls": ms_per_step_forward_calls,
+        "forward_calls_step": "one snn_subbit_forward per layer (front kernel + convolution)",
         "ms_per_step_separate_calls": ms_per_step_separate,
         "ms_per_step_inference": ms_per_step_inference,
         "inference_step": "weights prepared once (snn_subbit_prepare); per layer snn_pack_activations + snn_subbit_conv2d_prepared",

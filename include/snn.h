@@ -209,6 +209,31 @@ int snn_subbit_conv2d_sign_prepared(const snn_conv_desc *desc, const void *x_pac
                                     void *workspace, size_t ws_bytes, void *stream);
 
 /*
+ * The weights-side work of a whole stack of layers in ONE launch: for every layer the projection of
+ * its real-valued kernels (Eq. 2 / Eq. 5; idx_out as snn_project_kernels writes it) and the tables
+ * of snn_subbit_prepare (beta == NULL; follow with snn_subbit_conv2d_prepared) or of
+ * snn_subbit_prepare_sign (beta given; follow with snn_subbit_conv2d_sign_prepared).  A training
+ * step's forward pass is then this call plus, per layer, the packing (where the input is fp32) and
+ * one convolution launch.
+ *   layers    host array of n_layers entries (read during the call only); all pointers inside are
+ *             device pointers with the meanings and sizes of the single-layer calls; desc.act must be
+ *             SNN_ACT_BIN_ROWS; workspace: SNN_WS_SUBBIT bytes, 256-byte aligned, one per layer
+ * Errors: INVALID_ARG; UNSUPPORTED if some layer is outside the matrix-core kernel (K > 64, or
+ * C_in = 1 with K <= 32); WORKSPACE; LAUNCH.  On error nothing is enqueued.
+ */
+typedef struct snn_layer_weights {
+    snn_conv_desc desc;
+    const float *w;            /* [C_out][C_in][9] */
+    const uint16_t *codebook;  /* [K] */
+    const float *alpha;        /* [C_out] */
+    const float *beta;         /* [C_out], or NULL for the fp32 output */
+    uint16_t *idx_out;         /* [C_out][C_in] */
+    void *workspace;
+    size_t ws_bytes;
+} snn_layer_weights;
+int snn_subbit_project_prepare_many(const snn_layer_weights *layers, int n_layers, void *stream);
+
+/*
  * The same with the projection of the layer's real-valued kernels in front (Alg. 1 forward of a
  * layer inside a stack): idx_out = project(w) as snn_project_kernels computes it, then
  * snn_subbit_conv2d_sign with it; two launches.

@@ -31,7 +31,7 @@ EXPORTS = ("snn_pack_activations", "snn_project_kernels", "snn_subbit_conv2d", "
            "snn_subbit_prepare", "snn_subbit_conv2d_prepared", "snn_packed_index_bytes", "snn_pack_indices",
            "snn_subbit_prepare_packed",
            "snn_subbit_conv2d_sign", "snn_subbit_forward_sign", "snn_subbit_prepare_sign",
-           "snn_subbit_conv2d_sign_prepared", "snn_project_backward",
+           "snn_subbit_conv2d_sign_prepared", "snn_subbit_project_prepare_many", "snn_project_backward",
            "snn_project_backward_workspace_bytes", "snn_subset_update", "snn_bnn_conv2d",
            "snn_workspace_bytes", "snn_packed_bytes", "snn_status_string")
 
@@ -40,6 +40,12 @@ class snn_conv_desc(ctypes.Structure):
     _fields_ = [("N", ctypes.c_int32), ("C_in", ctypes.c_int32), ("C_out", ctypes.c_int32),
                 ("H", ctypes.c_int32), ("W", ctypes.c_int32), ("stride", ctypes.c_int32),
                 ("K", ctypes.c_int32), ("act", ctypes.c_int32)]
+
+
+class snn_layer_weights(ctypes.Structure):
+    _fields_ = [("desc", snn_conv_desc), ("w", ctypes.c_void_p), ("codebook", ctypes.c_void_p), ("alpha", ctypes.c_void_p),
+                ("beta", ctypes.c_void_p), ("idx_out", ctypes.c_void_p), ("workspace", ctypes.c_void_p),
+                ("ws_bytes", ctypes.c_size_t)]
 
 
 class SnnError(RuntimeError):
@@ -85,6 +91,8 @@ def lib():
         L.snn_subbit_prepare_sign.restype = i32
         L.snn_subbit_conv2d_sign_prepared.argtypes = [dp, vp, vp, vp, sz, vp]
         L.snn_subbit_conv2d_sign_prepared.restype = i32
+        L.snn_subbit_project_prepare_many.argtypes = [ctypes.POINTER(snn_layer_weights), i32, vp]
+        L.snn_subbit_project_prepare_many.restype = i32
         L.snn_subbit_forward_sign.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.snn_subbit_forward_sign.restype = i32
         L.snn_project_backward.argtypes = [vp, vp, vp, i64, i32, vp, vp, vp, sz, vp]
@@ -306,6 +314,37 @@ def snn_subbit_conv2d_sign_prepared(desc, x, workspace, out=None):
     _check(lib().snn_subbit_conv2d_sign_prepared(ctypes.byref(desc), _ptr(x), _ptr(out), _ptr(workspace),
                                                  workspace.numel(), _stream()), "snn_subbit_conv2d_sign_prepared")
     return out
+
+
+def layer_weights_array(layers):
+    """layers: list of dicts with keys desc, w, codebook, alpha, idx_out, workspace and optionally beta
+    (torch tensors) -> a ctypes array for snn_subbit_project_prepare_many; build it once and reuse it
+    (the tensors must stay alive)."""
+    arr = (snn_layer_weights * len(layers))()
+    for i, L in enumerate(layers):
+        _dev(L["w"], torch.float32, "w")
+        _dev(L["codebook"], torch.int16, "codebook")
+        _dev(L["alpha"], torch.float32, "alpha")
+        _dev(L["idx_out"], torch.int16, "idx_out")
+        d = L["desc"]
+        if L["w"].numel() != d.C_out * d.C_in * 9 or L["idx_out"].numel() != d.C_out * d.C_in:
+            raise ValueError("w / idx_out have the wrong size")
+        arr[i].desc = d
+        arr[i].w = L["w"].data_ptr()
+        arr[i].codebook = L["codebook"].data_ptr()
+        arr[i].alpha = L["alpha"].data_ptr()
+        beta = L.get("beta")
+        if beta is not None:
+            _dev(beta, torch.float32, "beta")
+        arr[i].beta = beta.data_ptr() if beta is not None else None
+        arr[i].idx_out = L["idx_out"].data_ptr()
+        arr[i].workspace = L["workspace"].data_ptr()
+        arr[i].ws_bytes = L["workspace"].numel()
+    return arr
+
+
+def snn_subbit_project_prepare_many(arr):
+    _check(lib().snn_subbit_project_prepare_many(arr, len(arr), _stream()), "snn_subbit_project_prepare_many")
 
 
 def snn_subbit_forward_sign(desc, x, w, codebook, alpha, beta, idx_out=None, out=None, workspace=None):

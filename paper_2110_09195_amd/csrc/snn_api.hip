@@ -1,6 +1,8 @@
 // C entry points of the library: argument checks, workspace sizing, dispatch.
 #include "snn_internal.h"
 
+#include <vector>
+
 using namespace snn;
 
 namespace {
@@ -203,6 +205,34 @@ int snn_subbit_conv2d_sign_prepared(const snn_conv_desc *desc, const void *x_pac
     if (!workspace || ws_bytes < need || ((uintptr_t)workspace & 255u)) return SNN_ERR_WORKSPACE;
     return launch_subbit_sign(g, x_packed, nullptr, nullptr, nullptr, nullptr, (uint32_t *)out_packed, workspace,
                               (hipStream_t)stream, SNN_PHASE_CONVOLVE);
+}
+
+int snn_subbit_project_prepare_many(const snn_layer_weights *layers, int n_layers, void *stream)
+{
+    if (n_layers < 0 || (n_layers > 0 && !layers)) return SNN_ERR_INVALID_ARG;
+    if (n_layers == 0) return SNN_OK;
+    std::vector<Geom> gs(n_layers);
+    std::vector<const float *> w(n_layers), alpha(n_layers), beta(n_layers);
+    std::vector<const uint16_t *> cb(n_layers);
+    std::vector<uint16_t *> idx(n_layers);
+    std::vector<void *> ws(n_layers);
+    for (int l = 0; l < n_layers; ++l) {
+        const snn_layer_weights &L = layers[l];
+        if (!desc_ok(&L.desc, true) || !L.w || !L.codebook || !L.alpha || !L.idx_out) return SNN_ERR_INVALID_ARG;
+        if (L.desc.act != SNN_ACT_BIN_ROWS) return SNN_ERR_UNSUPPORTED;
+        gs[l] = make_geom(L.desc);
+        if (!subbit_mfma_supported(gs[l])) return SNN_ERR_UNSUPPORTED;
+        const size_t need = subbit_workspace_bytes(gs[l], SNN_ACT_BIN_ROWS);
+        if (!L.workspace || L.ws_bytes < need || ((uintptr_t)L.workspace & 255u)) return SNN_ERR_WORKSPACE;
+        w[l] = L.w;
+        cb[l] = L.codebook;
+        alpha[l] = L.alpha;
+        beta[l] = L.beta;
+        idx[l] = L.idx_out;
+        ws[l] = L.workspace;
+    }
+    return launch_subbit_prepare_many(n_layers, gs.data(), w.data(), cb.data(), alpha.data(), beta.data(), idx.data(), ws.data(),
+                                      (hipStream_t)stream);
 }
 
 int snn_subbit_forward_sign(const snn_conv_desc *desc, const void *x_packed, const float *w, const uint16_t *codebook,

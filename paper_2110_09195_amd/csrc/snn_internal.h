@@ -109,6 +109,10 @@ int launch_subbit_forward_mfma(const Geom &g, const float *x, const float *w, co
                                const float *alpha, uint16_t *idx_out, float *y, uint32_t *xr, void *ws, hipStream_t s,
                                const SignEpilogue *sign = nullptr);
 
+int launch_subbit_prepare_many(int n_layers, const Geom *gs, const float *const *w, const uint16_t *const *codebook,
+                               const float *const *alpha, const float *const *beta, uint16_t *const *idx_out,
+                               void *const *ws, hipStream_t s);
+
 // the two calls that end in the sign epilogue (packed rows in, packed rows out); UNSUPPORTED where
 // the matrix-core kernel does not apply
 int launch_subbit_sign(const Geom &g, const void *x_packed, const uint16_t *codebook, const uint16_t *idx,

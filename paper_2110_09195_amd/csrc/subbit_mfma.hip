@@ -293,46 +293,30 @@ void subbit_mfma_prep_kernel(const uint16_t *__restrict__ codebook, const void *
 //                       input is packed already
 // The few channel blocks ride along with the bandwidth-bound packing blocks instead of costing two
 // launches of their own.
-struct FrontParams {
-    const float *x;           // activations [rows][W]
-    uint32_t *xr;             // packed rows
-    int64_t rows;
-    int W, WW, rows_per_block, vec;
+// The weights-side work of one layer (what the channel and table roles need).
+struct WeightParams {
     const float *w;           // [C_out][C_in][9]
     const uint16_t *codebook;
     const float *alpha;
+    const float *beta;        // sign epilogue: the finishing table holds thresholds (see fin_entry); else nullptr
     uint16_t *idx_out;        // [C_out][C_in]
     uint32_t *sel;
     uint2 *fin;
     uint32_t *lut;
     int C_in, C_out, COP, CB, K, pair, lut_blocks;
-    const float *beta;        // sign epilogue: the finishing table holds thresholds (see fin_entry); else nullptr
-    int64_t pack_blocks;      // 0: the activations are packed already
 };
+constexpr int FRONT_LDS_WORDS = 64 * 12 + 64 + 4 * 9;   // coef[K][12] floats, zero-bit patterns, per-wave counts
 
-__global__ __launch_bounds__(256)
-void subbit_front_kernel(const FrontParams p)
+// One block = one output channel `co` of a layer: projection of its C_in kernels, index out,
+// selector words, finishing table row.  A thread projects two kernels at a time (input channels
+// tid and tid + 256 of a group of 512); the kernels of the first group are requested before
+// anything else, those of the next group before the current one is worked on, so that the block
+// waits for memory once.
+__device__ inline void weight_channel_block(const WeightParams &p, int co, uint32_t *lds)
 {
-    static_assert(PACK_THREADS == 256, "one block size for all roles");
-    // pack role: PACK_LDS_WORDS words; channel role: coef[K][12] floats, zero-bit patterns, per-wave counts
-    __shared__ __align__(16) uint32_t lds[64 * 12 + 64 + 4 * 9];
     const int tid = threadIdx.x;
-    const int b = blockIdx.x;
-    if (b >= p.COP + p.lut_blocks) {
-        static_assert(PACK_LDS_WORDS <= 64 * 12, "the packing role's bit stream fits");
-        pack_rows_block(p.x, p.xr, p.rows, p.W, p.WW, p.rows_per_block, p.vec, (int64_t)(b - p.COP - p.lut_blocks), lds);
-        return;
-    }
-    if (b >= p.COP) {
-        prep_lut_block(p.codebook, p.K, p.pair, b - p.COP, p.lut);
-        return;
-    }
-    // ---- one output channel ----
-    // A thread projects two kernels at a time (input channels tid and tid + 256 of a group of
-    // 512); the kernels of the first group are requested before anything else, those of the next
-    // group before the current one is worked on, so that the block waits for memory once.
     const int K = p.K, C_in = p.C_in;
-    const int co = b, lane = tid & 63, wave = tid >> 6;
+    const int lane = tid & 63, wave = tid >> 6;
     const bool real = co < p.C_out;               // channels past C_out pad the last wave tile: no member, no output
     auto load_kernels = [&](int c0, float (&d)[2][9]) {
 #pragma unroll
@@ -361,8 +345,17 @@ void subbit_front_kernel(const FrontParams p)
     for (int c0 = 0; c0 < C_in; c0 += 512) {
         float nx[2][9];
         if (c0 + 512 < C_in) load_kernels(c0 + 512, nx);
-        int best[2];
-        project_argmax<2>(wt, coef, K, best);
+        // waves whose 64 input channels lie past C_in have nothing to project; with at most 256 channels
+        // left in the group the second kernel of every thread is empty as well (all wave-uniform)
+        int best[2] = {0, 0};
+        const int wave_ci = c0 + (tid & ~63);
+        if (real && wave_ci + 256 < C_in) {
+            project_argmax<2>(wt, coef, K, best);
+        } else if (real && wave_ci < C_in) {
+            int b1[1];
+            project_argmax<1>(*(const float (*)[1][9]) & wt[0], coef, K, b1);
+            best[0] = b1[0];
+        }
 #pragma unroll
         for (int q = 0; q < 2; ++q) {
             const int ci = c0 + 256 * q + tid;
@@ -394,6 +387,59 @@ void subbit_front_kernel(const FrontParams p)
             if ((inv >> t) & 1u) sum += (int)(wsum[t] + wsum[9 + t] + wsum[18 + t] + wsum[27 + t]);
         p.fin[co * 16 + tid] = fin_entry(2 * sum + (border_valid_taps(tid) - 8) * C_in, a, p.beta, co, real, C_in);
     }
+}
+
+struct FrontParams {
+    const float *x;           // activations [rows][W]
+    uint32_t *xr;             // packed rows
+    int64_t rows;
+    int W, WW, rows_per_block, vec;
+    int64_t pack_blocks;      // 0: the activations are packed already
+    WeightParams wp;
+};
+
+__global__ __launch_bounds__(256)
+void subbit_front_kernel(const FrontParams p)
+{
+    static_assert(PACK_THREADS == 256, "one block size for all roles");
+    static_assert(PACK_LDS_WORDS <= FRONT_LDS_WORDS, "the packing role's bit stream fits");
+    __shared__ __align__(16) uint32_t lds[FRONT_LDS_WORDS];
+    const int b = blockIdx.x;
+    if (b >= p.wp.COP + p.wp.lut_blocks) {
+        pack_rows_block(p.x, p.xr, p.rows, p.W, p.WW, p.rows_per_block, p.vec, (int64_t)(b - p.wp.COP - p.wp.lut_blocks), lds);
+        return;
+    }
+    if (b >= p.wp.COP) {
+        prep_lut_block(p.wp.codebook, p.wp.K, p.wp.pair, b - p.wp.COP, p.wp.lut);
+        return;
+    }
+    weight_channel_block(p.wp, b, lds);
+}
+
+// The weights-side work of up to PREP_MANY_MAX layers in ONE launch (projection, selector /
+// finishing / lookup tables of every layer): the blocks of layer l are [first_block[l], first_block[l + 1]),
+// COP channel blocks followed by the table blocks.
+constexpr int PREP_MANY_MAX = 32;
+struct PrepManyParams {
+    int n_layers;
+    int first_block[PREP_MANY_MAX + 1];
+    WeightParams layer[PREP_MANY_MAX];
+};
+
+__global__ __launch_bounds__(256)
+void subbit_prepare_many_kernel(const PrepManyParams p)
+{
+    __shared__ __align__(16) uint32_t lds[FRONT_LDS_WORDS];
+    const int b = blockIdx.x;
+    int l = 0;
+    while (l + 1 < p.n_layers && b >= p.first_block[l + 1]) ++l;      // block-uniform
+    const WeightParams &wp = p.layer[l];
+    const int lb = b - p.first_block[l];
+    if (lb >= wp.COP) {
+        prep_lut_block(wp.codebook, wp.K, wp.pair, lb - wp.COP, wp.lut);
+        return;
+    }
+    weight_channel_block(wp, lb, lds);
 }
 
 // Buffer accesses: a scalar resource descriptor and scalar offset carry the wave-uniform part of the
@@ -1144,7 +1190,59 @@ int launch_mf_conv(const MfPlan &pl, const MfParams &prm, hipStream_t s)
     return SNN_ERR_UNSUPPORTED;
 }
 
+WeightParams weight_params(const MfPlan &pl, const Geom &g, const MfParams &prm, const float *w, const uint16_t *codebook,
+                           const float *alpha, const float *beta, uint16_t *idx_out)
+{
+    WeightParams wp;
+    wp.w = w;
+    wp.codebook = codebook;
+    wp.alpha = alpha;
+    wp.beta = beta;
+    wp.idx_out = idx_out;
+    wp.sel = (uint32_t *)prm.sel;
+    wp.fin = (uint2 *)prm.fin;
+    wp.lut = (uint32_t *)prm.lut;
+    wp.C_in = g.C_in;
+    wp.C_out = g.C_out;
+    wp.COP = pl.COP;
+    wp.CB = pl.cfg.CB;
+    wp.K = g.K;
+    wp.pair = pl.pair ? 1 : 0;
+    wp.lut_blocks = (512 * (pl.pair ? 6 : 12) + 255) / 256;
+    return wp;
+}
+
 }  // namespace
+
+// Weights-side work of several layers in one launch (groups of PREP_MANY_MAX); every layer must be one
+// the matrix-core kernel takes.  beta[l] non-null: thresholds for the sign epilogue.
+int launch_subbit_prepare_many(int n_layers, const Geom *gs, const float *const *w, const uint16_t *const *codebook,
+                               const float *const *alpha, const float *const *beta, uint16_t *const *idx_out,
+                               void *const *ws, hipStream_t s)
+{
+    for (int l0 = 0; l0 < n_layers; l0 += PREP_MANY_MAX) {
+        PrepManyParams pm;
+        pm.n_layers = n_layers - l0 < PREP_MANY_MAX ? n_layers - l0 : PREP_MANY_MAX;
+        int64_t blocks = 0;
+        for (int i = 0; i < pm.n_layers; ++i) {
+            const int l = l0 + i;
+            const bool sign = beta[l] != nullptr;
+            const MfPlan pl = mf_plan(gs[l], sign);
+            if (pl.n_wgs > 0x7fffffffLL || pl.lds > 160 * 1024 || pl.n_pxblocks > 0x7fffffffLL) return SNN_ERR_UNSUPPORTED;
+            const MfParams prm = mf_params(pl, gs[l], nullptr, nullptr, ws[l], nullptr);
+            pm.layer[i] = weight_params(pl, gs[l], prm, w[l], codebook[l], alpha[l], beta[l], idx_out[l]);
+            pm.first_block[i] = (int)blocks;
+            blocks += pl.COP + pm.layer[i].lut_blocks;
+            if (blocks > 0x7fffffffLL) return SNN_ERR_UNSUPPORTED;
+        }
+        pm.first_block[pm.n_layers] = (int)blocks;
+        for (int i = pm.n_layers + 1; i <= PREP_MANY_MAX; ++i) pm.first_block[i] = (int)blocks;
+        hipLaunchKernelGGL(subbit_prepare_many_kernel, dim3((unsigned)blocks), dim3(256), 0, s, pm);
+        const int rc = check_launch();
+        if (rc != SNN_OK) return rc;
+    }
+    return SNN_OK;
+}
 
 int launch_subbit_mfma(const Geom &g, const void *x, const uint16_t *codebook, const uint16_t *idx,
                        const float *alpha, float *y, void *ws, hipStream_t s, const SignEpilogue *sign, int phases, int tau)
@@ -1185,22 +1283,8 @@ int launch_subbit_forward_mfma(const Geom &g, const float *x, const float *w, co
     fp.rows_per_block = pk.rows_per_block;
     fp.vec = pk.vec;
     fp.pack_blocks = x ? pk.blocks : 0;
-    fp.w = w;
-    fp.codebook = codebook;
-    fp.alpha = alpha;
-    fp.idx_out = idx_out;
-    fp.sel = (uint32_t *)prm.sel;
-    fp.fin = (uint2 *)prm.fin;
-    fp.lut = (uint32_t *)prm.lut;
-    fp.C_in = g.C_in;
-    fp.C_out = g.C_out;
-    fp.COP = pl.COP;
-    fp.CB = pl.cfg.CB;
-    fp.K = g.K;
-    fp.pair = pl.pair ? 1 : 0;
-    fp.lut_blocks = (512 * (pl.pair ? 6 : 12) + 255) / 256;
-    fp.beta = sign ? sign->beta : nullptr;
-    const int64_t blocks = (int64_t)pl.COP + fp.lut_blocks + fp.pack_blocks;
+    fp.wp = weight_params(pl, g, prm, w, codebook, alpha, sign ? sign->beta : nullptr, idx_out);
+    const int64_t blocks = (int64_t)pl.COP + fp.wp.lut_blocks + fp.pack_blocks;
     if (blocks > 0x7fffffffLL) return SNN_ERR_UNSUPPORTED;
     hipLaunchKernelGGL(subbit_front_kernel, dim3((unsigned)blocks), dim3(256), 0, s, fp);
     return launch_mf_conv(pl, prm, s);

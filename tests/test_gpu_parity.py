@@ -503,6 +503,49 @@ def test_prepared_sign_stack_equals_the_single_calls(oracle):
             assert (G.host_u32(xp).reshape(want.shape) == want).all(), (rep, li)
 
 
+def test_project_prepare_many(oracle):
+    """The weights-side work of a mixed stack in one launch (fp32-output layers and sign layers, odd
+    channel counts, K up to 64, more layers than one launch group takes), then one convolution launch
+    per layer: indices, fp32 outputs and packed sign outputs against the oracle."""
+    import torch
+    g = np.random.default_rng(777)
+    shapes = [(2, 24, 40, 9, 11, 1, 32, False), (2, 40, 64, 9, 11, 2, 32, True), (1, 7, 8, 5, 70, 1, 64, False),
+              (3, 45, 150, 13, 11, 1, 32, True), (2, 33, 70, 14, 14, 2, 40, True), (2, 130, 96, 8, 8, 2, 7, False)]
+    shapes = shapes * 6                                   # 36 layers: two launch groups
+    layers, host = [], []
+    for (N, C_in, C_out, H, W, stride, K, sign) in shapes:
+        cb, alpha = synth.codebook(g, K), synth.alpha(g, C_out)
+        w = synth.real_kernels(g, C_out * C_in)
+        beta = (0.5 * g.standard_normal(C_out)).astype(np.float32) if sign else None
+        d = B.make_desc(N, C_in, C_out, H, W, stride, K, B.SNN_ACT_BIN_ROWS)
+        L = {"desc": d, "w": G.dev(w), "codebook": G.dev(cb), "alpha": G.dev(alpha),
+             "idx_out": torch.empty((C_out, C_in), dtype=torch.int16, device="cuda"),
+             "workspace": B.alloc_workspace(d, B.SNN_WS_SUBBIT)}
+        if sign:
+            L["beta"] = G.dev(beta)
+        layers.append(L)
+        host.append((w, cb, alpha, beta))
+    arr = B.layer_weights_array(layers)
+    B.snn_subbit_project_prepare_many(arr)
+    torch.cuda.synchronize()
+    for li, ((N, C_in, C_out, H, W, stride, K, sign), L, (w, cb, alpha, beta)) in enumerate(zip(shapes, layers, host)):
+        idx_ref, _ = oracle.project(w, cb)
+        assert (G.host_u16(L["idx_out"]).reshape(-1) == idx_ref).all(), li
+        x = g.standard_normal((N, C_in, H, W), dtype=np.float32)
+        xs, codes = oracle.sign(x), oracle.expand(cb, idx_ref.reshape(C_out, C_in))
+        xp = G.dev(oracle.pack_rows(x).reshape(-1))
+        if sign:
+            want, _ = oracle.conv_sign(xs, codes, alpha, beta, stride)
+            got = B.snn_subbit_conv2d_sign_prepared(L["desc"], xp, L["workspace"])
+            torch.cuda.synchronize()
+            assert (G.host_u32(got).reshape(want.shape) == want).all(), li
+        else:
+            _, Y = oracle.conv_bin(xs, codes, alpha, stride)
+            y = B.snn_subbit_conv2d_prepared(L["desc"], xp, L["alpha"], L["workspace"])
+            torch.cuda.synchronize()
+            assert (y.cpu().numpy() == Y).all(), li
+
+
 def test_subbit_forward_sign_chain(oracle):
     """A stack of layers passing 1-bit activations: every layer's packed output is the next layer's
     input, on the GPU and in the oracle; compared after every layer."""
