@@ -417,6 +417,32 @@ def main():
     t_su = event_time(subset_update, reps) if not args.headline_only else [0.0] * len(st)
     bwd_bytes = sum(L.C_out * L.C_in * (36 + 36 + 2 + 36) for L in layers)
 
+    # 1x1 layers of a bottleneck network (appendix, Table 5): shapes of ResNet-50 at batch 64, K = 32 members of {+-1}^8
+    conv1x1 = None
+    if not args.headline_only and args.workload == "resnet18" and not args.layer:
+        conv1x1 = []
+        for (ci, co, hw) in [(64, 256, 56), (256, 64, 56), (512, 128, 28), (128, 512, 28), (1024, 256, 14), (2048, 512, 7)]:
+            gq = synth.rng(cfg_no, 400 + ci + co)
+            d1 = B.make_desc(64, ci, co, hw, hw, 1, 32, B.SNN_ACT_BIN_CHANNELS)
+            x1 = torch.randint(-2**31, 2**31 - 1, (B.snn_packed_bytes(64, ci, hw, hw, B.SNN_ACT_BIN_CHANNELS) // 4,),
+                               dtype=torch.int32, device="cuda")
+            cb1 = dev(gq.permutation(256)[:32].astype(np.uint16))
+            idx1 = dev(gq.integers(0, 32, size=(co, ci // 8)).astype(np.uint16))
+            al1 = dev(synth.alpha(gq, co))
+            y1 = torch.empty((64, co, hw, hw), dtype=torch.float32, device="cuda")
+            ws1 = B.alloc_workspace(d1, B.SNN_WS_CONV1X1)
+            B.snn_subbit_conv1x1(d1, x1, cb1, idx1, al1, y=y1, workspace=ws1)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(reps):
+                B.snn_subbit_conv1x1(d1, x1, cb1, idx1, al1, y=y1, workspace=ws1)
+            e1.record()
+            torch.cuda.synchronize()
+            us = e0.elapsed_time(e1) / reps * 1e3
+            ops = 2.0 * ci * co * 64 * hw * hw
+            conv1x1.append({"layer": "%d->%d %dx%d" % (ci, co, hw, hw), "us": us, "gops_eq": ops / (us * 1e-6) / 1e9})
+
     dense_ops = sum(L.dense_ops for L in layers)
     gather_adds = sum(accounting.stage2_gather_adds(L) for L in layers)
     responses = sum(accounting.stage1_responses(L) for L in layers)
@@ -555,6 +581,7 @@ def main():
                              "note": "per-call HIP-event times summed over the layers (each includes ~8 us of event and "
                                      "launch overhead); Alg. 1 backward lines, outside the step"},
         "chained_1bit_stack": chained,
+        "conv1x1_resnet50_shapes": conv1x1,
         "roofline": roofline,
         "cpu_baseline": cpu,
     }

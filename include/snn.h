@@ -63,6 +63,7 @@ extern "C" {
 #define SNN_WS_SUBBIT 0
 #define SNN_WS_BNN    1
 #define SNN_WS_FORWARD 2
+#define SNN_WS_CONV1X1 3
 
 /* One 3x3 layer (Sec. 3 notation: c_in, c_out, H, W of the input). */
 typedef struct snn_conv_desc {
@@ -274,6 +275,28 @@ size_t snn_project_backward_workspace_bytes(int64_t n, int K);
  */
 int snn_subset_update(const float *p, int8_t *m, float theta, int K, uint16_t *codebook_out,
                       uint8_t *dup_out, void *stream);
+
+/*
+ * The extension to 1x1 layers (appendix "Extending to Bottleneck with 1x1 Kernels", Table 5): the
+ * c_out x c_in weights are cut into vectors of 8 consecutive input channels, every vector is a
+ * member of a layer-specific subset of {+-1}^8 (K = 2^tau' members, tau' / 8 bit per weight) and
+ * is stored as its index.  Computed with the same sharing as the 3x3 layer: per pixel and group
+ * of 8 channels the responses of the K members once, then per output channel the gather by
+ * index and the sum over the c_in / 8 groups;  y = alpha * S, no padding, stride 1 or 2.
+ *   desc       host; act must be SNN_ACT_BIN_CHANNELS (+-1 activations, 32 channels per word);
+ *              C_in a multiple of 8; K <= 256 (this build: K <= 64, else UNSUPPORTED)
+ *   x          device, uint32 [N][H][W][ceil(C_in/32)]
+ *   codebook8  device, uint16 [K], 8-bit codes: element j of the vector (input channel 8 g + j) at
+ *              bit 7 - j, +1 -> 1
+ *   idx        device, uint16 [C_out][C_in / 8], values < K
+ *   alpha, y_nchw: as for snn_subbit_conv2d;  H_out = floor((H - 1) / stride) + 1
+ *   workspace  device, >= snn_workspace_bytes(desc, SNN_WS_CONV1X1) bytes, 256-byte aligned
+ * Errors: INVALID_ARG; UNSUPPORTED (other desc->act, C_in not a multiple of 8, K > 64, or
+ * C_in = 8 with K <= 32); WORKSPACE; LAUNCH.
+ */
+int snn_subbit_conv1x1(const snn_conv_desc *desc, const void *x, const uint16_t *codebook8,
+                       const uint16_t *idx, const float *alpha, float *y_nchw, void *workspace,
+                       size_t ws_bytes, void *stream);
 
 /*
  * Sec. 3: the 1-bit layer a = lambda * (w_bar o a_bar), "o" = XNOR + bit count over words of

@@ -18,6 +18,8 @@ from .oracle import (  # noqa: F401
     project_backward,
     subset_update,
     pack_indices,
+    decode8,
+    conv1x1_bin,
     conv_f32,
     two_stage_bin,
     two_stage_f32,

@@ -240,3 +240,28 @@ def pack_indices(idx, tau):
     padded = np.zeros(words * 32, dtype=np.uint8)
     padded[:bits.size] = bits
     return np.packbits(padded, bitorder="little").view(np.uint32)
+
+
+# ---- 1x1 layers (appendix: vectors of 8 input channels from a subset of {+-1}^8) ------------------------
+
+def decode8(code):
+    """8-bit code -> the +-1 vector: element j at bit 7 - j, bit 1 is +1 (the 3x3 reading applied to 8 elements)."""
+    return np.array([1 if (int(code) >> (7 - j)) & 1 else -1 for j in range(8)], dtype=np.int64)
+
+
+def conv1x1_bin(xs, codebook8, idx, alpha, stride=1):
+    """xs: int8 NCHW in {+1,-1}, C_in a multiple of 8; idx: [C_out][C_in / 8] into codebook8.
+    The weight of (c_out, input channel 8 g + j) is element j of member idx[c_out][g]; the layer
+    is the plain 1x1 convolution with those weights on the pixels (stride * h_out, stride * w_out).
+    Returns (S int64, Y float32) [N][C_out][Ho][Wo], Y = (float)S * alpha."""
+    xs = np.asarray(xs, dtype=np.int64)
+    N, C_in, H, W = xs.shape
+    idx = np.asarray(idx).astype(np.int64)
+    C_out, G = idx.shape
+    assert C_in == 8 * G and stride in (1, 2)
+    members = np.stack([decode8(c) for c in np.asarray(codebook8).reshape(-1)])      # [K][8]
+    wmat = members[idx].reshape(C_out, C_in)                                         # [C_out][G][8] -> [C_out][C_in]
+    sub = xs[:, :, ::stride, ::stride]
+    S = np.einsum("oc,nchw->nohw", wmat, sub)
+    Y = (S.astype(np.float32) * _c(alpha, np.float32)[None, :, None, None]).astype(np.float32)
+    return S, Y

@@ -26,10 +26,11 @@ SNN_ACT_F32 = 2
 SNN_WS_SUBBIT = 0
 SNN_WS_BNN = 1
 SNN_WS_FORWARD = 2
+SNN_WS_CONV1X1 = 3
 
 EXPORTS = ("snn_pack_activations", "snn_project_kernels", "snn_subbit_conv2d", "snn_subbit_forward",
            "snn_subbit_prepare", "snn_subbit_conv2d_prepared", "snn_packed_index_bytes", "snn_pack_indices",
-           "snn_subbit_prepare_packed",
+           "snn_subbit_prepare_packed", "snn_subbit_conv1x1",
            "snn_subbit_conv2d_sign", "snn_subbit_forward_sign", "snn_subbit_prepare_sign",
            "snn_subbit_conv2d_sign_prepared", "snn_subbit_project_prepare_many", "snn_project_backward",
            "snn_project_backward_workspace_bytes", "snn_subset_update", "snn_bnn_conv2d",
@@ -101,6 +102,8 @@ def lib():
         L.snn_project_backward_workspace_bytes.restype = sz
         L.snn_subset_update.argtypes = [vp, vp, ctypes.c_float, i32, vp, vp, vp]
         L.snn_subset_update.restype = i32
+        L.snn_subbit_conv1x1.argtypes = [dp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.snn_subbit_conv1x1.restype = i32
         L.snn_bnn_conv2d.argtypes = [dp, vp, vp, vp, vp, vp, sz, vp]
         L.snn_bnn_conv2d.restype = i32
         L.snn_workspace_bytes.argtypes = [dp, i32]
@@ -400,6 +403,20 @@ def snn_subset_update(p, m, theta):
     dup = torch.empty(K, dtype=torch.uint8, device=p.device)
     _check(lib().snn_subset_update(_ptr(p), _ptr(m), float(theta), K, _ptr(cb), _ptr(dup), _stream()), "snn_subset_update")
     return cb, dup
+
+
+def snn_subbit_conv1x1(desc, x, codebook8, idx, alpha, y=None, workspace=None):
+    """x: packed int32 channels layout; codebook8 int16 [K] (8-bit codes); idx int16 [C_out][C_in/8]."""
+    _dev(x, torch.int32, "x")
+    _dev(codebook8, torch.int16, "codebook8")
+    _dev(idx, torch.int16, "idx")
+    _dev(alpha, torch.float32, "alpha")
+    y = _conv_out(desc, y, x.device)
+    if workspace is None:
+        workspace = alloc_workspace(desc, SNN_WS_CONV1X1, x.device)
+    _check(lib().snn_subbit_conv1x1(ctypes.byref(desc), _ptr(x), _ptr(codebook8), _ptr(idx), _ptr(alpha), _ptr(y),
+                                    _ptr(workspace), workspace.numel(), _stream()), "snn_subbit_conv1x1")
+    return y
 
 
 def snn_bnn_conv2d(desc, x, w9, alpha, y=None, workspace=None):

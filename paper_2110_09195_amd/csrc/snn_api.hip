@@ -67,6 +67,11 @@ size_t snn_workspace_bytes(const snn_conv_desc *desc, int which)
         if (!desc_ok(desc, true) || desc->act != SNN_ACT_BIN_ROWS) return 0;
         return subbit_forward_workspace_bytes(make_geom(*desc));
     }
+    if (which == SNN_WS_CONV1X1) {
+        if (!desc_ok(desc, true) || desc->act != SNN_ACT_BIN_CHANNELS) return 0;
+        const Geom g = make_geom(*desc);
+        return subbit_conv1x1_supported(g) ? subbit_conv1x1_workspace_bytes(g) : 0;
+    }
     if (which == SNN_WS_BNN) {
         if (!desc_ok(desc, false) || !bnn_supported(desc)) return 0;
         return bnn_workspace_bytes(make_geom(*desc), desc->act);
@@ -269,6 +274,18 @@ int snn_subset_update(const float *p, int8_t *m, float theta, int K, uint16_t *c
 {
     if (!p || !m || !codebook_out || !dup_out || K < 1 || K > 512 || !(theta >= 0.0f)) return SNN_ERR_INVALID_ARG;
     return launch_subset_update(p, m, theta, K, codebook_out, dup_out, (hipStream_t)stream);
+}
+
+int snn_subbit_conv1x1(const snn_conv_desc *desc, const void *x, const uint16_t *codebook8, const uint16_t *idx,
+                       const float *alpha, float *y_nchw, void *workspace, size_t ws_bytes, void *stream)
+{
+    if (!desc_ok(desc, true) || !x || !codebook8 || !idx || !alpha || !y_nchw || desc->K > 256) return SNN_ERR_INVALID_ARG;
+    if (desc->act != SNN_ACT_BIN_CHANNELS) return SNN_ERR_UNSUPPORTED;
+    const Geom g = make_geom(*desc);
+    if (!subbit_conv1x1_supported(g)) return SNN_ERR_UNSUPPORTED;
+    const size_t need = subbit_conv1x1_workspace_bytes(g);
+    if (!workspace || ws_bytes < need || ((uintptr_t)workspace & 255u)) return SNN_ERR_WORKSPACE;
+    return launch_subbit_conv1x1(g, x, codebook8, idx, alpha, y_nchw, workspace, (hipStream_t)stream);
 }
 
 int snn_bnn_conv2d(const snn_conv_desc *desc, const void *x, const uint16_t *w9, const float *alpha,

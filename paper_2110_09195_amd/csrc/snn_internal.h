@@ -132,6 +132,12 @@ int launch_subbit_forward(const Geom &g, const float *x, const float *w, const u
 // the write-back at the kernel's end (measured: the kernels that follow run faster).
 __device__ inline void store_output(float *p, float v) { __builtin_nontemporal_store(v, p); }
 
+// 1x1 layers: vectors of 8 input channels from a subset of {+-1}^8 (packed-channels input)
+bool subbit_conv1x1_supported(const Geom &g);
+size_t subbit_conv1x1_workspace_bytes(const Geom &g);
+int launch_subbit_conv1x1(const Geom &g, const void *x, const uint16_t *codebook, const uint16_t *idx, const float *alpha,
+                          float *y, void *ws, hipStream_t s);
+
 // training side (Alg. 1 backward lines)
 size_t project_backward_workspace_bytes(int64_t n, int K);
 int launch_project_backward(const float *w, const float *g_wbar, const uint16_t *idx, int64_t n, int K, float *g_w,

@@ -57,7 +57,9 @@ struct MfParams {
     // bit = ((float)S * alpha[co] + beta[co] >= 0), packed rows [N][C_out][H_out][ceil(W_out / 32)];
     // `fin` then holds thresholds (fin_entry)
     uint32_t *sign_out;
-    int n_pxblocks;           // blocks of up to 32 pixels (see PixelMap)
+    int n_pxblocks;           // blocks of up to 32 pixels (see pixel_of)
+    // 1x1 layers (WM == 3): x is packed channels [N][H][W][cw_bytes / 4]; g.C_in counts groups of 8 input channels
+    uint32_t x_bytes, cw_bytes;
     Geom g;
     int COP;                  // C_out padded to whole wave tiles
     int KS;                   // waves that split the channel pairs of one tile: 1, 2 or 4
@@ -100,18 +102,22 @@ __host__ __device__ inline uint32_t fp6_of_int(int v)
 //     zero bits of the selected code at the taps that border type `type` puts outside the image
 //   lut[window] = 32 FP6 codes of m_k - 4 (0 for k >= K)
 // one thread per 32-bit word of the table; a row is 6 words of 32 FP6 codes per lane half
-__device__ inline void prep_lut_block(const uint16_t *__restrict__ codebook, int K, int pair, int block, uint32_t *__restrict__ lut)
+// `taps` = 9: 512 rows indexed by the 3x3 window; `taps` = 8 (1x1 layers): 256 rows indexed by the signs
+// of 8 consecutive input channels, member element j at code bit 7 - j, channel 8 g + j at window bit j.
+__device__ inline void prep_lut_block(const uint16_t *__restrict__ codebook, int K, int pair, int block, uint32_t *__restrict__ lut,
+                                      int taps = 9)
 {
     const int wpr = pair ? 6 : 12;
     const int i = block * 256 + (int)threadIdx.x;
-    if (i < 512 * wpr) {
+    if (i < (taps == 9 ? 512 : 256) * wpr) {
         const int win = i / wpr, wh = i - win * wpr;
         const int half = wh / 6, w = wh - 6 * half;
         uint32_t word = 0;
         for (int kl = (32 * w) / 6; kl <= (32 * w + 31) / 6; ++kl) {
             const int k = 32 * half + kl;
             if (k >= K) break;
-            const int m = 9 - __popc((uint32_t)win ^ code_to_window_order(codebook[k] & 511u));
+            const int m = taps == 9 ? 9 - __popc((uint32_t)win ^ code_to_window_order(codebook[k] & 511u))
+                                    : 8 - __popc(((uint32_t)win ^ (__brev((uint32_t)codebook[k] & 255u) >> 24)) & 255u);
             const int at = 6 * kl - 32 * w;                // position of the code's bit 0 in this word
             const uint32_t code = fp6_of_int(m - 4);
             word |= at >= 0 ? code << at : code >> -at;
@@ -216,7 +222,7 @@ __global__ __launch_bounds__(256)
 void subbit_mfma_prep_kernel(const uint16_t *__restrict__ codebook, const void *__restrict__ idx, int tau, int C_in,
                              int C_out, int COP, int CB, int K, int pair, int sel_blocks, int lut_blocks,
                              const float *__restrict__ alpha, uint32_t *__restrict__ sel, uint2 *__restrict__ fin,
-                             uint32_t *__restrict__ lut, const float *__restrict__ beta)
+                             uint32_t *__restrict__ lut, const float *__restrict__ beta, int taps)
 {
     const int tid = threadIdx.x;
     const int b = blockIdx.x;
@@ -243,7 +249,13 @@ void subbit_mfma_prep_kernel(const uint16_t *__restrict__ codebook, const void *
         return;
     }
     if (b >= (int)gridDim.x - lut_blocks) {
-        prep_lut_block(codebook, K, pair, b - ((int)gridDim.x - lut_blocks), lut);
+        prep_lut_block(codebook, K, pair, b - ((int)gridDim.x - lut_blocks), lut, taps);
+        return;
+    }
+    if (taps == 8) {
+        // 1x1 layers have no border: S = 2 acc, nothing to correct
+        const int co = (b - sel_blocks) * 4 + (tid >> 6);
+        if (co < COP && (tid & 63) < 16) fin[co * 16 + (tid & 63)] = make_uint2(0u, __float_as_uint(co < C_out ? alpha[co] : 0.0f));
         return;
     }
     // one wave per output channel; the zero-bit patterns of the K codes go through LDS so that the
@@ -491,6 +503,10 @@ __global__ __launch_bounds__(MF_WAVES * 64, 2)
 void subbit_mfma_kernel(const MfParams p)
 {
     static_assert(!STG || WM == 1 || WM == 2, "staging needs rows that are consecutive in memory");
+    // WM == 3: a 1x1 layer.  The "window" of a pixel and step is the byte of the signs of 8 consecutive
+    // input channels (packed-channels input), a "channel" of the steps is such a group of 8, the table
+    // has 256 rows of match counts m_k - 4 out of 8, there is no border, and S = 2 acc.
+    constexpr bool ONE = WM == 3;
     constexpr int NBLK = PB * CB;
     constexpr int MF_LROW = mf_lrow(PAIR);
     const Geom &g = p.g;
@@ -566,7 +582,7 @@ void subbit_mfma_kernel(const MfParams p)
     // The lookup table image was built once by the preparation kernel.  Its words are requested
     // first of all, so that they travel while the lanes work out their geometry.
     constexpr int HALVES = PAIR ? 1 : 2;
-    constexpr int LUT_WORDS = 512 * 6 * HALVES / (MF_WAVES * 64);     // per thread
+    constexpr int LUT_WORDS = (WM == 3 ? 256 : 512) * 6 * HALVES / (MF_WAVES * 64);     // per thread
     uint32_t lutw[LUT_WORDS];
 #pragma unroll
     for (int i = 0; i < LUT_WORDS; ++i) lutw[i] = p.lut[i * (MF_WAVES * 64) + tid];
@@ -611,6 +627,12 @@ void subbit_mfma_kernel(const MfParams p)
         int n, ho, wo;
         const bool ok = pixel_of(pb, n_l, n, ho, wo);
         yoff[pb] = ok ? (uint32_t)((n * g.C_out + 4 * h) * g.HoWo + ho * g.Wo + wo) * 4u : 0xffffffffu;
+        if constexpr (ONE) {
+            ptype[pb] = 0;
+            xoff[pb] = (uint32_t)((n * g.H + ho * g.stride) * g.W + wo * g.stride) * p.cw_bytes;
+            sh[pb] = m7[pb] = lsh[pb] = vm[pb] = loff[pb] = 0;
+            continue;
+        }
         ptype[pb] = border_type(ho, wo, g.H, g.W, g.stride);
         vm[pb] = ~border_invalid_window(ptype[pb]) & 0x1ffu;
         const int hc = ho * g.stride, first = wo * g.stride - 1;
@@ -623,17 +645,27 @@ void subbit_mfma_kernel(const MfParams p)
         xoff[pb] = (uint32_t)(((n * g.C_in + (PAIR ? h : 0)) * g.H + (hc == 0 ? 0 : hc - 1)) * g.WW + jlo) * 4u;
         loff[pb] = stage_wave + (uint32_t)((PAIR ? h * MF_STAGE_SLOTS : 0) + (n * g.H + (hc == 0 ? 0 : hc - 1) - R_first) * SW + piece) * 4u;
     }
-    const __amdgpu_buffer_rsrc_t xres = make_rsrc(p.x, (uint32_t)g.N * (uint32_t)g.C_in * plane_bytes);
+    const __amdgpu_buffer_rsrc_t xres = make_rsrc(p.x, ONE ? p.x_bytes : (uint32_t)g.N * (uint32_t)g.C_in * plane_bytes);
     const uint32_t lut_base = (uint32_t)(uintptr_t)smem;
 
     constexpr bool ONE_WORD = WM == 1 || STG;      // a lane cuts its window row out of one 32-bit piece
     struct Raw {
-        uint32_t lo[PB][3], hi[ONE_WORD ? 1 : PB][3];
+        uint32_t lo[PB][3], hi[ONE_WORD || ONE ? 1 : PB][3];
+        uint32_t byte_shift;                       // 1x1: position of the lane's group inside the word loaded
     };
     // step c -> first channel of the pair (the last step of an odd C_in starts one channel early)
     const int last_first = g.C_in - 2;
     const uint32_t row_bytes = (uint32_t)g.WW * 4u;
     auto load_raw = [&](int c, Raw &r) {
+        if constexpr (ONE) {
+            // the word that holds the lane's group of 8 channels (4 groups per word)
+            const uint32_t grp = (uint32_t)(PAIR ? min(2 * c, last_first) + h : c);
+            const uint32_t word_off = (grp >> 2) << 2;
+            r.byte_shift = (grp & 3u) << 3;
+#pragma unroll
+            for (int pb = 0; pb < PB; ++pb) r.lo[pb][0] = buf_load1(xres, xoff[pb] + word_off, 0u);
+            return;
+        }
         const uint32_t co = (uint32_t)(PAIR ? min(2 * c, last_first) : c) * plane_bytes;
 #pragma unroll
         for (int pb = 0; pb < PB; ++pb) {
@@ -699,12 +731,17 @@ void subbit_mfma_kernel(const MfParams p)
     auto make_B = [&](const Raw &r, v8i (&B)[PB]) {
 #pragma unroll
         for (int pb = 0; pb < PB; ++pb) {
-            uint32_t row[3];
+            uint32_t w;
+            if constexpr (ONE) {
+                w = (r.lo[pb][0] >> r.byte_shift) & 0xffu;
+            } else {
+                uint32_t row[3];
 #pragma unroll
-            for (int dy = 0; dy < 3; ++dy)
-                row[dy] = __builtin_amdgcn_alignbit(ONE_WORD ? r.lo[pb][dy] : r.hi[pb][dy], r.lo[pb][dy], sh[pb]);
-            const uint32_t m = m7[pb];
-            const uint32_t w = (((row[0] & m) | ((row[1] & m) << 3) | ((row[2] & m) << 6)) << lsh[pb]) & vm[pb];
+                for (int dy = 0; dy < 3; ++dy)
+                    row[dy] = __builtin_amdgcn_alignbit(ONE_WORD ? r.lo[pb][dy] : r.hi[pb][dy], r.lo[pb][dy], sh[pb]);
+                const uint32_t m = m7[pb];
+                w = (((row[0] & m) | ((row[1] & m) << 3) | ((row[2] & m) << 6)) << lsh[pb]) & vm[pb];
+            }
             const uint32_t addr = lut_base + w * MF_LROW + (PAIR ? 0u : 32u * (uint32_t)h);
             const u32x4 q0 = *(lds_cu32x4 *)(uintptr_t)addr;
             const u32x2 q1 = *(lds_cu32x2 *)(uintptr_t)(addr + 16);
@@ -737,7 +774,7 @@ void subbit_mfma_kernel(const MfParams p)
     // sets).  Deeper rings where a step's loads are few registers.  With staging the rows come out of
     // LDS two steps ahead (two sets again, so that no LDS read is waited for in the step that issues
     // it), and the one staged word per step sits in a ring of its own, SRING steps ahead.
-    constexpr int RAW_REGS = (STG ? 0 : PB * (WM == 1 ? 3 : 6)) + CB;
+    constexpr int RAW_REGS = (STG ? 0 : WM == 3 ? PB + 1 : PB * (WM == 1 ? 3 : 6)) + CB;
     constexpr int RING = RAW_REGS <= 16 ? 3 : 2;
     constexpr int SRING = 6;
     constexpr int UNROLL = STG ? 6 : RING % 2 == 0 ? RING : 2 * RING;
@@ -804,7 +841,7 @@ void subbit_mfma_kernel(const MfParams p)
                     acc[cb][pb] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(A[cur][cb], B[cur][pb], acc[cb][pb], 4 /* A: FP4 */,
                                                                                   2 /* B: FP6 e2m3 */, 0, 127, 0, 127);
             constexpr int NMF = CB * PB;
-            constexpr int NVM = (STG ? 1 : PB * (WM == 1 ? 1 : WM == 2 ? 2 : 3)) + 1;   // loads of a step
+            constexpr int NVM = (STG ? 1 : PB * (WM == 1 || WM == 3 ? 1 : WM == 2 ? 2 : 3)) + 1;   // loads of a step
             constexpr int NDS = 2 * PB + (STG ? PB * 2 : 0);                     // LDS reads of a step
             constexpr int DS_PER = (NDS + NMF - 1) / NMF;
             constexpr int NVA = PB * 11 + CB * 4 + 4;                       // vector ALU instructions of a step (estimate)
@@ -1033,6 +1070,7 @@ struct MfPlan {
     MfCfg cfg;
     bool pair;        // K <= 32: two input channels per step
     bool stage;       // the rows of a tile fit the staging slots
+    bool one;         // 1x1 layer (g.C_in = groups of 8 input channels)
     int KS, COP, n_cotiles, npairs;
     long long n_pxblocks, n_pxtiles, n_tiles, n_wgs;
     size_t lds;
@@ -1056,9 +1094,10 @@ int64_t mf_pxblocks(const Geom &g, bool aligned)
     return (int64_t)g.N * g.Ho * ((g.Wo + 31) / 32);
 }
 
-MfPlan mf_plan(const Geom &g, bool aligned = false)
+MfPlan mf_plan(const Geom &g, bool aligned = false, bool one = false)
 {
     MfPlan pl;
+    pl.one = one;
     // tile of a wave: 128 accumulator registers (PB x CB = 8); few channels -> more pixels per wave
     if (g.C_out <= 64) pl.cfg = {4, 2};
     else pl.cfg = {2, 4};
@@ -1092,9 +1131,9 @@ MfPlan mf_plan(const Geom &g, bool aligned = false)
     // matrix instructions per window (measured; with four blocks the loop is bound by the matrix pipe
     // and the extra LDS traffic costs a little).  SNN_MFMA_STAGE = 1 / 0 forces it on wherever it fits / off.
     const int stage_env = env_int("SNN_MFMA_STAGE", -1);
-    pl.stage = g.WW <= 2 && tile_rows * (g.WW == 2 ? 3 : 1) <= MF_STAGE_SLOTS &&
+    pl.stage = !one && g.WW <= 2 && tile_rows * (g.WW == 2 ? 3 : 1) <= MF_STAGE_SLOTS &&
                (stage_env < 0 ? pl.cfg.CB == 2 : stage_env != 0);
-    const size_t lut_bytes = (size_t)512 * mf_lrow(pl.pair) + (pl.stage ? (size_t)MF_WAVES * MF_STAGE_BYTES : 0);
+    const size_t lut_bytes = (size_t)(one ? 256 : 512) * mf_lrow(pl.pair) + (pl.stage ? (size_t)MF_WAVES * MF_STAGE_BYTES : 0);
     const int nblk = pl.cfg.PB * pl.cfg.CB;
     const size_t red_bytes = KS > 1 ? (size_t)(MF_WAVES / KS) * (nblk > 4 ? nblk / 2 : nblk) * (KS - 1) * 4096 : 0;
     const size_t fin_bytes = (size_t)MF_WAVES * 32 * pl.cfg.CB * 16 * 8;
@@ -1128,6 +1167,7 @@ int launch_mf_one(const MfPlan &pl, const MfParams &prm, hipStream_t s)
 template <int PB, int CB, bool PAIR>
 int launch_mf_pair(const MfPlan &pl, const MfParams &prm, hipStream_t s)
 {
+    if (pl.one) return launch_mf_one<PB, CB, 3, PAIR, false>(pl, prm, s);
     if (prm.g.WW == 1) return pl.stage ? launch_mf_one<PB, CB, 1, PAIR, true>(pl, prm, s) : launch_mf_one<PB, CB, 1, PAIR, false>(pl, prm, s);
     if (prm.g.WW == 2) return pl.stage ? launch_mf_one<PB, CB, 2, PAIR, true>(pl, prm, s) : launch_mf_one<PB, CB, 2, PAIR, false>(pl, prm, s);
     return launch_mf_one<PB, CB, 0, PAIR, false>(pl, prm, s);
@@ -1173,6 +1213,8 @@ MfParams mf_params(const MfPlan &pl, const Geom &g, const void *x, float *y, voi
     prm.n_cotiles = pl.n_cotiles;
     prm.n_tiles = pl.n_tiles;
     prm.n_pxblocks = (int)pl.n_pxblocks;
+    prm.x_bytes = 0;
+    prm.cw_bytes = 0;
 #ifdef SNN_MF_TRACE
     prm.trace = (unsigned long long *)ws;
 #endif
@@ -1257,7 +1299,7 @@ int launch_subbit_mfma(const Geom &g, const void *x, const uint16_t *codebook, c
     if (phases & SNN_PHASE_PREPARE)
         hipLaunchKernelGGL(subbit_mfma_prep_kernel, dim3((unsigned)(sel_blocks + corr_blocks + lut_blocks)), dim3(256), 0, s,
                            codebook, (const void *)idx, tau, g.C_in, g.C_out, pl.COP, pl.cfg.CB, g.K, pl.pair ? 1 : 0, sel_blocks, lut_blocks, alpha,
-                           (uint32_t *)prm.sel, (uint2 *)prm.fin, (uint32_t *)prm.lut, sign ? sign->beta : nullptr);
+                           (uint32_t *)prm.sel, (uint2 *)prm.fin, (uint32_t *)prm.lut, sign ? sign->beta : nullptr, 9);
     if (!(phases & SNN_PHASE_CONVOLVE)) return check_launch();
     return launch_mf_conv(pl, prm, s);
 }
@@ -1287,6 +1329,50 @@ int launch_subbit_forward_mfma(const Geom &g, const float *x, const float *w, co
     const int64_t blocks = (int64_t)pl.COP + fp.wp.lut_blocks + fp.pack_blocks;
     if (blocks > 0x7fffffffLL) return SNN_ERR_UNSUPPORTED;
     hipLaunchKernelGGL(subbit_front_kernel, dim3((unsigned)blocks), dim3(256), 0, s, fp);
+    return launch_mf_conv(pl, prm, s);
+}
+
+// ---- 1x1 layers (the extension to bottleneck blocks: vectors of 8 input channels) -----------------------------
+// The same kernel with the byte of 8 channel signs as the window; `g` is the real layer, the kernel sees
+// C_in / 8 groups as its input channels.
+namespace {
+
+Geom groups_geom(const Geom &g)
+{
+    Geom gk = g;
+    gk.C_in = g.C_in / 8;
+    return gk;
+}
+
+}  // namespace
+
+bool subbit_conv1x1_supported(const Geom &g)
+{
+    const int G = g.C_in / 8;
+    const int64_t x_words = (int64_t)g.N * g.H * g.W * g.CW;
+    const int64_t sel_words = (int64_t)2 * (G + 1) * (g.C_out + 127);
+    const int64_t y_words = (int64_t)g.P * g.C_out;
+    return g.C_in % 8 == 0 && g.K <= 64 && (g.K > 32 || G >= 2) && x_words < ((int64_t)1 << 30) && sel_words < ((int64_t)1 << 30) &&
+           y_words < ((int64_t)1 << 30) && g.P < ((int64_t)1 << 31) - 4096;
+}
+
+size_t subbit_conv1x1_workspace_bytes(const Geom &g) { return mf_plan(groups_geom(g), false, true).bytes; }
+
+int launch_subbit_conv1x1(const Geom &g, const void *x, const uint16_t *codebook, const uint16_t *idx, const float *alpha,
+                          float *y, void *ws, hipStream_t s)
+{
+    const Geom gk = groups_geom(g);
+    const MfPlan pl = mf_plan(gk, false, true);
+    if (pl.n_wgs > 0x7fffffffLL || pl.lds > 160 * 1024 || pl.n_pxblocks > 0x7fffffffLL) return SNN_ERR_UNSUPPORTED;
+    MfParams prm = mf_params(pl, gk, x, y, ws, nullptr);
+    prm.cw_bytes = (uint32_t)g.CW * 4u;
+    prm.x_bytes = (uint32_t)((size_t)g.N * g.H * g.W * g.CW * 4u);
+    const int sel_blocks = (pl.COP / 32) * ((gk.C_in + 31) / 32);
+    const int corr_blocks = (pl.COP + 3) / 4;
+    const int lut_blocks = (256 * (pl.pair ? 6 : 12) + 255) / 256;
+    hipLaunchKernelGGL(subbit_mfma_prep_kernel, dim3((unsigned)(sel_blocks + corr_blocks + lut_blocks)), dim3(256), 0, s, codebook,
+                       (const void *)idx, 0, gk.C_in, g.C_out, pl.COP, pl.cfg.CB, g.K, pl.pair ? 1 : 0, sel_blocks, lut_blocks, alpha,
+                       (uint32_t *)prm.sel, (uint2 *)prm.fin, (uint32_t *)prm.lut, (const float *)nullptr, 8);
     return launch_mf_conv(pl, prm, s);
 }
 

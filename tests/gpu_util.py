@@ -129,3 +129,14 @@ def subset_update(p, m, theta):
     cb, dup = B.snn_subset_update(dev(p.astype(np.float32)), md, theta)
     torch.cuda.synchronize()
     return md.cpu().numpy(), host_u16(cb), dup.cpu().numpy()
+
+
+def subbit_conv1x1(x, codebook8, idx, alpha, stride=1):
+    """x: fp32 NCHW (its sign is the activation), packed into the channels layout by the library."""
+    N, C_in, H, W = x.shape
+    C_out = idx.shape[0]
+    d = B.make_desc(N, C_in, C_out, H, W, stride, int(codebook8.size), B.SNN_ACT_BIN_CHANNELS)
+    xp = B.snn_pack_activations(dev(x), B.SNN_ACT_BIN_CHANNELS)
+    y = B.snn_subbit_conv1x1(d, xp, dev(codebook8), dev(idx.astype(np.uint16)), dev(alpha))
+    torch.cuda.synchronize()
+    return y.cpu().numpy()

@@ -633,6 +633,61 @@ def test_prepare_from_packed_indices(oracle, case):
     assert (y.cpu().numpy() == Y).all()
 
 
+# ---- 1x1 layers ---------------------------------------------------------------------------------------------------------
+
+CONV1X1_CASES = [
+    # N, C_in, C_out, H, W, stride, K
+    (2, 16, 8, 6, 6, 1, 32), (3, 64, 64, 14, 14, 1, 32), (2, 40, 70, 9, 11, 1, 16), (2, 256, 64, 7, 7, 1, 32),
+    (2, 64, 256, 8, 8, 2, 8), (1, 24, 33, 5, 70, 1, 32), (2, 136, 150, 13, 11, 2, 20), (1, 16, 3, 1, 1, 1, 2),
+    (2, 72, 40, 9, 9, 1, 64), (1, 8, 36, 6, 40, 1, 40), (3, 1024, 96, 4, 4, 1, 32), (5, 48, 600, 3, 3, 1, 32),
+]
+
+
+@pytest.mark.parametrize("case", CONV1X1_CASES)
+def test_subbit_conv1x1(oracle, case):
+    _say("subbit_conv1x1", case)
+    N, C_in, C_out, H, W, stride, K = case
+    g = np.random.default_rng(6000 + sum(case))
+    x = g.standard_normal((N, C_in, H, W), dtype=np.float32)
+    cb = g.permutation(256)[:K].astype(np.uint16)
+    idx = g.integers(0, K, size=(C_out, C_in // 8))
+    alpha = synth.alpha(g, C_out)
+    _, Y = oracle.conv1x1_bin(oracle.sign(x), cb, idx, alpha, stride)
+    y = G.subbit_conv1x1(x, cb, idx, alpha, stride)
+    assert y.shape == Y.shape
+    assert (y == Y).all(), np.argwhere(y != Y)[:5]
+
+
+@pytest.mark.parametrize("tile", ["4,2", "2,4", "2,2", "1,4", "1,2"])
+@pytest.mark.parametrize("split", [1, 2, 4])
+def test_subbit_conv1x1_every_tile_and_split(oracle, tile, split, monkeypatch):
+    monkeypatch.setenv("SNN_MFMA_TILE", tile)
+    monkeypatch.setenv("SNN_MFMA_KS", str(split))
+    for case in [(3, 88, 150, 13, 11, 1, 32), (2, 40, 70, 16, 12, 2, 32), (1, 56, 33, 5, 70, 1, 64), (2, 264, 40, 5, 5, 1, 7)]:
+        N, C_in, C_out, H, W, stride, K = case
+        _say("subbit_conv1x1", tile, split, case)
+        g = np.random.default_rng(6100 + sum(case))
+        x = g.standard_normal((N, C_in, H, W), dtype=np.float32)
+        cb = g.permutation(256)[:K].astype(np.uint16)
+        idx = g.integers(0, K, size=(C_out, C_in // 8))
+        alpha = synth.alpha(g, C_out)
+        _, Y = oracle.conv1x1_bin(oracle.sign(x), cb, idx, alpha, stride)
+        y = G.subbit_conv1x1(x, cb, idx, alpha, stride)
+        assert (y == Y).all(), np.argwhere(y != Y)[:5]
+
+
+def test_subbit_conv1x1_refuses_what_it_does_not_take():
+    import torch
+    one = torch.zeros(64, dtype=torch.int32, device="cuda")
+    h16 = torch.zeros(64, dtype=torch.int16, device="cuda")
+    f32 = torch.zeros(64, dtype=torch.float32, device="cuda")
+    for (C_in, K) in [(12, 32), (8, 32), (16, 100)]:
+        d = B.make_desc(1, C_in, 4, 2, 2, 1, K, B.SNN_ACT_BIN_CHANNELS)
+        with pytest.raises(B.SnnError) as e:
+            B.snn_subbit_conv1x1(d, one, h16, h16, f32, y=torch.empty(16, device="cuda"), workspace=torch.empty(1 << 20, dtype=torch.uint8, device="cuda"))
+        assert e.value.status == B.SNN_ERR_UNSUPPORTED
+
+
 # ---- seeded random layers -------------------------------------------------------------------------------------------------
 
 def _random_layers(seed, count):
