@@ -55,3 +55,49 @@ def test_conv1x1_closed_forms(oracle):
     xs = _rand_pm1(g, (2, 24, 3, 3))
     S, _ = oracle.conv1x1_bin(xs, g.permutation(256)[:16].astype(np.uint16), g.integers(0, 16, size=(6, 3)), np.ones(6, dtype=np.float32))
     assert (S % 2 == 0).all() and (np.abs(S) <= 24).all()
+
+
+def test_conv1x1_full_set_is_an_ordinary_binary_layer(oracle):
+    # with all 256 vectors as the subset and idx = the code of sign(w), the layer is the 1-bit 1x1 layer
+    g = np.random.default_rng(11)
+    N, C_in, C_out, H, W = 2, 32, 6, 3, 4
+    xs = _rand_pm1(g, (N, C_in, H, W))
+    wsign = _rand_pm1(g, (C_out, C_in))
+    codes = np.zeros((C_out, C_in // 8), dtype=np.int64)
+    for j in range(8):
+        codes = codes * 2 + (wsign[:, j::8] > 0)               # element j of every group, first element most significant
+    S, _ = oracle.conv1x1_bin(xs, np.arange(256, dtype=np.uint16), codes, np.ones(C_out, dtype=np.float32))
+    ref = np.einsum("oc,nchw->nohw", wsign.astype(np.int64), xs.astype(np.int64))
+    assert (S == ref).all()
+
+
+def test_conv1x1_single_element_isolation(oracle):
+    # flipping element j of the vector of group gg changes S by -2 x[8 gg + j]: pins element order and channel grouping
+    g = np.random.default_rng(12)
+    G = 3
+    xs = _rand_pm1(g, (1, 8 * G, 2, 3))
+    one = np.ones(1, dtype=np.float32)
+    for gg in range(G):
+        for j in range(8):
+            code = int(g.integers(0, 256)) | (1 << (7 - j))
+            cb = np.array([code, code ^ (1 << (7 - j)), int(g.integers(0, 256))], dtype=np.uint16)
+            base = np.full((1, G), 2)
+            a, b = base.copy(), base.copy()
+            a[0, gg], b[0, gg] = 0, 1
+            Sa, _ = oracle.conv1x1_bin(xs, cb, a, one)
+            Sb, _ = oracle.conv1x1_bin(xs, cb, b, one)
+            assert ((Sa - Sb)[0, 0] == 2 * xs[0, 8 * gg + j].astype(np.int64)).all()
+
+
+def test_conv1x1_inputs_tell_the_readings_apart(oracle):
+    # the stated reading differs, on these inputs, from LSB-first element order and from strided channel grouping
+    g = np.random.default_rng(13)
+    G, C_out = 4, 5
+    xs = _rand_pm1(g, (1, 8 * G, 3, 3))
+    cb = g.permutation(256)[:8].astype(np.uint16)
+    idx = g.integers(0, 8, size=(C_out, G))
+    S, _ = oracle.conv1x1_bin(xs, cb, idx, np.ones(C_out, dtype=np.float32))
+    w_lsb = np.array([[1 if (int(cb[idx[co, c // 8]]) >> (c % 8)) & 1 else -1 for c in range(8 * G)] for co in range(C_out)])
+    w_strided = np.array([[1 if (int(cb[idx[co, c % G]]) >> (7 - c // G)) & 1 else -1 for c in range(8 * G)] for co in range(C_out)])
+    for wrong in (w_lsb, w_strided):
+        assert (np.einsum("oc,nchw->nohw", wrong, xs.astype(np.int64)) != S).any()
