@@ -64,6 +64,7 @@ extern "C" {
 #define SNN_WS_BNN    1
 #define SNN_WS_FORWARD 2
 #define SNN_WS_CONV1X1 3
+#define SNN_WS_BNN_DENSE 4
 
 /* One 3x3 layer (Sec. 3 notation: c_in, c_out, H, W of the input). */
 typedef struct snn_conv_desc {
@@ -311,6 +312,26 @@ int snn_subbit_conv1x1(const snn_conv_desc *desc, const void *x, const uint16_t 
 int snn_bnn_conv2d(const snn_conv_desc *desc, const void *x, const uint16_t *w9,
                    const float *alpha, float *y_nchw, void *workspace, size_t ws_bytes,
                    void *stream);
+
+/*
+ * The same 1-bit layer (Sec. 3) evaluated as a dense contraction on the matrix cores instead of
+ * XNOR + bit count: +-1 weights and activations as FP4 operands, zero for taps outside the
+ * image, fp32 accumulation (exact: |S| <= 9 C_in < 2^24).  Results are identical to
+ * snn_bnn_conv2d.  It is the dense yardstick of this chip for the cost model of Sec. 4.5: a
+ * sub-bit layer expanded to its c_out x c_in kernels (w9[co][ci] = codebook[idx[co][ci]]) runs
+ * through it unchanged.
+ *   desc      host; act must be SNN_ACT_BIN_CHANNELS; K ignored
+ *   x         device, uint32 [N][H][W][ceil(C_in/32)]
+ *   w9        device, uint16 [C_out][C_in], one 9-bit code per kernel
+ *   alpha, y_nchw, stream: as for snn_bnn_conv2d
+ *   workspace device, >= snn_workspace_bytes(desc, SNN_WS_BNN_DENSE) bytes, 256-byte aligned
+ *             (the weights in operand layout, rewritten by every call)
+ * Errors: INVALID_ARG; UNSUPPORTED for any other desc->act, for packed inputs of 2^29 words
+ * (2 GiB) or more and for 2^31 output pixels or more; WORKSPACE; LAUNCH.
+ */
+int snn_bnn_conv2d_dense(const snn_conv_desc *desc, const void *x, const uint16_t *w9,
+                         const float *alpha, float *y_nchw, void *workspace, size_t ws_bytes,
+                         void *stream);
 
 /* Bytes of workspace the given entry point (SNN_WS_*) needs for this layer; 0 if desc is
  * invalid or the combination is unsupported.  Host-only, no device work. */

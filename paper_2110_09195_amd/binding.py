@@ -27,13 +27,14 @@ SNN_WS_SUBBIT = 0
 SNN_WS_BNN = 1
 SNN_WS_FORWARD = 2
 SNN_WS_CONV1X1 = 3
+SNN_WS_BNN_DENSE = 4
 
 EXPORTS = ("snn_pack_activations", "snn_project_kernels", "snn_subbit_conv2d", "snn_subbit_forward",
            "snn_subbit_prepare", "snn_subbit_conv2d_prepared", "snn_packed_index_bytes", "snn_pack_indices",
            "snn_subbit_prepare_packed", "snn_subbit_conv1x1",
            "snn_subbit_conv2d_sign", "snn_subbit_forward_sign", "snn_subbit_prepare_sign",
            "snn_subbit_conv2d_sign_prepared", "snn_subbit_project_prepare_many", "snn_project_backward",
-           "snn_project_backward_workspace_bytes", "snn_subset_update", "snn_bnn_conv2d",
+           "snn_project_backward_workspace_bytes", "snn_subset_update", "snn_bnn_conv2d", "snn_bnn_conv2d_dense",
            "snn_workspace_bytes", "snn_packed_bytes", "snn_status_string")
 
 
@@ -106,6 +107,8 @@ def lib():
         L.snn_subbit_conv1x1.restype = i32
         L.snn_bnn_conv2d.argtypes = [dp, vp, vp, vp, vp, vp, sz, vp]
         L.snn_bnn_conv2d.restype = i32
+        L.snn_bnn_conv2d_dense.argtypes = [dp, vp, vp, vp, vp, vp, sz, vp]
+        L.snn_bnn_conv2d_dense.restype = i32
         L.snn_workspace_bytes.argtypes = [dp, i32]
         L.snn_workspace_bytes.restype = sz
         L.snn_packed_bytes.argtypes = [i32, i32, i32, i32, i32]
@@ -428,4 +431,16 @@ def snn_bnn_conv2d(desc, x, w9, alpha, y=None, workspace=None):
         workspace = alloc_workspace(desc, SNN_WS_BNN, x.device)
     _check(lib().snn_bnn_conv2d(ctypes.byref(desc), _ptr(x), _ptr(w9), _ptr(alpha), _ptr(y), _ptr(workspace),
                                 workspace.numel(), _stream()), "snn_bnn_conv2d")
+    return y
+
+
+def snn_bnn_conv2d_dense(desc, x, w9, alpha, y=None, workspace=None):
+    """x: packed int32 (channels layout); w9 int16 [C_out][C_in]; the 1-bit layer on the matrix cores."""
+    _dev(w9, torch.int16, "w9")
+    _dev(alpha, torch.float32, "alpha")
+    y = _conv_out(desc, y, x.device)
+    if workspace is None:
+        workspace = alloc_workspace(desc, SNN_WS_BNN_DENSE, x.device)
+    _check(lib().snn_bnn_conv2d_dense(ctypes.byref(desc), _ptr(x), _ptr(w9), _ptr(alpha), _ptr(y), _ptr(workspace),
+                                      workspace.numel(), _stream()), "snn_bnn_conv2d_dense")
     return y

@@ -72,6 +72,11 @@ size_t snn_workspace_bytes(const snn_conv_desc *desc, int which)
         const Geom g = make_geom(*desc);
         return subbit_conv1x1_supported(g) ? subbit_conv1x1_workspace_bytes(g) : 0;
     }
+    if (which == SNN_WS_BNN_DENSE) {
+        if (!desc_ok(desc, false) || desc->act != SNN_ACT_BIN_CHANNELS) return 0;
+        const Geom g = make_geom(*desc);
+        return dense_fp4_supported(g) ? dense_fp4_workspace_bytes(g) : 0;
+    }
     if (which == SNN_WS_BNN) {
         if (!desc_ok(desc, false) || !bnn_supported(desc)) return 0;
         return bnn_workspace_bytes(make_geom(*desc), desc->act);
@@ -297,6 +302,18 @@ int snn_bnn_conv2d(const snn_conv_desc *desc, const void *x, const uint16_t *w9,
     const size_t need = bnn_workspace_bytes(g, desc->act);
     if (need > 0 && (!workspace || ws_bytes < need || ((uintptr_t)workspace & 255u))) return SNN_ERR_WORKSPACE;
     return launch_bnn(g, desc->act, x, w9, alpha, y_nchw, workspace, (hipStream_t)stream);
+}
+
+int snn_bnn_conv2d_dense(const snn_conv_desc *desc, const void *x, const uint16_t *w9, const float *alpha,
+                         float *y_nchw, void *workspace, size_t ws_bytes, void *stream)
+{
+    if (!desc_ok(desc, false) || !x || !w9 || !alpha || !y_nchw) return SNN_ERR_INVALID_ARG;
+    if (desc->act != SNN_ACT_BIN_CHANNELS) return SNN_ERR_UNSUPPORTED;
+    const Geom g = make_geom(*desc);
+    if (!dense_fp4_supported(g)) return SNN_ERR_UNSUPPORTED;
+    const size_t need = dense_fp4_workspace_bytes(g);
+    if (!workspace || ws_bytes < need || ((uintptr_t)workspace & 255u)) return SNN_ERR_WORKSPACE;
+    return launch_dense_fp4(g, x, w9, alpha, y_nchw, workspace, (hipStream_t)stream);
 }
 
 }  // extern "C"

@@ -64,6 +64,16 @@ def bnn_bin(x, w9, alpha, stride=1):
     return y.cpu().numpy()
 
 
+def bnn_dense(x, w9, alpha, stride=1):
+    N, C_in, H, W = x.shape
+    C_out = w9.shape[0]
+    d = B.make_desc(N, C_in, C_out, H, W, stride, 512, B.SNN_ACT_BIN_CHANNELS)
+    xp = B.snn_pack_activations(dev(x), B.SNN_ACT_BIN_CHANNELS)
+    y = B.snn_bnn_conv2d_dense(d, xp, dev(w9), dev(alpha))
+    torch.cuda.synchronize()
+    return y.cpu().numpy()
+
+
 def bnn_f32(x, w9, alpha, stride=1):
     N, C_in, H, W = x.shape
     C_out = w9.shape[0]

@@ -5,6 +5,7 @@ import sys
 
 import numpy as np
 import pytest
+import torch
 
 from paper_2110_09195_amd import binding as B
 from paper_2110_09195_amd import synth
@@ -79,6 +80,40 @@ def test_bnn_bin(oracle, case):
     y = G.bnn_bin(x, w9, alpha, stride)
     assert y.shape == Y.shape
     assert (y == Y).all(), np.argwhere(y != Y)[:5]
+
+
+# the dense matrix-core evaluation of the same layer: every tile shape, ragged pixel and channel tails
+DENSE_CASES = BNN_CASES + [(4, 64, 64, 56, 56, 1), (4, 128, 128, 28, 28, 2), (2, 96, 130, 9, 11, 1), (5, 33, 65, 6, 7, 1)]
+
+
+@pytest.mark.parametrize("tile", [None, 0, 1, 2, 3])
+@pytest.mark.parametrize("case", DENSE_CASES)
+def test_bnn_dense(oracle, case, tile, monkeypatch):
+    if tile is not None and case in BNN_CASES[:8]:
+        pytest.skip("tile shapes are swept on the larger cases")
+    _say("bnn_dense", (case, tile))
+    if tile is not None:
+        monkeypatch.setenv("SNN_DENSE_TILE", str(tile))
+    N, C_in, C_out, H, W, stride = case
+    g = np.random.default_rng(sum(case) + 7)
+    x = g.standard_normal((N, C_in, H, W), dtype=np.float32)
+    w9 = g.integers(0, 512, size=(C_out, C_in)).astype(np.uint16)
+    alpha = synth.alpha(g, C_out)
+    _, Y = oracle.conv_bin(oracle.sign(x), w9, alpha, stride)
+    y = G.bnn_dense(x, w9, alpha, stride)
+    assert y.shape == Y.shape
+    assert (y == Y).all(), np.argwhere(y != Y)[:5]
+
+
+def test_bnn_dense_refusals():
+    d = B.make_desc(2, 16, 8, 6, 6, 1, 512, B.SNN_ACT_BIN_ROWS)
+    assert B.snn_workspace_bytes(d, B.SNN_WS_BNN_DENSE) == 0
+    xp = torch.zeros(2 * 16 * 6, dtype=torch.int32, device="cuda")
+    w9 = torch.zeros((8, 16), dtype=torch.int16, device="cuda")
+    al = torch.ones(8, dtype=torch.float32, device="cuda")
+    ws = torch.zeros(1 << 16, dtype=torch.uint8, device="cuda")
+    with pytest.raises(B.SnnError):
+        B.snn_bnn_conv2d_dense(d, xp, w9, al, workspace=ws)
 
 
 @pytest.mark.parametrize("case", [(2, 8, 8, 6, 6, 1), (3, 13, 9, 7, 5, 2), (4, 64, 64, 8, 8, 1), (1, 1, 1, 1, 1, 1)])
