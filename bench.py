@@ -159,7 +159,8 @@ def main():
         s["ws_sub"] = B.alloc_workspace(s["d_sub"], B.SNN_WS_SUBBIT)
         s["ws_bnn"] = B.alloc_workspace(s["d_bnn"], B.SNN_WS_BNN)
         s["ws_fwd"] = B.alloc_workspace(s["d_sub"], B.SNN_WS_FORWARD)
-        s["ws_dense"] = B.alloc_workspace(s["d_bnn"], B.SNN_WS_BNN_DENSE)
+        s["d_dense"] = B.make_desc(L.N, L.C_in, L.C_out, L.H, L.W, L.stride, L.K, B.SNN_ACT_BIN_CHANNELS)
+        s["ws_dense"] = B.alloc_workspace(s["d_dense"], B.SNN_WS_BNN_DENSE)
         st.append(s)
     torch.cuda.synchronize()
 
@@ -181,7 +182,12 @@ def main():
         B.snn_bnn_conv2d(s["d_bnn"], s["xc"], s["w9"], s["alpha"], y=s["yb"], workspace=s["ws_bnn"])
 
     def conv_dense(s):
-        B.snn_bnn_conv2d_dense(s["d_bnn"], s["xc"], s["w9"], s["alpha"], y=s["yb"], workspace=s["ws_dense"])
+        L = s["L"]
+        B.snn_subbit_conv2d_dense(s["d_dense"], s["xc"], s["cb"], s["idx"].view(L.C_out, L.C_in), s["alpha"], y=s["yb"],
+                                  workspace=s["ws_dense"])
+
+    def conv_dense_prepared(s):
+        B.snn_dense_conv2d_prepared(s["d_dense"], s["xc"], s["alpha"], s["ws_dense"], y=s["yb"])
 
     def forward(s):
         L = s["L"]
@@ -220,12 +226,17 @@ def main():
             pack_channels(s)
             conv_bnn(s)
 
-    # the 1-bit layers as dense FP4 contractions on the matrix cores (context: what a dense
-    # evaluation of the same decoded kernels costs on this chip)
+    # the same sub-bit layers (same subsets and indices) as dense FP4 contractions on the matrix
+    # cores, without the sharing of Sec. 4.5: context for what that sharing buys on this chip
     def step_dense():
         for s in st:
             pack_channels(s)
             conv_dense(s)
+
+    def step_dense_inference():
+        for s in st:
+            pack_channels(s)
+            conv_dense_prepared(s)
 
     # decoded kernels for the 1-bit baseline (input preparation, outside every timed region)
     for s in st:
@@ -277,7 +288,7 @@ def main():
     t1 = time.perf_counter()
     ms_per_step_bnn = (t1 - t0) * 1e3 / args.steps
 
-    ms_per_step_dense = None
+    ms_per_step_dense = ms_per_step_dense_inference = None
     if not args.headline_only:
         for _ in range(args.warmup):
             step_dense()
@@ -288,6 +299,15 @@ def main():
         torch.cuda.synchronize()
         t1 = time.perf_counter()
         ms_per_step_dense = (t1 - t0) * 1e3 / args.steps
+        for _ in range(args.warmup):
+            step_dense_inference()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            step_dense_inference()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        ms_per_step_dense_inference = (t1 - t0) * 1e3 / args.steps
 
     # ---- the same stack as a chain of 1-bit activations (resnet18 workload only) ---------------------------
     # Layer i's convolution ends in the next layer's binarisation (snn_subbit_forward_sign): the packed
@@ -414,6 +434,7 @@ def main():
     t_sub = event_time(conv_sub, reps)
     t_bnn = event_time(conv_bnn, reps)
     t_dense = event_time(conv_dense, reps)
+    t_dense_k = event_time(conv_dense_prepared, reps)
     t_proj = event_time(project, reps)
     t_pr = event_time(pack_rows, reps)
     t_pc = event_time(pack_channels, reps)
@@ -525,11 +546,13 @@ def main():
     print("sum: subbit %.1f us, bnn %.1f us, project %.1f us, pack rows %.1f us, pack channels %.1f us; "
           "step %.1f us, bnn step %.1f us" % (sum(t_sub) * 1e3, sum(t_bnn) * 1e3, sum(t_proj) * 1e3, sum(t_pr) * 1e3,
                                                 sum(t_pc) * 1e3, ms_per_step * 1e3, ms_per_step_bnn * 1e3), file=sys.stderr)
-    print("dense FP4 matrix-core evaluation of the decoded 1-bit layers, per layer (us, incl. its weight expansion): "
-          + " ".join("%.1f" % (v * 1e3) for v in t_dense), file=sys.stderr)
+    print("the same sub-bit layers as dense FP4 contractions (snn_subbit_conv2d_dense), per layer, us, with / without "
+          "the weight expansion kernel: " + " ".join("%.1f/%.1f" % (a * 1e3, b * 1e3) for a, b in zip(t_dense, t_dense_k)),
+          file=sys.stderr)
     if ms_per_step_dense is not None:
-        print("dense step (pack channels + dense conv per layer): %.1f us; dense conv calls alone: %.1f us" % (
-            ms_per_step_dense * 1e3, sum(t_dense) * 1e3), file=sys.stderr)
+        print("dense step (pack channels + dense conv per layer): %.1f us, with prepared weights %.1f us; dense conv "
+              "calls alone: %.1f us, prepared %.1f us" % (ms_per_step_dense * 1e3, ms_per_step_dense_inference * 1e3,
+                                                         sum(t_dense) * 1e3, sum(t_dense_k) * 1e3), file=sys.stderr)
     print("step as one snn_subbit_forward per layer: %.1f us" % (ms_per_step_forward_calls * 1e3), file=sys.stderr)
     print("step as three separate calls per layer: %.1f us" % (ms_per_step_separate * 1e3), file=sys.stderr)
     print("inference step (weights prepared once; pack + conv per layer): %.1f us; conv kernels alone: %.1f us" % (
@@ -611,11 +634,15 @@ def main():
                                      "launch overhead); Alg. 1 backward lines, outside the step"},
         "chained_1bit_stack": chained,
         "dense_fp4_context": {
-            "what": "the same decoded 1-bit layers through snn_bnn_conv2d_dense (dense FP4 contraction on the matrix "
-                    "cores; per-call events include the weight expansion kernel); context, not the paper's method",
-            "ms_per_step": ms_per_step_dense, "conv_us": sum(t_dense) * 1e3,
+            "what": "the same sub-bit layers (subset + indices) through snn_subbit_conv2d_dense: kernels looked up and "
+                    "expanded by a preparation kernel, then a dense FP4 contraction on the matrix cores without the "
+                    "sharing of Sec. 4.5; context, not the paper's method",
+            "ms_per_step": ms_per_step_dense, "ms_per_step_inference": ms_per_step_dense_inference,
+            "conv_us": sum(t_dense) * 1e3, "conv_prepared_us": sum(t_dense_k) * 1e3,
             "conv_us_per_layer": [v * 1e3 for v in t_dense],
-            "subbit_over_dense_conv": sum(t_sub) / sum(t_dense)},
+            "conv_prepared_us_per_layer": [v * 1e3 for v in t_dense_k],
+            "subbit_over_dense_conv": sum(t_sub) / sum(t_dense),
+            "subbit_over_dense_conv_prepared": sum(t_kern) / sum(t_dense_k)},
         "conv1x1_resnet50_shapes": conv1x1,
         "roofline": roofline,
         "cpu_baseline": cpu,

@@ -333,6 +333,32 @@ int snn_bnn_conv2d_dense(const snn_conv_desc *desc, const void *x, const uint16_
                          const float *alpha, float *y_nchw, void *workspace, size_t ws_bytes,
                          void *stream);
 
+/*
+ * A sub-bit layer (Sec. 4.2: kernels given as indices into the layer's subset) through the same
+ * dense contraction: the preparation kernel looks the kernels up (w9[co][ci] =
+ * codebook[idx[co][ci]]) while it expands them.  Same results as snn_subbit_conv2d on the same
+ * layer; the sharing of Sec. 4.5 is NOT used (it is the comparison point for it).
+ *   desc      host; act must be SNN_ACT_BIN_CHANNELS; K = subset size
+ *   codebook  device, uint16 [K];  idx  device, uint16 [C_out][C_in], values < K
+ *   the rest as for snn_bnn_conv2d_dense (workspace: SNN_WS_BNN_DENSE).
+ */
+int snn_subbit_conv2d_dense(const snn_conv_desc *desc, const void *x, const uint16_t *codebook,
+                            const uint16_t *idx, const float *alpha, float *y_nchw,
+                            void *workspace, size_t ws_bytes, void *stream);
+
+/*
+ * The two halves of the dense calls for weights that stay fixed: snn_dense_prepare expands the
+ * kernels into the workspace (codebook == NULL: `codes` are 9-bit kernel codes [C_out][C_in] and
+ * desc->K is ignored; else `codes` are indices into codebook[K]); snn_dense_conv2d_prepared is
+ * the contraction alone, one launch, any number of times.  The workspace (SNN_WS_BNN_DENSE bytes,
+ * 256-byte aligned) belongs to the library between the two calls; together they give the same
+ * result as the one-call forms.  Errors as for snn_bnn_conv2d_dense.
+ */
+int snn_dense_prepare(const snn_conv_desc *desc, const uint16_t *codebook, const uint16_t *codes,
+                      void *workspace, size_t ws_bytes, void *stream);
+int snn_dense_conv2d_prepared(const snn_conv_desc *desc, const void *x, const float *alpha,
+                              float *y_nchw, void *workspace, size_t ws_bytes, void *stream);
+
 /* Bytes of workspace the given entry point (SNN_WS_*) needs for this layer; 0 if desc is
  * invalid or the combination is unsupported.  Host-only, no device work. */
 size_t snn_workspace_bytes(const snn_conv_desc *desc, int which);

@@ -35,6 +35,7 @@ EXPORTS = ("snn_pack_activations", "snn_project_kernels", "snn_subbit_conv2d", "
            "snn_subbit_conv2d_sign", "snn_subbit_forward_sign", "snn_subbit_prepare_sign",
            "snn_subbit_conv2d_sign_prepared", "snn_subbit_project_prepare_many", "snn_project_backward",
            "snn_project_backward_workspace_bytes", "snn_subset_update", "snn_bnn_conv2d", "snn_bnn_conv2d_dense",
+           "snn_subbit_conv2d_dense", "snn_dense_prepare", "snn_dense_conv2d_prepared",
            "snn_workspace_bytes", "snn_packed_bytes", "snn_status_string")
 
 
@@ -109,6 +110,12 @@ def lib():
         L.snn_bnn_conv2d.restype = i32
         L.snn_bnn_conv2d_dense.argtypes = [dp, vp, vp, vp, vp, vp, sz, vp]
         L.snn_bnn_conv2d_dense.restype = i32
+        L.snn_subbit_conv2d_dense.argtypes = [dp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.snn_subbit_conv2d_dense.restype = i32
+        L.snn_dense_prepare.argtypes = [dp, vp, vp, vp, sz, vp]
+        L.snn_dense_prepare.restype = i32
+        L.snn_dense_conv2d_prepared.argtypes = [dp, vp, vp, vp, vp, sz, vp]
+        L.snn_dense_conv2d_prepared.restype = i32
         L.snn_workspace_bytes.argtypes = [dp, i32]
         L.snn_workspace_bytes.restype = sz
         L.snn_packed_bytes.argtypes = [i32, i32, i32, i32, i32]
@@ -443,4 +450,34 @@ def snn_bnn_conv2d_dense(desc, x, w9, alpha, y=None, workspace=None):
         workspace = alloc_workspace(desc, SNN_WS_BNN_DENSE, x.device)
     _check(lib().snn_bnn_conv2d_dense(ctypes.byref(desc), _ptr(x), _ptr(w9), _ptr(alpha), _ptr(y), _ptr(workspace),
                                       workspace.numel(), _stream()), "snn_bnn_conv2d_dense")
+    return y
+
+
+def snn_subbit_conv2d_dense(desc, x, codebook, idx, alpha, y=None, workspace=None):
+    """A sub-bit layer (codebook int16 [K], idx int16 [C_out][C_in]) through the dense contraction."""
+    _dev(codebook, torch.int16, "codebook")
+    _dev(idx, torch.int16, "idx")
+    _dev(alpha, torch.float32, "alpha")
+    y = _conv_out(desc, y, x.device)
+    if workspace is None:
+        workspace = alloc_workspace(desc, SNN_WS_BNN_DENSE, x.device)
+    _check(lib().snn_subbit_conv2d_dense(ctypes.byref(desc), _ptr(x), _ptr(codebook), _ptr(idx), _ptr(alpha), _ptr(y),
+                                         _ptr(workspace), workspace.numel(), _stream()), "snn_subbit_conv2d_dense")
+    return y
+
+
+def snn_dense_prepare(desc, codebook, codes, workspace):
+    """codebook None: codes are 9-bit kernel codes; else indices into codebook.  Fills the workspace."""
+    _dev(codes, torch.int16, "codes")
+    if codebook is not None:
+        _dev(codebook, torch.int16, "codebook")
+    _check(lib().snn_dense_prepare(ctypes.byref(desc), _ptr(codebook) if codebook is not None else None, _ptr(codes),
+                                   _ptr(workspace), workspace.numel(), _stream()), "snn_dense_prepare")
+
+
+def snn_dense_conv2d_prepared(desc, x, alpha, workspace, y=None):
+    _dev(alpha, torch.float32, "alpha")
+    y = _conv_out(desc, y, x.device)
+    _check(lib().snn_dense_conv2d_prepared(ctypes.byref(desc), _ptr(x), _ptr(alpha), _ptr(y), _ptr(workspace),
+                                           workspace.numel(), _stream()), "snn_dense_conv2d_prepared")
     return y

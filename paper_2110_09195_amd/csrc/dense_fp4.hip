@@ -79,8 +79,8 @@ __device__ inline v8i expand_signs(uint32_t w, uint32_t table)
 // weights -> operand layout.  One thread per (co block, channel block, lane): the lane's row is output
 // channel 32 b + lane % 32, its 32 contraction slots are channels 64 s + 32 (lane / 32) + j.
 __global__ __launch_bounds__(256)
-void dense_fp4_prep_kernel(const uint16_t *__restrict__ w9, int C_in, int C_out, int ncb64, int n_coblocks,
-                           u32x4 *__restrict__ wq)
+void dense_fp4_prep_kernel(const uint16_t *__restrict__ codebook, int K, const uint16_t *__restrict__ w9, int C_in,
+                           int C_out, int ncb64, int n_coblocks, u32x4 *__restrict__ wq)
 {
     const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (i >= (int64_t)n_coblocks * ncb64 * 64) return;
@@ -96,7 +96,15 @@ void dense_fp4_prep_kernel(const uint16_t *__restrict__ w9, int C_in, int C_out,
         // 32 independent loads in flight
         uint32_t code[32];
 #pragma unroll
-        for (int j = 0; j < 32; ++j) code[j] = c0 + j < C_in ? w9[(int64_t)co * C_in + c0 + j] & 511u : 0x8000u;
+        for (int j = 0; j < 32; ++j) code[j] = c0 + j < C_in ? (uint32_t)w9[(int64_t)co * C_in + c0 + j] : 0x8000u;
+        if (codebook) {
+            // a sub-bit layer: the entries are indices into the layer's subset (Sec. 4.2)
+#pragma unroll
+            for (int j = 0; j < 32; ++j)
+                if (c0 + j < C_in) code[j] = codebook[min(code[j], (uint32_t)K - 1u)];     // (an index >= K is the caller's error: no fault)
+        }
+#pragma unroll
+        for (int j = 0; j < 32; ++j) code[j] &= 0x81ffu;
 #pragma unroll
         for (int j = 0; j < 32; ++j) {
             have |= (code[j] >> 15 ^ 1u) << j;
@@ -331,15 +339,20 @@ size_t dense_fp4_workspace_bytes(const Geom &g)
     return bytes;
 }
 
-int launch_dense_fp4(const Geom &g, const void *x, const uint16_t *w9, const float *alpha, float *y, void *ws,
-                     hipStream_t s)
+int launch_dense_fp4(const Geom &g, const void *x, const uint16_t *codebook, const uint16_t *w9, const float *alpha,
+                     float *y, void *ws, hipStream_t s, int phases)
 {
     const DensePlan pl = dense_plan(g);
-    const int64_t prep_threads = (int64_t)pl.n_coblocks * pl.ncb64 * 64;
-    hipLaunchKernelGGL(dense_fp4_prep_kernel, dim3((unsigned)((prep_threads + 255) / 256)), dim3(256), 0, s, w9, g.C_in,
-                       g.C_out, pl.ncb64, pl.n_coblocks, (u32x4 *)ws);
-    const int rc = check_launch();
-    if (rc != SNN_OK) return rc;
+    if (phases & SNN_PHASE_PREPARE) {
+        // all co blocks the workspace has room for (the largest tile's rounding), whatever tile runs later
+        const int n_coblocks = ((g.C_out + 31) / 32 + 3) / 4 * 4;
+        const int64_t prep_threads = (int64_t)n_coblocks * pl.ncb64 * 64;
+        hipLaunchKernelGGL(dense_fp4_prep_kernel, dim3((unsigned)((prep_threads + 255) / 256)), dim3(256), 0, s, codebook,
+                           g.K, w9, g.C_in, g.C_out, pl.ncb64, n_coblocks, (u32x4 *)ws);
+        const int rc = check_launch();
+        if (rc != SNN_OK) return rc;
+    }
+    if (!(phases & SNN_PHASE_CONVOLVE)) return SNN_OK;
     DenseParams prm;
     prm.x = (const uint32_t *)x;
     prm.wq = (const u32x4 *)ws;

@@ -304,16 +304,45 @@ int snn_bnn_conv2d(const snn_conv_desc *desc, const void *x, const uint16_t *w9,
     return launch_bnn(g, desc->act, x, w9, alpha, y_nchw, workspace, (hipStream_t)stream);
 }
 
-int snn_bnn_conv2d_dense(const snn_conv_desc *desc, const void *x, const uint16_t *w9, const float *alpha,
-                         float *y_nchw, void *workspace, size_t ws_bytes, void *stream)
+namespace {
+int dense_call(const snn_conv_desc *desc, bool subbit, const void *x, const uint16_t *codebook, const uint16_t *codes,
+               const float *alpha, float *y, void *workspace, size_t ws_bytes, void *stream, int phases)
 {
-    if (!desc_ok(desc, false) || !x || !w9 || !alpha || !y_nchw) return SNN_ERR_INVALID_ARG;
+    if (!desc_ok(desc, subbit)) return SNN_ERR_INVALID_ARG;
+    if ((phases & SNN_PHASE_PREPARE) && (!codes || (subbit && !codebook))) return SNN_ERR_INVALID_ARG;
+    if ((phases & SNN_PHASE_CONVOLVE) && (!x || !alpha || !y)) return SNN_ERR_INVALID_ARG;
     if (desc->act != SNN_ACT_BIN_CHANNELS) return SNN_ERR_UNSUPPORTED;
     const Geom g = make_geom(*desc);
     if (!dense_fp4_supported(g)) return SNN_ERR_UNSUPPORTED;
     const size_t need = dense_fp4_workspace_bytes(g);
     if (!workspace || ws_bytes < need || ((uintptr_t)workspace & 255u)) return SNN_ERR_WORKSPACE;
-    return launch_dense_fp4(g, x, w9, alpha, y_nchw, workspace, (hipStream_t)stream);
+    return launch_dense_fp4(g, x, subbit ? codebook : nullptr, codes, alpha, y, workspace, (hipStream_t)stream, phases);
+}
+}  // namespace
+
+int snn_bnn_conv2d_dense(const snn_conv_desc *desc, const void *x, const uint16_t *w9, const float *alpha,
+                         float *y_nchw, void *workspace, size_t ws_bytes, void *stream)
+{
+    return dense_call(desc, false, x, nullptr, w9, alpha, y_nchw, workspace, ws_bytes, stream, SNN_PHASE_BOTH);
+}
+
+int snn_subbit_conv2d_dense(const snn_conv_desc *desc, const void *x, const uint16_t *codebook, const uint16_t *idx,
+                            const float *alpha, float *y_nchw, void *workspace, size_t ws_bytes, void *stream)
+{
+    return dense_call(desc, true, x, codebook, idx, alpha, y_nchw, workspace, ws_bytes, stream, SNN_PHASE_BOTH);
+}
+
+int snn_dense_prepare(const snn_conv_desc *desc, const uint16_t *codebook, const uint16_t *codes, void *workspace,
+                      size_t ws_bytes, void *stream)
+{
+    return dense_call(desc, codebook != nullptr, nullptr, codebook, codes, nullptr, nullptr, workspace, ws_bytes, stream,
+                      SNN_PHASE_PREPARE);
+}
+
+int snn_dense_conv2d_prepared(const snn_conv_desc *desc, const void *x, const float *alpha, float *y_nchw,
+                              void *workspace, size_t ws_bytes, void *stream)
+{
+    return dense_call(desc, false, x, nullptr, nullptr, alpha, y_nchw, workspace, ws_bytes, stream, SNN_PHASE_CONVOLVE);
 }
 
 }  // extern "C"

@@ -80,15 +80,16 @@ size_t bnn_workspace_bytes(const Geom &g, int act);
 int launch_bnn(const Geom &g, int act, const void *x, const uint16_t *w9, const float *alpha,
                float *y, void *ws, hipStream_t s);
 
-// the same 1-bit layer as a dense FP4 contraction on the matrix cores (+-1 activations, packed channels)
-bool dense_fp4_supported(const Geom &g);
-size_t dense_fp4_workspace_bytes(const Geom &g);
-int launch_dense_fp4(const Geom &g, const void *x, const uint16_t *w9, const float *alpha, float *y, void *ws,
-                     hipStream_t s);
-
 // A sub-bit convolution is a small preparation kernel (weights -> tables in the workspace) and the
 // convolution proper; callers whose weights stay fixed run the two separately.
 enum : int { SNN_PHASE_PREPARE = 1, SNN_PHASE_CONVOLVE = 2, SNN_PHASE_BOTH = 3 };
+
+// the same 1-bit layer as a dense FP4 contraction on the matrix cores (+-1 activations, packed channels)
+bool dense_fp4_supported(const Geom &g);
+size_t dense_fp4_workspace_bytes(const Geom &g);
+// codebook == nullptr: `codes` are 9-bit kernel codes; else indices into the codebook (a sub-bit layer)
+int launch_dense_fp4(const Geom &g, const void *x, const uint16_t *codebook, const uint16_t *codes, const float *alpha,
+                     float *y, void *ws, hipStream_t s, int phases);
 
 size_t subbit_workspace_bytes(const Geom &g, int act);
 int launch_subbit(const Geom &g, int act, const void *x, const uint16_t *codebook,

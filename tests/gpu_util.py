@@ -74,6 +74,21 @@ def bnn_dense(x, w9, alpha, stride=1):
     return y.cpu().numpy()
 
 
+def subbit_dense(x, codebook, idx, alpha, stride=1, prepared=False):
+    N, C_in, H, W = x.shape
+    C_out = idx.shape[0]
+    d = B.make_desc(N, C_in, C_out, H, W, stride, int(codebook.size), B.SNN_ACT_BIN_CHANNELS)
+    xp = B.snn_pack_activations(dev(x), B.SNN_ACT_BIN_CHANNELS)
+    if prepared:
+        ws = B.alloc_workspace(d, B.SNN_WS_BNN_DENSE)
+        B.snn_dense_prepare(d, dev(codebook), dev(idx), ws)
+        y = B.snn_dense_conv2d_prepared(d, xp, dev(alpha), ws)
+    else:
+        y = B.snn_subbit_conv2d_dense(d, xp, dev(codebook), dev(idx), dev(alpha))
+    torch.cuda.synchronize()
+    return y.cpu().numpy()
+
+
 def bnn_f32(x, w9, alpha, stride=1):
     N, C_in, H, W = x.shape
     C_out = w9.shape[0]

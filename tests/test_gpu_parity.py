@@ -194,6 +194,38 @@ def test_subbit_bin_matrix_core_kernel_every_tile_and_split(oracle, tile, split,
         assert (y == Y).all(), np.argwhere(y != Y)[:5]
 
 
+@pytest.mark.parametrize("prepared", [False, True])
+@pytest.mark.parametrize("case", SUBBIT_CASES)
+def test_subbit_dense(oracle, case, prepared):
+    """The same sub-bit layers through the dense matrix-core contraction (kernels looked up in the
+    subset by the preparation kernel), in one call and as prepare + prepared convolution."""
+    _say("subbit_dense", (case, prepared))
+    N, C_in, C_out, H, W, stride, K, dist = case
+    x, cb, idx, alpha = _inputs(sum(case[:7]), N, C_in, C_out, H, W, K, dist)
+    _, Y = oracle.conv_bin(oracle.sign(x), oracle.expand(cb, idx), alpha, stride)
+    y = G.subbit_dense(x, cb, idx, alpha, stride, prepared)
+    assert y.shape == Y.shape
+    assert (y == Y).all(), np.argwhere(y != Y)[:5]
+
+
+def test_dense_prepared_weights_are_reused(oracle):
+    """One preparation, several inputs; 9-bit codes given directly (no subset)."""
+    g = np.random.default_rng(77)
+    N, C_in, C_out, H, W = 3, 70, 45, 9, 12
+    w9 = g.integers(0, 512, size=(C_out, C_in)).astype(np.uint16)
+    alpha = synth.alpha(g, C_out)
+    d = B.make_desc(N, C_in, C_out, H, W, 1, 512, B.SNN_ACT_BIN_CHANNELS)
+    ws = B.alloc_workspace(d, B.SNN_WS_BNN_DENSE)
+    B.snn_dense_prepare(d, None, G.dev(w9), ws)
+    for _ in range(2):
+        x = g.standard_normal((N, C_in, H, W), dtype=np.float32)
+        _, Y = oracle.conv_bin(oracle.sign(x), w9, alpha, 1)
+        xp = B.snn_pack_activations(G.dev(x), B.SNN_ACT_BIN_CHANNELS)
+        y = B.snn_dense_conv2d_prepared(d, xp, G.dev(alpha), ws)
+        torch.cuda.synchronize()
+        assert (y.cpu().numpy() == Y).all()
+
+
 @pytest.mark.parametrize("case", SUBBIT_CASES)
 def test_subbit_bin_fallback_kernel(oracle, case, monkeypatch):
     """With the matrix-core kernel switched off (a tuning override, read at every call) every
