@@ -566,7 +566,7 @@ def main():
     if not args.no_cpu:
         import oracle
         oracle.build()
-        n_img = 32 if args.workload == "resnet18" else 16
+        n_img = 64 if args.workload == "resnet18" else 16
         t_cpu = 0.0
         ops_cpu = 0
         for s in st:
