@@ -582,6 +582,8 @@ def main():
             t_cpu += time.perf_counter() - c0
             ops_cpu += L.dense_ops // L.N * x.shape[0]
             assert (s["y"][:n_img].cpu().numpy() == Y).all(), "GPU result differs from the oracle on " + L.name
+            # (s["yb"] was last written by the dense contraction of the same layer)
+            assert (s["yb"][:n_img].cpu().numpy() == Y).all(), "dense-path result differs from the oracle on " + L.name
         if chained is not None:
             # the chain, first two images, layer by layer against the oracle (images are independent)
             xs = oracle.sign(st[0]["x"][:2].cpu().numpy())

@@ -9,6 +9,10 @@
  * gathers the pre-computed responses by index and sums them along c_in), plus the 1-bit
  * XNOR/popcount convolution it is compared with (Sec. 3), the sign/bit-packing of
  * activations (Alg. 1 forward) and the nearest-subset-member projection (Eq. 2 / Eq. 5).
+ * Around these: the convolution ending in the next layer's sign (1-bit activations from layer to
+ * layer), the training-side lines of Alg. 1 (Eq. 3, Eq. 4, the gradient of the subset), the
+ * tau-bit index storage of Sec. 4.4, the extension to 1x1 layers (appendix) and, as a yardstick, the
+ * same layers as dense contractions on the matrix cores.
  *
  * General rules for every entry point
  *   - Every data pointer is a DEVICE pointer owned by the caller (hipMalloc / a torch CUDA
@@ -16,8 +20,10 @@
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Every call only
  *     enqueues work on that stream and returns without synchronising.
  *   - The library never allocates, frees or keeps device memory; scratch space is the
- *     caller's `workspace` (size from snn_workspace_bytes), used only during the call.
- *     Two calls that share a workspace must be ordered (same stream, or synchronised).
+ *     caller's `workspace` (size from snn_workspace_bytes), used only during the call -
+ *     except between a *_prepare call and the *_prepared calls that follow it, which read
+ *     what the preparation left there.  Two calls that share a workspace must be ordered
+ *     (same stream, or synchronised).
  *   - Return value: SNN_OK (0) or a negative SNN_ERR_* code.  On error nothing has been
  *     enqueued.  No exceptions, no aborts, nothing printed.
  *   - Values of idx[] must be < K and values of codebook[] / w9[] must be < 512; this is
