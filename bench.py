@@ -365,7 +365,30 @@ def main():
         torch.cuda.synchronize()
         t1 = time.perf_counter()
         ms_chained_inf = (t1 - t0) * 1e3 / args.steps
+        # the same chain through the dense contraction (packed channels from layer to layer; context)
+        for s in st:
+            L = s["L"]
+            B.snn_dense_prepare(s["d_dense"], s["cb"], s["idx"].view(L.C_out, L.C_in), s["ws_dense"])
+            s["out_bits_c"] = torch.empty(B.snn_packed_bytes(L.N, L.C_out, L.H_out, L.W_out, B.SNN_ACT_BIN_CHANNELS) // 4,
+                                          dtype=torch.int32, device="cuda")
+
+        def step_chained_dense():
+            xin = B.snn_pack_activations(st[0]["x"], B.SNN_ACT_BIN_CHANNELS, out=st[0]["xc"])
+            for s in st:
+                B.snn_dense_conv2d_sign_prepared(s["d_dense"], xin, s["alpha"], s["beta"], s["ws_dense"], out=s["out_bits_c"])
+                xin = s["out_bits_c"]
+
+        for _ in range(args.warmup):
+            step_chained_dense()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            step_chained_dense()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        ms_chained_dense = (t1 - t0) * 1e3 / args.steps
         chained = {"ms_per_step": ms_chained, "gops_eq": dense_ops_of(layers) / (ms_chained * 1e-3) / 1e9,
+                   "ms_per_step_inference_dense_context": ms_chained_dense,
                    "ms_per_step_inference": ms_chained_inf,
                    "inference_step": "weights prepared once (snn_subbit_prepare_sign); pack the first input, then one "
                                      "snn_subbit_conv2d_sign_prepared launch per layer",
@@ -558,8 +581,10 @@ def main():
     print("inference step (weights prepared once; pack + conv per layer): %.1f us; conv kernels alone: %.1f us" % (
         ms_per_step_inference * 1e3, sum(t_kern) * 1e3), file=sys.stderr)
     if chained is not None:
-        print("chained 1-bit stack (prepare_many + conv_sign per layer): %.1f us; with prepared weights: %.1f us" % (
-            chained["ms_per_step"] * 1e3, chained["ms_per_step_inference"] * 1e3), file=sys.stderr)
+        print("chained 1-bit stack (prepare_many + conv_sign per layer): %.1f us; with prepared weights: %.1f us; the "
+              "same through the dense contraction (prepared weights): %.1f us" % (
+                  chained["ms_per_step"] * 1e3, chained["ms_per_step_inference"] * 1e3,
+                  chained["ms_per_step_inference_dense_context"] * 1e3), file=sys.stderr)
 
     # ---- cpu_baseline: the oracle on a bounded sample of the same workload --------------------------------
     cpu = None
@@ -595,6 +620,9 @@ def main():
                 per_img = L.C_out * L.H_out * ((L.W_out + 31) // 32)
                 got = s["out_bits"][:2 * per_img].cpu().numpy().view(np.uint32).reshape(want.shape)
                 assert (got == want).all(), "chained GPU result differs from the oracle on " + L.name
+                want_c = oracle.pack_channels(xs)
+                got_c = s["out_bits_c"][:want_c.size].cpu().numpy().view(np.uint32).reshape(want_c.shape)
+                assert (got_c == want_c).all(), "chained dense-path result differs from the oracle on " + L.name
             chained["checked"] = "first 2 images of every layer's packed output equal the oracle's chain"
         cpu = {"value": ops_cpu / t_cpu / 1e9, "unit": "GOPS-equivalent", "cores": oracle.threads(), "kind": "oracle",
                "sample": "same %d layers, first %d images of the batch (project + sign + direct conv), %.1f s" % (

@@ -365,6 +365,22 @@ int snn_dense_prepare(const snn_conv_desc *desc, const uint16_t *codebook, const
 int snn_dense_conv2d_prepared(const snn_conv_desc *desc, const void *x, const float *alpha,
                               float *y_nchw, void *workspace, size_t ws_bytes, void *stream);
 
+/*
+ * The prepared dense contraction ending in the next layer's binarisation (Alg. 1 forward,
+ * sign(a^i), after the channel-wise affine alpha, beta; same definition as
+ * snn_subbit_conv2d_sign): packed channels in, packed channels out, no fp32 activations.
+ *   bit c % 32 of out[n][ho][wo][c / 32] = (fl(fl((float)S * alpha[c]) + beta[c]) >= 0)
+ *   desc, x, alpha, workspace: as for snn_dense_conv2d_prepared (after snn_dense_prepare)
+ *   beta        device, float [C_out]
+ *   out_packed  device, uint32 [N][H_out][W_out][ceil(C_out/32)] (snn_packed_bytes(N, C_out,
+ *               H_out, W_out, SNN_ACT_BIN_CHANNELS) bytes), fully overwritten, unused high bits 0:
+ *               the input of the next layer's dense call as it is
+ * Errors as for snn_dense_conv2d_prepared.
+ */
+int snn_dense_conv2d_sign_prepared(const snn_conv_desc *desc, const void *x, const float *alpha,
+                                   const float *beta, void *out_packed, void *workspace,
+                                   size_t ws_bytes, void *stream);
+
 /* Bytes of workspace the given entry point (SNN_WS_*) needs for this layer; 0 if desc is
  * invalid or the combination is unsupported.  Host-only, no device work. */
 size_t snn_workspace_bytes(const snn_conv_desc *desc, int which);

@@ -36,6 +36,7 @@ EXPORTS = ("snn_pack_activations", "snn_project_kernels", "snn_subbit_conv2d", "
            "snn_subbit_conv2d_sign_prepared", "snn_subbit_project_prepare_many", "snn_project_backward",
            "snn_project_backward_workspace_bytes", "snn_subset_update", "snn_bnn_conv2d", "snn_bnn_conv2d_dense",
            "snn_subbit_conv2d_dense", "snn_dense_prepare", "snn_dense_conv2d_prepared",
+           "snn_dense_conv2d_sign_prepared",
            "snn_workspace_bytes", "snn_packed_bytes", "snn_status_string")
 
 
@@ -116,6 +117,8 @@ def lib():
         L.snn_dense_prepare.restype = i32
         L.snn_dense_conv2d_prepared.argtypes = [dp, vp, vp, vp, vp, sz, vp]
         L.snn_dense_conv2d_prepared.restype = i32
+        L.snn_dense_conv2d_sign_prepared.argtypes = [dp, vp, vp, vp, vp, vp, sz, vp]
+        L.snn_dense_conv2d_sign_prepared.restype = i32
         L.snn_workspace_bytes.argtypes = [dp, i32]
         L.snn_workspace_bytes.restype = sz
         L.snn_packed_bytes.argtypes = [i32, i32, i32, i32, i32]
@@ -481,3 +484,21 @@ def snn_dense_conv2d_prepared(desc, x, alpha, workspace, y=None):
     _check(lib().snn_dense_conv2d_prepared(ctypes.byref(desc), _ptr(x), _ptr(alpha), _ptr(y), _ptr(workspace),
                                            workspace.numel(), _stream()), "snn_dense_conv2d_prepared")
     return y
+
+
+def snn_dense_conv2d_sign_prepared(desc, x, alpha, beta, workspace, out=None):
+    """Packed channels in, the next layer's packed channels out (int32 [N*Ho*Wo*ceil(C_out/32)])."""
+    _dev(alpha, torch.float32, "alpha")
+    _dev(beta, torch.float32, "beta")
+    Ho = (desc.H - 1) // desc.stride + 1
+    Wo = (desc.W - 1) // desc.stride + 1
+    words = snn_packed_bytes(desc.N, desc.C_out, Ho, Wo, SNN_ACT_BIN_CHANNELS) // 4
+    if out is None:
+        out = torch.empty(words, dtype=torch.int32, device=x.device)
+    _dev(out, torch.int32, "out")
+    if out.numel() < words:
+        raise ValueError("out is too small")
+    _check(lib().snn_dense_conv2d_sign_prepared(ctypes.byref(desc), _ptr(x), _ptr(alpha), _ptr(beta), _ptr(out),
+                                                _ptr(workspace), workspace.numel(), _stream()),
+           "snn_dense_conv2d_sign_prepared")
+    return out

@@ -32,7 +32,9 @@ struct DenseParams {
     const uint32_t *x;      // [N][H][W][CW]
     const u32x4 *wq;        // [co block][channel block of 64][tap][lane]: 32 FP4 codes
     const float *alpha;
+    const float *beta;      // sign epilogue only
     float *y;
+    uint32_t *sign_out;     // sign epilogue only: [N][Ho][Wo][ceil(C_out / 32)]
     Geom g;
     int ncb64;              // channel blocks of 64
     int n_cotiles;          // tiles of CB co blocks
@@ -131,7 +133,7 @@ void dense_fp4_prep_kernel(const uint16_t *__restrict__ codebook, int K, const u
 // instructions) earlier.
 constexpr int CHUNK_ENTRIES = 9 * 64;                       // 16-byte entries per co block and channel block
 
-template <int PB, int CB>
+template <int PB, int CB, bool SIGN>
 __global__ __launch_bounds__(256)
 void dense_fp4_kernel(DenseParams p)
 {
@@ -148,7 +150,7 @@ void dense_fp4_kernel(DenseParams p)
     // the lane's output pixel in each pixel block, its input corner and the taps inside the image
     uint32_t base[PB];                                      // byte offset of the window's corner word (mod 2^32)
     uint32_t inside[PB];
-    int64_t y_off[PB];                                      // of channel 0 at the lane's pixel; -1: no pixel
+    int64_t y_off[PB];                                      // of channel 0 (sign epilogue: word 0) at the lane's pixel; -1: no pixel
 #pragma unroll
     for (int pb = 0; pb < PB; ++pb) {
         const int64_t q = ((int64_t)pxtile * PB + pb) * 32 + (lane & 31);
@@ -156,7 +158,7 @@ void dense_fp4_kernel(DenseParams p)
         const int qq = ok ? (int)q : 0;                     // P < 2^31
         const int n = qq / g.HoWo;
         const int r = qq - n * g.HoWo;
-        y_off[pb] = ok ? (int64_t)n * g.C_out * g.HoWo + r : -1;
+        y_off[pb] = !ok ? -1 : SIGN ? (int64_t)qq * ((g.C_out + 31) / 32) : (int64_t)n * g.C_out * g.HoWo + r;
         const int ho = r / g.Wo, wo = r - ho * g.Wo;
         const int hi0 = ho * g.stride - 1, wi0 = wo * g.stride - 1;
         base[pb] = (uint32_t)(((n * g.H + hi0) * g.W + wi0) * g.CW + h) * 4u;
@@ -256,6 +258,38 @@ void dense_fp4_kernel(DenseParams p)
             const int co = (cotile * CB + cb) * 32 + 8 * (r / 4) + (r % 4) + 4 * h;
             al[cb][r] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(ares, co * 4, 0, 0));
         }
+    if constexpr (SIGN) {
+        // The next layer's sign: bit = (fl(fl(S alpha) + beta) >= 0).  A lane holds 16 of the 32 channels
+        // of a block for its pixel (rows 8 j + i + 4 h, i < 4); the other lane half holds the rest: one
+        // exchange across the halves, and lane half 0 stores the word of 32 channels.
+        const __amdgpu_buffer_rsrc_t bres = make_rsrc(p.beta, (uint32_t)g.C_out * 4u);
+        float be[CB][16];
+#pragma unroll
+        for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int co = (cotile * CB + cb) * 32 + 8 * (r / 4) + (r % 4) + 4 * h;
+                be[cb][r] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(bres, co * 4, 0, 0));
+            }
+#pragma unroll
+        for (int cb = 0; cb < CB; ++cb) {
+            const int co0 = (cotile * CB + cb) * 32;
+            if (co0 >= g.C_out) continue;                                    // (wave-uniform)
+            const uint32_t real = g.C_out - co0 >= 32 ? 0xffffffffu : (1u << (g.C_out - co0)) - 1u;
+#pragma unroll
+            for (int pb = 0; pb < PB; ++pb) {
+                uint32_t m = 0;
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    m |= (mul_then_add(acc[cb][pb][r], al[cb][r], be[cb][r]) >= 0.0f ? 1u : 0u) << (8 * (r / 4) + (r % 4));
+                m <<= 4 * h;
+                m |= (uint32_t)__shfl_xor((int)m, 32);
+                if (h == 0 && y_off[pb] >= 0) p.sign_out[y_off[pb] + (cotile * CB + cb)] = m & real;
+            }
+        }
+        DENSE_TRACE(4);
+        return;
+    }
 #pragma unroll
     for (int cb = 0; cb < CB; ++cb)
 #pragma unroll
@@ -305,16 +339,22 @@ DensePlan dense_plan(const Geom &g)
     return pl;
 }
 
-template <int PB, int CB>
-int launch_dense_one(const DenseParams &prm, int64_t wgs, hipStream_t s)
+template <int PB, int CB, bool SIGN>
+int launch_dense_cfg(const DenseParams &prm, int64_t wgs, hipStream_t s)
 {
-    auto kern = dense_fp4_kernel<PB, CB>;
+    auto kern = dense_fp4_kernel<PB, CB, SIGN>;
     const size_t lds = (size_t)2 * CB * CHUNK_ENTRIES * 16;
     if (lds > 64 * 1024 &&
         hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
         return SNN_ERR_LAUNCH;
     hipLaunchKernelGGL(kern, dim3((unsigned)wgs), dim3(256), lds, s, prm);
     return check_launch();
+}
+
+template <int PB, int CB>
+int launch_dense_one(const DenseParams &prm, int64_t wgs, hipStream_t s)
+{
+    return prm.sign_out ? launch_dense_cfg<PB, CB, true>(prm, wgs, s) : launch_dense_cfg<PB, CB, false>(prm, wgs, s);
 }
 
 }  // namespace
@@ -340,7 +380,7 @@ size_t dense_fp4_workspace_bytes(const Geom &g)
 }
 
 int launch_dense_fp4(const Geom &g, const void *x, const uint16_t *codebook, const uint16_t *w9, const float *alpha,
-                     float *y, void *ws, hipStream_t s, int phases)
+                     float *y, void *ws, hipStream_t s, int phases, const float *beta, uint32_t *sign_out)
 {
     const DensePlan pl = dense_plan(g);
     if (phases & SNN_PHASE_PREPARE) {
@@ -357,7 +397,9 @@ int launch_dense_fp4(const Geom &g, const void *x, const uint16_t *codebook, con
     prm.x = (const uint32_t *)x;
     prm.wq = (const u32x4 *)ws;
     prm.alpha = alpha;
+    prm.beta = beta;
     prm.y = y;
+    prm.sign_out = sign_out;
     prm.g = g;
     prm.ncb64 = pl.ncb64;
     prm.n_cotiles = pl.n_cotiles;

@@ -306,17 +306,19 @@ int snn_bnn_conv2d(const snn_conv_desc *desc, const void *x, const uint16_t *w9,
 
 namespace {
 int dense_call(const snn_conv_desc *desc, bool subbit, const void *x, const uint16_t *codebook, const uint16_t *codes,
-               const float *alpha, float *y, void *workspace, size_t ws_bytes, void *stream, int phases)
+               const float *alpha, float *y, void *workspace, size_t ws_bytes, void *stream, int phases,
+               const float *beta = nullptr, uint32_t *sign_out = nullptr)
 {
     if (!desc_ok(desc, subbit)) return SNN_ERR_INVALID_ARG;
     if ((phases & SNN_PHASE_PREPARE) && (!codes || (subbit && !codebook))) return SNN_ERR_INVALID_ARG;
-    if ((phases & SNN_PHASE_CONVOLVE) && (!x || !alpha || !y)) return SNN_ERR_INVALID_ARG;
+    if ((phases & SNN_PHASE_CONVOLVE) && (!x || !alpha || (!y && !(beta && sign_out)))) return SNN_ERR_INVALID_ARG;
     if (desc->act != SNN_ACT_BIN_CHANNELS) return SNN_ERR_UNSUPPORTED;
     const Geom g = make_geom(*desc);
     if (!dense_fp4_supported(g)) return SNN_ERR_UNSUPPORTED;
     const size_t need = dense_fp4_workspace_bytes(g);
     if (!workspace || ws_bytes < need || ((uintptr_t)workspace & 255u)) return SNN_ERR_WORKSPACE;
-    return launch_dense_fp4(g, x, subbit ? codebook : nullptr, codes, alpha, y, workspace, (hipStream_t)stream, phases);
+    return launch_dense_fp4(g, x, subbit ? codebook : nullptr, codes, alpha, y, workspace, (hipStream_t)stream, phases, beta,
+                            sign_out);
 }
 }  // namespace
 
@@ -343,6 +345,14 @@ int snn_dense_conv2d_prepared(const snn_conv_desc *desc, const void *x, const fl
                               void *workspace, size_t ws_bytes, void *stream)
 {
     return dense_call(desc, false, x, nullptr, nullptr, alpha, y_nchw, workspace, ws_bytes, stream, SNN_PHASE_CONVOLVE);
+}
+
+int snn_dense_conv2d_sign_prepared(const snn_conv_desc *desc, const void *x, const float *alpha, const float *beta,
+                                   void *out_packed, void *workspace, size_t ws_bytes, void *stream)
+{
+    if (!beta || !out_packed) return SNN_ERR_INVALID_ARG;
+    return dense_call(desc, false, x, nullptr, nullptr, alpha, nullptr, workspace, ws_bytes, stream, SNN_PHASE_CONVOLVE, beta,
+                      (uint32_t *)out_packed);
 }
 
 }  // extern "C"

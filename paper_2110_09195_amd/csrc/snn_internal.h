@@ -88,8 +88,11 @@ enum : int { SNN_PHASE_PREPARE = 1, SNN_PHASE_CONVOLVE = 2, SNN_PHASE_BOTH = 3 }
 bool dense_fp4_supported(const Geom &g);
 size_t dense_fp4_workspace_bytes(const Geom &g);
 // codebook == nullptr: `codes` are 9-bit kernel codes; else indices into the codebook (a sub-bit layer)
+// sign_out != nullptr: instead of y, the next layer's packed channels, bit = ((float)S * alpha[co] + beta[co] >= 0),
+// uint32 [N][H_out][W_out][ceil(C_out / 32)]
 int launch_dense_fp4(const Geom &g, const void *x, const uint16_t *codebook, const uint16_t *codes, const float *alpha,
-                     float *y, void *ws, hipStream_t s, int phases);
+                     float *y, void *ws, hipStream_t s, int phases, const float *beta = nullptr,
+                     uint32_t *sign_out = nullptr);
 
 size_t subbit_workspace_bytes(const Geom &g, int act);
 int launch_subbit(const Geom &g, int act, const void *x, const uint16_t *codebook,
@@ -138,6 +141,15 @@ int launch_subbit_forward(const Geom &g, const float *x, const float *w, const u
 // non-temporal store lets them drain to memory while the kernel runs instead of waiting in L2 for
 // the write-back at the kernel's end (measured: the kernels that follow run faster).
 __device__ inline void store_output(float *p, float v) { __builtin_nontemporal_store(v, p); }
+
+// fl(fl(a * b) + c): two fp32 roundings, never contracted into a fused multiply-add (the sign epilogue's
+// definition; a threshold that sits exactly on an attained value must compare equal)
+__device__ inline float mul_then_add(float a, float b, float c)
+{
+#pragma clang fp contract(off)
+    const float prod = a * b;
+    return prod + c;
+}
 
 // 1x1 layers: vectors of 8 input channels from a subset of {+-1}^8 (packed-channels input)
 bool subbit_conv1x1_supported(const Geom &g);

@@ -126,15 +126,6 @@ __device__ inline void prep_lut_block(const uint16_t *__restrict__ codebook, int
     }
 }
 
-// fl(fl(a * b) + c): two fp32 roundings, never contracted into a fused multiply-add (the sign epilogue's
-// definition; a threshold that sits exactly on an attained value must compare equal)
-__device__ inline float mul_then_add(float a, float b, float c)
-{
-#pragma clang fp contract(off)
-    const float prod = a * b;
-    return prod + c;
-}
-
 // One entry of the finishing table, for output channel co and border type `type`:
 //   corr_term = 2 corr + C_in (valid_taps(type) - 8), so that S = 2 acc - corr_term for the accumulator acc.
 // fp32 output (beta == nullptr): {corr_term, alpha}; the epilogue computes y = float(S) * alpha.

@@ -639,6 +639,61 @@ def test_subbit_forward_sign_chain(oracle):
         shape = (N, C_out, want.shape[2], xs.shape[3])
 
 
+@pytest.mark.parametrize("tile", [None, 0, 1, 4])
+@pytest.mark.parametrize("case", [c for c in FORWARD_CASES if c[1] > 1][:12] + [(2, 96, 130, 9, 11, 1, 32, "uniform"),
+                                                                              (3, 64, 33, 7, 7, 2, 16, "uniform")])
+def test_dense_conv2d_sign(oracle, case, tile, monkeypatch):
+    """The dense contraction ending in the next layer's sign: packed channels in and out."""
+    _say("dense_conv2d_sign", (case, tile))
+    if tile is not None:
+        monkeypatch.setenv("SNN_DENSE_TILE", str(tile))
+    N, C_in, C_out, H, W, stride, K, dist = case
+    x, cb, idx, alpha = _inputs(7100 + sum(case[:7]), N, C_in, C_out, H, W, K, dist)
+    g = np.random.default_rng(7101 + sum(case[:7]))
+    alpha[::4] *= -1.0
+    xs = oracle.sign(x)
+    codes = oracle.expand(cb, idx)
+    _, Y = oracle.conv_bin(xs, codes, alpha, stride)
+    beta = _beta_near_outputs(g, Y, C_out)
+    _, nxt = oracle.conv_sign(xs, codes, alpha, beta, stride)
+    want = oracle.pack_channels(nxt)
+    d = B.make_desc(N, C_in, C_out, H, W, stride, K, B.SNN_ACT_BIN_CHANNELS)
+    ws = B.alloc_workspace(d, B.SNN_WS_BNN_DENSE)
+    B.snn_dense_prepare(d, G.dev(cb), G.dev(idx), ws)
+    got = B.snn_dense_conv2d_sign_prepared(d, G.dev(oracle.pack_channels(x)), G.dev(alpha), G.dev(beta), ws)
+    torch.cuda.synchronize()
+    got = got.cpu().numpy().view(np.uint32).reshape(want.shape)
+    assert (got == want).all(), np.argwhere(got != want)[:5]
+
+
+def test_dense_sign_chain(oracle):
+    """A stack of layers passing 1-bit activations in the packed-channels layout through the dense
+    contraction; the GPU's output feeds the GPU's next layer, compared with the oracle after every layer."""
+    g = np.random.default_rng(4343)
+    N, H, W = 3, 20, 20
+    chain = [(24, 40, 1, 32), (40, 40, 1, 32), (40, 72, 2, 16), (72, 72, 1, 64), (72, 130, 2, 32), (130, 96, 1, 32)]
+    x = g.standard_normal((N, chain[0][0], H, W), dtype=np.float32)
+    xs = oracle.sign(x)
+    xp = G.dev(oracle.pack_channels(x))
+    for li, (C_in, C_out, stride, K) in enumerate(chain):
+        _say("dense chain layer", li, (C_in, C_out, stride, K))
+        cb = synth.codebook(g, K)
+        idx = synth.indices(g, C_out, C_in, K, "uniform")
+        alpha = synth.alpha(g, C_out)
+        codes = oracle.expand(cb, idx)
+        _, Y = oracle.conv_bin(xs, codes, alpha, stride)
+        beta = _beta_near_outputs(g, Y, C_out)
+        d = B.make_desc(N, C_in, C_out, H, W, stride, K, B.SNN_ACT_BIN_CHANNELS)
+        ws = B.alloc_workspace(d, B.SNN_WS_BNN_DENSE)
+        B.snn_dense_prepare(d, G.dev(cb), G.dev(idx), ws)
+        xp = B.snn_dense_conv2d_sign_prepared(d, xp, G.dev(alpha), G.dev(beta), ws)
+        torch.cuda.synchronize()
+        _, xs = oracle.conv_sign(xs, codes, alpha, beta, stride)
+        want = oracle.pack_channels(xs)
+        assert (xp.cpu().numpy().view(np.uint32).reshape(want.shape) == want).all(), li
+        H, W = xs.shape[2], xs.shape[3]
+
+
 # ---- the convolution in two halves (fixed weights) ----------------------------------------------------------------------
 
 @pytest.mark.parametrize("case", [SUBBIT_CASES[1], SUBBIT_CASES[2], SUBBIT_CASES[9], SUBBIT_CASES[13], SUBBIT_CASES[16]])
