@@ -137,7 +137,7 @@ template <int PB, int CB, bool SIGN>
 __global__ __launch_bounds__(256)
 void dense_fp4_kernel(DenseParams p)
 {
-    extern __shared__ __align__(16) unsigned char smem[];   // [2][CB][9][64] x 16 bytes
+    extern __shared__ __align__(16) unsigned char smem[];   // [2][CB][9][64] x 16 bytes of weights, then [2][CB * 32] floats
     const Geom &g = p.g;
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -145,8 +145,36 @@ void dense_fp4_kernel(DenseParams p)
     DENSE_TRACE(0);
     const int cotile = (int)blockIdx.x / p.n_pxgroups;
     const int pxgroup = (int)blockIdx.x - cotile * p.n_pxgroups;
+    // alpha (and beta) of the tile's channels, one per thread: channels past the end read 0
+    const __amdgpu_buffer_rsrc_t ares = make_rsrc(p.alpha, (uint32_t)g.C_out * 4u);
+    const __amdgpu_buffer_rsrc_t bres = make_rsrc(SIGN ? p.beta : p.alpha, (uint32_t)g.C_out * 4u);
+    const uint32_t scale_off = tid < CB * 32 ? (uint32_t)(cotile * CB * 32 + tid) * 4u : OFF_BIT;
+    const float early_alpha = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(ares, (int)scale_off, 0, 0));
+    const float early_beta = SIGN ? __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(bres, (int)scale_off, 0, 0)) : 0.0f;
     const int pxtile = pxgroup * 4 + wave;                  // past the last tile: a wave without pixels, still loading weights
 
+    const uint32_t cb_stride = (uint32_t)p.ncb64 * 9u * 1024u;      // bytes between the co blocks of the tile
+    const __amdgpu_buffer_rsrc_t wres = make_rsrc(p.wq, (uint32_t)p.n_cotiles * CB * cb_stride);
+    const uint32_t w_tile = (uint32_t)cotile * CB * cb_stride;
+    // this thread's share of a weight chunk: entries tid, tid + 256, ... of the CB x 576
+    constexpr int TOTAL = CB * CHUNK_ENTRIES;
+    constexpr int NW = (TOTAL + 255) / 256;
+    uint32_t w_src[NW];                                     // byte offset inside the tile's weights, channel block 0
+#pragma unroll
+    for (int i = 0; i < NW; ++i) {
+        const int e = tid + 256 * i;
+        const int cb = e / CHUNK_ENTRIES, rest = e - cb * CHUNK_ENTRIES;
+        w_src[i] = e < TOTAL ? w_tile + (uint32_t)cb * cb_stride + (uint32_t)rest * 16u : OFF_BIT;
+    }
+    u32x4 wreg[NW];
+    auto fetch_w = [&](int s) {
+#pragma unroll
+        for (int i = 0; i < NW; ++i)
+            wreg[i] = __builtin_amdgcn_raw_buffer_load_b128(wres, (int)w_src[i], (int)((uint32_t)s * 9216u), 0);
+    };
+    fetch_w(0);
+
+    // (the first weights are on their way while the lanes work out their geometry)
     // the lane's output pixel in each pixel block, its input corner and the taps inside the image
     uint32_t base[PB];                                      // byte offset of the window's corner word (mod 2^32)
     uint32_t inside[PB];
@@ -177,23 +205,8 @@ void dense_fp4_kernel(DenseParams p)
             for (int r = 0; r < 16; ++r) acc[cb][pb][r] = 0.0f;
 
     const __amdgpu_buffer_rsrc_t xres = make_rsrc(p.x, (uint32_t)g.N * (uint32_t)(g.H * g.W) * (uint32_t)g.CW * 4u);
-    const uint32_t cb_stride = (uint32_t)p.ncb64 * 9u * 1024u;      // bytes between the co blocks of the tile
-    const __amdgpu_buffer_rsrc_t wres = make_rsrc(p.wq, (uint32_t)p.n_cotiles * CB * cb_stride);
-    const uint32_t w_tile = (uint32_t)cotile * CB * cb_stride;
     const int cw_h = g.CW - h;
-    const __amdgpu_buffer_rsrc_t ares = make_rsrc(p.alpha, (uint32_t)g.C_out * 4u);     // channels past the end read 0
 
-    // this thread's share of a weight chunk: entries tid, tid + 256, ... of the CB x 576
-    constexpr int TOTAL = CB * CHUNK_ENTRIES;
-    constexpr int NW = (TOTAL + 255) / 256;
-    uint32_t w_src[NW];                                     // byte offset inside the tile's weights, channel block 0
-#pragma unroll
-    for (int i = 0; i < NW; ++i) {
-        const int e = tid + 256 * i;
-        const int cb = e / CHUNK_ENTRIES, rest = e - cb * CHUNK_ENTRIES;
-        w_src[i] = e < TOTAL ? w_tile + (uint32_t)cb * cb_stride + (uint32_t)rest * 16u : OFF_BIT;
-    }
-    u32x4 wreg[NW];
     uint32_t xn[9][PB], xc[9][PB];
 
     // 1 where the lane half has a word of channels in block s (2 s + h < CW) and tap t of pixel block pb
@@ -202,10 +215,7 @@ void dense_fp4_kernel(DenseParams p)
         const uint32_t have_word = (uint32_t)(2 * s - cw_h) >> 31;
         return 0u - ((inside[pb] >> t) & have_word);
     };
-    auto fetch = [&](int s) {
-#pragma unroll
-        for (int i = 0; i < NW; ++i)
-            wreg[i] = __builtin_amdgcn_raw_buffer_load_b128(wres, (int)w_src[i], (int)((uint32_t)s * 9216u), 0);
+    auto fetch_x = [&](int s) {
 #pragma unroll
         for (int t = 0; t < 9; ++t) {
             const uint32_t toff = (uint32_t)(((t / 3) * g.W + (t % 3)) * g.CW + 2 * s) * 4u;
@@ -216,7 +226,13 @@ void dense_fp4_kernel(DenseParams p)
     };
 
     DENSE_TRACE(1);
-    fetch(0);
+    fetch_x(0);
+    // the tile's scales (and offsets) wait in LDS for the epilogue: requested first of all, stored now
+    float *const scale_lds = (float *)(smem + 2 * TOTAL * 16);              // [2][CB * 32]
+    if (tid < CB * 32) {
+        scale_lds[tid] = early_alpha;
+        if constexpr (SIGN) scale_lds[CB * 32 + tid] = early_beta;
+    }
     for (int s = 0; s < p.ncb64; ++s) {
         unsigned char *buf = smem + (s & 1) * (TOTAL * 16);
 #pragma unroll
@@ -229,7 +245,10 @@ void dense_fp4_kernel(DenseParams p)
         // One barrier per channel block: a wave that writes buffer (s + 1) & 1 in the next round has passed
         // this barrier, hence every wave has finished reading that buffer in round s - 1.
         __syncthreads();
-        fetch(min(s + 1, p.ncb64 - 1));                     // (the last round repeats its own loads: unused)
+        if (s + 1 < p.ncb64) {
+            fetch_w(s + 1);
+            fetch_x(s + 1);
+        }
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int t = 0; t < 9; ++t) {
@@ -248,29 +267,21 @@ void dense_fp4_kernel(DenseParams p)
     }
 
     DENSE_TRACE(2);
-    // y = alpha * S; lanes 0..31 of a register are 32 consecutive pixels of one channel.  All scales are
-    // requested before the first store (a load issued between stores would wait for its own round trip).
+    // y = alpha * S; lanes 0..31 of a register are 32 consecutive pixels of one channel
     float al[CB][16];
 #pragma unroll
     for (int cb = 0; cb < CB; ++cb)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int co = (cotile * CB + cb) * 32 + 8 * (r / 4) + (r % 4) + 4 * h;
-            al[cb][r] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(ares, co * 4, 0, 0));
-        }
+        for (int r = 0; r < 16; ++r) al[cb][r] = scale_lds[cb * 32 + 8 * (r / 4) + (r % 4) + 4 * h];
     if constexpr (SIGN) {
         // The next layer's sign: bit = (fl(fl(S alpha) + beta) >= 0).  A lane holds 16 of the 32 channels
         // of a block for its pixel (rows 8 j + i + 4 h, i < 4); the other lane half holds the rest: one
         // exchange across the halves, and lane half 0 stores the word of 32 channels.
-        const __amdgpu_buffer_rsrc_t bres = make_rsrc(p.beta, (uint32_t)g.C_out * 4u);
         float be[CB][16];
 #pragma unroll
         for (int cb = 0; cb < CB; ++cb)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int co = (cotile * CB + cb) * 32 + 8 * (r / 4) + (r % 4) + 4 * h;
-                be[cb][r] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(bres, co * 4, 0, 0));
-            }
+            for (int r = 0; r < 16; ++r) be[cb][r] = scale_lds[CB * 32 + cb * 32 + 8 * (r / 4) + (r % 4) + 4 * h];
 #pragma unroll
         for (int cb = 0; cb < CB; ++cb) {
             const int co0 = (cotile * CB + cb) * 32;
@@ -343,7 +354,7 @@ template <int PB, int CB, bool SIGN>
 int launch_dense_cfg(const DenseParams &prm, int64_t wgs, hipStream_t s)
 {
     auto kern = dense_fp4_kernel<PB, CB, SIGN>;
-    const size_t lds = (size_t)2 * CB * CHUNK_ENTRIES * 16;
+    const size_t lds = (size_t)2 * CB * CHUNK_ENTRIES * 16 + 2 * CB * 32 * sizeof(float);
     if (lds > 64 * 1024 &&
         hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
         return SNN_ERR_LAUNCH;
