@@ -573,7 +573,7 @@ def main():
           "the weight expansion kernel: " + " ".join("%.1f/%.1f" % (a * 1e3, b * 1e3) for a, b in zip(t_dense, t_dense_k)),
           file=sys.stderr)
     if ms_per_step_dense is not None:
-        print("dense step (pack channels + dense conv per layer): %.1f us, with prepared weights %.1f us; dense conv "
+        print("dense step (pack channels + dense conv per layer; the indices are given, no projection): %.1f us, with prepared weights %.1f us; dense conv "
               "calls alone: %.1f us, prepared %.1f us" % (ms_per_step_dense * 1e3, ms_per_step_dense_inference * 1e3,
                                                          sum(t_dense) * 1e3, sum(t_dense_k) * 1e3), file=sys.stderr)
     print("step as one snn_subbit_forward per layer: %.1f us" % (ms_per_step_forward_calls * 1e3), file=sys.stderr)
@@ -666,7 +666,10 @@ def main():
         "dense_fp4_context": {
             "what": "the same sub-bit layers (subset + indices) through snn_subbit_conv2d_dense: kernels looked up and "
                     "expanded by a preparation kernel, then a dense FP4 contraction on the matrix cores without the "
-                    "sharing of Sec. 4.5; context, not the paper's method",
+                    "sharing of Sec. 4.5; context, not the paper's method.  ms_per_step = pack channels + the one-call dense "
+                    "convolution per layer with the indices given (unlike the headline step it does not project the "
+                    "real-valued kernels); ms_per_step_inference = pack channels + the prepared convolution per layer, "
+                    "to be compared with the top-level ms_per_step_inference",
             "ms_per_step": ms_per_step_dense, "ms_per_step_inference": ms_per_step_dense_inference,
             "conv_us": sum(t_dense) * 1e3, "conv_prepared_us": sum(t_dense_k) * 1e3,
             "conv_us_per_layer": [v * 1e3 for v in t_dense],
