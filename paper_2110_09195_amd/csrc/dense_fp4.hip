@@ -12,8 +12,10 @@
 // One contraction step = one tap and 64 input channels: lane half h of the wave holds channels
 // 64 s + 32 h .. + 31, i.e. one 32-bit word of the packed-channels input per pixel, which four
 // v_perm_b32 pairs turn into the 32 FP4 codes (2 bits -> 1 byte through a 4-entry byte table; the
-// table is zero where the tap lies outside the image).  The weights are expanded once per call into
-// the operand layout (preparation kernel), 16 bytes per lane and step, and are read from L1/L2.
+// table is zero where the tap lies outside the image).  The weights are expanded into the operand
+// layout by a preparation kernel (16 bytes per lane and step; from 9-bit codes, or from indices into a
+// layer's subset), and the four waves of a workgroup share them through LDS.  An optional epilogue
+// replaces y by the next layer's sign bits in the packed-channels layout.
 #include <cstdlib>
 
 #include "snn_internal.h"
@@ -376,7 +378,7 @@ bool dense_fp4_supported(const Geom &g)
     const int64_t x_words = (int64_t)g.N * g.H * g.W * g.CW;
     const int64_t w_bytes = (int64_t)(((g.C_out + 31) / 32 + 3) / 4 * 4) * ((g.C_in + 63) / 64) * 9 * 1024;
     return x_words < ((int64_t)1 << 29) && w_bytes < ((int64_t)1 << 31) && g.P < ((int64_t)1 << 31) - 64 &&
-           (((g.P + 31) / 32) * ((g.C_out + 31) / 32) + 3) / 4 < ((int64_t)1 << 31);
+           ((g.P + 31) / 32) * ((g.C_out + 31) / 32) < ((int64_t)1 << 31);
 }
 
 size_t dense_fp4_workspace_bytes(const Geom &g)
