@@ -9,7 +9,8 @@
 // One v_mfma_scale_f32_32x32x64_f8f6f4 covers 32 output channels x 32 pixels and 64 contraction
 // slots, of which lanes 0-31 supply the first 32 and lanes 32-63 the rest.  For K <= 32 the slots
 // are (channel parity, subset member k): TWO input channels per instruction, the even one in the
-// low lanes.  For 32 < K <= 64 they are the members k of ONE input channel.
+// low lanes.  For 32 < K <= 64 they are the members k of ONE input channel.  For K <= 16 a lane
+// half can hold two channels of 16 slots each, FOUR channels per instruction (used on long layers).
 //   A operand (FP4 e2m1): the one-hot row of an output channel, 32 nibbles, made from a
 //     pre-computed byte selector with four v_perm_b32;
 //   B operand (FP6 e2m3): the table row itself, stored as m_k - 4 in [-4, 5] (exact in e2m3), read
@@ -63,7 +64,7 @@ struct MfParams {
     Geom g;
     int COP;                  // C_out padded to whole wave tiles
     int KS;                   // waves that split the channel pairs of one tile: 1, 2 or 4
-    int npairs;               // steps: (C_in + 1) / 2 of two input channels (K <= 32), else C_in of one
+    int npairs;               // steps: (C_in + 1) / 2 of two input channels (K <= 32), C_in of one, or (C_in + 3) / 4 of four (QUAD)
     int pairs_per_split;
     int n_cotiles;
     long long n_tiles;        // pixel tiles * channel tiles
@@ -191,6 +192,14 @@ __device__ inline uint32_t sel_word(uint32_t k)
 // where the convolution's step / lane half expects it; k < 0: no member (padding channel).
 __device__ inline void store_sel(uint32_t *__restrict__ sel, int COP, int C_in, int pair, int pos, int ci, int k)
 {
+    if (pair == 2) {
+        // four channels per step (K <= 16): channel ci is slot-half (ci % 2) of lane half (ci / 2) % 2 of step
+        // ci / 4; the second channel of a lane half owns slots 16 .. 31.  Channels from C_in up to the next
+        // multiple of four get "no member" (the caller passes them with k < 0).
+        const int c = ci >> 2, h = (ci >> 1) & 1, j = ci & 1;
+        sel[(((int64_t)c * 2 + h) * 2 + j) * COP + pos] = k >= 0 ? sel_word((uint32_t)k + 16u * (uint32_t)j) : MF_SEL_NONE;
+        return;
+    }
     const uint32_t s = k >= 0 ? sel_word((uint32_t)k) : MF_SEL_NONE;
     if (!pair) {
         // one channel per step; the member's half (k / 32) gets the selector, the other one nothing
@@ -230,7 +239,7 @@ void subbit_mfma_prep_kernel(const uint16_t *__restrict__ codebook, const void *
         for (int e = tid; e < 1024; e += 256) {
             const int co_l = e % 32, ci_l = e / 32;
             const int ci = ci0 + ci_l;
-            if (ci >= C_in) continue;
+            if (ci >= (pair == 2 ? (C_in + 3) / 4 * 4 : C_in)) continue;
             const uint32_t k = tile[co_l][ci_l];
             // position inside a row of COP selectors: [wave tile][channel in block][block]
             const int co = co0 + co_l, tilew = 32 * CB;
@@ -377,6 +386,7 @@ __device__ inline void weight_channel_block(const WeightParams &p, int co, uint3
                 for (int t = 0; t < 9; ++t) wt[q][t] = nx[q][t];
         }
     }
+    if (p.pair == 2 && C_in + tid < (C_in + 3) / 4 * 4) store_sel(p.sel, p.COP, C_in, 2, pos, C_in + tid, -1);
     if (lane == 0) {
 #pragma unroll
         for (int t = 0; t < 9; ++t) wsum[wave * 9 + t] = (uint32_t)zeros[t];
@@ -480,7 +490,7 @@ __device__ inline u32x4 buf_load4(__amdgpu_buffer_rsrc_t r, uint32_t lane_off, u
 // ---- the convolution ------------------------------------------------------------------------------
 // PB, CB: blocks of 32 pixels / 32 output channels per wave.  WM: words per packed row, 1 or 2
 // (the three window rows of a lane are then one contiguous load), or 0 for wider rows.
-// PAIR: two input channels per step (K <= 32), else one (K <= 64).
+// PAIR: two input channels per step (K <= 32), else one (K <= 64); QUAD (with PAIR): four (K <= 16).
 // STG: the packed rows a tile touches are few (at most MF_STAGE_SLOTS pieces per channel, WM = 1
 // or 2).  Then the lanes do not fetch their own three rows from memory, 31 of 32 of those reads
 // being the same words: per step ONE load brings every piece the wave needs (lane s of a half:
@@ -489,11 +499,15 @@ __device__ inline u32x4 buf_load4(__amdgpu_buffer_rsrc_t r, uint32_t lane_off, u
 // word is one piece; a row of two words is three overlapping pieces, bits [0,32), [16,48) and
 // [32,64), so that every window of three columns lies inside one of them.  The memory pipeline,
 // which otherwise bounds the layers with few output channels, sees one instruction instead of 3 PB.
-template <int PB, int CB, int WM, bool PAIR, bool STG>
+template <int PB, int CB, int WM, bool PAIR, bool STG, bool QUAD = false>
 __global__ __launch_bounds__(MF_WAVES * 64, 2)
 void subbit_mfma_kernel(const MfParams p)
 {
     static_assert(!STG || WM == 1 || WM == 2, "staging needs rows that are consecutive in memory");
+    // QUAD: subsets of at most 16 members.  A lane half then holds TWO input channels per step (channels
+    // 4 c + 2 h and 4 c + 2 h + 1): 16 table values each in its operand, and two one-hot selectors, the
+    // second one in slots 16 .. 31.  Half as many steps, twice the window work per step.
+    static_assert(!QUAD || (PAIR && !STG && WM != 3), "four channels per step: 3x3 layers, rows loaded directly");
     // WM == 3: a 1x1 layer.  The "window" of a pixel and step is the byte of the signs of 8 consecutive
     // input channels (packed-channels input), a "channel" of the steps is such a group of 8, the table
     // has 256 rows of match counts m_k - 4 out of 8, there is no border, and S = 2 acc.
@@ -633,7 +647,7 @@ void subbit_mfma_kernel(const MfParams p)
         sh[pb] = STG ? (uint32_t)(col - 16 * piece) : (uint32_t)(col & 31);
         m7[pb] = first < 0 ? 3u : 7u;
         lsh[pb] = (first < 0 ? 1u : 0u) + (hc == 0 ? 3u : 0u);
-        xoff[pb] = (uint32_t)(((n * g.C_in + (PAIR ? h : 0)) * g.H + (hc == 0 ? 0 : hc - 1)) * g.WW + jlo) * 4u;
+        xoff[pb] = (uint32_t)(((n * g.C_in + (QUAD ? 2 * h : PAIR ? h : 0)) * g.H + (hc == 0 ? 0 : hc - 1)) * g.WW + jlo) * 4u;
         loff[pb] = stage_wave + (uint32_t)((PAIR ? h * MF_STAGE_SLOTS : 0) + (n * g.H + (hc == 0 ? 0 : hc - 1) - R_first) * SW + piece) * 4u;
     }
     const __amdgpu_buffer_rsrc_t xres = make_rsrc(p.x, ONE ? p.x_bytes : (uint32_t)g.N * (uint32_t)g.C_in * plane_bytes);
@@ -642,6 +656,7 @@ void subbit_mfma_kernel(const MfParams p)
     constexpr bool ONE_WORD = WM == 1 || STG;      // a lane cuts its window row out of one 32-bit piece
     struct Raw {
         uint32_t lo[PB][3], hi[ONE_WORD || ONE ? 1 : PB][3];
+        uint32_t lo2[QUAD ? PB : 1][3], hi2[QUAD && !ONE_WORD ? PB : 1][3];      // QUAD: the lane half's second channel
         uint32_t byte_shift;                       // 1x1: position of the lane's group inside the word loaded
     };
     // step c -> first channel of the pair (the last step of an odd C_in starts one channel early)
@@ -657,31 +672,37 @@ void subbit_mfma_kernel(const MfParams p)
             for (int pb = 0; pb < PB; ++pb) r.lo[pb][0] = buf_load1(xres, xoff[pb] + word_off, 0u);
             return;
         }
-        const uint32_t co = (uint32_t)(PAIR ? min(2 * c, last_first) : c) * plane_bytes;
-#pragma unroll
-        for (int pb = 0; pb < PB; ++pb) {
+        // QUAD: channels 4 c + 2 h + {0, 1}; those past C_in read the next image or, past the tensor, zeros:
+        // their selectors say "no member"
+        const uint32_t co = (uint32_t)(QUAD ? 4 * c : PAIR ? min(2 * c, last_first) : c) * plane_bytes;
+        auto rows_of = [&](uint32_t cof, uint32_t (&lo)[3], uint32_t (&hi)[3], int pb) {
             if constexpr (WM == 1) {                 // rows are consecutive words
-                const u32x3 v = buf_load3(xres, xoff[pb], co);
-                r.lo[pb][0] = v.x;
-                r.lo[pb][1] = v.y;
-                r.lo[pb][2] = v.z;
+                const u32x3 v = buf_load3(xres, xoff[pb], cof);
+                lo[0] = v.x;
+                lo[1] = v.y;
+                lo[2] = v.z;
             } else if constexpr (WM == 2) {          // rows are consecutive word pairs
-                const u32x4 v = buf_load4(xres, xoff[pb], co);
-                const u32x2 w = buf_load2(xres, xoff[pb] + 16u, co);
-                r.lo[pb][0] = v.x;
-                r.hi[pb][0] = v.y;
-                r.lo[pb][1] = v.z;
-                r.hi[pb][1] = v.w;
-                r.lo[pb][2] = w.x;
-                r.hi[pb][2] = w.y;
+                const u32x4 v = buf_load4(xres, xoff[pb], cof);
+                const u32x2 w = buf_load2(xres, xoff[pb] + 16u, cof);
+                lo[0] = v.x;
+                hi[0] = v.y;
+                lo[1] = v.z;
+                hi[1] = v.w;
+                lo[2] = w.x;
+                hi[2] = w.y;
             } else {
 #pragma unroll
                 for (int dy = 0; dy < 3; ++dy) {
-                    const u32x2 v = buf_load2(xres, xoff[pb] + (uint32_t)dy * row_bytes, co);
-                    r.lo[pb][dy] = v.x;
-                    r.hi[pb][dy] = v.y;
+                    const u32x2 v = buf_load2(xres, xoff[pb] + (uint32_t)dy * row_bytes, cof);
+                    lo[dy] = v.x;
+                    hi[dy] = v.y;
                 }
             }
+        };
+#pragma unroll
+        for (int pb = 0; pb < PB; ++pb) {
+            rows_of(co, r.lo[pb], r.hi[ONE_WORD ? 0 : pb], pb);
+            if constexpr (QUAD) rows_of(co + plane_bytes, r.lo2[pb], r.hi2[ONE_WORD ? 0 : pb], pb);
         }
     };
     typedef std::conditional_t<WM == 2, u32x2, uint32_t> Staged;
@@ -701,50 +722,65 @@ void subbit_mfma_kernel(const MfParams p)
             for (int dy = 0; dy < 3; ++dy) r.lo[pb][dy] = *(lds_cu32 *)(uintptr_t)(loff[pb] + (uint32_t)(dy * SW) * 4u);
     };
     // selectors of the lane's CB channel blocks are contiguous: [step][half][tile][channel in block][block]
-    const uint32_t sel_step_bytes = 2u * (uint32_t)p.COP * 4u;
+    // (QUAD: [step][half][channel of the half][...], two selectors per channel block)
+    constexpr int NSEL = QUAD ? 2 * CB : CB;
+    const uint32_t sel_step_bytes = (QUAD ? 4u : 2u) * (uint32_t)p.COP * 4u;
     const __amdgpu_buffer_rsrc_t sres = make_rsrc(p.sel, (uint32_t)p.npairs * sel_step_bytes);
-    const uint32_t sel_lane = (uint32_t)(h * p.COP + co0 + n_l * CB) * 4u;
-    auto load_sel = [&](int c, uint32_t (&s)[CB]) {
+    const uint32_t sel_lane = (uint32_t)((QUAD ? 2 * h : h) * p.COP + co0 + n_l * CB) * 4u;
+    auto load_sel = [&](int c, uint32_t (&s)[NSEL]) {
         static_assert(CB == 2 || CB == 4, "selector loads are 8 or 16 bytes");
-        if constexpr (CB == 4) {
-            const u32x4 v = buf_load4(sres, sel_lane, (uint32_t)c * sel_step_bytes);
-            s[0] = v.x;
-            s[1] = v.y;
-            s[2] = v.z;
-            s[3] = v.w;
-        } else {
-            const u32x2 v = buf_load2(sres, sel_lane, (uint32_t)c * sel_step_bytes);
-            s[0] = v.x;
-            s[1] = v.y;
+#pragma unroll
+        for (int j = 0; j < (QUAD ? 2 : 1); ++j) {
+            const uint32_t at = sel_lane + (uint32_t)(j * p.COP) * 4u;
+            if constexpr (CB == 4) {
+                const u32x4 v = buf_load4(sres, at, (uint32_t)c * sel_step_bytes);
+                s[j * CB + 0] = v.x;
+                s[j * CB + 1] = v.y;
+                s[j * CB + 2] = v.z;
+                s[j * CB + 3] = v.w;
+            } else {
+                const u32x2 v = buf_load2(sres, at, (uint32_t)c * sel_step_bytes);
+                s[j * CB + 0] = v.x;
+                s[j * CB + 1] = v.y;
+            }
         }
     };
     // table rows of the PB pixels -> B operands (24 bytes: 32 FP6 values)
     auto make_B = [&](const Raw &r, v8i (&B)[PB]) {
 #pragma unroll
         for (int pb = 0; pb < PB; ++pb) {
-            uint32_t w;
-            if constexpr (ONE) {
-                w = (r.lo[pb][0] >> r.byte_shift) & 0xffu;
-            } else {
+            auto window = [&](const uint32_t (&lo)[3], const uint32_t (&hi)[3]) -> uint32_t {
                 uint32_t row[3];
 #pragma unroll
-                for (int dy = 0; dy < 3; ++dy)
-                    row[dy] = __builtin_amdgcn_alignbit(ONE_WORD ? r.lo[pb][dy] : r.hi[pb][dy], r.lo[pb][dy], sh[pb]);
+                for (int dy = 0; dy < 3; ++dy) row[dy] = __builtin_amdgcn_alignbit(ONE_WORD ? lo[dy] : hi[dy], lo[dy], sh[pb]);
                 const uint32_t m = m7[pb];
-                w = (((row[0] & m) | ((row[1] & m) << 3) | ((row[2] & m) << 6)) << lsh[pb]) & vm[pb];
+                return (((row[0] & m) | ((row[1] & m) << 3) | ((row[2] & m) << 6)) << lsh[pb]) & vm[pb];
+            };
+            if constexpr (QUAD) {
+                // 16 table values (three words) per channel
+                const uint32_t wa = window(r.lo[pb], r.hi[ONE_WORD ? 0 : pb]), wb = window(r.lo2[pb], r.hi2[ONE_WORD ? 0 : pb]);
+                const u32x4 qa = *(lds_cu32x4 *)(uintptr_t)(lut_base + wa * MF_LROW);
+                const u32x4 qb = *(lds_cu32x4 *)(uintptr_t)(lut_base + wb * MF_LROW);
+                B[pb] = (v8i){(int)qa.x, (int)qa.y, (int)qa.z, (int)qb.x, (int)qb.y, (int)qb.z, 0, 0};
+                continue;
             }
+            uint32_t w;
+            if constexpr (ONE) w = (r.lo[pb][0] >> r.byte_shift) & 0xffu;
+            else w = window(r.lo[pb], r.hi[ONE_WORD ? 0 : pb]);
             const uint32_t addr = lut_base + w * MF_LROW + (PAIR ? 0u : 32u * (uint32_t)h);
             const u32x4 q0 = *(lds_cu32x4 *)(uintptr_t)addr;
             const u32x2 q1 = *(lds_cu32x2 *)(uintptr_t)(addr + 16);
             B[pb] = (v8i){(int)q0.x, (int)q0.y, (int)q0.z, (int)q0.w, (int)q1.x, (int)q1.y, 0, 0};
         }
     };
-    auto make_A = [&](const uint32_t (&s)[CB], v8i (&A)[CB]) {
+    auto make_A = [&](const uint32_t (&s)[NSEL], v8i (&A)[CB]) {
 #pragma unroll
-        for (int cb = 0; cb < CB; ++cb)
-            A[cb] = (v8i){(int)__builtin_amdgcn_perm(0u, 0x00002002u, s[cb]), (int)__builtin_amdgcn_perm(0u, 0x20020000u, s[cb]),
-                          (int)__builtin_amdgcn_perm(0x00002002u, 0u, s[cb]), (int)__builtin_amdgcn_perm(0x20020000u, 0u, s[cb]),
+        for (int cb = 0; cb < CB; ++cb) {
+            const uint32_t sa = s[cb], sb = s[QUAD ? CB + cb : cb];       // QUAD: words 2, 3 come from the second channel's selector
+            A[cb] = (v8i){(int)__builtin_amdgcn_perm(0u, 0x00002002u, sa), (int)__builtin_amdgcn_perm(0u, 0x20020000u, sa),
+                          (int)__builtin_amdgcn_perm(0x00002002u, 0u, sb), (int)__builtin_amdgcn_perm(0x20020000u, 0u, sb),
                           0, 0, 0, 0};
+        }
     };
 
     v16f acc[CB][PB];
@@ -765,14 +801,14 @@ void subbit_mfma_kernel(const MfParams p)
     // sets).  Deeper rings where a step's loads are few registers.  With staging the rows come out of
     // LDS two steps ahead (two sets again, so that no LDS read is waited for in the step that issues
     // it), and the one staged word per step sits in a ring of its own, SRING steps ahead.
-    constexpr int RAW_REGS = (STG ? 0 : WM == 3 ? PB + 1 : PB * (WM == 1 ? 3 : 6)) + CB;
+    constexpr int RAW_REGS = (STG ? 0 : WM == 3 ? PB + 1 : PB * (WM == 1 ? 3 : 6) * (QUAD ? 2 : 1)) + NSEL;
     constexpr int RING = RAW_REGS <= 16 ? 3 : 2;
     constexpr int SRING = 6;
     constexpr int UNROLL = STG ? 6 : RING % 2 == 0 ? RING : 2 * RING;
     static_assert(UNROLL % RING == 0 && UNROLL % 2 == 0 && (!STG || UNROLL % SRING == 0), "register sets rotate with the unrolled steps");
     Raw raw[STG ? 2 : RING];
     Staged stg[SRING];
-    uint32_t sel[RING][CB];
+    uint32_t sel[RING][NSEL];
     v8i A[2][CB], B[2][PB];
     if constexpr (STG) {
 #pragma unroll
@@ -832,10 +868,11 @@ void subbit_mfma_kernel(const MfParams p)
                     acc[cb][pb] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(A[cur][cb], B[cur][pb], acc[cb][pb], 4 /* A: FP4 */,
                                                                                   2 /* B: FP6 e2m3 */, 0, 127, 0, 127);
             constexpr int NMF = CB * PB;
-            constexpr int NVM = (STG ? 1 : PB * (WM == 1 || WM == 3 ? 1 : WM == 2 ? 2 : 3)) + 1;   // loads of a step
+            constexpr int NCH = QUAD ? 2 : 1;
+            constexpr int NVM = (STG ? 1 : NCH * PB * (WM == 1 || WM == 3 ? 1 : WM == 2 ? 2 : 3)) + NCH;   // loads of a step
             constexpr int NDS = 2 * PB + (STG ? PB * 2 : 0);                     // LDS reads of a step
             constexpr int DS_PER = (NDS + NMF - 1) / NMF;
-            constexpr int NVA = PB * 11 + CB * 4 + 4;                       // vector ALU instructions of a step (estimate)
+            constexpr int NVA = NCH * PB * 11 + CB * 4 + 4;                 // vector ALU instructions of a step (estimate)
             constexpr int VM_PER = (NVM + NMF - 1) / NMF, VA_PER = (NVA + NMF - 1) / NMF;
 #pragma unroll
             for (int m = 0; m < NMF; ++m) {
@@ -1060,6 +1097,7 @@ struct MfCfg {
 struct MfPlan {
     MfCfg cfg;
     bool pair;        // K <= 32: two input channels per step
+    bool quad;        // K <= 16 (3x3 layers): four
     bool stage;       // the rows of a tile fit the staging slots
     bool one;         // 1x1 layer (g.C_in = groups of 8 input channels)
     int KS, COP, n_cotiles, npairs;
@@ -1105,10 +1143,28 @@ MfPlan mf_plan(const Geom &g, bool aligned = false, bool one = false)
     pl.n_pxtiles = (pl.n_pxblocks + pl.cfg.PB - 1) / pl.cfg.PB;
     pl.n_tiles = pl.n_pxtiles * pl.n_cotiles;
     pl.pair = g.K <= 32;
+    pl.quad = false;
     pl.npairs = pl.pair ? (g.C_in + 1) / 2 : g.C_in;
     // split the channel pairs over waves while the tiles alone leave SIMDs idle (1024 SIMDs, two waves each)
-    int KS = 1;
-    while (KS < 4 && pl.n_tiles * KS < 1536 && pl.npairs / (2 * KS) >= 8) KS *= 2;
+    auto split_of = [&](int steps) {
+        int ks = 1;
+        while (ks < 4 && pl.n_tiles * ks < 1536 && steps / (2 * ks) >= 8) ks *= 2;
+        return ks;
+    };
+    int KS = split_of(pl.npairs);
+    // Subsets of at most 16 members: four channels per step halve the matrix instructions and double the
+    // window work of a step (and give up the staged rows).  Measured: a gain (1.2x) only where a wave has
+    // long runs of steps - many input channels on tiles of four channel blocks - and a loss on short ones.
+    // SNN_MFMA_QUAD = 1 / 0 forces it on wherever it applies / off.
+    if (g.K <= 16 && !one) {
+        const int quad_env = env_int("SNN_MFMA_QUAD", -1);
+        const bool pays = pl.cfg.CB == 4 && (int64_t)(pl.npairs / KS) * pl.cfg.PB * pl.cfg.CB >= 768;
+        if (quad_env < 0 ? pays : quad_env != 0) {
+            pl.quad = true;
+            pl.npairs = (g.C_in + 3) / 4;
+            KS = split_of(pl.npairs);
+        }
+    }
     const int ks_env = env_int("SNN_MFMA_KS", 0);
     if (ks_env == 1 || ks_env == 2 || ks_env == 4) KS = ks_env;
     pl.KS = KS;
@@ -1122,7 +1178,7 @@ MfPlan mf_plan(const Geom &g, bool aligned = false, bool one = false)
     // matrix instructions per window (measured; with four blocks the loop is bound by the matrix pipe
     // and the extra LDS traffic costs a little).  SNN_MFMA_STAGE = 1 / 0 forces it on wherever it fits / off.
     const int stage_env = env_int("SNN_MFMA_STAGE", -1);
-    pl.stage = !one && g.WW <= 2 && tile_rows * (g.WW == 2 ? 3 : 1) <= MF_STAGE_SLOTS &&
+    pl.stage = !one && !pl.quad && g.WW <= 2 && tile_rows * (g.WW == 2 ? 3 : 1) <= MF_STAGE_SLOTS &&
                (stage_env < 0 ? pl.cfg.CB == 2 : stage_env != 0);
     const size_t lut_bytes = (size_t)(one ? 256 : 512) * mf_lrow(pl.pair) + (pl.stage ? (size_t)MF_WAVES * MF_STAGE_BYTES : 0);
     const int nblk = pl.cfg.PB * pl.cfg.CB;
@@ -1135,7 +1191,7 @@ MfPlan mf_plan(const Geom &g, bool aligned = false, bool one = false)
     o += 4096;                // clock samples
 #endif
     pl.off_sel = o;
-    o += align_up((size_t)pl.npairs * 2 * pl.COP * sizeof(uint32_t), 256);
+    o += align_up((size_t)pl.npairs * (pl.quad ? 4 : 2) * pl.COP * sizeof(uint32_t), 256);
     pl.off_fin = o;
     o += align_up((size_t)pl.COP * 16 * sizeof(uint2), 256);
     pl.off_lut = o;
@@ -1144,10 +1200,10 @@ MfPlan mf_plan(const Geom &g, bool aligned = false, bool one = false)
     return pl;
 }
 
-template <int PB, int CB, int WM, bool PAIR, bool STG>
+template <int PB, int CB, int WM, bool PAIR, bool STG, bool QUAD = false>
 int launch_mf_one(const MfPlan &pl, const MfParams &prm, hipStream_t s)
 {
-    auto kern = subbit_mfma_kernel<PB, CB, WM, PAIR, STG>;
+    auto kern = subbit_mfma_kernel<PB, CB, WM, PAIR, STG, QUAD>;
     if (pl.lds > 64 * 1024 &&
         hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)pl.lds) != hipSuccess)
         return SNN_ERR_LAUNCH;
@@ -1165,8 +1221,17 @@ int launch_mf_pair(const MfPlan &pl, const MfParams &prm, hipStream_t s)
 }
 
 template <int PB, int CB>
+int launch_mf_quad(const MfPlan &pl, const MfParams &prm, hipStream_t s)
+{
+    if (prm.g.WW == 1) return launch_mf_one<PB, CB, 1, true, false, true>(pl, prm, s);
+    if (prm.g.WW == 2) return launch_mf_one<PB, CB, 2, true, false, true>(pl, prm, s);
+    return launch_mf_one<PB, CB, 0, true, false, true>(pl, prm, s);
+}
+
+template <int PB, int CB>
 int launch_mf(const MfPlan &pl, const MfParams &prm, hipStream_t s)
 {
+    if (pl.quad) return launch_mf_quad<PB, CB>(pl, prm, s);
     return pl.pair ? launch_mf_pair<PB, CB, true>(pl, prm, s) : launch_mf_pair<PB, CB, false>(pl, prm, s);
 }
 
@@ -1240,7 +1305,7 @@ WeightParams weight_params(const MfPlan &pl, const Geom &g, const MfParams &prm,
     wp.COP = pl.COP;
     wp.CB = pl.cfg.CB;
     wp.K = g.K;
-    wp.pair = pl.pair ? 1 : 0;
+    wp.pair = pl.quad ? 2 : pl.pair ? 1 : 0;
     wp.lut_blocks = (512 * (pl.pair ? 6 : 12) + 255) / 256;
     return wp;
 }
@@ -1289,7 +1354,7 @@ int launch_subbit_mfma(const Geom &g, const void *x, const uint16_t *codebook, c
     const int lut_blocks = (512 * (pl.pair ? 6 : 12) + 255) / 256;
     if (phases & SNN_PHASE_PREPARE)
         hipLaunchKernelGGL(subbit_mfma_prep_kernel, dim3((unsigned)(sel_blocks + corr_blocks + lut_blocks)), dim3(256), 0, s,
-                           codebook, (const void *)idx, tau, g.C_in, g.C_out, pl.COP, pl.cfg.CB, g.K, pl.pair ? 1 : 0, sel_blocks, lut_blocks, alpha,
+                           codebook, (const void *)idx, tau, g.C_in, g.C_out, pl.COP, pl.cfg.CB, g.K, pl.quad ? 2 : pl.pair ? 1 : 0, sel_blocks, lut_blocks, alpha,
                            (uint32_t *)prm.sel, (uint2 *)prm.fin, (uint32_t *)prm.lut, sign ? sign->beta : nullptr, 9);
     if (!(phases & SNN_PHASE_CONVOLVE)) return check_launch();
     return launch_mf_conv(pl, prm, s);

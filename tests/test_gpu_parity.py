@@ -194,6 +194,59 @@ def test_subbit_bin_matrix_core_kernel_every_tile_and_split(oracle, tile, split,
         assert (y == Y).all(), np.argwhere(y != Y)[:5]
 
 
+QUAD_LAYERS = [(3, 45, 150, 13, 11, 1, 16), (2, 20, 70, 16, 12, 2, 9), (2, 34, 40, 9, 40, 1, 16), (1, 8, 33, 5, 70, 1, 5),
+               (2, 130, 96, 8, 8, 2, 7), (1, 2, 3, 1, 1, 1, 2), (7, 5, 8, 3, 7, 2, 12), (2, 6, 40, 12, 56, 1, 16),
+               (1, 4, 33, 6, 64, 1, 16), (2, 7, 40, 9, 11, 1, 1), (2, 257, 130, 6, 6, 1, 16)]
+
+
+@pytest.mark.parametrize("tile", ["4,2", "2,4", "2,2", "1,4", "1,2"])
+@pytest.mark.parametrize("split", [1, 2, 4])
+def test_subbit_bin_four_channels_per_step(oracle, tile, split, monkeypatch):
+    """Subsets of at most 16 members with four input channels per matrix instruction, forced on (the
+    library itself selects that form only for long layers): every tile and split, channel counts that
+    are not multiples of four, rows of one, two and three words, both strides."""
+    monkeypatch.setenv("SNN_MFMA_TILE", tile)
+    monkeypatch.setenv("SNN_MFMA_KS", str(split))
+    monkeypatch.setenv("SNN_MFMA_QUAD", "1")
+    for seed, (N, C_in, C_out, H, W, stride, K) in enumerate(QUAD_LAYERS):
+        _say("subbit_bin four channels", tile, split, (N, C_in, C_out, H, W, stride, K))
+        x, cb, idx, alpha = _inputs(1900 + seed, N, C_in, C_out, H, W, K)
+        _, Y = oracle.conv_bin(oracle.sign(x), oracle.expand(cb, idx), alpha, stride)
+        y = G.subbit_bin(x, cb, idx, alpha, stride)
+        assert (y == Y).all(), np.argwhere(y != Y)[:5]
+
+
+@pytest.mark.parametrize("quad", ["1", "0"])
+def test_four_channels_per_step_forward_sign_and_prepared(oracle, quad, monkeypatch):
+    """The other entry points on the same form: the one-call forward (its front kernel writes the
+    selectors), the sign epilogue, and prepare + prepared convolution; quad = 0 is the same run with
+    the form switched off."""
+    monkeypatch.setenv("SNN_MFMA_QUAD", quad)
+    for seed, (N, C_in, C_out, H, W, stride, K) in enumerate(QUAD_LAYERS[:5] + QUAD_LAYERS[9:]):
+        _say("four channels: forward / sign / prepared", quad, (N, C_in, C_out, H, W, stride, K))
+        g = np.random.default_rng(2900 + seed)
+        x = g.standard_normal((N, C_in, H, W), dtype=np.float32)
+        cb = synth.codebook(g, K)
+        w = _latent_kernels(g, cb, C_out, C_in, "uniform")
+        alpha = synth.alpha(g, C_out)
+        idx_ref, _ = oracle.project(w, cb)
+        codes = oracle.expand(cb, idx_ref.reshape(C_out, C_in))
+        xs = oracle.sign(x)
+        _, Y = oracle.conv_bin(xs, codes, alpha, stride)
+        y, idx = G.subbit_forward(x, w, cb, alpha, C_out, stride)
+        assert (idx.reshape(-1) == idx_ref.reshape(-1)).all()
+        assert (y == Y).all(), np.argwhere(y != Y)[:5]
+        beta = _beta_near_outputs(g, Y, C_out)
+        want, _ = oracle.conv_sign(xs, codes, alpha, beta, stride)
+        got = G.subbit_sign(oracle.pack_rows(x), x.shape, cb, idx_ref.reshape(C_out, C_in), alpha, beta, stride)
+        assert (got == want).all(), np.argwhere(got != want)[:5]
+        d = B.make_desc(N, C_in, C_out, H, W, stride, K, B.SNN_ACT_BIN_ROWS)
+        ws = B.snn_subbit_prepare(d, G.dev(cb), G.dev(idx_ref.reshape(C_out, C_in)), G.dev(alpha))
+        y2 = B.snn_subbit_conv2d_prepared(d, G.dev(oracle.pack_rows(x).reshape(-1)), G.dev(alpha), ws)
+        torch.cuda.synchronize()
+        assert (y2.cpu().numpy() == Y).all()
+
+
 @pytest.mark.parametrize("prepared", [False, True])
 @pytest.mark.parametrize("case", SUBBIT_CASES)
 def test_subbit_dense(oracle, case, prepared):
