@@ -885,8 +885,8 @@ def _random_layers(seed, count):
 @pytest.mark.parametrize("chunk", range(6))
 def test_random_layers_all_entry_points(oracle, chunk):
     """Seeded random shapes (tiny images, rows around the word boundaries, odd channel counts, both
-    strides, subsets up to 64) through the plain convolution, the one-call forward and the sign
-    epilogue, each bit-exact against the oracle."""
+    strides, subsets up to 64) through the plain convolution, the one-call forward, the sign
+    epilogue and the dense contraction (fp32 and sign outputs), each bit-exact against the oracle."""
     for case in _random_layers(9000 + chunk, 12):
         N, C_in, C_out, H, W, stride, K = case
         _say("random layer", case)
@@ -903,11 +903,21 @@ def test_random_layers_all_entry_points(oracle, chunk):
         assert (y == Y).all(), (case, np.argwhere(y != Y)[:3])
         y1, idx1 = G.subbit_forward(x, w, cb, alpha, C_out, stride)
         assert (idx1.reshape(C_out, C_in) == idx_ref).all() and (y1 == Y).all(), case
+        beta = _beta_near_outputs(g, Y, C_out)
+        want, nxt = oracle.conv_sign(xs, codes, alpha, beta, stride)
         if _matrix_core_layer(case):
-            beta = _beta_near_outputs(g, Y, C_out)
-            want, _ = oracle.conv_sign(xs, codes, alpha, beta, stride)
             got = G.subbit_sign(oracle.pack_rows(x), x.shape, cb, idx_ref, alpha, beta, stride)
             assert (got == want).all(), (case, np.argwhere(got != want)[:3])
+        # the dense contraction of the same layer, fp32 output and sign epilogue
+        yd = G.subbit_dense(x, cb, idx_ref, alpha, stride, prepared=True)
+        assert (yd == Y).all(), (case, np.argwhere(yd != Y)[:3])
+        d = B.make_desc(N, C_in, C_out, H, W, stride, K, B.SNN_ACT_BIN_CHANNELS)
+        ws = B.alloc_workspace(d, B.SNN_WS_BNN_DENSE)
+        B.snn_dense_prepare(d, G.dev(cb), G.dev(idx_ref), ws)
+        bits = B.snn_dense_conv2d_sign_prepared(d, G.dev(oracle.pack_channels(x)), G.dev(alpha), G.dev(beta), ws)
+        torch.cuda.synchronize()
+        want_c = oracle.pack_channels(nxt)
+        assert (bits.cpu().numpy().view(np.uint32).reshape(want_c.shape) == want_c).all(), case
 
 
 # ---- training side: Alg. 1 backward lines ------------------------------------------------------------------------------
