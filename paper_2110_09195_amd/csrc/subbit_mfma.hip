@@ -470,6 +470,7 @@ __device__ inline void buf_store(__amdgpu_buffer_rsrc_t r, float v, uint32_t lan
     __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(v), r, (int)lane_off, (int)uniform_off, 2 /* nt */);
 }
 typedef uint32_t u32x3 __attribute__((ext_vector_type(3)));
+typedef __attribute__((address_space(3))) const u32x3 lds_cu32x3;
 __device__ inline uint32_t buf_load1(__amdgpu_buffer_rsrc_t r, uint32_t lane_off, uint32_t uniform_off)
 {
     return __builtin_amdgcn_raw_buffer_load_b32(r, (int)lane_off, (int)uniform_off, 0);
@@ -759,8 +760,8 @@ void subbit_mfma_kernel(const MfParams p)
             if constexpr (QUAD) {
                 // 16 table values (three words) per channel
                 const uint32_t wa = window(r.lo[pb], r.hi[ONE_WORD ? 0 : pb]), wb = window(r.lo2[pb], r.hi2[ONE_WORD ? 0 : pb]);
-                const u32x4 qa = *(lds_cu32x4 *)(uintptr_t)(lut_base + wa * MF_LROW);
-                const u32x4 qb = *(lds_cu32x4 *)(uintptr_t)(lut_base + wb * MF_LROW);
+                const u32x3 qa = *(lds_cu32x3 *)(uintptr_t)(lut_base + wa * MF_LROW);
+                const u32x3 qb = *(lds_cu32x3 *)(uintptr_t)(lut_base + wb * MF_LROW);
                 B[pb] = (v8i){(int)qa.x, (int)qa.y, (int)qa.z, (int)qb.x, (int)qb.y, (int)qb.z, 0, 0};
                 continue;
             }
