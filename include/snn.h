@@ -306,6 +306,20 @@ int snn_subbit_conv1x1(const snn_conv_desc *desc, const void *x, const uint16_t 
                        size_t ws_bytes, void *stream);
 
 /*
+ * The projection of Eq. 2 / Eq. 5 for 1x1 layers (appendix, Table 5): for each real-valued vector
+ * of 8 consecutive input-channel weights, the index of the nearest member of the layer's subset of
+ * {+-1}^8, arg max_k <P'_k, w>, accumulated in fp32 from 0 over elements 0..7 in order (add where
+ * the member's element is +1, subtract where it is -1); among equal scores the lowest index wins.
+ *   w          device, float [n][8], 16-byte aligned (the c_out x c_in weights of a 1x1 layer
+ *              row by row are exactly the [c_out * c_in / 8][8] vectors, in idx order)
+ *   codebook8  device, uint16 [K], 8-bit codes (element j at bit 7 - j, +1 -> 1), 1 <= K <= 256
+ *   idx_out    device, uint16 [n]
+ * n = 0 is allowed and does nothing.  Errors: INVALID_ARG (also for a misaligned w).
+ */
+int snn_project_vectors8(const float *w, int64_t n, const uint16_t *codebook8, int K,
+                         uint16_t *idx_out, void *stream);
+
+/*
  * Sec. 3: the 1-bit layer a = lambda * (w_bar o a_bar), "o" = XNOR + bit count over words of
  * 32 input channels.  The baseline every sub-bit number is compared with.
  *   desc      host; act = SNN_ACT_BIN_CHANNELS (+-1 activations) or SNN_ACT_F32; K ignored

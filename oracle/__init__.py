@@ -20,6 +20,7 @@ from .oracle import (  # noqa: F401
     pack_indices,
     decode8,
     conv1x1_bin,
+    project8,
     conv_f32,
     two_stage_bin,
     two_stage_f32,

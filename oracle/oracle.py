@@ -249,6 +249,23 @@ def decode8(code):
     return np.array([1 if (int(code) >> (7 - j)) & 1 else -1 for j in range(8)], dtype=np.int64)
 
 
+def project8(w, codebook8):
+    """Nearest member of a subset of {+-1}^8 for each vector of 8 weights (appendix, Table 5; Eq. 2 /
+    Eq. 5 with 8 elements): arg max_k of the inner product, accumulated in fp32 from 0 over elements
+    0..7 in order (add or subtract), lowest index among equal scores.  Returns (idx uint16 [n],
+    score float32 [n])."""
+    w = _c(w, np.float32).reshape(-1, 8)
+    codebook8 = _c(codebook8, np.uint16)
+    K = codebook8.size
+    signs = np.stack([decode8(int(c)) for c in codebook8]).astype(np.float32)        # [K][8], +-1
+    score = np.zeros((w.shape[0], K), dtype=np.float32)
+    for j in range(8):
+        # fp32 add / subtract of w_j: multiplying by +-1 is exact, the sum rounds once
+        score = (score + w[:, j:j + 1] * signs[None, :, j]).astype(np.float32)
+    idx = np.argmax(score, axis=1)                                                     # first maximum
+    return idx.astype(np.uint16), score[np.arange(w.shape[0]), idx]
+
+
 def conv1x1_bin(xs, codebook8, idx, alpha, stride=1):
     """xs: int8 NCHW in {+1,-1}, C_in a multiple of 8; idx: [C_out][C_in / 8] into codebook8.
     The weight of (c_out, input channel 8 g + j) is element j of member idx[c_out][g]; the layer

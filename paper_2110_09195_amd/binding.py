@@ -31,7 +31,7 @@ SNN_WS_BNN_DENSE = 4
 
 EXPORTS = ("snn_pack_activations", "snn_project_kernels", "snn_subbit_conv2d", "snn_subbit_forward",
            "snn_subbit_prepare", "snn_subbit_conv2d_prepared", "snn_packed_index_bytes", "snn_pack_indices",
-           "snn_subbit_prepare_packed", "snn_subbit_conv1x1",
+           "snn_subbit_prepare_packed", "snn_subbit_conv1x1", "snn_project_vectors8",
            "snn_subbit_conv2d_sign", "snn_subbit_forward_sign", "snn_subbit_prepare_sign",
            "snn_subbit_conv2d_sign_prepared", "snn_subbit_project_prepare_many", "snn_project_backward",
            "snn_project_backward_workspace_bytes", "snn_subset_update", "snn_bnn_conv2d", "snn_bnn_conv2d_dense",
@@ -117,6 +117,8 @@ def lib():
         L.snn_dense_prepare.restype = i32
         L.snn_dense_conv2d_prepared.argtypes = [dp, vp, vp, vp, vp, sz, vp]
         L.snn_dense_conv2d_prepared.restype = i32
+        L.snn_project_vectors8.argtypes = [vp, ctypes.c_int64, vp, ctypes.c_int, vp, vp]
+        L.snn_project_vectors8.restype = i32
         L.snn_dense_conv2d_sign_prepared.argtypes = [dp, vp, vp, vp, vp, vp, sz, vp]
         L.snn_dense_conv2d_sign_prepared.restype = i32
         L.snn_workspace_bytes.argtypes = [dp, i32]
@@ -501,4 +503,21 @@ def snn_dense_conv2d_sign_prepared(desc, x, alpha, beta, workspace, out=None):
     _check(lib().snn_dense_conv2d_sign_prepared(ctypes.byref(desc), _ptr(x), _ptr(alpha), _ptr(beta), _ptr(out),
                                                 _ptr(workspace), workspace.numel(), _stream()),
            "snn_dense_conv2d_sign_prepared")
+    return out
+
+
+def snn_project_vectors8(w, codebook8, out=None):
+    """w float32 [n][8] (or any shape with 8 n elements), codebook8 int16 [K <= 256] -> int16 [n] indices."""
+    _dev(w, torch.float32, "w")
+    _dev(codebook8, torch.int16, "codebook8")
+    if w.numel() % 8:
+        raise ValueError("w must hold whole vectors of 8")
+    n = w.numel() // 8
+    if out is None:
+        out = torch.empty(n, dtype=torch.int16, device=w.device)
+    _dev(out, torch.int16, "out")
+    if out.numel() < n:
+        raise ValueError("out is too small")
+    _check(lib().snn_project_vectors8(_ptr(w), n, _ptr(codebook8), int(codebook8.numel()), _ptr(out), _stream()),
+           "snn_project_vectors8")
     return out

@@ -52,7 +52,41 @@ void project_kernel(const float *__restrict__ w, int64_t n, const uint16_t *__re
         if (q * PROJ_THREADS + tid < cnt) idx_out[c0 + q * PROJ_THREADS + tid] = (uint16_t)best[q];
 }
 
+// The same projection for the vectors of 8 input channels of a 1x1 layer (appendix, Table 5): members
+// of a subset of {+-1}^8, element j at code bit 7 - j.  A vector is run through the 9-tap chain with
+// a ninth element 0.0f: adding +-0 changes neither a sum nor a comparison, so the result is that of
+// the sequential sum over the 8 elements.
+__global__ __launch_bounds__(PROJ_THREADS)
+void project8_kernel(const float *__restrict__ w, int64_t n, const uint16_t *__restrict__ codebook8, int K,
+                     uint16_t *__restrict__ idx_out)
+{
+    extern __shared__ __align__(16) float lds[];
+    float *coef = lds;                                       // [K][12]
+    uint16_t *code9 = (uint16_t *)(lds + K * 12);            // [K]: the 8-bit codes as 9-bit ones, last tap +1
+    const int tid = threadIdx.x;
+    for (int k = tid; k < K; k += PROJ_THREADS) code9[k] = (uint16_t)(((codebook8[k] & 255u) << 1) | 1u);
+    __syncthreads();
+    project_fill_coef(coef, code9, K, tid, PROJ_THREADS);
+    __syncthreads();
+    const int64_t v = (int64_t)blockIdx.x * PROJ_THREADS + tid;
+    if (v >= n) return;
+    const float4 a = ((const float4 *)w)[2 * v], b = ((const float4 *)w)[2 * v + 1];     // 32-byte vectors: aligned
+    const float wt[1][9] = {{a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w, 0.0f}};
+    int best[1];
+    project_argmax<1>(wt, coef, K, best);
+    idx_out[v] = (uint16_t)best[0];
+}
+
 }  // namespace
+
+int launch_project8(const float *w, int64_t n, const uint16_t *codebook8, int K, uint16_t *idx_out, hipStream_t s)
+{
+    const int64_t blocks = (n + PROJ_THREADS - 1) / PROJ_THREADS;
+    if (blocks > 0x7fffffffLL) return SNN_ERR_INVALID_ARG;
+    const size_t lds = (size_t)K * 12 * sizeof(float) + (size_t)K * sizeof(uint16_t);      // <= 12.5 KB
+    hipLaunchKernelGGL(project8_kernel, dim3((unsigned)blocks), dim3(PROJ_THREADS), lds, s, w, n, codebook8, K, idx_out);
+    return check_launch();
+}
 
 int launch_project(const float *w, int64_t n, const uint16_t *codebook, int K, uint16_t *idx_out,
                    hipStream_t s)

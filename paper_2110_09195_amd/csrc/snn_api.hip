@@ -108,6 +108,16 @@ int snn_project_kernels(const float *w, int64_t n, const uint16_t *codebook, int
     return launch_project(w, n, codebook, K, idx_out, (hipStream_t)stream);
 }
 
+int snn_project_vectors8(const float *w, int64_t n, const uint16_t *codebook8, int K, uint16_t *idx_out,
+                         void *stream)
+{
+    if (n < 0 || K < 1 || K > 256 || !codebook8) return SNN_ERR_INVALID_ARG;
+    if (n == 0) return SNN_OK;
+    if (!w || !idx_out || ((uintptr_t)w & 15u)) return SNN_ERR_INVALID_ARG;
+    if (n >= ((int64_t)1 << 40)) return SNN_ERR_INVALID_ARG;
+    return launch_project8(w, n, codebook8, K, idx_out, (hipStream_t)stream);
+}
+
 int snn_subbit_conv2d(const snn_conv_desc *desc, const void *x, const uint16_t *codebook,
                       const uint16_t *idx, const float *alpha, float *y_nchw, void *workspace,
                       size_t ws_bytes, void *stream)

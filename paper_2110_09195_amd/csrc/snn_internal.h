@@ -75,6 +75,7 @@ int launch_pack_channels(const float *x, uint32_t *out, int N, int C, int H, int
 
 int launch_project(const float *w, int64_t n, const uint16_t *codebook, int K, uint16_t *idx_out,
                    hipStream_t s);
+int launch_project8(const float *w, int64_t n, const uint16_t *codebook8, int K, uint16_t *idx_out, hipStream_t s);
 
 size_t bnn_workspace_bytes(const Geom &g, int act);
 int launch_bnn(const Geom &g, int act, const void *x, const uint16_t *w9, const float *alpha,

@@ -851,6 +851,49 @@ def test_subbit_conv1x1_every_tile_and_split(oracle, tile, split, monkeypatch):
         assert (y == Y).all(), np.argwhere(y != Y)[:5]
 
 
+@pytest.mark.parametrize("n,K", [(1, 1), (255, 32), (256, 16), (257, 8), (5000, 256), (64 * 256, 32), (512 * 2048 // 8, 32)])
+def test_project_vectors8(oracle, n, K):
+    """Nearest subset member of {+-1}^8 per vector of 8 weights: indices bit-exact against the oracle,
+    including exact ties (small integers) and zeros."""
+    _say("project_vectors8", (n, K))
+    g = np.random.default_rng(31 * n + K)
+    w = g.standard_normal((n, 8)).astype(np.float32)
+    w[::7] = np.round(w[::7] * 2)
+    w[::11] = 0.0
+    cb = g.permutation(256)[:K].astype(np.uint16)
+    want, _ = oracle.project8(w, cb)
+    got = B.snn_project_vectors8(G.dev(w), G.dev(cb))
+    torch.cuda.synchronize()
+    assert (G.host_u16(got) == want).all()
+
+
+def test_project_vectors8_then_conv1x1(oracle):
+    """Projection of a 1x1 layer's real-valued weights, then the layer itself, against the oracle."""
+    g = np.random.default_rng(77)
+    N, C_in, C_out, H, W, K = 3, 64, 40, 9, 7, 32
+    x = g.standard_normal((N, C_in, H, W)).astype(np.float32)
+    w = g.standard_normal((C_out, C_in)).astype(np.float32)
+    cb = g.permutation(256)[:K].astype(np.uint16)
+    alpha = synth.alpha(g, C_out)
+    idx_ref, _ = oracle.project8(w, cb)
+    idx = B.snn_project_vectors8(G.dev(w), G.dev(cb))
+    torch.cuda.synchronize()
+    assert (G.host_u16(idx) == idx_ref).all()
+    _, Y = oracle.conv1x1_bin(oracle.sign(x).astype(np.int8), cb, idx_ref.reshape(C_out, C_in // 8), alpha, 1)
+    y = G.subbit_conv1x1(x, cb, idx_ref.reshape(C_out, C_in // 8), alpha, 1)
+    assert (y == Y).all()
+
+
+def test_project_vectors8_refusals():
+    w = torch.zeros(17, dtype=torch.float32, device="cuda")
+    cb = torch.zeros(4, dtype=torch.int16, device="cuda")
+    with pytest.raises(B.SnnError):                                 # a misaligned pointer
+        B.snn_project_vectors8(w[1:], cb)
+    with pytest.raises(B.SnnError):                                 # K > 256
+        B.snn_project_vectors8(w[:16], torch.zeros(300, dtype=torch.int16, device="cuda"))
+    assert B.snn_project_vectors8(w[:0], cb).numel() == 0
+
+
 def test_subbit_conv1x1_refuses_what_it_does_not_take():
     import torch
     one = torch.zeros(64, dtype=torch.int32, device="cuda")

@@ -101,3 +101,47 @@ def test_conv1x1_inputs_tell_the_readings_apart(oracle):
     w_strided = np.array([[1 if (int(cb[idx[co, c % G]]) >> (7 - c // G)) & 1 else -1 for c in range(8 * G)] for co in range(C_out)])
     for wrong in (w_lsb, w_strided):
         assert (np.einsum("oc,nchw->nohw", wrong, xs.astype(np.int64)) != S).any()
+
+
+# ---- projection of 8-vectors onto a subset of {+-1}^8 -------------------------------------------------
+
+def test_project8_full_set_is_the_sign_pattern(oracle):
+    # with all 256 members the nearest one is sign(w) (Eq. 1 applied to 8 elements) and the score is the 1-norm
+    g = np.random.default_rng(21)
+    w = g.standard_normal((500, 8)).astype(np.float32)
+    idx, score = oracle.project8(w, np.arange(256, dtype=np.uint16))
+    want = np.zeros(500, dtype=np.int64)
+    for j in range(8):
+        want = want * 2 + (w[:, j] >= 0)
+    assert (idx == want).all()
+    assert np.allclose(score, np.abs(w).sum(axis=1), rtol=1e-6)
+
+
+def test_project8_members_project_to_themselves_and_brute_force(oracle):
+    g = np.random.default_rng(22)
+    cb = g.permutation(256)[:32].astype(np.uint16)
+    members = np.array([[1.0 if (int(c) >> (7 - j)) & 1 else -1.0 for j in range(8)] for c in cb], dtype=np.float32)
+    idx, score = oracle.project8(members, cb)
+    assert (idx == np.arange(32)).all() and (score == 8.0).all()
+    # float64 brute-force arg min of the squared distance agrees except at float-level near ties
+    w = g.standard_normal((4000, 8)).astype(np.float32)
+    idx, _ = oracle.project8(w, cb)
+    d2 = ((w[:, None, :].astype(np.float64) - members[None, :, :].astype(np.float64)) ** 2).sum(axis=2)
+    best = d2.argmin(axis=1)
+    differ = np.nonzero(idx != best)[0]
+    for i in differ:
+        assert abs(d2[i, idx[i]] - d2[i, best[i]]) < 1e-5
+    assert differ.size < 5
+
+
+def test_project8_ties_go_to_the_lowest_index_and_order_matters(oracle):
+    cb = np.array([0b11110000, 0b00001111, 0b11111111, 0b11110000], dtype=np.uint16)
+    idx, _ = oracle.project8(np.zeros((1, 8), dtype=np.float32), cb)
+    assert idx[0] == 0                                             # all scores 0
+    idx, _ = oracle.project8(np.array([[1, 1, 1, 1, 0, 0, 0, 0]], dtype=np.float32), cb)
+    assert idx[0] == 0                                             # members 0, 2 and 3 score 4: the first wins
+    # sequential fp32 summation: (2^24 + 1) - 2^24 in this order loses the 1, the other order keeps it
+    big = np.float32(2.0 ** 24)
+    w = np.array([[big, 1.0, -big, 0, 0, 0, 0, 0], [big, -big, 1.0, 0, 0, 0, 0, 0]], dtype=np.float32)
+    _, score = oracle.project8(w, np.array([255], dtype=np.uint16))
+    assert score[0] == 0.0 and score[1] == 1.0
