@@ -72,6 +72,15 @@ __global__ void bnn_prep_f32_kernel(const uint16_t *__restrict__ w9, int64_t n, 
         flips[i] = (~code_to_window_order(w9[i] & 511u)) & 511u;
 }
 
+// popcount(v) + acc as the one instruction it is (written out: the compiler otherwise counts into fresh
+// registers and adds them up three at a time, half an instruction more per word)
+__device__ inline int count_add(uint32_t v, int acc)
+{
+    int r;
+    asm("v_bcnt_u32_b32 %0, %1, %2" : "=v"(r) : "v"(v), "v"(acc));
+    return r;
+}
+
 // Variant for C_in <= 512: a block is 256 output pixels (one per lane) x a chunk of CH output channels.
 // The chunk's weight words, border corrections and scales are staged in LDS once; a lane keeps its
 // 3x3 window of up to 8 words per tap (256 input channels) in registers and walks the chunk's
@@ -172,16 +181,16 @@ void bnn_regs_kernel(const uint32_t *__restrict__ x, const uint32_t *__restrict_
 #pragma unroll
                     for (int q = 0; q < WPP / 4; ++q) {
                         const uint4 v = *(const uint4 *)(wt + 4 * q);
-                        m0 = __popc(xr[t][4 * q] ^ v.x) + m0;
-                        m1 = __popc(xr[t][4 * q + 1] ^ v.y) + m1;
-                        m0 = __popc(xr[t][4 * q + 2] ^ v.z) + m0;
-                        m1 = __popc(xr[t][4 * q + 3] ^ v.w) + m1;
+                        m0 = count_add(xr[t][4 * q] ^ v.x, m0);
+                        m1 = count_add(xr[t][4 * q + 1] ^ v.y, m1);
+                        m0 = count_add(xr[t][4 * q + 2] ^ v.z, m0);
+                        m1 = count_add(xr[t][4 * q + 3] ^ v.w, m1);
                     }
                 } else {
 #pragma unroll
                     for (int cw = 0; cw < WPP; ++cw) {
-                        if (cw & 1) m1 = __popc(xr[t][cw] ^ wt[cw]) + m1;
-                        else m0 = __popc(xr[t][cw] ^ wt[cw]) + m0;
+                        if (cw & 1) m1 = count_add(xr[t][cw] ^ wt[cw], m1);
+                        else m0 = count_add(xr[t][cw] ^ wt[cw], m0);
                     }
                 }
             }
