@@ -242,6 +242,31 @@ typedef struct snn_layer_weights {
 int snn_subbit_project_prepare_many(const snn_layer_weights *layers, int n_layers, void *stream);
 
 /*
+ * snn_subbit_conv2d_prepared for several layers that do not depend on each other (each reads its own
+ * input), e.g. the 3x3 layers of a network whose inputs are all resident: the two stages of Sec. 4.5
+ * for every layer, as few launches as possible (layers whose form the shared kernel holds go
+ * sixteen to a launch, any other layer gets a launch of its own).  The results are those of one
+ * snn_subbit_conv2d_prepared call per layer, bit for bit; what changes is that the layers share the
+ * chip instead of each ending with a few busy compute units.
+ *   layers[l].desc       host; act must be SNN_ACT_BIN_ROWS, K <= 64 (C_in >= 2 if K <= 32)
+ *   layers[l].x_packed   device, packed rows of the layer's input
+ *   layers[l].y_nchw     device, float [N][C_out][H_out][W_out], fully overwritten; the outputs of
+ *                        different layers must not overlap
+ *   layers[l].workspace  device, as prepared by snn_subbit_prepare / snn_subbit_prepare_packed /
+ *                        snn_subbit_project_prepare_many (beta == NULL) for the same desc; read only
+ * Errors: INVALID_ARG; UNSUPPORTED (a layer outside the matrix-core kernel); WORKSPACE; LAUNCH.  All
+ * layers are checked before anything is enqueued.
+ */
+typedef struct snn_layer_io {
+    snn_conv_desc desc;
+    const void *x_packed;
+    float *y_nchw;
+    void *workspace;
+    size_t ws_bytes;
+} snn_layer_io;
+int snn_subbit_conv2d_prepared_many(const snn_layer_io *layers, int n_layers, void *stream);
+
+/*
  * The same with the projection of the layer's real-valued kernels in front (Alg. 1 forward of a
  * layer inside a stack): idx_out = project(w) as snn_project_kernels computes it, then
  * snn_subbit_conv2d_sign with it; two launches.

@@ -33,7 +33,8 @@ EXPORTS = ("snn_pack_activations", "snn_project_kernels", "snn_subbit_conv2d", "
            "snn_subbit_prepare", "snn_subbit_conv2d_prepared", "snn_packed_index_bytes", "snn_pack_indices",
            "snn_subbit_prepare_packed", "snn_subbit_conv1x1", "snn_project_vectors8",
            "snn_subbit_conv2d_sign", "snn_subbit_forward_sign", "snn_subbit_prepare_sign",
-           "snn_subbit_conv2d_sign_prepared", "snn_subbit_project_prepare_many", "snn_project_backward",
+           "snn_subbit_conv2d_sign_prepared", "snn_subbit_project_prepare_many", "snn_subbit_conv2d_prepared_many",
+           "snn_project_backward",
            "snn_project_backward_workspace_bytes", "snn_subset_update", "snn_bnn_conv2d", "snn_bnn_conv2d_dense",
            "snn_subbit_conv2d_dense", "snn_dense_prepare", "snn_dense_conv2d_prepared",
            "snn_dense_conv2d_sign_prepared",
@@ -50,6 +51,11 @@ class snn_layer_weights(ctypes.Structure):
     _fields_ = [("desc", snn_conv_desc), ("w", ctypes.c_void_p), ("codebook", ctypes.c_void_p), ("alpha", ctypes.c_void_p),
                 ("beta", ctypes.c_void_p), ("idx_out", ctypes.c_void_p), ("workspace", ctypes.c_void_p),
                 ("ws_bytes", ctypes.c_size_t)]
+
+
+class snn_layer_io(ctypes.Structure):
+    _fields_ = [("desc", snn_conv_desc), ("x_packed", ctypes.c_void_p), ("y_nchw", ctypes.c_void_p),
+                ("workspace", ctypes.c_void_p), ("ws_bytes", ctypes.c_size_t)]
 
 
 class SnnError(RuntimeError):
@@ -97,6 +103,8 @@ def lib():
         L.snn_subbit_conv2d_sign_prepared.restype = i32
         L.snn_subbit_project_prepare_many.argtypes = [ctypes.POINTER(snn_layer_weights), i32, vp]
         L.snn_subbit_project_prepare_many.restype = i32
+        L.snn_subbit_conv2d_prepared_many.argtypes = [ctypes.POINTER(snn_layer_io), i32, vp]
+        L.snn_subbit_conv2d_prepared_many.restype = i32
         L.snn_subbit_forward_sign.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.snn_subbit_forward_sign.restype = i32
         L.snn_project_backward.argtypes = [vp, vp, vp, i64, i32, vp, vp, vp, sz, vp]
@@ -363,6 +371,30 @@ def layer_weights_array(layers):
 
 def snn_subbit_project_prepare_many(arr):
     _check(lib().snn_subbit_project_prepare_many(arr, len(arr), _stream()), "snn_subbit_project_prepare_many")
+
+
+def layer_io_array(layers):
+    """layers: list of dicts with keys desc, x (packed int32 rows), y (float32 output), workspace (prepared) ->
+    a ctypes array for snn_subbit_conv2d_prepared_many; build it once and reuse it (the tensors must stay alive)."""
+    arr = (snn_layer_io * len(layers))()
+    for i, L in enumerate(layers):
+        _dev(L["x"], torch.int32, "x")
+        _dev(L["y"], torch.float32, "y")
+        d = L["desc"]
+        if L["x"].numel() * 4 != snn_packed_bytes(d.N, d.C_in, d.H, d.W, SNN_ACT_BIN_ROWS):
+            raise ValueError("x has the wrong size")
+        if L["y"].numel() != d.N * d.C_out * ((d.H - 1) // d.stride + 1) * ((d.W - 1) // d.stride + 1):
+            raise ValueError("y has the wrong size")
+        arr[i].desc = d
+        arr[i].x_packed = L["x"].data_ptr()
+        arr[i].y_nchw = L["y"].data_ptr()
+        arr[i].workspace = L["workspace"].data_ptr()
+        arr[i].ws_bytes = L["workspace"].numel()
+    return arr
+
+
+def snn_subbit_conv2d_prepared_many(arr):
+    _check(lib().snn_subbit_conv2d_prepared_many(arr, len(arr), _stream()), "snn_subbit_conv2d_prepared_many")
 
 
 def snn_subbit_forward_sign(desc, x, w, codebook, alpha, beta, idx_out=None, out=None, workspace=None):

@@ -2,8 +2,8 @@
 
     python -m paper_2110_09195_amd.build [extra hipcc flags]
 
-The shared object is written next to this file (libsnn_hip.so) so that it travels with the
-source tree; nothing is installed.  Object files go to a temporary directory.
+The shared objects are written next to this file (libsnn_hip.so, the product, and libsnn_peaks.so,
+the measured-peak probes that bench.py runs) so that they travel with the source tree; nothing is installed.  Object files go to a temporary directory.
 """
 import concurrent.futures
 import os
@@ -15,6 +15,9 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libsnn_hip.so")
+# the measured-peak probes of include/snn_peaks.h: a library of their own, loaded by bench.py only
+PEAKS_LIB = os.path.join(HERE, "libsnn_peaks.so")
+PEAKS_SOURCES = ["peaks.hip"]
 SOURCES = ["snn_api.hip", "pack.hip", "project.hip", "bnn_conv.hip", "subbit_conv.hip", "subbit_f32.hip",
            "subbit_mfma.hip", "train_ops.hip", "dense_fp4.hip"]
 
@@ -38,12 +41,13 @@ def build(verbose=False, extra=()):
             subprocess.run(cmd, check=True)
             return obj
 
-        with concurrent.futures.ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as pool:
-            objs = list(pool.map(compile_one, SOURCES))
-        cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-fno-gpu-rdc"] + objs + ["-o", LIB]
-        if verbose:
-            print(" ".join(cmd), flush=True)
-        subprocess.run(cmd, check=True)
+        with concurrent.futures.ThreadPoolExecutor(max_workers=8) as pool:
+            objs = list(pool.map(compile_one, SOURCES + PEAKS_SOURCES))
+        for lib, part in ((LIB, objs[:len(SOURCES)]), (PEAKS_LIB, objs[len(SOURCES):])):
+            cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-fno-gpu-rdc"] + part + ["-o", lib]
+            if verbose:
+                print(" ".join(cmd), flush=True)
+            subprocess.run(cmd, check=True)
     return LIB
 
 

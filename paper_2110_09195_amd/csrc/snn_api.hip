@@ -255,6 +255,29 @@ int snn_subbit_project_prepare_many(const snn_layer_weights *layers, int n_layer
                                       (hipStream_t)stream);
 }
 
+int snn_subbit_conv2d_prepared_many(const snn_layer_io *layers, int n_layers, void *stream)
+{
+    if (n_layers < 0 || (n_layers > 0 && !layers)) return SNN_ERR_INVALID_ARG;
+    if (n_layers == 0) return SNN_OK;
+    std::vector<Geom> gs(n_layers);
+    std::vector<const void *> x(n_layers);
+    std::vector<float *> y(n_layers);
+    std::vector<void *> ws(n_layers);
+    for (int l = 0; l < n_layers; ++l) {
+        const snn_layer_io &L = layers[l];
+        if (!desc_ok(&L.desc, true) || !L.x_packed || !L.y_nchw) return SNN_ERR_INVALID_ARG;
+        if (L.desc.act != SNN_ACT_BIN_ROWS) return SNN_ERR_UNSUPPORTED;
+        gs[l] = make_geom(L.desc);
+        if (!subbit_mfma_supported(gs[l])) return SNN_ERR_UNSUPPORTED;
+        const size_t need = subbit_workspace_bytes(gs[l], SNN_ACT_BIN_ROWS);
+        if (!L.workspace || L.ws_bytes < need || ((uintptr_t)L.workspace & 255u)) return SNN_ERR_WORKSPACE;
+        x[l] = L.x_packed;
+        y[l] = L.y_nchw;
+        ws[l] = L.workspace;
+    }
+    return launch_subbit_mfma_many(n_layers, gs.data(), x.data(), y.data(), ws.data(), (hipStream_t)stream);
+}
+
 int snn_subbit_forward_sign(const snn_conv_desc *desc, const void *x_packed, const float *w, const uint16_t *codebook,
                             const float *alpha, const float *beta, uint16_t *idx_out, void *out_packed,
                             void *workspace, size_t ws_bytes, void *stream)

@@ -120,6 +120,9 @@ int launch_subbit_forward_mfma(const Geom &g, const float *x, const float *w, co
                                const float *alpha, uint16_t *idx_out, float *y, uint32_t *xr, void *ws, hipStream_t s,
                                const SignEpilogue *sign = nullptr);
 
+// the convolutions of several prepared layers (matrix-core kernel, +-1 activations in packed rows, fp32 output)
+int launch_subbit_mfma_many(int n_layers, const Geom *gs, const void *const *x, float *const *y, void *const *ws, hipStream_t s);
+
 int launch_subbit_prepare_many(int n_layers, const Geom *gs, const float *const *w, const uint16_t *const *codebook,
                                const float *const *alpha, const float *const *beta, uint16_t *const *idx_out,
                                void *const *ws, hipStream_t s);

@@ -69,14 +69,23 @@ struct MfParams {
     int n_cotiles;
     long long n_tiles;        // pixel tiles * channel tiles
 #ifdef SNN_MF_TRACE
-    unsigned long long *trace;    // tuning builds: wall-clock samples of two workgroups, 16 per wave
+    unsigned long long *trace;    // tuning builds: wall-clock samples, 16 words per wave
+    int trace_block0, trace_layer;
 #endif
 };
 #ifdef SNN_MF_TRACE
+// tuning builds: every wave records the wall clock (10 ns ticks) at eight marks and, at the last one, writes
+// them with its hardware id to trace[16 * wave number]
 #define MF_TRACE(slot)                                                                          \
     do {                                                                                        \
-        if ((blockIdx.x == 3 || blockIdx.x == gridDim.x / 2) && (threadIdx.x & 63) == 0)        \
-            p.trace[((blockIdx.x == 3 ? 0 : 4) + (threadIdx.x >> 6)) * 16 + (slot)] = wall_clock64(); \
+        mf_t[(slot)] = wall_clock64();                                                          \
+        if ((slot) == 7 && (threadIdx.x & 63) == 0) {                                           \
+            unsigned long long *mf_o = p.trace + ((size_t)(p.trace_block0 + block) * MF_WAVES + (threadIdx.x >> 6)) * 16; \
+            for (int mf_i = 0; mf_i < 8; ++mf_i) mf_o[mf_i] = mf_t[mf_i];                       \
+            mf_o[8] = __builtin_amdgcn_s_getreg((4 << 0) | (0 << 6) | (31 << 11));              \
+            mf_o[9] = __builtin_amdgcn_s_getreg((20 << 0) | (0 << 6) | (31 << 11));             \
+            mf_o[10] = (unsigned long long)p.trace_layer;                                       \
+        }                                                                                       \
     } while (0)
 #else
 #define MF_TRACE(slot) do { } while (0)
@@ -500,9 +509,11 @@ __device__ inline u32x4 buf_load4(__amdgpu_buffer_rsrc_t r, uint32_t lane_off, u
 // word is one piece; a row of two words is three overlapping pieces, bits [0,32), [16,48) and
 // [32,64), so that every window of three columns lies inside one of them.  The memory pipeline,
 // which otherwise bounds the layers with few output channels, sees one instruction instead of 3 PB.
+// `block` is the workgroup's number inside the layer (the launch of one layer passes blockIdx.x, the
+// launch that walks several layers the offset from the layer's first workgroup); `smem` the
+// workgroup's dynamic LDS.
 template <int PB, int CB, int WM, bool PAIR, bool STG, bool QUAD = false>
-__global__ __launch_bounds__(MF_WAVES * 64, 2)
-void subbit_mfma_kernel(const MfParams p)
+__device__ __forceinline__ void mf_tile_body(const MfParams &p, const unsigned block, unsigned char *const smem)
 {
     static_assert(!STG || WM == 1 || WM == 2, "staging needs rows that are consecutive in memory");
     // QUAD: subsets of at most 16 members.  A lane half then holds TWO input channels per step (channels
@@ -517,7 +528,6 @@ void subbit_mfma_kernel(const MfParams p)
     constexpr int MF_LROW = mf_lrow(PAIR);
     const Geom &g = p.g;
 
-    extern __shared__ __align__(16) unsigned char smem[];
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -526,7 +536,7 @@ void subbit_mfma_kernel(const MfParams p)
     const int KS = p.KS;
     const int split = wave & (KS - 1);
     const int tile_in_wg = wave / KS;
-    const long long tile = (long long)blockIdx.x * (MF_WAVES / KS) + tile_in_wg;
+    const long long tile = (long long)block * (MF_WAVES / KS) + tile_in_wg;
     const bool active = tile < p.n_tiles;                       // wave-uniform
     const long long tl = active ? tile : p.n_tiles - 1;
     const int co_tile = (int)(tl % p.n_cotiles);
@@ -583,6 +593,9 @@ void subbit_mfma_kernel(const MfParams p)
         return ok;
     };
 
+#ifdef SNN_MF_TRACE
+    unsigned long long mf_t[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+#endif
     MF_TRACE(0);
 
     // The lookup table image was built once by the preparation kernel.  Its words are requested
@@ -1089,6 +1102,48 @@ void subbit_mfma_kernel(const MfParams p)
     MF_TRACE(7);
 }
 
+template <int PB, int CB, int WM, bool PAIR, bool STG, bool QUAD = false>
+__global__ __launch_bounds__(MF_WAVES * 64, 2)
+void subbit_mfma_kernel(const MfParams p)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    mf_tile_body<PB, CB, WM, PAIR, STG, QUAD>(p, blockIdx.x, smem);
+}
+
+// Several layers in ONE launch: workgroups [first_block[l], first_block[l + 1]) run layer l.  The
+// layers of a stack that do not depend on each other (each has its own input) then share the
+// chip: no launch ends with a few busy compute units, and while the workgroups of one layer store
+// their outputs those of the next are in their matrix loops.  Only the forms the default plan picks
+// for subsets of up to 32 members are compiled in (`variant`, see mf_many_variant).
+constexpr int MF_MANY_MAX = 16;
+struct MfManyParams {
+    int n_layers;
+    int first_block[MF_MANY_MAX + 1];
+    int variant[MF_MANY_MAX];
+    MfParams layer[MF_MANY_MAX];
+};
+
+__global__ __launch_bounds__(MF_WAVES * 64, 2)
+void subbit_mfma_many_kernel(const MfManyParams pm)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int b = blockIdx.x;
+    int l = 0;
+    while (l + 1 < pm.n_layers && b >= pm.first_block[l + 1]) ++l;      // block-uniform
+    const MfParams &p = pm.layer[l];
+    const unsigned block = (unsigned)(b - pm.first_block[l]);
+    switch (pm.variant[l]) {
+    case 0: mf_tile_body<4, 2, 0, true, false>(p, block, smem); break;
+    case 1: mf_tile_body<4, 2, 1, true, false>(p, block, smem); break;
+    case 2: mf_tile_body<4, 2, 2, true, false>(p, block, smem); break;
+    case 3: mf_tile_body<4, 2, 1, true, true>(p, block, smem); break;
+    case 4: mf_tile_body<4, 2, 2, true, true>(p, block, smem); break;
+    case 5: mf_tile_body<2, 4, 0, true, false>(p, block, smem); break;
+    case 6: mf_tile_body<2, 4, 1, true, false>(p, block, smem); break;
+    default: mf_tile_body<2, 4, 2, true, false>(p, block, smem); break;
+    }
+}
+
 // ---- host side -------------------------------------------------------------------------------------
 
 struct MfCfg {
@@ -1189,7 +1244,7 @@ MfPlan mf_plan(const Geom &g, bool aligned = false, bool one = false)
     if (fin_bytes > pl.lds) pl.lds = fin_bytes;
     size_t o = 0;
 #ifdef SNN_MF_TRACE
-    o += 4096;                // clock samples
+    o += 4 << 20;             // clock samples
 #endif
     pl.off_sel = o;
     o += align_up((size_t)pl.npairs * (pl.quad ? 4 : 2) * pl.COP * sizeof(uint32_t), 256);
@@ -1274,6 +1329,8 @@ MfParams mf_params(const MfPlan &pl, const Geom &g, const void *x, float *y, voi
     prm.cw_bytes = 0;
 #ifdef SNN_MF_TRACE
     prm.trace = (unsigned long long *)ws;
+    prm.trace_block0 = 0;
+    prm.trace_layer = 0;
 #endif
     return prm;
 }
@@ -1359,6 +1416,89 @@ int launch_subbit_mfma(const Geom &g, const void *x, const uint16_t *codebook, c
                            (uint32_t *)prm.sel, (uint2 *)prm.fin, (uint32_t *)prm.lut, sign ? sign->beta : nullptr, 9);
     if (!(phases & SNN_PHASE_CONVOLVE)) return check_launch();
     return launch_mf_conv(pl, prm, s);
+}
+
+// The convolutions of several prepared layers (fp32 output).  Layers whose plan is one of the forms
+// compiled into subbit_mfma_many_kernel share launches of up to MF_MANY_MAX layers; any other layer
+// gets a launch of its own.
+namespace {
+
+int mf_many_variant(const MfPlan &pl, const Geom &g)
+{
+    if (pl.one || pl.quad || !pl.pair) return -1;
+    const int wm = g.WW <= 2 ? g.WW : 0;
+    if (pl.cfg.PB == 4 && pl.cfg.CB == 2) return pl.stage ? (wm == 1 ? 3 : 4) : wm;
+    if (pl.cfg.PB == 2 && pl.cfg.CB == 4 && !pl.stage) return 5 + wm;
+    return -1;
+}
+
+}  // namespace
+
+int launch_subbit_mfma_many(int n_layers, const Geom *gs, const void *const *x, float *const *y, void *const *ws, hipStream_t s)
+{
+    static bool lds_attr_set = false;
+    MfManyParams pm;
+    pm.n_layers = 0;
+    int64_t blocks = 0;
+    size_t lds = 0;
+    auto flush = [&]() -> int {
+        if (pm.n_layers == 0) return SNN_OK;
+        pm.first_block[pm.n_layers] = (int)blocks;
+        for (int i = pm.n_layers + 1; i <= MF_MANY_MAX; ++i) pm.first_block[i] = (int)blocks;
+        if (lds > 64 * 1024 && !lds_attr_set) {
+            if (hipFuncSetAttribute((const void *)subbit_mfma_many_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)
+                return SNN_ERR_LAUNCH;
+            lds_attr_set = true;
+        }
+        hipLaunchKernelGGL(subbit_mfma_many_kernel, dim3((unsigned)blocks), dim3(MF_WAVES * 64), lds, s, pm);
+        pm.n_layers = 0;
+        blocks = 0;
+        lds = 0;
+        return check_launch();
+    };
+    const int target_steps = env_int("SNN_MANY_STEPS", 0);
+    for (int l = 0; l < n_layers; ++l) {
+        MfPlan pl = mf_plan(gs[l]);
+        if (target_steps > 0) {
+            int ks = 1;
+            while (ks < 4 && pl.npairs / (2 * ks) >= target_steps) ks *= 2;
+            pl.KS = ks;
+            pl.n_wgs = (pl.n_tiles * ks + MF_WAVES - 1) / MF_WAVES;
+            const int nblk = pl.cfg.PB * pl.cfg.CB;
+            const size_t lut_bytes = (size_t)512 * mf_lrow(pl.pair) + (pl.stage ? (size_t)MF_WAVES * MF_STAGE_BYTES : 0);
+            const size_t red_bytes = ks > 1 ? (size_t)(MF_WAVES / ks) * (nblk > 4 ? nblk / 2 : nblk) * (ks - 1) * 4096 : 0;
+            const size_t fin_bytes = (size_t)MF_WAVES * 32 * pl.cfg.CB * 16 * 8;
+            pl.lds = lut_bytes > red_bytes ? lut_bytes : red_bytes;
+            if (fin_bytes > pl.lds) pl.lds = fin_bytes;
+        }
+        if (pl.n_wgs > 0x7fffffffLL || pl.lds > 160 * 1024 || pl.n_pxblocks > 0x7fffffffLL) return SNN_ERR_UNSUPPORTED;
+        const MfParams prm = mf_params(pl, gs[l], x[l], y[l], ws[l], nullptr);
+        const int variant = mf_many_variant(pl, gs[l]);
+        if (variant < 0 || blocks + pl.n_wgs > 0x7fffffffLL) {
+            int rc = flush();
+            if (rc != SNN_OK) return rc;
+            if (variant < 0) {
+                rc = launch_mf_conv(pl, prm, s);
+                if (rc != SNN_OK) return rc;
+                continue;
+            }
+        }
+        pm.layer[pm.n_layers] = prm;
+#ifdef SNN_MF_TRACE
+        pm.layer[pm.n_layers].trace = (unsigned long long *)ws[0];
+        pm.layer[pm.n_layers].trace_block0 = (int)blocks;
+        pm.layer[pm.n_layers].trace_layer = l;
+#endif
+        pm.variant[pm.n_layers] = variant;
+        pm.first_block[pm.n_layers] = (int)blocks;
+        blocks += pl.n_wgs;
+        if (pl.lds > lds) lds = pl.lds;
+        if (++pm.n_layers == MF_MANY_MAX) {
+            const int rc = flush();
+            if (rc != SNN_OK) return rc;
+        }
+    }
+    return flush();
 }
 
 // Alg. 1 forward of a layer in two launches: the front kernel (projection, selector / finishing /
