@@ -127,6 +127,21 @@ int snn_subbit_conv2d(const snn_conv_desc *desc, const void *x, const uint16_t *
                       void *workspace, size_t ws_bytes, void *stream);
 
 /*
+ * snn_subbit_conv2d for callers that cannot allocate device memory or pass a workspace: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, results
+ * and errors as snn_subbit_conv2d, without `workspace` / `ws_bytes`: the tables the call builds live
+ * in a buffer inside the library, SNN_NOALLOC_MAX_WORKSPACE_BYTES per GPU, held until the process
+ * ends.  The call allocates and frees nothing.  A layer whose tables need more
+ * (snn_workspace_bytes(desc, SNN_WS_SUBBIT) > SNN_NOALLOC_MAX_WORKSPACE_BYTES) is refused with
+ * SNN_ERR_WORKSPACE and nothing is enqueued; SNN_ERR_LAUNCH also if the buffer's address cannot be
+ * obtained.  All calls on one GPU share the buffer: every call rebuilds what it reads, and calls
+ * that overlap on one GPU (different streams, or threads) race - issue them on one stream.
+ */
+#define SNN_NOALLOC_MAX_WORKSPACE_BYTES (4 * 1024 * 1024)
+int snn_subbit_conv2d_noalloc(const snn_conv_desc *desc, const void *x, const uint16_t *codebook,
+                              const uint16_t *idx, const float *alpha, float *y_nchw, void *stream);
+
+/*
  * snn_subbit_conv2d in two halves, for weights that stay fixed over many calls (inference):
  * snn_subbit_prepare turns codebook, idx and alpha into the tables the convolution reads (one small
  * launch; to be repeated whenever one of them changes), snn_subbit_conv2d_prepared is the

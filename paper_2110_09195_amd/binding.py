@@ -29,7 +29,7 @@ SNN_WS_FORWARD = 2
 SNN_WS_CONV1X1 = 3
 SNN_WS_BNN_DENSE = 4
 
-EXPORTS = ("snn_pack_activations", "snn_project_kernels", "snn_subbit_conv2d", "snn_subbit_forward",
+EXPORTS = ("snn_pack_activations", "snn_project_kernels", "snn_subbit_conv2d", "snn_subbit_conv2d_noalloc", "snn_subbit_forward",
            "snn_subbit_prepare", "snn_subbit_conv2d_prepared", "snn_packed_index_bytes", "snn_pack_indices",
            "snn_subbit_prepare_packed", "snn_subbit_conv1x1", "snn_project_vectors8",
            "snn_subbit_conv2d_sign", "snn_subbit_forward_sign", "snn_subbit_prepare_sign",
@@ -83,6 +83,8 @@ def lib():
         L.snn_project_kernels.restype = i32
         L.snn_subbit_conv2d.argtypes = [dp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.snn_subbit_conv2d.restype = i32
+        L.snn_subbit_conv2d_noalloc.argtypes = [dp, vp, vp, vp, vp, vp, vp]
+        L.snn_subbit_conv2d_noalloc.restype = i32
         L.snn_subbit_prepare.argtypes = [dp, vp, vp, vp, vp, sz, vp]
         L.snn_subbit_prepare.restype = i32
         L.snn_subbit_conv2d_prepared.argtypes = [dp, vp, vp, vp, vp, sz, vp]
@@ -231,6 +233,20 @@ def snn_subbit_conv2d(desc, x, codebook, idx, alpha, y=None, workspace=None):
         workspace = alloc_workspace(desc, SNN_WS_SUBBIT, x.device)
     _check(lib().snn_subbit_conv2d(ctypes.byref(desc), _ptr(x), _ptr(codebook), _ptr(idx), _ptr(alpha), _ptr(y),
                                    _ptr(workspace), workspace.numel(), _stream()), "snn_subbit_conv2d")
+    return y
+
+
+def snn_subbit_conv2d_noalloc(desc, x, codebook, idx, alpha, y):
+    """snn_subbit_conv2d without a workspace (the library's own per-GPU buffer); `y` must be given:
+    neither the call nor this wrapper allocates."""
+    _dev(codebook, torch.int16, "codebook")
+    _dev(idx, torch.int16, "idx")
+    _dev(alpha, torch.float32, "alpha")
+    _dev(y, torch.float32, "y")
+    if y.numel() != desc.N * desc.C_out * ((desc.H - 1) // desc.stride + 1) * ((desc.W - 1) // desc.stride + 1):
+        raise ValueError("y has the wrong size")
+    _check(lib().snn_subbit_conv2d_noalloc(ctypes.byref(desc), _ptr(x), _ptr(codebook), _ptr(idx), _ptr(alpha), _ptr(y),
+                                           _stream()), "snn_subbit_conv2d_noalloc")
     return y
 
 

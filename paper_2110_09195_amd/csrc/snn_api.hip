@@ -1,11 +1,36 @@
 // C entry points of the library: argument checks, workspace sizing, dispatch.
 #include "snn_internal.h"
 
+#include <mutex>
 #include <vector>
 
 using namespace snn;
 
+// Scratch memory of snn_subbit_conv2d_noalloc: the convolution's workspace for callers that cannot
+// allocate.  One copy per GPU the library runs on, held until the process ends.  In host code the
+// name below is only a handle for hipGetSymbolAddress; the device address it returns is what the
+// kernels receive.
+static __device__ __align__(256) unsigned char scratch[SNN_NOALLOC_MAX_WORKSPACE_BYTES];
+
 namespace {
+
+constexpr int NOALLOC_MAX_DEVICES = 64;
+void *g_scratch_ptr[NOALLOC_MAX_DEVICES];
+std::mutex g_scratch_mutex;
+
+// Device address of `scratch` on the current device (looked up once per device), or nullptr.
+void *scratch_on_current_device()
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= NOALLOC_MAX_DEVICES) return nullptr;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess) return nullptr;
+        g_scratch_ptr[dev] = ptr;
+    }
+    return g_scratch_ptr[dev];
+}
 
 bool desc_ok(const snn_conv_desc *d, bool need_K)
 {
@@ -128,6 +153,19 @@ int snn_subbit_conv2d(const snn_conv_desc *desc, const void *x, const uint16_t *
     const size_t need = subbit_workspace_bytes(g, desc->act);
     if (need > 0 && (!workspace || ws_bytes < need || ((uintptr_t)workspace & 255u))) return SNN_ERR_WORKSPACE;
     return launch_subbit(g, desc->act, x, codebook, idx, alpha, y_nchw, workspace, (hipStream_t)stream);
+}
+
+int snn_subbit_conv2d_noalloc(const snn_conv_desc *desc, const void *x, const uint16_t *codebook, const uint16_t *idx,
+                              const float *alpha, float *y_nchw, void *stream)
+{
+    if (!desc_ok(desc, true) || !x || !codebook || !idx || !alpha || !y_nchw) return SNN_ERR_INVALID_ARG;
+    if (!subbit_act_supported(desc->act)) return SNN_ERR_UNSUPPORTED;
+    const Geom g = make_geom(*desc);
+    const size_t need = subbit_workspace_bytes(g, desc->act);
+    if (need > (size_t)SNN_NOALLOC_MAX_WORKSPACE_BYTES) return SNN_ERR_WORKSPACE;
+    void *ws = scratch_on_current_device();
+    if (!ws) return SNN_ERR_LAUNCH;
+    return launch_subbit(g, desc->act, x, codebook, idx, alpha, y_nchw, ws, (hipStream_t)stream);
 }
 
 int snn_subbit_prepare(const snn_conv_desc *desc, const uint16_t *codebook, const uint16_t *idx, const float *alpha,
