@@ -19,7 +19,7 @@ LIB = os.path.join(HERE, "libsnn_hip.so")
 PEAKS_LIB = os.path.join(HERE, "libsnn_peaks.so")
 PEAKS_SOURCES = ["peaks.hip"]
 SOURCES = ["snn_api.hip", "pack.hip", "project.hip", "bnn_conv.hip", "subbit_conv.hip", "subbit_f32.hip",
-           "subbit_mfma.hip", "train_ops.hip", "dense_fp4.hip"]
+           "subbit_mfma.hip", "subbit_stack.hip", "train_ops.hip", "dense_fp4.hip"]
 
 # Packed-fp32 VALU forms are switched off for all device code of this library.
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",

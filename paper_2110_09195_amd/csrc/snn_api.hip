@@ -313,6 +313,8 @@ int snn_subbit_conv2d_prepared_many(const snn_layer_io *layers, int n_layers, vo
         y[l] = L.y_nchw;
         ws[l] = L.workspace;
     }
+    if (subbit_stack_supported(n_layers, gs.data()))
+        return launch_subbit_stack(n_layers, gs.data(), x.data(), y.data(), ws.data(), (hipStream_t)stream);
     return launch_subbit_mfma_many(n_layers, gs.data(), x.data(), y.data(), ws.data(), (hipStream_t)stream);
 }
 

@@ -123,6 +123,11 @@ int launch_subbit_forward_mfma(const Geom &g, const float *x, const float *w, co
 // the convolutions of several prepared layers (matrix-core kernel, +-1 activations in packed rows, fp32 output)
 int launch_subbit_mfma_many(int n_layers, const Geom *gs, const void *const *x, float *const *y, void *const *ws, hipStream_t s);
 
+// the same with resident workers (one wave each) that draw (layer, tile) items from a counter in the first
+// layer's workspace; `supported` says whether every layer has a form that kernel holds (at most 16 layers)
+bool subbit_stack_supported(int n_layers, const Geom *gs);
+int launch_subbit_stack(int n_layers, const Geom *gs, const void *const *x, float *const *y, void *const *ws, hipStream_t s);
+
 int launch_subbit_prepare_many(int n_layers, const Geom *gs, const float *const *w, const uint16_t *const *codebook,
                                const float *const *alpha, const float *const *beta, uint16_t *const *idx_out,
                                void *const *ws, hipStream_t s);

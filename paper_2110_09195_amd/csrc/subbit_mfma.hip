@@ -23,6 +23,7 @@
 // channel pairs; the KS waves that split the channels of one tile sit in one workgroup and add
 // their partial sums through LDS.
 #include "front_ops.h"
+#include "subbit_mfma_plan.h"
 
 #include <type_traits>
 
@@ -40,13 +41,7 @@ typedef __attribute__((address_space(3))) u32x4 lds_u32x4;
 typedef __attribute__((address_space(3))) const uint32_t lds_cu32;
 typedef __attribute__((address_space(3))) uint32_t lds_u32;
 
-constexpr int MF_WAVES = 4;                    // waves per workgroup
 constexpr uint32_t MF_SEL_NONE = 0x0c0c0c0cu;  // v_perm_b32 selector bytes that produce 0x00
-constexpr int MF_STAGE_SLOTS = 32;             // packed words a wave stages per input channel and step
-constexpr int MF_STAGE_BYTES = 2 * MF_STAGE_SLOTS * 4 + 32;   // per wave: two channels + room for reads past the last slot
-// Table row stride in LDS: 24 bytes (32 FP6 values) per lane half, each half padded to 32 bytes in
-// the two-half form, the row padded to an odd number of 16-byte pieces (fewer bank conflicts).
-__host__ __device__ constexpr int mf_lrow(bool pair) { return pair ? 48 : 80; }
 
 struct MfParams {
     const uint32_t *x;        // packed rows [N][C_in][H][WW]
@@ -68,28 +63,7 @@ struct MfParams {
     int pairs_per_split;
     int n_cotiles;
     long long n_tiles;        // pixel tiles * channel tiles
-#ifdef SNN_MF_TRACE
-    unsigned long long *trace;    // tuning builds: wall-clock samples, 16 words per wave
-    int trace_block0, trace_layer;
-#endif
 };
-#ifdef SNN_MF_TRACE
-// tuning builds: every wave records the wall clock (10 ns ticks) at eight marks and, at the last one, writes
-// them with its hardware id to trace[16 * wave number]
-#define MF_TRACE(slot)                                                                          \
-    do {                                                                                        \
-        mf_t[(slot)] = wall_clock64();                                                          \
-        if ((slot) == 7 && (threadIdx.x & 63) == 0) {                                           \
-            unsigned long long *mf_o = p.trace + ((size_t)(p.trace_block0 + block) * MF_WAVES + (threadIdx.x >> 6)) * 16; \
-            for (int mf_i = 0; mf_i < 8; ++mf_i) mf_o[mf_i] = mf_t[mf_i];                       \
-            mf_o[8] = __builtin_amdgcn_s_getreg((4 << 0) | (0 << 6) | (31 << 11));              \
-            mf_o[9] = __builtin_amdgcn_s_getreg((20 << 0) | (0 << 6) | (31 << 11));             \
-            mf_o[10] = (unsigned long long)p.trace_layer;                                       \
-        }                                                                                       \
-    } while (0)
-#else
-#define MF_TRACE(slot) do { } while (0)
-#endif
 
 // FP6 e2m3 code of an integer in [-7, 7]
 __host__ __device__ inline uint32_t fp6_of_int(int v)
@@ -133,6 +107,9 @@ __device__ inline void prep_lut_block(const uint16_t *__restrict__ codebook, int
             word |= at >= 0 ? code << at : code >> -at;
         }
         lut[i] = word;
+        // the same table a second time for the kernel of subbit_stack.hip, behind the first image (whose region is
+        // sized for 48-byte rows and holds 24-byte ones): the first four words of all rows, then the last two
+        if (pair && taps == 9) lut[MF_LUT_SPLIT_WORDS + (w < 4 ? 4 * win + w : 2048 + 2 * win + (w - 4))] = word;
     }
 }
 
@@ -227,14 +204,31 @@ __device__ inline void store_sel(uint32_t *__restrict__ sel, int COP, int C_in, 
     sel[((int64_t)c * 2 + h) * COP + pos] = s;
 }
 
+// Tables for the launch that walks a stack of layers (fp32 output): the finishing table again, laid out
+// so that a lane reads the entries of four consecutive output channels with one access:
+// negcorr[type][co] = -(2 corr + C_in (valid_taps(type) - 8)) as int16 (|.| <= 10 C_in, C_in <= 3000),
+// alphap[co] = alpha (0 for padding channels); and the two scheduling words, zeroed.
+struct StackTables {
+    int16_t *negcorr;
+    float *alphap;
+    uint32_t *sched;
+    int COP;
+};
+__device__ inline void store_stack_entry(const StackTables &st, int co, int type, int corr_term, float a)
+{
+    st.negcorr[type * st.COP + co] = (int16_t)(-corr_term);
+    if (type == 0) st.alphap[co] = a;
+}
+
 __global__ __launch_bounds__(256)
 void subbit_mfma_prep_kernel(const uint16_t *__restrict__ codebook, const void *__restrict__ idx, int tau, int C_in,
                              int C_out, int COP, int CB, int K, int pair, int sel_blocks, int lut_blocks,
                              const float *__restrict__ alpha, uint32_t *__restrict__ sel, uint2 *__restrict__ fin,
-                             uint32_t *__restrict__ lut, const float *__restrict__ beta, int taps)
+                             uint32_t *__restrict__ lut, const float *__restrict__ beta, int taps, StackTables st)
 {
     const int tid = threadIdx.x;
     const int b = blockIdx.x;
+    if (b == (int)gridDim.x - 1 && tid < 2) st.sched[tid] = 0u;
     if (b < sel_blocks) {
         // tile of 32 output channels x 32 input channels: read along c_in, write along c_out
         __shared__ uint16_t tile[32][33];
@@ -264,7 +258,10 @@ void subbit_mfma_prep_kernel(const uint16_t *__restrict__ codebook, const void *
     if (taps == 8) {
         // 1x1 layers have no border: S = 2 acc, nothing to correct
         const int co = (b - sel_blocks) * 4 + (tid >> 6);
-        if (co < COP && (tid & 63) < 16) fin[co * 16 + (tid & 63)] = make_uint2(0u, __float_as_uint(co < C_out ? alpha[co] : 0.0f));
+        if (co < COP && (tid & 63) < 16) {
+            fin[co * 16 + (tid & 63)] = make_uint2(0u, __float_as_uint(co < C_out ? alpha[co] : 0.0f));
+            store_stack_entry(st, co, tid & 63, 0, co < C_out ? alpha[co] : 0.0f);
+        }
         return;
     }
     // one wave per output channel; the zero-bit patterns of the K codes go through LDS so that the
@@ -301,6 +298,7 @@ void subbit_mfma_prep_kernel(const uint16_t *__restrict__ codebook, const void *
             if ((inv >> t) & 1u) s += zeros[t];
         const float a = co < C_out ? alpha[co] : 0.0f;
         fin[co * 16 + lane] = fin_entry(2 * s + (border_valid_taps(lane) - 8) * C_in, a, beta, co, co < C_out, C_in);
+        if (!beta) store_stack_entry(st, co, lane, 2 * s + (border_valid_taps(lane) - 8) * C_in, a);
     }
 }
 
@@ -325,6 +323,7 @@ struct WeightParams {
     uint2 *fin;
     uint32_t *lut;
     int C_in, C_out, COP, CB, K, pair, lut_blocks;
+    StackTables st;
 };
 constexpr int FRONT_LDS_WORDS = 64 * 12 + 64 + 4 * 9;   // coef[K][12] floats, zero-bit patterns, per-wave counts
 
@@ -408,7 +407,9 @@ __device__ inline void weight_channel_block(const WeightParams &p, int co, uint3
         for (int t = 0; t < 9; ++t)
             if ((inv >> t) & 1u) sum += (int)(wsum[t] + wsum[9 + t] + wsum[18 + t] + wsum[27 + t]);
         p.fin[co * 16 + tid] = fin_entry(2 * sum + (border_valid_taps(tid) - 8) * C_in, a, p.beta, co, real, C_in);
+        if (!p.beta) store_stack_entry(p.st, co, tid, 2 * sum + (border_valid_taps(tid) - 8) * C_in, a);
     }
+    if (co == 0 && tid < 2) p.st.sched[tid] = 0u;
 }
 
 struct FrontParams {
@@ -592,11 +593,6 @@ __device__ __forceinline__ void mf_tile_body(const MfParams &p, const unsigned b
         }
         return ok;
     };
-
-#ifdef SNN_MF_TRACE
-    unsigned long long mf_t[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-#endif
-    MF_TRACE(0);
 
     // The lookup table image was built once by the preparation kernel.  Its words are requested
     // first of all, so that they travel while the lanes work out their geometry.
@@ -842,9 +838,7 @@ __device__ __forceinline__ void mf_tile_body(const MfParams &p, const unsigned b
         const int half = rest / 6, col = rest - 6 * half;
         ((uint32_t *)smem)[row * (MF_LROW / 4) + half * 8 + col] = lutw[i];
     }
-    MF_TRACE(1);
     __syncthreads();                               // table visible
-    MF_TRACE(2);
 
     if (c_begin < c_end) {
         if constexpr (STG) {
@@ -919,8 +913,6 @@ __device__ __forceinline__ void mf_tile_body(const MfParams &p, const unsigned b
         for (; c + UNROLL <= c_end; c += UNROLL) group(c, std::false_type{});
         if (c < c_end) group(c, std::true_type{});
     }
-
-    MF_TRACE(3);
     // The {correction, alpha} pairs of the wave's output channels are requested now (the operand
     // registers of the loop are free) and travel during the reduction.
     // The KS waves of a tile share one copy: each fetches a KS-th of it.
@@ -984,20 +976,17 @@ __device__ __forceinline__ void mf_tile_body(const MfParams &p, const unsigned b
             }
         }
     }
-    MF_TRACE(4);
     // ---- epilogue: S = 2 M' - fin.x, y = float(S) * alpha ---------------------------------------------
     // The {correction, alpha} pairs of the wave's output channels go through LDS (one 8-byte read
     // per output); stores use a scalar channel offset.  Register r of a block: output channel
     // 8 * (r / 4) + 4 * h + r % 4, pixel n_l.
     __syncthreads();                               // table / partial sums no longer read
-    MF_TRACE(5);
     const uint32_t fin_wave = (uint32_t)(uintptr_t)smem + (uint32_t)tile_in_wg * FIN_BYTES;
 #pragma unroll
     for (int i = 0; i < FIN_PIECES; ++i)
         if (i < FIN_PIECES / KS) *(lds_u32x4 *)(uintptr_t)(fin_wave + (uint32_t)((fin_first + i) * 64 + lane) * 16u) = finv[i];
     if (KS > 1) __syncthreads();                   // the other waves' parts
     if (!active) return;
-    MF_TRACE(6);
     if (p.sign_out) {
         // ---- sign epilogue: bit = ((float)S * alpha + beta >= 0) = (acc * mult >= thr), the next layer's packed rows
         // The 32 lanes of a half hold the pixels of one block of one channel: a ballot turns their signs
@@ -1079,7 +1068,6 @@ __device__ __forceinline__ void mf_tile_body(const MfParams &p, const unsigned b
                 }
             }
         }
-        MF_TRACE(7);
         return;
     }
     const __amdgpu_buffer_rsrc_t yres = make_rsrc(p.y, (uint32_t)((size_t)g.N * g.C_out * g.HoWo * 4u));
@@ -1099,7 +1087,6 @@ __device__ __forceinline__ void mf_tile_body(const MfParams &p, const unsigned b
                 if (cs + 4 * h < g.C_out) buf_store(yres, v, yoff[pb], (uint32_t)cs * chan_bytes);
             }
         }
-    MF_TRACE(7);
 }
 
 template <int PB, int CB, int WM, bool PAIR, bool STG, bool QUAD = false>
@@ -1146,115 +1133,6 @@ void subbit_mfma_many_kernel(const MfManyParams pm)
 
 // ---- host side -------------------------------------------------------------------------------------
 
-struct MfCfg {
-    int PB, CB;
-};
-
-struct MfPlan {
-    MfCfg cfg;
-    bool pair;        // K <= 32: two input channels per step
-    bool quad;        // K <= 16 (3x3 layers): four
-    bool stage;       // the rows of a tile fit the staging slots
-    bool one;         // 1x1 layer (g.C_in = groups of 8 input channels)
-    int KS, COP, n_cotiles, npairs;
-    long long n_pxblocks, n_pxtiles, n_tiles, n_wgs;
-    size_t lds;
-    size_t off_sel, off_fin, off_lut, bytes;
-};
-
-int env_int(const char *name, int dflt)
-{
-    const char *e = getenv(name);
-    return e ? atoi(e) : dflt;
-}
-
-// blocks of up to 32 pixels: 32 consecutive pixels each, or (sign epilogue) whole output words
-int64_t mf_pxblocks(const Geom &g, bool aligned)
-{
-    if (!aligned) return (g.P + 31) / 32;
-    if (g.Wo <= 32) {
-        const int rows_pb = 32 / g.Wo;
-        return (int64_t)g.N * ((g.Ho + rows_pb - 1) / rows_pb);
-    }
-    return (int64_t)g.N * g.Ho * ((g.Wo + 31) / 32);
-}
-
-MfPlan mf_plan(const Geom &g, bool aligned = false, bool one = false)
-{
-    MfPlan pl;
-    pl.one = one;
-    // tile of a wave: 128 accumulator registers (PB x CB = 8); few channels -> more pixels per wave
-    if (g.C_out <= 64) pl.cfg = {4, 2};
-    else pl.cfg = {2, 4};
-    // tuning override "PB,CB"
-    if (const char *e = getenv("SNN_MFMA_TILE")) {
-        int a = 0, b = 0;
-        if (sscanf(e, "%d,%d", &a, &b) == 2 && ((a == 4 && b == 2) || (a == 2 && b == 4) || (a == 2 && b == 2) || (a == 1 && b == 4) || (a == 1 && b == 2)))
-            pl.cfg = {a, b};
-    }
-    const int cow = 32 * pl.cfg.CB, pxw = 32 * pl.cfg.PB;
-    pl.COP = (g.C_out + cow - 1) / cow * cow;
-    pl.n_cotiles = pl.COP / cow;
-    pl.n_pxblocks = mf_pxblocks(g, aligned);
-    pl.n_pxtiles = (pl.n_pxblocks + pl.cfg.PB - 1) / pl.cfg.PB;
-    pl.n_tiles = pl.n_pxtiles * pl.n_cotiles;
-    pl.pair = g.K <= 32;
-    pl.quad = false;
-    pl.npairs = pl.pair ? (g.C_in + 1) / 2 : g.C_in;
-    // split the channel pairs over waves while the tiles alone leave SIMDs idle (1024 SIMDs, two waves each)
-    auto split_of = [&](int steps) {
-        int ks = 1;
-        while (ks < 4 && pl.n_tiles * ks < 1536 && steps / (2 * ks) >= 8) ks *= 2;
-        return ks;
-    };
-    int KS = split_of(pl.npairs);
-    // Subsets of at most 16 members: four channels per step halve the matrix instructions and double the
-    // window work of a step (and give up the staged rows).  Measured: a gain (1.2x) only where a wave has
-    // long runs of steps - many input channels on tiles of four channel blocks - and a loss on short ones.
-    // SNN_MFMA_QUAD = 1 / 0 forces it on wherever it applies / off.
-    if (g.K <= 16 && !one) {
-        const int quad_env = env_int("SNN_MFMA_QUAD", -1);
-        const bool pays = pl.cfg.CB == 4 && (int64_t)(pl.npairs / KS) * pl.cfg.PB * pl.cfg.CB >= 768;
-        if (quad_env < 0 ? pays : quad_env != 0) {
-            pl.quad = true;
-            pl.npairs = (g.C_in + 3) / 4;
-            KS = split_of(pl.npairs);
-        }
-    }
-    const int ks_env = env_int("SNN_MFMA_KS", 0);
-    if (ks_env == 1 || ks_env == 2 || ks_env == 4) KS = ks_env;
-    pl.KS = KS;
-    pl.n_wgs = (pl.n_tiles * KS + MF_WAVES - 1) / MF_WAVES;
-    // Rows a tile of pxw consecutive pixels can touch, numbered over the whole batch: a change of
-    // output row moves the first row loaded by at most `stride`, a change of image by one more
-    // (the top row of an image is not preceded by a padding row), and the last pixel loads three.
-    const int64_t row_changes = (g.Wo - 1 + pxw - 1) / g.Wo, image_changes = ((int64_t)g.HoWo - 1 + pxw - 1) / g.HoWo;
-    const int64_t tile_rows = g.stride * row_changes + image_changes + 3;
-    // Staging pays where the memory pipeline is the bound: two channel blocks per wave, i.e. only two
-    // matrix instructions per window (measured; with four blocks the loop is bound by the matrix pipe
-    // and the extra LDS traffic costs a little).  SNN_MFMA_STAGE = 1 / 0 forces it on wherever it fits / off.
-    const int stage_env = env_int("SNN_MFMA_STAGE", -1);
-    pl.stage = !one && !pl.quad && g.WW <= 2 && tile_rows * (g.WW == 2 ? 3 : 1) <= MF_STAGE_SLOTS &&
-               (stage_env < 0 ? pl.cfg.CB == 2 : stage_env != 0);
-    const size_t lut_bytes = (size_t)(one ? 256 : 512) * mf_lrow(pl.pair) + (pl.stage ? (size_t)MF_WAVES * MF_STAGE_BYTES : 0);
-    const int nblk = pl.cfg.PB * pl.cfg.CB;
-    const size_t red_bytes = KS > 1 ? (size_t)(MF_WAVES / KS) * (nblk > 4 ? nblk / 2 : nblk) * (KS - 1) * 4096 : 0;
-    const size_t fin_bytes = (size_t)MF_WAVES * 32 * pl.cfg.CB * 16 * 8;
-    pl.lds = lut_bytes > red_bytes ? lut_bytes : red_bytes;
-    if (fin_bytes > pl.lds) pl.lds = fin_bytes;
-    size_t o = 0;
-#ifdef SNN_MF_TRACE
-    o += 4 << 20;             // clock samples
-#endif
-    pl.off_sel = o;
-    o += align_up((size_t)pl.npairs * (pl.quad ? 4 : 2) * pl.COP * sizeof(uint32_t), 256);
-    pl.off_fin = o;
-    o += align_up((size_t)pl.COP * 16 * sizeof(uint2), 256);
-    pl.off_lut = o;
-    o += align_up((size_t)512 * mf_lrow(pl.pair), 256);
-    pl.bytes = o;
-    return pl;
-}
 
 template <int PB, int CB, int WM, bool PAIR, bool STG, bool QUAD = false>
 int launch_mf_one(const MfPlan &pl, const MfParams &prm, hipStream_t s)
@@ -1304,7 +1182,14 @@ bool subbit_mfma_supported(const Geom &g)
            y_words < ((int64_t)1 << 30) && g.P < ((int64_t)1 << 31) - 4096;
 }
 
-size_t subbit_mfma_workspace_bytes(const Geom &g) { return mf_plan(g).bytes; }
+// The plain and the sign-epilogue form cut the pixels into blocks differently and may therefore split
+// the input channels differently (and, for small subsets, pick different table layouts): the size
+// covers both, so that one workspace serves every entry point of a layer.
+size_t subbit_mfma_workspace_bytes(const Geom &g)
+{
+    const size_t a = mf_plan(g, false).bytes, b = mf_plan(g, true).bytes;
+    return a > b ? a : b;
+}
 
 namespace {
 
@@ -1327,11 +1212,6 @@ MfParams mf_params(const MfPlan &pl, const Geom &g, const void *x, float *y, voi
     prm.n_pxblocks = (int)pl.n_pxblocks;
     prm.x_bytes = 0;
     prm.cw_bytes = 0;
-#ifdef SNN_MF_TRACE
-    prm.trace = (unsigned long long *)ws;
-    prm.trace_block0 = 0;
-    prm.trace_layer = 0;
-#endif
     return prm;
 }
 
@@ -1344,6 +1224,16 @@ int launch_mf_conv(const MfPlan &pl, const MfParams &prm, hipStream_t s)
     if (c.PB == 1 && c.CB == 4) return launch_mf<1, 4>(pl, prm, s);
     if (c.PB == 1 && c.CB == 2) return launch_mf<1, 2>(pl, prm, s);
     return SNN_ERR_UNSUPPORTED;
+}
+
+StackTables stack_tables(const MfPlan &pl, void *ws)
+{
+    StackTables st;
+    st.negcorr = (int16_t *)((char *)ws + pl.off_negcorr);
+    st.alphap = (float *)((char *)ws + pl.off_alphap);
+    st.sched = (uint32_t *)((char *)ws + pl.off_sched);
+    st.COP = pl.COP;
+    return st;
 }
 
 WeightParams weight_params(const MfPlan &pl, const Geom &g, const MfParams &prm, const float *w, const uint16_t *codebook,
@@ -1365,6 +1255,7 @@ WeightParams weight_params(const MfPlan &pl, const Geom &g, const MfParams &prm,
     wp.K = g.K;
     wp.pair = pl.quad ? 2 : pl.pair ? 1 : 0;
     wp.lut_blocks = (512 * (pl.pair ? 6 : 12) + 255) / 256;
+    wp.st = stack_tables(pl, (char *)prm.sel - pl.off_sel);
     return wp;
 }
 
@@ -1413,7 +1304,7 @@ int launch_subbit_mfma(const Geom &g, const void *x, const uint16_t *codebook, c
     if (phases & SNN_PHASE_PREPARE)
         hipLaunchKernelGGL(subbit_mfma_prep_kernel, dim3((unsigned)(sel_blocks + corr_blocks + lut_blocks)), dim3(256), 0, s,
                            codebook, (const void *)idx, tau, g.C_in, g.C_out, pl.COP, pl.cfg.CB, g.K, pl.quad ? 2 : pl.pair ? 1 : 0, sel_blocks, lut_blocks, alpha,
-                           (uint32_t *)prm.sel, (uint2 *)prm.fin, (uint32_t *)prm.lut, sign ? sign->beta : nullptr, 9);
+                           (uint32_t *)prm.sel, (uint2 *)prm.fin, (uint32_t *)prm.lut, sign ? sign->beta : nullptr, 9, stack_tables(pl, ws));
     if (!(phases & SNN_PHASE_CONVOLVE)) return check_launch();
     return launch_mf_conv(pl, prm, s);
 }
@@ -1456,10 +1347,12 @@ int launch_subbit_mfma_many(int n_layers, const Geom *gs, const void *const *x, 
         lds = 0;
         return check_launch();
     };
-    const int target_steps = env_int("SNN_MANY_STEPS", 0);
+    // In a shared launch the split of the input channels over waves is chosen for the length of a wave's
+    // run (about 64 steps: measured best on the ResNet-18 stack), not to fill the chip with one layer.
+    const int target_steps = 64;
     for (int l = 0; l < n_layers; ++l) {
         MfPlan pl = mf_plan(gs[l]);
-        if (target_steps > 0) {
+        {
             int ks = 1;
             while (ks < 4 && pl.npairs / (2 * ks) >= target_steps) ks *= 2;
             pl.KS = ks;
@@ -1484,11 +1377,6 @@ int launch_subbit_mfma_many(int n_layers, const Geom *gs, const void *const *x, 
             }
         }
         pm.layer[pm.n_layers] = prm;
-#ifdef SNN_MF_TRACE
-        pm.layer[pm.n_layers].trace = (unsigned long long *)ws[0];
-        pm.layer[pm.n_layers].trace_block0 = (int)blocks;
-        pm.layer[pm.n_layers].trace_layer = l;
-#endif
         pm.variant[pm.n_layers] = variant;
         pm.first_block[pm.n_layers] = (int)blocks;
         blocks += pl.n_wgs;
@@ -1569,7 +1457,7 @@ int launch_subbit_conv1x1(const Geom &g, const void *x, const uint16_t *codebook
     const int lut_blocks = (256 * (pl.pair ? 6 : 12) + 255) / 256;
     hipLaunchKernelGGL(subbit_mfma_prep_kernel, dim3((unsigned)(sel_blocks + corr_blocks + lut_blocks)), dim3(256), 0, s, codebook,
                        (const void *)idx, 0, gk.C_in, g.C_out, pl.COP, pl.cfg.CB, g.K, pl.pair ? 1 : 0, sel_blocks, lut_blocks, alpha,
-                       (uint32_t *)prm.sel, (uint2 *)prm.fin, (uint32_t *)prm.lut, (const float *)nullptr, 8);
+                       (uint32_t *)prm.sel, (uint2 *)prm.fin, (uint32_t *)prm.lut, (const float *)nullptr, 8, stack_tables(pl, ws));
     return launch_mf_conv(pl, prm, s);
 }
 

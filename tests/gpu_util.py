@@ -15,6 +15,38 @@ def dev(a):
     return torch.from_numpy(a).cuda()
 
 
+GUARD_BYTES = 256      # on each side of a guarded buffer (keeps the 256-byte alignment of the payload)
+
+
+class Guarded:
+    """A device buffer with guard bytes in front of and behind the payload: `t` is the payload (a view), and
+    check() asserts that the library wrote nothing outside it."""
+
+    def __init__(self, numel, dtype, fill=None):
+        size = torch.empty((), dtype=dtype).element_size()
+        assert GUARD_BYTES % size == 0
+        g = GUARD_BYTES // size
+        self.raw = torch.empty(numel + 2 * g, dtype=dtype, device="cuda")
+        self.bytes = self.raw.view(torch.uint8)
+        self.bytes.fill_(0xA5)
+        self.t = self.raw[g:g + numel]
+        if fill is not None:
+            self.t.fill_(fill)
+        self.n_bytes = numel * size
+
+    def check(self, what=""):
+        torch.cuda.synchronize()
+        front = self.bytes[:GUARD_BYTES]
+        back = self.bytes[GUARD_BYTES + self.n_bytes:]
+        assert bool((front == 0xA5).all()), "bytes in front of %s were overwritten" % what
+        assert bool((back == 0xA5).all()), "bytes behind %s were overwritten" % what
+
+
+def guarded_workspace(desc, which):
+    """A workspace of exactly the size the library asks for, with guard bytes around it."""
+    return Guarded(max(int(B.snn_workspace_bytes(desc, which)), 256), torch.uint8)
+
+
 def host_u32(t):
     return t.cpu().numpy().view(np.uint32)
 
@@ -25,8 +57,9 @@ def host_u16(t):
 
 def pack(x, layout):
     N, C, H, W = x.shape
-    out = B.snn_pack_activations(dev(x), layout)
-    torch.cuda.synchronize()
+    g = Guarded(B.snn_packed_bytes(N, C, H, W, layout) // 4, torch.int32)
+    out = B.snn_pack_activations(dev(x), layout, out=g.t)
+    g.check("the packed activations")
     words = host_u32(out)
     if layout == B.SNN_ACT_BIN_ROWS:
         return words.reshape(N, C, H, (W + 31) // 32)
@@ -40,8 +73,12 @@ def subbit_bin(x, codebook, idx, alpha, stride=1, packed=None):
     C_out = idx.shape[0]
     d = B.make_desc(N, C_in, C_out, H, W, stride, int(codebook.size), B.SNN_ACT_BIN_ROWS)
     xp = dev(packed) if packed is not None else B.snn_pack_activations(dev(x), B.SNN_ACT_BIN_ROWS)
-    y = B.snn_subbit_conv2d(d, xp, dev(codebook), dev(idx), dev(alpha))
-    torch.cuda.synchronize()
+    Ho, Wo = B.out_hw(d)
+    gy = Guarded(N * C_out * Ho * Wo, torch.float32, fill=float("nan"))
+    gw = guarded_workspace(d, B.SNN_WS_SUBBIT)
+    y = B.snn_subbit_conv2d(d, xp, dev(codebook), dev(idx), dev(alpha), y=gy.t.view(N, C_out, Ho, Wo), workspace=gw.t)
+    gy.check("y")
+    gw.check("the workspace")
     return y.cpu().numpy()
 
 
@@ -59,8 +96,12 @@ def bnn_bin(x, w9, alpha, stride=1):
     C_out = w9.shape[0]
     d = B.make_desc(N, C_in, C_out, H, W, stride, 512, B.SNN_ACT_BIN_CHANNELS)
     xp = B.snn_pack_activations(dev(x), B.SNN_ACT_BIN_CHANNELS)
-    y = B.snn_bnn_conv2d(d, xp, dev(w9), dev(alpha))
-    torch.cuda.synchronize()
+    Ho, Wo = B.out_hw(d)
+    gy = Guarded(N * C_out * Ho * Wo, torch.float32, fill=float("nan"))
+    gw = guarded_workspace(d, B.SNN_WS_BNN)
+    y = B.snn_bnn_conv2d(d, xp, dev(w9), dev(alpha), y=gy.t.view(N, C_out, Ho, Wo), workspace=gw.t)
+    gy.check("y")
+    gw.check("the workspace")
     return y.cpu().numpy()
 
 
@@ -99,8 +140,9 @@ def bnn_f32(x, w9, alpha, stride=1):
 
 
 def project(w, codebook):
-    out = B.snn_project_kernels(dev(w.reshape(-1, 9)), dev(codebook))
-    torch.cuda.synchronize()
+    g = Guarded(w.size // 9, torch.int16)
+    out = B.snn_project_kernels(dev(w.reshape(-1, 9)), dev(codebook), out=g.t)
+    g.check("the projected indices")
     return host_u16(out)
 
 
@@ -128,9 +170,12 @@ def subbit_sign(xp, shape, codebook, idx, alpha, beta, stride=1):
     N, C_in, H, W = shape
     C_out = idx.shape[0]
     d = B.make_desc(N, C_in, C_out, H, W, stride, int(codebook.size), B.SNN_ACT_BIN_ROWS)
-    out = B.snn_subbit_conv2d_sign(d, dev(xp.reshape(-1)), dev(codebook), dev(idx), dev(alpha), dev(beta))
-    torch.cuda.synchronize()
     Ho, Wo = B.out_hw(d)
+    go = Guarded(N * C_out * Ho * ((Wo + 31) // 32), torch.int32)
+    gw = guarded_workspace(d, B.SNN_WS_SUBBIT)
+    out = B.snn_subbit_conv2d_sign(d, dev(xp.reshape(-1)), dev(codebook), dev(idx), dev(alpha), dev(beta), out=go.t, workspace=gw.t)
+    go.check("the packed output")
+    gw.check("the workspace")
     return host_u32(out).reshape(N, C_out, Ho, (Wo + 31) // 32)
 
 
