@@ -27,8 +27,9 @@
  *   - Return value: SNN_OK (0) or a negative SNN_ERR_* code.  On error nothing has been
  *     enqueued.  No exceptions, no aborts, nothing printed.
  *   - Values of idx[] must be < K and values of codebook[] / w9[] must be < 512; this is
- *     not checked on the device (out-of-range values give undefined results, but only
- *     memory inside the library's own tables is read with them: they are masked).
+ *     not reported by the device: the table-building kernels read an index >= K as K - 1 and
+ *     mask a code to 9 bits, so that only memory inside the library's own tables is ever read
+ *     with them; the result for such input is that of the clamped value, with no error.
  *
  * Conventions (identical in the CPU oracle the library is tested against)
  *   - Kernel code (Sec. 4.1): a binary 3x3 kernel is flattened row-major, +1 -> bit 1,
@@ -268,7 +269,11 @@ int snn_subbit_project_prepare_many(const snn_layer_weights *layers, int n_layer
  *   layers[l].y_nchw     device, float [N][C_out][H_out][W_out], fully overwritten; the outputs of
  *                        different layers must not overlap
  *   layers[l].workspace  device, as prepared by snn_subbit_prepare / snn_subbit_prepare_packed /
- *                        snn_subbit_project_prepare_many (beta == NULL) for the same desc; read only
+ *                        snn_subbit_project_prepare_many (beta == NULL) for the same desc.  The tables
+ *                        are only read.  Two scheduling words at the end of layers[0].workspace (zero after
+ *                        preparation) count work items while the call runs and are zero again when it
+ *                        ends: calls that share that workspace must be ordered, like any two calls that
+ *                        share a workspace.
  * Errors: INVALID_ARG; UNSUPPORTED (a layer outside the matrix-core kernel); WORKSPACE; LAUNCH.  All
  * layers are checked before anything is enqueued.
  */
@@ -300,7 +305,8 @@ int snn_subbit_forward_sign(const snn_conv_desc *desc, const void *x_packed, con
  *   g_p[k][t] = sum over the kernels c with idx[c] == k of g_wbar[c][t]
  *               (the gradient of the subset tensor p, taken as that of its sign memory m:
  *                backward of Eq. 5 / the p-update of Alg. 1); summed in fp32, per block of 512
- *                kernels in unspecified order, the block sums then in a fixed order
+ *                kernels in unspecified order (LDS float atomics), the block sums then in a fixed
+ *                order: g_p can differ in its last bits from run to run on the same input
  *   w, g_wbar  device, float [n][9];  idx  device, uint16 [n], values < K (as snn_project_kernels wrote them)
  *   g_w        device, float [n][9], fully overwritten;  g_p  device, float [K][9], fully overwritten
  *   workspace  device, >= snn_project_backward_workspace_bytes(n, K) bytes, 256-byte aligned
@@ -445,6 +451,35 @@ size_t snn_packed_bytes(int N, int C, int H, int W, int layout);
 
 /* Static, human-readable name of a status code. */
 const char *snn_status_string(int status);
+
+/* Contraction slots per input channel that the matrix-core form of the sub-bit convolution spends on
+ * this layer as launched (Sec. 4.5: the method needs one of them, the gather; the others multiply a zero
+ * of the one-hot operand): 32 (two channels per matrix instruction, K <= 32), 16 (four channels,
+ * K <= 16 on long channel runs), 64 (one channel, 32 < K <= 64); 0 where a kernel without matrix
+ * instructions runs the layer (K > 64, C_in = 1, fp32 activations); negative SNN_ERR_* for an invalid desc.
+ * Host-only; for the roofline accounting of a benchmark. */
+int snn_subbit_slots_per_channel(const snn_conv_desc *desc);
+
+/* Tuning and test switches.  Each knob holds SNN_TUNE_AUTO (the library's own choice) unless set; a knob's
+ * first value is read ONCE, when the library first looks at any knob, from the environment variable named like
+ * the knob without "TUNE_" (SNN_MFMA_TILE as "PB,CB").  They select among kernel forms that all compute the same result.
+ * Table layouts in a workspace depend on them: a workspace written by a prepare call must be used under the
+ * settings it was written under (not checked), and snn_workspace_bytes answers for the settings in force
+ * when it is called.  Process-wide,
+ * not synchronised with calls in flight on other threads.
+ * snn_set_tuning returns SNN_ERR_INVALID_ARG for an unknown knob or a value outside the knob's list. */
+#define SNN_TUNE_AUTO (-1)
+#define SNN_TUNE_SUBBIT_MFMA 0 /* 0: layers the matrix-core kernel supports go to the LDS-gather kernel */
+#define SNN_TUNE_MFMA_TILE   1 /* 10 * PB + CB, blocks of 32 pixels x 32 channels per wave: 42, 24, 22, 14, 12 */
+#define SNN_TUNE_MFMA_KS     2 /* waves that share a tile's input channels: 1, 2, 4 */
+#define SNN_TUNE_MFMA_STAGE  3 /* 0 / 1: packed rows staged in LDS wherever they fit */
+#define SNN_TUNE_MFMA_QUAD   4 /* 0 / 1: four channels per matrix instruction wherever K <= 16 */
+#define SNN_TUNE_STACK       5 /* 0: snn_subbit_conv2d_prepared_many runs one workgroup per tile group */
+#define SNN_TUNE_BNN_REGS    6 /* 0: the 1-bit kernel without register-resident windows */
+#define SNN_TUNE_DENSE_TILE  7 /* 0 .. 4: tile shape of the dense contraction */
+#define SNN_TUNE_COUNT       8
+int snn_set_tuning(int knob, int value);
+int snn_get_tuning(int knob); /* SNN_TUNE_AUTO for an unknown knob */
 
 #ifdef __cplusplus
 }

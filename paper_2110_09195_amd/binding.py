@@ -38,7 +38,8 @@ EXPORTS = ("snn_pack_activations", "snn_project_kernels", "snn_subbit_conv2d", "
            "snn_project_backward_workspace_bytes", "snn_subset_update", "snn_bnn_conv2d", "snn_bnn_conv2d_dense",
            "snn_subbit_conv2d_dense", "snn_dense_prepare", "snn_dense_conv2d_prepared",
            "snn_dense_conv2d_sign_prepared",
-           "snn_workspace_bytes", "snn_packed_bytes", "snn_status_string")
+           "snn_workspace_bytes", "snn_packed_bytes", "snn_status_string", "snn_subbit_slots_per_channel",
+           "snn_set_tuning", "snn_get_tuning")
 
 
 class snn_conv_desc(ctypes.Structure):
@@ -137,6 +138,12 @@ def lib():
         L.snn_packed_bytes.restype = sz
         L.snn_status_string.argtypes = [i32]
         L.snn_status_string.restype = ctypes.c_char_p
+        L.snn_subbit_slots_per_channel.argtypes = [dp]
+        L.snn_subbit_slots_per_channel.restype = i32
+        L.snn_set_tuning.argtypes = [i32, i32]
+        L.snn_set_tuning.restype = i32
+        L.snn_get_tuning.argtypes = [i32]
+        L.snn_get_tuning.restype = i32
         _lib = L
     return _lib
 
@@ -174,6 +181,27 @@ def out_hw(desc):
 
 def snn_packed_bytes(N, C, H, W, layout):
     return int(lib().snn_packed_bytes(N, C, H, W, layout))
+
+
+SNN_TUNE_AUTO = -1
+(SNN_TUNE_SUBBIT_MFMA, SNN_TUNE_MFMA_TILE, SNN_TUNE_MFMA_KS, SNN_TUNE_MFMA_STAGE, SNN_TUNE_MFMA_QUAD, SNN_TUNE_STACK,
+ SNN_TUNE_BNN_REGS, SNN_TUNE_DENSE_TILE) = range(8)
+SNN_TUNE_COUNT = 8
+
+
+def snn_set_tuning(knob, value):
+    _check(lib().snn_set_tuning(knob, value), "snn_set_tuning")
+
+
+def snn_get_tuning(knob):
+    return int(lib().snn_get_tuning(knob))
+
+
+def snn_subbit_slots_per_channel(desc):
+    r = int(lib().snn_subbit_slots_per_channel(ctypes.byref(desc)))
+    if r < 0:
+        _check(r, "snn_subbit_slots_per_channel")
+    return r
 
 
 def snn_workspace_bytes(desc, which):

@@ -381,7 +381,7 @@ int launch_bnn(const Geom &g, int act, const void *x, const uint16_t *w9, const 
 
     // (its window loads use 32-bit byte offsets whose top bit means "outside": packed inputs below 2 GiB)
     if (g.CW <= 16 && (int64_t)g.N * g.H * g.W * g.CW < ((int64_t)1 << 29) &&
-        !(getenv("SNN_BNN_REGS") && atoi(getenv("SNN_BNN_REGS")) == 0)) {
+        tuning(SNN_TUNE_BNN_REGS) != 0) {
         // register-resident windows (C_in <= 512)
         int CWT = 1;
         while (CWT < g.CW) CWT <<= 1;

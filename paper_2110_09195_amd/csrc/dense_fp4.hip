@@ -333,14 +333,11 @@ DensePlan dense_plan(const Geom &g)
     // Measured on the layers of a ResNet-18 at batch 64: one pixel block per wave (more waves per SIMD,
     // whose store and compute phases then overlap) and four output-channel blocks while that still
     // leaves a few hundred workgroups, else two.  The two-pixel-block shapes remain selectable
-    // (SNN_DENSE_TILE = 0 / 1) for tuning on larger batches.
+    // (knob SNN_TUNE_DENSE_TILE = 0 / 1) for tuning on larger batches.
     static const int shapes[5][2] = {{2, 4}, {2, 2}, {1, 2}, {1, 1}, {1, 4}};
     const int64_t groups = (pxblocks + 3) / 4;
     int pick = coblocks >= 4 && groups * ((coblocks + 3) / 4) >= 300 ? 4 : coblocks >= 2 ? 2 : 3;
-    if (const char *e = getenv("SNN_DENSE_TILE")) {
-        const int v = atoi(e);
-        if (v >= 0 && v < 5) pick = v;
-    }
+    if (const int v = tuning(SNN_TUNE_DENSE_TILE); v >= 0) pick = v;
     pl.PB = shapes[pick][0];
     pl.CB = shapes[pick][1];
     pl.n_cotiles = (coblocks + pl.CB - 1) / pl.CB;
@@ -357,9 +354,8 @@ int launch_dense_cfg(const DenseParams &prm, int64_t wgs, hipStream_t s)
 {
     auto kern = dense_fp4_kernel<PB, CB, SIGN>;
     const size_t lds = (size_t)2 * CB * CHUNK_ENTRIES * 16 + 2 * CB * 32 * sizeof(float);
-    if (lds > 64 * 1024 &&
-        hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
-        return SNN_ERR_LAUNCH;
+    static LdsGrant grant;
+    if (grant_dynamic_lds((const void *)kern, lds, grant) != SNN_OK) return SNN_ERR_LAUNCH;
     hipLaunchKernelGGL(kern, dim3((unsigned)wgs), dim3(256), lds, s, prm);
     return check_launch();
 }

@@ -1,6 +1,10 @@
 // C entry points of the library: argument checks, workspace sizing, dispatch.
 #include "snn_internal.h"
 
+#include <stdio.h>
+#include <stdlib.h>
+
+#include <atomic>
 #include <mutex>
 #include <vector>
 
@@ -32,6 +36,39 @@ void *scratch_on_current_device()
     return g_scratch_ptr[dev];
 }
 
+// ---- tuning knobs -----------------------------------------------------------------------------------------
+std::atomic<int> g_tune[SNN_TUNE_COUNT];
+std::once_flag g_tune_once;
+
+bool tuning_value_ok(int knob, int v)
+{
+    if (v == SNN_TUNE_AUTO) return true;
+    switch (knob) {
+    case SNN_TUNE_MFMA_TILE: return v == 42 || v == 24 || v == 22 || v == 14 || v == 12;
+    case SNN_TUNE_MFMA_KS: return v == 1 || v == 2 || v == 4;
+    case SNN_TUNE_DENSE_TILE: return v >= 0 && v < 5;
+    default: return v == 0 || v == 1;
+    }
+}
+
+void tuning_from_environment()
+{
+    static const char *const names[SNN_TUNE_COUNT] = {"SNN_SUBBIT_MFMA", "SNN_MFMA_TILE", "SNN_MFMA_KS", "SNN_MFMA_STAGE",
+                                                      "SNN_MFMA_QUAD",   "SNN_STACK",     "SNN_BNN_REGS", "SNN_DENSE_TILE"};
+    for (int k = 0; k < SNN_TUNE_COUNT; ++k) {
+        int v = SNN_TUNE_AUTO;
+        if (const char *e = getenv(names[k])) {
+            int a = 0, b = 0;
+            if (k == SNN_TUNE_MFMA_TILE)
+                v = sscanf(e, "%d,%d", &a, &b) == 2 ? 10 * a + b : SNN_TUNE_AUTO;
+            else
+                v = atoi(e);
+            if (!tuning_value_ok(k, v)) v = SNN_TUNE_AUTO;
+        }
+        g_tune[k].store(v);
+    }
+}
+
 bool desc_ok(const snn_conv_desc *d, bool need_K)
 {
     if (!d) return false;
@@ -57,7 +94,29 @@ bool bnn_supported(const snn_conv_desc *d)
 
 }  // namespace
 
+int snn::tuning(int knob)
+{
+    std::call_once(g_tune_once, tuning_from_environment);
+    return knob >= 0 && knob < SNN_TUNE_COUNT ? g_tune[knob].load(std::memory_order_relaxed) : SNN_TUNE_AUTO;
+}
+
 extern "C" {
+
+int snn_set_tuning(int knob, int value)
+{
+    if (knob < 0 || knob >= SNN_TUNE_COUNT || !tuning_value_ok(knob, value)) return SNN_ERR_INVALID_ARG;
+    std::call_once(g_tune_once, tuning_from_environment);
+    g_tune[knob].store(value);
+    return SNN_OK;
+}
+
+int snn_get_tuning(int knob) { return tuning(knob); }
+
+int snn_subbit_slots_per_channel(const snn_conv_desc *desc)
+{
+    if (!desc_ok(desc, true)) return SNN_ERR_INVALID_ARG;
+    return subbit_slots_per_channel(make_geom(*desc), desc->act);
+}
 
 const char *snn_status_string(int status)
 {
@@ -313,7 +372,7 @@ int snn_subbit_conv2d_prepared_many(const snn_layer_io *layers, int n_layers, vo
         y[l] = L.y_nchw;
         ws[l] = L.workspace;
     }
-    if (subbit_stack_supported(n_layers, gs.data()))
+    if (tuning(SNN_TUNE_STACK) != 0 && subbit_stack_supported(n_layers, gs.data()))
         return launch_subbit_stack(n_layers, gs.data(), x.data(), y.data(), ws.data(), (hipStream_t)stream);
     return launch_subbit_mfma_many(n_layers, gs.data(), x.data(), y.data(), ws.data(), (hipStream_t)stream);
 }

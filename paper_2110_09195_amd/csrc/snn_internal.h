@@ -5,6 +5,8 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "snn.h"
 
 namespace snn {
@@ -34,6 +36,9 @@ inline Geom make_geom(const snn_conv_desc &d)
 }
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// Value of a tuning knob (SNN_TUNE_*): SNN_TUNE_AUTO unless set through snn_set_tuning or, once, from the environment.
+int tuning(int knob);
 
 // Border type of an output pixel: which rows / columns of its 3x3 window lie outside the image.
 //   bit 0: top row, bit 1: bottom row, bit 2: left column, bit 3: right column.
@@ -96,6 +101,9 @@ int launch_dense_fp4(const Geom &g, const void *x, const uint16_t *codebook, con
                      uint32_t *sign_out = nullptr);
 
 size_t subbit_workspace_bytes(const Geom &g, int act);
+// one-hot slots per input channel of the form a layer is launched in (0: no matrix instructions)
+int subbit_slots_per_channel(const Geom &g, int act);
+int subbit_mfma_slots_per_channel(const Geom &g);
 int launch_subbit(const Geom &g, int act, const void *x, const uint16_t *codebook,
                   const uint16_t *idx, const float *alpha, float *y, void *ws, hipStream_t s,
                   int phases = SNN_PHASE_BOTH);
@@ -171,6 +179,25 @@ size_t project_backward_workspace_bytes(int64_t n, int K);
 int launch_project_backward(const float *w, const float *g_wbar, const uint16_t *idx, int64_t n, int K, float *g_w,
                             float *g_p, void *ws, hipStream_t s);
 int launch_subset_update(const float *p, int8_t *m, float theta, int K, uint16_t *codebook, uint8_t *dup, hipStream_t s);
+
+// A kernel that asks for more than 64 KB of dynamic LDS needs its limit raised first: once per kernel, device
+// and size (a launcher keeps one LdsGrant per kernel instantiation).
+struct LdsGrant {
+    static constexpr int MAX_DEVICES = 64;
+    std::atomic<size_t> bytes[MAX_DEVICES];
+};
+
+inline int grant_dynamic_lds(const void *kernel, size_t lds, LdsGrant &grant)
+{
+    if (lds <= 64 * 1024) return SNN_OK;
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) return SNN_ERR_LAUNCH;
+    const bool tracked = dev >= 0 && dev < LdsGrant::MAX_DEVICES;
+    if (tracked && grant.bytes[dev].load(std::memory_order_acquire) >= lds) return SNN_OK;
+    if (hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) return SNN_ERR_LAUNCH;
+    if (tracked) grant.bytes[dev].store(lds, std::memory_order_release);
+    return SNN_OK;
+}
 
 inline int check_launch()
 {

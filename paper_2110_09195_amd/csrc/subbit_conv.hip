@@ -259,19 +259,17 @@ template <int J, int NW>
 int launch_direct(const SbPlan &pl, const SbParams &prm, dim3 grid, hipStream_t s)
 {
     auto kern = subbit_direct_kernel<J, NW>;
-    if (pl.lds > 64 * 1024 && hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                                  (int)pl.lds) != hipSuccess)
-        return SNN_ERR_LAUNCH;
+    static LdsGrant grant;
+    if (grant_dynamic_lds((const void *)kern, pl.lds, grant) != SNN_OK) return SNN_ERR_LAUNCH;
     hipLaunchKernelGGL(kern, grid, dim3(NW * 64), pl.lds, s, prm, pl.CIC);
     return check_launch();
 }
 
-// The matrix-core kernel takes every layer it supports; SNN_SUBBIT_MFMA=0 (a tuning and test
-// override, read at every call) sends those layers to the fallback kernel instead.
+// The matrix-core kernel takes every layer it supports; the knob SNN_TUNE_SUBBIT_MFMA = 0 (tuning and tests)
+// sends those layers to the fallback kernel instead.
 bool use_mfma(const Geom &g)
 {
-    const char *e = getenv("SNN_SUBBIT_MFMA");
-    return subbit_mfma_supported(g) && !(e && e[0] == '0');
+    return subbit_mfma_supported(g) && tuning(SNN_TUNE_SUBBIT_MFMA) != 0;
 }
 
 }  // namespace
@@ -279,6 +277,12 @@ bool use_mfma(const Geom &g)
 int launch_subbit_f32(const Geom &g, const void *x, const uint16_t *codebook, const uint16_t *idx,
                       const float *alpha, float *y, void *ws, hipStream_t s, int phases);
 size_t subbit_f32_workspace_bytes(const Geom &g);
+
+int subbit_slots_per_channel(const Geom &g, int act)
+{
+    if (act == SNN_ACT_F32 || !use_mfma(g)) return 0;
+    return subbit_mfma_slots_per_channel(g);
+}
 
 size_t subbit_workspace_bytes(const Geom &g, int act)
 {

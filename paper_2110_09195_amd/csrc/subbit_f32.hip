@@ -180,10 +180,8 @@ int launch_subbit_f32(const Geom &g, const void *x, const uint16_t *codebook, co
 #define SNN_F32_CASE(J_)                                                                                       \
     case J_: {                                                                                                 \
         auto kern = subbit_f32_kernel<J_, 4>;                                                                  \
-        if (lds > 64 * 1024 &&                                                                                 \
-            hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) !=   \
-                hipSuccess)                                                                                    \
-            return SNN_ERR_LAUNCH;                                                                             \
+        static LdsGrant grant;                                                                                 \
+        if (grant_dynamic_lds((const void *)kern, lds, grant) != SNN_OK) return SNN_ERR_LAUNCH;                \
         hipLaunchKernelGGL(kern, grid, dim3(256), lds, s, (const float *)x, codes, offs, alpha, y, g, COP,     \
                            CIC);                                                                               \
     } break;

@@ -1138,9 +1138,8 @@ template <int PB, int CB, int WM, bool PAIR, bool STG, bool QUAD = false>
 int launch_mf_one(const MfPlan &pl, const MfParams &prm, hipStream_t s)
 {
     auto kern = subbit_mfma_kernel<PB, CB, WM, PAIR, STG, QUAD>;
-    if (pl.lds > 64 * 1024 &&
-        hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)pl.lds) != hipSuccess)
-        return SNN_ERR_LAUNCH;
+    static LdsGrant grant;
+    if (grant_dynamic_lds((const void *)kern, pl.lds, grant) != SNN_OK) return SNN_ERR_LAUNCH;
     hipLaunchKernelGGL(kern, dim3((unsigned)pl.n_wgs), dim3(MF_WAVES * 64), pl.lds, s, prm);
     return check_launch();
 }
@@ -1180,6 +1179,12 @@ bool subbit_mfma_supported(const Geom &g)
     const int64_t y_words = (int64_t)g.P * g.C_out;
     return g.K <= 64 && (g.K > 32 || g.C_in >= 2) && x_words < ((int64_t)1 << 30) && sel_words < ((int64_t)1 << 30) &&
            y_words < ((int64_t)1 << 30) && g.P < ((int64_t)1 << 31) - 4096;
+}
+
+int subbit_mfma_slots_per_channel(const Geom &g)
+{
+    const MfPlan pl = mf_plan(g, false);
+    return pl.quad ? 16 : pl.pair ? 32 : 64;
 }
 
 // The plain and the sign-epilogue form cut the pixels into blocks differently and may therefore split
@@ -1327,7 +1332,7 @@ int mf_many_variant(const MfPlan &pl, const Geom &g)
 
 int launch_subbit_mfma_many(int n_layers, const Geom *gs, const void *const *x, float *const *y, void *const *ws, hipStream_t s)
 {
-    static bool lds_attr_set = false;
+    static LdsGrant grant;
     MfManyParams pm;
     pm.n_layers = 0;
     int64_t blocks = 0;
@@ -1336,11 +1341,7 @@ int launch_subbit_mfma_many(int n_layers, const Geom *gs, const void *const *x, 
         if (pm.n_layers == 0) return SNN_OK;
         pm.first_block[pm.n_layers] = (int)blocks;
         for (int i = pm.n_layers + 1; i <= MF_MANY_MAX; ++i) pm.first_block[i] = (int)blocks;
-        if (lds > 64 * 1024 && !lds_attr_set) {
-            if (hipFuncSetAttribute((const void *)subbit_mfma_many_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)
-                return SNN_ERR_LAUNCH;
-            lds_attr_set = true;
-        }
+        if (grant_dynamic_lds((const void *)subbit_mfma_many_kernel, lds, grant) != SNN_OK) return SNN_ERR_LAUNCH;
         hipLaunchKernelGGL(subbit_mfma_many_kernel, dim3((unsigned)blocks), dim3(MF_WAVES * 64), lds, s, pm);
         pm.n_layers = 0;
         blocks = 0;

@@ -2,9 +2,6 @@
 // the workspace.  Shared by the translation units that launch kernels on those tables.
 #pragma once
 
-#include <stdio.h>
-#include <stdlib.h>
-
 #include "snn_internal.h"
 
 namespace snn {
@@ -40,12 +37,6 @@ struct MfPlan {
     size_t off_sched;     // two words: next work item, workers that have left; zero between launches
 };
 
-inline int env_int(const char *name, int dflt)
-{
-    const char *e = getenv(name);
-    return e ? atoi(e) : dflt;
-}
-
 // blocks of up to 32 pixels: 32 consecutive pixels each, or (sign epilogue) whole output words
 inline int64_t mf_pxblocks(const Geom &g, bool aligned)
 {
@@ -64,12 +55,7 @@ inline MfPlan mf_plan(const Geom &g, bool aligned = false, bool one = false)
     // tile of a wave: 128 accumulator registers (PB x CB = 8); few channels -> more pixels per wave
     if (g.C_out <= 64) pl.cfg = {4, 2};
     else pl.cfg = {2, 4};
-    // tuning override "PB,CB"
-    if (const char *e = getenv("SNN_MFMA_TILE")) {
-        int a = 0, b = 0;
-        if (sscanf(e, "%d,%d", &a, &b) == 2 && ((a == 4 && b == 2) || (a == 2 && b == 4) || (a == 2 && b == 2) || (a == 1 && b == 4) || (a == 1 && b == 2)))
-            pl.cfg = {a, b};
-    }
+    if (const int t = tuning(SNN_TUNE_MFMA_TILE); t > 0) pl.cfg = {t / 10, t % 10};
     const int cow = 32 * pl.cfg.CB, pxw = 32 * pl.cfg.PB;
     pl.COP = (g.C_out + cow - 1) / cow * cow;
     pl.n_cotiles = pl.COP / cow;
@@ -89,9 +75,9 @@ inline MfPlan mf_plan(const Geom &g, bool aligned = false, bool one = false)
     // Subsets of at most 16 members: four channels per step halve the matrix instructions and double the
     // window work of a step (and give up the staged rows).  Measured: a gain (1.2x) only where a wave has
     // long runs of steps - many input channels on tiles of four channel blocks - and a loss on short ones.
-    // SNN_MFMA_QUAD = 1 / 0 forces it on wherever it applies / off.
+    // The knob SNN_TUNE_MFMA_QUAD = 1 / 0 forces it on wherever it applies / off.
     if (g.K <= 16 && !one) {
-        const int quad_env = env_int("SNN_MFMA_QUAD", -1);
+        const int quad_env = tuning(SNN_TUNE_MFMA_QUAD);
         const bool pays = pl.cfg.CB == 4 && (int64_t)(pl.npairs / KS) * pl.cfg.PB * pl.cfg.CB >= 768;
         if (quad_env < 0 ? pays : quad_env != 0) {
             pl.quad = true;
@@ -99,8 +85,7 @@ inline MfPlan mf_plan(const Geom &g, bool aligned = false, bool one = false)
             KS = split_of(pl.npairs);
         }
     }
-    const int ks_env = env_int("SNN_MFMA_KS", 0);
-    if (ks_env == 1 || ks_env == 2 || ks_env == 4) KS = ks_env;
+    if (const int ks = tuning(SNN_TUNE_MFMA_KS); ks > 0) KS = ks;
     pl.KS = KS;
     pl.n_wgs = (pl.n_tiles * KS + MF_WAVES - 1) / MF_WAVES;
     // Rows a tile of pxw consecutive pixels can touch, numbered over the whole batch: a change of
@@ -110,8 +95,8 @@ inline MfPlan mf_plan(const Geom &g, bool aligned = false, bool one = false)
     const int64_t tile_rows = g.stride * row_changes + image_changes + 3;
     // Staging pays where the memory pipeline is the bound: two channel blocks per wave, i.e. only two
     // matrix instructions per window (measured; with four blocks the loop is bound by the matrix pipe
-    // and the extra LDS traffic costs a little).  SNN_MFMA_STAGE = 1 / 0 forces it on wherever it fits / off.
-    const int stage_env = env_int("SNN_MFMA_STAGE", -1);
+    // and the extra LDS traffic costs a little).  The knob SNN_TUNE_MFMA_STAGE = 1 / 0 forces it on wherever it fits / off.
+    const int stage_env = tuning(SNN_TUNE_MFMA_STAGE);
     pl.stage = !one && !pl.quad && g.WW <= 2 && tile_rows * (g.WW == 2 ? 3 : 1) <= MF_STAGE_SLOTS &&
                (stage_env < 0 ? pl.cfg.CB == 2 : stage_env != 0);
     const size_t lut_bytes = (size_t)(one ? 256 : 512) * mf_lrow(pl.pair) + (pl.stage ? (size_t)MF_WAVES * MF_STAGE_BYTES : 0);

@@ -101,3 +101,48 @@ def test_invalid_arguments_are_status_codes_not_crashes(L):
     assert ws_fwd >= ws_conv + binding.snn_packed_bytes(d.N, d.C_in, d.H, d.W, binding.SNN_ACT_BIN_ROWS)
     d.act = binding.SNN_ACT_F32
     assert binding.snn_workspace_bytes(d, binding.SNN_WS_FORWARD) == 0
+
+
+def test_tuning_knobs_and_slots(L, tune):
+    B = binding
+    for knob in range(B.SNN_TUNE_COUNT):
+        assert B.snn_get_tuning(knob) == B.SNN_TUNE_AUTO
+    assert B.snn_get_tuning(99) == B.SNN_TUNE_AUTO
+    assert L.snn_set_tuning(99, 1) == B.SNN_ERR_INVALID_ARG
+    assert L.snn_set_tuning(B.SNN_TUNE_MFMA_TILE, 33) == B.SNN_ERR_INVALID_ARG
+    assert L.snn_set_tuning(B.SNN_TUNE_MFMA_KS, 3) == B.SNN_ERR_INVALID_ARG
+    assert L.snn_set_tuning(B.SNN_TUNE_STACK, 2) == B.SNN_ERR_INVALID_ARG
+    # slots per channel of the form a layer is launched in (Sec. 4.5: the gather needs one)
+    rows = B.SNN_ACT_BIN_ROWS
+    assert B.snn_subbit_slots_per_channel(B.make_desc(64, 256, 256, 14, 14, 1, 32, rows)) == 32
+    assert B.snn_subbit_slots_per_channel(B.make_desc(64, 256, 256, 14, 14, 1, 64, rows)) == 64
+    assert B.snn_subbit_slots_per_channel(B.make_desc(64, 256, 256, 14, 14, 1, 512, rows)) == 0
+    assert B.snn_subbit_slots_per_channel(B.make_desc(64, 1, 256, 14, 14, 1, 32, rows)) == 0
+    assert B.snn_subbit_slots_per_channel(B.make_desc(64, 64, 64, 8, 8, 1, 32, B.SNN_ACT_F32)) == 0
+    assert B.snn_subbit_slots_per_channel(B.make_desc(256, 512, 512, 7, 7, 1, 16, rows)) == 16   # long channel runs
+    assert B.snn_subbit_slots_per_channel(B.make_desc(64, 64, 64, 56, 56, 1, 16, rows)) == 32
+    tune("MFMA_QUAD", 0)
+    assert B.snn_get_tuning(B.SNN_TUNE_MFMA_QUAD) == 0
+    assert B.snn_subbit_slots_per_channel(B.make_desc(256, 512, 512, 7, 7, 1, 16, rows)) == 32
+    tune("SUBBIT_MFMA", 0)
+    assert B.snn_subbit_slots_per_channel(B.make_desc(64, 256, 256, 14, 14, 1, 32, rows)) == 0
+    bad = B.make_desc(64, 256, 256, 14, 14, 1, 32, rows)
+    bad.stride = 3
+    assert L.snn_subbit_slots_per_channel(ctypes.byref(bad)) == B.SNN_ERR_INVALID_ARG
+
+
+def test_workspace_covers_both_pixel_block_forms(L, tune):
+    """The plain and the sign-epilogue calls cut the pixels differently and can pick different table layouts
+    (four channels per step only in one of them): the reported size is the larger of the two.  Shapes on which
+    the two differ, with the byte counts of the larger layout worked out by hand: selector rows of
+    ceil(C_in / 4) * 4 * COP words + finishing table + table image + the stack kernel's tables."""
+    B = binding
+    for N, C_in in ((112, 386), (224, 258)):
+        d = B.make_desc(N, C_in, 256, 14, 14, 1, 16, B.SNN_ACT_BIN_ROWS)
+        COP = 256
+        sel = (C_in + 3) // 4 * 4 * COP * 4
+        assert B.snn_workspace_bytes(d, B.SNN_WS_SUBBIT) >= sel + COP * 16 * 8 + 512 * 48
+        tune("MFMA_QUAD", 0)
+        smaller = B.snn_workspace_bytes(d, B.SNN_WS_SUBBIT)
+        tune("MFMA_QUAD", B.SNN_TUNE_AUTO)
+        assert smaller < B.snn_workspace_bytes(d, B.SNN_WS_SUBBIT)

@@ -45,7 +45,7 @@ def test_params_columns(row):
     if bits == "1bit":
         total = sum(accounting.storage_bits(l) for l in layers)
     else:
-        # the tables ignore the 9 * 2^tau subset bits ("can be ignored as it is shared per layer")
+        # Sec. 4.4: the 9 * 2^tau subset bits of a layer are left out of #Params
         total = sum(accounting.storage_bits(l, int(bits)) - 9 * (1 << int(bits)) for l in layers)
     assert abs(total / 1e6 - float(value)) <= 0.006 * max(1.0, float(value) / 10), (total / 1e6, value)
 

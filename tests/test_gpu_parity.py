@@ -88,12 +88,12 @@ DENSE_CASES = BNN_CASES + [(4, 64, 64, 56, 56, 1), (4, 128, 128, 28, 28, 2), (2,
 
 @pytest.mark.parametrize("tile", [None, 0, 1, 2, 3])
 @pytest.mark.parametrize("case", DENSE_CASES)
-def test_bnn_dense(oracle, case, tile, monkeypatch):
+def test_bnn_dense(oracle, case, tile, tune):
     if tile is not None and case in BNN_CASES[:8]:
         pytest.skip("tile shapes are swept on the larger cases")
     _say("bnn_dense", (case, tile))
     if tile is not None:
-        monkeypatch.setenv("SNN_DENSE_TILE", str(tile))
+        tune("DENSE_TILE", tile)
     N, C_in, C_out, H, W, stride = case
     g = np.random.default_rng(sum(case) + 7)
     x = g.standard_normal((N, C_in, H, W), dtype=np.float32)
@@ -170,16 +170,16 @@ def test_subbit_bin(oracle, case):
 @pytest.mark.parametrize("tile", ["4,2", "2,4", "2,2", "1,4", "1,2"])
 @pytest.mark.parametrize("split", [1, 2, 4])
 @pytest.mark.parametrize("stage", [1, 0])
-def test_subbit_bin_matrix_core_kernel_every_tile_and_split(oracle, tile, split, stage, monkeypatch):
+def test_subbit_bin_matrix_core_kernel_every_tile_and_split(oracle, tile, split, stage, tune):
     """Every instantiated wave tile of the matrix-core kernel and every split of the input
     channels over waves, forced on layers with ragged edges: odd and even C_in, C_out not a
     multiple of 32, rows of one, two and three packed words, both strides, a pixel tail, tiles
     that run over several small images, and both forms of a step (two channels of K <= 32
     members, one channel of K <= 64).  stage = 1 lets the kernel stage a tile's rows through LDS
     wherever they fit (rows of one or two words), stage = 0 makes every lane load its own rows."""
-    monkeypatch.setenv("SNN_MFMA_TILE", tile)
-    monkeypatch.setenv("SNN_MFMA_KS", str(split))
-    monkeypatch.setenv("SNN_MFMA_STAGE", str(stage))
+    tune("MFMA_TILE", tile)
+    tune("MFMA_KS", split)
+    tune("MFMA_STAGE", stage)
     for seed, (N, C_in, C_out, H, W, stride, K) in enumerate([(3, 45, 150, 13, 11, 1, 32), (2, 20, 70, 16, 12, 2, 32),
                                                              (2, 34, 40, 9, 40, 1, 20), (1, 8, 33, 5, 70, 1, 32),
                                                              (2, 130, 96, 8, 8, 2, 7), (1, 2, 3, 1, 1, 1, 2),
@@ -201,13 +201,13 @@ QUAD_LAYERS = [(3, 45, 150, 13, 11, 1, 16), (2, 20, 70, 16, 12, 2, 9), (2, 34, 4
 
 @pytest.mark.parametrize("tile", ["4,2", "2,4", "2,2", "1,4", "1,2"])
 @pytest.mark.parametrize("split", [1, 2, 4])
-def test_subbit_bin_four_channels_per_step(oracle, tile, split, monkeypatch):
+def test_subbit_bin_four_channels_per_step(oracle, tile, split, tune):
     """Subsets of at most 16 members with four input channels per matrix instruction, forced on (the
     library itself selects that form only for long layers): every tile and split, channel counts that
     are not multiples of four, rows of one, two and three words, both strides."""
-    monkeypatch.setenv("SNN_MFMA_TILE", tile)
-    monkeypatch.setenv("SNN_MFMA_KS", str(split))
-    monkeypatch.setenv("SNN_MFMA_QUAD", "1")
+    tune("MFMA_TILE", tile)
+    tune("MFMA_KS", split)
+    tune("MFMA_QUAD", "1")
     for seed, (N, C_in, C_out, H, W, stride, K) in enumerate(QUAD_LAYERS):
         _say("subbit_bin four channels", tile, split, (N, C_in, C_out, H, W, stride, K))
         x, cb, idx, alpha = _inputs(1900 + seed, N, C_in, C_out, H, W, K)
@@ -217,11 +217,11 @@ def test_subbit_bin_four_channels_per_step(oracle, tile, split, monkeypatch):
 
 
 @pytest.mark.parametrize("quad", ["1", "0"])
-def test_four_channels_per_step_forward_sign_and_prepared(oracle, quad, monkeypatch):
+def test_four_channels_per_step_forward_sign_and_prepared(oracle, quad, tune):
     """The other entry points on the same form: the one-call forward (its front kernel writes the
     selectors), the sign epilogue, and prepare + prepared convolution; quad = 0 is the same run with
     the form switched off."""
-    monkeypatch.setenv("SNN_MFMA_QUAD", quad)
+    tune("MFMA_QUAD", quad)
     for seed, (N, C_in, C_out, H, W, stride, K) in enumerate(QUAD_LAYERS[:5] + QUAD_LAYERS[9:]):
         _say("four channels: forward / sign / prepared", quad, (N, C_in, C_out, H, W, stride, K))
         g = np.random.default_rng(2900 + seed)
@@ -280,12 +280,12 @@ def test_dense_prepared_weights_are_reused(oracle):
 
 
 @pytest.mark.parametrize("case", SUBBIT_CASES)
-def test_subbit_bin_fallback_kernel(oracle, case, monkeypatch):
-    """With the matrix-core kernel switched off (a tuning override, read at every call) every
+def test_subbit_bin_fallback_kernel(oracle, case, tune):
+    """With the matrix-core kernel switched off (a tuning knob) every
     case runs through the fallback kernel that otherwise only sees K > 64 and single-channel
     layers."""
     _say("subbit_bin fallback", case)
-    monkeypatch.setenv("SNN_SUBBIT_MFMA", "0")
+    tune("SUBBIT_MFMA", "0")
     N, C_in, C_out, H, W, stride, K, dist = case
     x, cb, idx, alpha = _inputs(sum(case[:7]), N, C_in, C_out, H, W, K, dist)
     _, Y = oracle.conv_bin(oracle.sign(x), oracle.expand(cb, idx), alpha, stride)
@@ -491,12 +491,12 @@ def _latent_kernels(g, cb, C_out, C_in, dist):
 
 @pytest.mark.parametrize("case", FORWARD_CASES)
 @pytest.mark.parametrize("mfma", ["1", "0"])
-def test_subbit_forward(oracle, case, mfma, monkeypatch):
+def test_subbit_forward(oracle, case, mfma, tune):
     """snn_subbit_forward against the oracle's three steps (project, sign, direct convolution with
     the decoded kernels): indices and outputs bit-exact.  mfma = 0 routes every case through the
     path that launches the three operations one after the other."""
     _say("subbit_forward", case, mfma)
-    monkeypatch.setenv("SNN_SUBBIT_MFMA", mfma)
+    tune("SUBBIT_MFMA", mfma)
     N, C_in, C_out, H, W, stride, K, dist = case
     g = np.random.default_rng(4000 + sum(case[:7]))
     x = g.standard_normal((N, C_in, H, W), dtype=np.float32)
@@ -575,9 +575,9 @@ def test_subbit_conv2d_sign(oracle, case):
 
 @pytest.mark.parametrize("tile", ["4,2", "2,4", "2,2", "1,4", "1,2"])
 @pytest.mark.parametrize("split", [1, 2, 4])
-def test_subbit_conv2d_sign_every_tile_and_split(oracle, tile, split, monkeypatch):
-    monkeypatch.setenv("SNN_MFMA_TILE", tile)
-    monkeypatch.setenv("SNN_MFMA_KS", str(split))
+def test_subbit_conv2d_sign_every_tile_and_split(oracle, tile, split, tune):
+    tune("MFMA_TILE", tile)
+    tune("MFMA_KS", split)
     for seed, (N, C_in, C_out, H, W, stride, K) in enumerate([(3, 45, 150, 13, 11, 1, 32), (2, 20, 70, 16, 12, 2, 32),
                                                              (2, 34, 40, 9, 40, 1, 20), (1, 8, 33, 5, 70, 1, 32),
                                                              (9, 6, 40, 5, 5, 1, 32), (2, 6, 40, 12, 56, 1, 32),
@@ -695,11 +695,11 @@ def test_subbit_forward_sign_chain(oracle):
 @pytest.mark.parametrize("tile", [None, 0, 1, 4])
 @pytest.mark.parametrize("case", [c for c in FORWARD_CASES if c[1] > 1][:12] + [(2, 96, 130, 9, 11, 1, 32, "uniform"),
                                                                               (3, 64, 33, 7, 7, 2, 16, "uniform")])
-def test_dense_conv2d_sign(oracle, case, tile, monkeypatch):
+def test_dense_conv2d_sign(oracle, case, tile, tune):
     """The dense contraction ending in the next layer's sign: packed channels in and out."""
     _say("dense_conv2d_sign", (case, tile))
     if tile is not None:
-        monkeypatch.setenv("SNN_DENSE_TILE", str(tile))
+        tune("DENSE_TILE", tile)
     N, C_in, C_out, H, W, stride, K, dist = case
     x, cb, idx, alpha = _inputs(7100 + sum(case[:7]), N, C_in, C_out, H, W, K, dist)
     g = np.random.default_rng(7101 + sum(case[:7]))
@@ -835,9 +835,9 @@ def test_subbit_conv1x1(oracle, case):
 
 @pytest.mark.parametrize("tile", ["4,2", "2,4", "2,2", "1,4", "1,2"])
 @pytest.mark.parametrize("split", [1, 2, 4])
-def test_subbit_conv1x1_every_tile_and_split(oracle, tile, split, monkeypatch):
-    monkeypatch.setenv("SNN_MFMA_TILE", tile)
-    monkeypatch.setenv("SNN_MFMA_KS", str(split))
+def test_subbit_conv1x1_every_tile_and_split(oracle, tile, split, tune):
+    tune("MFMA_TILE", tile)
+    tune("MFMA_KS", split)
     for case in [(3, 88, 150, 13, 11, 1, 32), (2, 40, 70, 16, 12, 2, 32), (1, 56, 33, 5, 70, 1, 64), (2, 264, 40, 5, 5, 1, 7)]:
         N, C_in, C_out, H, W, stride, K = case
         _say("subbit_conv1x1", tile, split, case)

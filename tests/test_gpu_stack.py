@@ -60,7 +60,11 @@ FORMS = [
 ]
 
 
-def test_many_every_form_in_one_call(oracle):
+@pytest.mark.parametrize("stack", [None, 0])
+def test_many_every_form_in_one_call(oracle, stack, tune):
+    """stack = 0: the launch with one workgroup per group of tiles instead of resident workers."""
+    if stack is not None:
+        tune("STACK", stack)
     layers = [_make(oracle, i, *c) for i, c in enumerate(FORMS)]
     io = B.layer_io_array(layers)
     for rep in range(3):             # the work counter is left at zero by every launch
@@ -79,7 +83,10 @@ def test_many_single_layer(oracle, case):
     _check(layers, "single layer")
 
 
-def test_many_more_layers_than_one_launch_holds(oracle):
+@pytest.mark.parametrize("stack", [None, 0])
+def test_many_more_layers_than_one_launch_holds(oracle, stack, tune):
+    if stack is not None:
+        tune("STACK", stack)
     cases = [(1, 4 + 2 * i, 8 + 8 * (i % 5), 5 + i % 3, 6 + i % 4, 1 + i % 2, 32) for i in range(19)]
     layers = [_make(oracle, 100 + i, *c) for i, c in enumerate(cases)]
     _say("many: 19 layers")
