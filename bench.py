@@ -1,26 +1,33 @@
 #!/usr/bin/env python3
 """Benchmark of the sub-bit 3x3 convolution path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload resnet18|cfg3|cfg4] [--no-cpu]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload resnet18|cfg1|cfg3|cfg4] [--no-cpu]
+                    [--headline-only] [--no-configs] [--no-traffic]
 
-One "step" is one pass of the whole path over one batch of synthetic input, i.e. the forward
-lines of Alg. 1 for every 3x3 layer of the workload: project the real-valued kernels onto the
-layer's subset (all layers in one launch, snn_subbit_project_prepare_many), then per layer
-binarise and pack the activations and run the sub-bit convolution (stage 1, stage 2, alpha
-scaling).  The same work as one snn_subbit_forward call per layer and through the three
-separate entry points (snn_project_kernels, snn_pack_activations, snn_subbit_conv2d) is timed
-next to it.  Inputs are resident in HBM before the timed region.  The same layers are
-then run through the library's 1-bit XNOR/popcount kernel (snn_bnn_conv2d on the decoded
-kernels) for the speed-up.
+One "step" is one pass of the whole path over one batch of synthetic input, i.e. the forward lines of
+Alg. 1 for every 3x3 layer of the workload:
+  * project the real-valued kernels of all layers onto their subsets and build the convolution's tables
+    (Eq. 2 / Eq. 5; one launch, snn_subbit_project_prepare_many),
+  * binarise and pack each layer's fp32 input (snn_pack_activations, one launch per layer),
+  * the sub-bit convolutions of all layers (Sec. 4.5: stage 1, stage 2, alpha scaling; one launch,
+    snn_subbit_conv2d_prepared_many).
+Inputs are resident in HBM before the timed region.  The same layers then run through the library's 1-bit
+XNOR/popcount kernel (snn_bnn_conv2d on the decoded kernels) for the speed-up.
 
-Prints ONE JSON line (metric of the benchmark spec: GOPS-equivalent of the dense convolution the
-layers equal, plus the speed-up over the 1-bit kernel), with a `roofline` object for the
-dominant kernel and a `cpu_baseline` object (the CPU oracle timed on a bounded sample).
-Per-layer detail goes to stderr.
+Prints ONE JSON line: the metric (GOPS-equivalent of the dense convolutions the layers equal, plus the speed-up
+over the 1-bit kernel), a `roofline` object for the convolution launch (algorithmic bytes, gather-adds and
+responses of Sec. 4.5, the one-hot slots the kernel spends per gather as launched, fractions against the vendor
+peaks and against peaks measured in this run by the probes of include/snn_peaks.h, HBM traffic from two
+rocprofv3 counter passes this script starts before it touches the GPU), a `configs` array (the other four
+workloads, each with its oracle check and a cold-cache series) and `cpu_baseline` (the CPU oracle timed on
+a bounded sample).  Per-layer detail goes to stderr.
 """
 import argparse
+import csv
 import json
 import os
+import shutil
+import subprocess
 import sys
 import time
 
@@ -28,14 +35,15 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-# MI355X: 256 CUs x 4 SIMD x 16 lanes x 2.4 GHz plain 32-bit VALU operations per second
-# (= the 157.3 TFLOP/s fp32 vector peak / 2 for FMA / 2 for the packed form).
-VALU_PEAK_LANE_OPS = 256 * 4 * 16 * 2.4e9
-# LDS: 128 bytes per clock per CU.
-LDS_PEAK_BYTES = 256 * 128 * 2.4e9
+# Vendor peaks of MI355X.
 HBM_PEAK_BYTES = 8.0e12
-# Dense matrix-core peak for FP6 / FP4 operands (the sub-bit kernel's v_mfma_scale_f32_32x32x64_f8f6f4).
-MFMA_FP6_FP4_PEAK_FLOPS = 10.1e15
+MFMA_FP6_FP4_PEAK_FLOPS = 10.1e15          # dense FP6 / FP4 operands (v_mfma_scale_f32_32x32x64_f8f6f4)
+# 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz plain 32-bit VALU operations per second (= the 157.3 TFLOP/s fp32
+# vector peak / 2 for FMA / 2 for the packed form)
+VALU_PEAK_LANE_OPS = 256 * 4 * 16 * 2.4e9
+MFMA_FLOP_32x32x64 = 2 * 32 * 32 * 64
+
+COPY_CAL_BYTES = 256 * 1024 * 1024           # the copy probe of the counter passes reads and writes this much
 
 
 def parse():
@@ -46,41 +54,491 @@ def parse():
     ap.add_argument("--workload", default="resnet18", choices=["resnet18", "cfg3", "cfg4", "cfg1"])
     ap.add_argument("--K", type=int, default=32)
     ap.add_argument("--layer", default=None, help="one custom layer instead of a workload: N,C_in,C_out,H,W,stride")
-    ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg and the oracle checks")
     ap.add_argument("--headline-only", action="store_true",
-                    help="skip the chained 1-bit stack and the training-side timings (profiling runs: every launch of a "
-                         "kernel then belongs to the headline path or to the 1-bit baseline)")
-    ap.add_argument("--calibrate-copy", action="store_true",
-                    help="also run a plain 256 MiB elementwise copy kernel once (reference for the HBM byte counters)")
+                    help="only the step, the 1-bit baseline and the per-kernel timings of the workload (profiling "
+                         "runs: no chained stack, dense context, training-side or 1x1 timings, no configs, no traffic)")
+    ap.add_argument("--no-configs", action="store_true", help="skip the `configs` array (workloads 1-4)")
+    ap.add_argument("--no-traffic", action="store_true", help="do not start the two rocprofv3 counter passes")
+    ap.add_argument("--counter-child", action="store_true",
+                    help="(internal) the program the counter passes profile: one copy probe of known size, then three "
+                         "launches of the workload's convolutions")
     return ap.parse_args()
 
 
-def _measured_traffic(args):
-    """HBM bytes per step of the sub-bit kernels from the committed rocprofv3 --pmc passes
-    (FETCH_SIZE + WRITE_SIZE, scaled by a plain copy kernel; profiles/subbit_stack_resnet18_b64_hbm_traffic.txt).
-    Only for the workload they were taken on; None otherwise."""
-    path = os.path.join(ROOT, "profiles", "subbit_stack_resnet18_b64_hbm_traffic.txt")
-    if args.layer or args.workload != "resnet18" or args.K != 32 or not os.path.exists(path):
-        return None
+# ---------------------------------------------------------------------------------------------------------------------
+# HBM traffic: two rocprofv3 --pmc passes over this script's --counter-child mode, started before the GPU is touched
+# ---------------------------------------------------------------------------------------------------------------------
+
+def _pmc_pass(counter, args, outdir):
+    """One rocprofv3 pass; returns {kernel name: [KiB readings]} for `counter`, or raises."""
+    rocprof = shutil.which("rocprofv3") or "/opt/rocm/bin/rocprofv3"
+    if not os.path.exists(rocprof):
+        raise RuntimeError("rocprofv3 not found")
+    if os.path.isdir(outdir):
+        shutil.rmtree(outdir)
+    os.makedirs(outdir)
+    child = [sys.executable, os.path.join(ROOT, "bench.py"), "--counter-child", "--workload", args.workload, "--K", str(args.K)]
+    if args.layer:
+        child += ["--layer", args.layer]
+    cmd = [rocprof, "--pmc", counter, "-d", outdir, "-o", "pass", "--output-format", "csv", "--"] + child
+    env = dict(os.environ, TMPDIR="/tmp")
+    r = subprocess.run(cmd, cwd="/tmp", env=env, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, timeout=150)
+    if r.returncode != 0:
+        raise RuntimeError("rocprofv3 --pmc %s ended with status %d: %s" % (counter, r.returncode, r.stdout.decode(errors="replace")[-400:]))
+    found = None
+    for base, _, files in os.walk(outdir):
+        for f in files:
+            if f.endswith("counter_collection.csv"):
+                found = os.path.join(base, f)
+    if not found:
+        raise RuntimeError("no counter_collection.csv under " + outdir)
+    per = {}
+    with open(found) as fh:
+        for row in csv.DictReader(fh):
+            if row["Counter_Name"] == counter:
+                per.setdefault(row["Kernel_Name"], []).append(float(row["Counter_Value"]))
+    return per
+
+
+def measure_traffic(args):
+    """HBM bytes of one convolution launch: FETCH_SIZE and WRITE_SIZE (KiB per dispatch), each scaled by what the same
+    counter reads for the copy probe (COPY_CAL_BYTES read, COPY_CAL_BYTES written).  None (and the reason on stderr)
+    if the passes cannot run."""
+    out_root = os.path.join(ROOT, "gpurun_out", "bench_pmc")
     try:
-        with open(path) as f:
-            d = json.loads("".join(l for l in f if not l.startswith("#")))
-        return {"bytes": d["bytes"], "fetch_bytes": d["fetch_bytes"], "write_bytes": d["write_bytes"],
-                "unit": "HBM bytes per step, all 16 launches (rocprofv3 FETCH_SIZE/WRITE_SIZE, copy-kernel scaled)"}
-    except (OSError, ValueError, KeyError):
+        res = {}
+        for counter in ("FETCH_SIZE", "WRITE_SIZE"):
+            per = _pmc_pass(counter, args, os.path.join(out_root, counter.lower()))
+            cal = [v for k, vs in per.items() if "copy_kernel" in k for v in vs]
+            conv = [v for k, vs in per.items() if "subbit_stack_kernel" in k or "subbit_mfma" in k for v in vs]
+            if not cal or not conv:
+                raise RuntimeError("kernels missing from the %s pass: %s" % (counter, sorted(per)))
+            scale = COPY_CAL_BYTES / (sum(cal) / len(cal) * 1024.0)
+            launches = 3
+            # a workload the stack kernel does not hold runs as several launches per call: sum per call
+            per_call = sum(conv) / launches
+            res[counter] = {"bytes": per_call * 1024.0 * scale, "scale": scale, "dispatches": len(conv)}
+        f, w = res["FETCH_SIZE"], res["WRITE_SIZE"]
+        return {"bytes": f["bytes"] + w["bytes"], "fetch_bytes": f["bytes"], "write_bytes": w["bytes"],
+                "fetch_scale": f["scale"], "write_scale": w["scale"],
+                "unit": "HBM bytes per convolution launch (rocprofv3 --pmc FETCH_SIZE, then WRITE_SIZE, KiB per dispatch, "
+                        "each scaled by the same counter's reading for a copy kernel that reads and writes 256 MiB)"}
+    except Exception as e:                                      # noqa: BLE001 - any failure means "not measured"
+        print("bench.py: HBM traffic not measured: %s" % e, file=sys.stderr)
         return None
 
 
-def dense_ops_of(layers):
-    return sum(L.dense_ops for L in layers)
+# ---------------------------------------------------------------------------------------------------------------------
+# helpers (torch is imported in main: the counter passes start first)
+# ---------------------------------------------------------------------------------------------------------------------
+
+def workload_of(args, synth):
+    if args.layer:
+        N, Ci, Co, H, W, st_ = [int(v) for v in args.layer.split(",")]
+        return ([synth.Layer("custom", N=N, C_in=Ci, C_out=Co, H=H, W=W, stride=st_, K=args.K)],
+                "custom layer %s, K=%d" % (args.layer, args.K), 9)
+    if args.workload == "resnet18":
+        return (synth.resnet18_stack(N=64, K=args.K),
+                "ResNet-18 3x3 conv stack (16 layers), batch 64, 224x224 shapes, binary activations, K=%d" % args.K, 5)
+    if args.workload == "cfg3":
+        return [synth.CFG3], "ResNet-18 stage-3 layer, batch 128, 256->256, 14x14, K=32, Zipf indices", 3
+    if args.workload == "cfg4":
+        return [synth.cfg4(args.K)], "ResNet-34 stage-4 layer, batch 256, 512->512, 7x7, K=%d" % args.K, 4
+    return [synth.CFG1], "ResNet-20 stage-1 layer, batch 8, 16->16, 32x32, K=32", 1
+
+
+class Bench:
+    """Timing helpers bound to torch and the binding."""
+
+    def __init__(self, torch, B, np, synth):
+        self.torch, self.B, self.np, self.synth = torch, B, np, synth
+        self._evict = None
+
+    def dev(self, a):
+        a = self.np.ascontiguousarray(a)
+        if a.dtype == self.np.uint16:
+            a = a.view(self.np.int16)
+        return self.torch.from_numpy(a).cuda()
+
+    def host_ms(self, fn, warmup, steps):
+        """Exactly `steps` calls between two synchronisations, wall clock."""
+        torch = self.torch
+        for _ in range(warmup):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / steps
+
+    def event_avg_us(self, fn, reps):
+        """`reps` launches back to back between one pair of events on the launch stream: microseconds per launch."""
+        torch = self.torch
+        fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e3 / reps
+
+    def event_each_us(self, fn, reps, before=None):
+        """One pair of events per launch, `before()` (untimed) ahead of each: sorted microseconds."""
+        torch = self.torch
+        fn()
+        torch.cuda.synchronize()
+        e0 = [torch.cuda.Event(enable_timing=True) for _ in range(reps)]
+        e1 = [torch.cuda.Event(enable_timing=True) for _ in range(reps)]
+        for r in range(reps):
+            if before is not None:
+                before()
+            e0[r].record()
+            fn()
+            e1[r].record()
+        torch.cuda.synchronize()
+        return sorted(a.elapsed_time(b) * 1e3 for a, b in zip(e0, e1))
+
+    def evict(self):
+        """512 MB written between launches: more than L2 and the memory-side cache hold."""
+        if self._evict is None:
+            self._evict = self.torch.empty(512 * 1024 * 1024, dtype=self.torch.uint8, device="cuda")
+        self._evict.fill_(1)
+
+    def cold_us(self, fn, reps=7):
+        ts = self.event_each_us(fn, reps, before=self.evict)
+        return ts[len(ts) // 2]
+
+    def layer_state(self, L, g, zipf_w=False, extra=()):
+        """Resident tensors of one layer: fp32 input, subset, real-valued kernels, alpha, buffers, workspaces."""
+        torch, B, np, synth = self.torch, self.B, self.np, self.synth
+        s = {"L": L}
+        s["x"] = self.dev(synth.activations(g, L.N, L.C_in, L.H, L.W))
+        s["cb"] = self.dev(synth.codebook(g, L.K))
+        if zipf_w:
+            # Zipf-skewed indices: the real-valued kernels are drawn around the subset members that skewed indices
+            # name, so that the projection reproduces a skewed index map
+            idx0 = synth.indices(g, L.C_out, L.C_in, L.K, "zipf")
+            cbh = s["cb"].cpu().numpy().view(np.uint16)
+            members = np.array([[1.0 if (int(c) >> (8 - t)) & 1 else -1.0 for t in range(9)] for c in cbh], dtype=np.float32)
+            w = members[idx0.reshape(-1)] + 0.3 * synth.real_kernels(g, L.C_out * L.C_in)
+        else:
+            w = synth.real_kernels(g, L.C_out * L.C_in)
+        s["w"] = self.dev(w.astype(np.float32))
+        s["alpha"] = self.dev(synth.alpha(g, L.C_out))
+        s["idx"] = torch.empty(L.C_out * L.C_in, dtype=torch.int16, device="cuda")
+        s["d_sub"] = B.make_desc(L.N, L.C_in, L.C_out, L.H, L.W, L.stride, L.K, B.SNN_ACT_BIN_ROWS)
+        s["d_bnn"] = B.make_desc(L.N, L.C_in, L.C_out, L.H, L.W, L.stride, 512, B.SNN_ACT_BIN_CHANNELS)
+        s["xr"] = torch.empty(B.snn_packed_bytes(L.N, L.C_in, L.H, L.W, B.SNN_ACT_BIN_ROWS) // 4, dtype=torch.int32, device="cuda")
+        s["xc"] = torch.empty(B.snn_packed_bytes(L.N, L.C_in, L.H, L.W, B.SNN_ACT_BIN_CHANNELS) // 4, dtype=torch.int32, device="cuda")
+        s["y"] = torch.empty((L.N, L.C_out, L.H_out, L.W_out), dtype=torch.float32, device="cuda")
+        s["yb"] = torch.empty_like(s["y"])
+        s["ws_sub"] = B.alloc_workspace(s["d_sub"], B.SNN_WS_SUBBIT)
+        s["ws_bnn"] = B.alloc_workspace(s["d_bnn"], B.SNN_WS_BNN)
+        if "forward" in extra:
+            s["ws_fwd"] = B.alloc_workspace(s["d_sub"], B.SNN_WS_FORWARD)
+        if "dense" in extra:
+            s["d_dense"] = B.make_desc(L.N, L.C_in, L.C_out, L.H, L.W, L.stride, L.K, B.SNN_ACT_BIN_CHANNELS)
+            s["ws_dense"] = B.alloc_workspace(s["d_dense"], B.SNN_WS_BNN_DENSE)
+        return s
+
+
+def measured_peaks(torch, np):
+    """The yardsticks of the roofline, from the probes of include/snn_peaks.h (median of 5 launches each)."""
+    from paper_2110_09195_amd import peaks as P
+
+    def timed(fn, reps=5):
+        fn()
+        torch.cuda.synchronize()
+        ts = []
+        for _ in range(reps):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            fn()
+            e1.record()
+            torch.cuda.synchronize()
+            ts.append(e0.elapsed_time(e1) * 1e-3)
+        return sorted(ts)[len(ts) // 2]
+
+    out = {}
+    a = torch.zeros(COPY_CAL_BYTES // 4, dtype=torch.int32, device="cuda")
+    b = torch.empty_like(a)
+    out["hbm_copy_GBps"] = 2 * COPY_CAL_BYTES / timed(lambda: P.copy(b, a)) / 1e9
+    out["hbm_write_GBps"] = COPY_CAL_BYTES / timed(lambda: P.fill(b, 0)) / 1e9
+    out["hbm_write_nontemporal_GBps"] = COPY_CAL_BYTES / timed(lambda: P.fill(b, 1)) / 1e9
+    del a, b
+    o = torch.empty(2048 * 320, dtype=torch.float32, device="cuda")
+    ops = [0]
+
+    def valu():
+        ops[0] = P.valu_xor_bcnt(o, 2000, 2048)
+    t = timed(valu)
+    out["valu_xor_bcnt_T_lane_ops"] = ops[0] / t / 1e12
+    names = {0: "random", 1: "onehot_x_counts", 2: "zeros"}
+    blocks, iters = 512, 4000
+    for pattern in (0, 1, 2):
+        n = [0]
+
+        def mf():
+            n[0] = P.mfma_f4f6(o, 0, pattern, iters, blocks)
+        t = timed(mf, 3)
+        clk = o[blocks * 256: blocks * 256 + blocks * 4].view(torch.int64).cpu().numpy().reshape(blocks, 2)
+        mhz = clk[:, 0] / (clk[:, 1] / 100e6) / 1e6
+        out["mfma_f4f6_%s_TFLOPs" % names[pattern]] = n[0] * MFMA_FLOP_32x32x64 / t / 1e12
+        out["mfma_f4f6_%s_shader_MHz" % names[pattern]] = float(np.median(mhz))
+        out["mfma_f4f6_%s_shader_clk_per_instr" % names[pattern]] = float(np.median(clk[:, 0]) / (iters * 8.0))
+    # candidate form of stage 2 without the matrix cores (byte-SWAR adds under wave-uniform register indices)
+    n_ci = 28 * 64
+    rng = np.random.default_rng(1)
+    idx_h = np.zeros(n_ci * 64 + 48, dtype=np.uint32)
+    idx_h[:n_ci * 64] = rng.integers(0, 32, n_ci * 64)
+    idx = torch.from_numpy(idx_h.view(np.int32)).cuda()
+    so = torch.zeros(2048 * 256, dtype=torch.int32, device="cuda")
+    g = [0]
+
+    def swar():
+        g[0] = P.swar_gather(so, idx, n_ci, 2048)
+    t = timed(swar, 3)
+    want = int(4 * np.array([(7 * k + 3) % 10 for k in range(32)])[idx_h[:n_ci * 64]].sum())
+    out["swar_gather_T_gather_adds"] = g[0] / t / 1e12
+    out["swar_gather_result_ok"] = bool((so.cpu().numpy() == want).all())
+    out["onehot_mfma_T_gather_adds_at_32_slots"] = out["mfma_f4f6_onehot_x_counts_TFLOPs"] / 64.0
+    out["note"] = ("probes of include/snn_peaks.h, median of 3-5 launches in this run; mfma: 512 workgroups x 4 waves x 8 "
+                   "independent accumulator sets, three operand patterns (the matrix cores' clock depends on the data)")
+    return out
+
+
+def conv_roofline(layers, slots, t_s, peaks, accounting):
+    """The roofline object of a sub-bit convolution launch (or of the launches of a list of layers): Sec. 4.5's own
+    units, the unit the kernel spends per gather as launched, fractions against vendor and measured peaks."""
+    gather_adds = sum(accounting.stage2_gather_adds(L) for L in layers)
+    responses = sum(accounting.stage1_responses(L) for L in layers)
+    out_bytes = sum(L.pixels * L.C_out * 4 for L in layers)
+    in_bytes = sum(L.N * L.C_in * L.H * ((L.W + 31) // 32) * 4 for L in layers)
+    idx_bytes = sum(L.C_in * L.C_out * 2 for L in layers)
+    alg_bytes = float(out_bytes + in_bytes + idx_bytes)
+    # flops the matrix cores execute for stage 2 as launched: 2 * slots per (pixel, c_out, c_in), channel counts
+    # rounded up to what one instruction holds (2 channels at 32 slots, 4 at 16, 1 at 64)
+    flops = 0.0
+    for L, sl in zip(layers, slots):
+        per_instr = 64 // sl
+        ci = (L.C_in + per_instr - 1) // per_instr * per_instr
+        flops += 2.0 * sl * L.pixels * L.C_out * ci
+    t_hbm = alg_bytes / HBM_PEAK_BYTES
+    t_unit = flops / MFMA_FP6_FP4_PEAK_FLOPS
+    r = {
+        "bound": "mfma" if t_unit >= t_hbm else "hbm",
+        "alg_bytes": alg_bytes, "alg_bytes_split": {"in_packed": in_bytes, "out_f32": out_bytes, "idx_u16": idx_bytes},
+        "gather_adds": gather_adds, "responses": responses,
+        "unit_used": "contraction slots of v_mfma_scale_f32_32x32x64_f8f6f4 (FP4 one-hot selector x FP6 match counts, fp32 "
+                     "accumulators): stage 1 is a table row per window (no arithmetic), stage 2 spends `slots_per_channel` "
+                     "multiply-adds per gather-add, of which one is not a multiplication by zero",
+        "slots_per_channel": sorted(set(slots)) if len(set(slots)) > 1 else slots[0],
+        "unit_flops_as_launched": flops,
+        "t_kernel_us": t_s * 1e6,
+        "t_floor_hbm_us": t_hbm * 1e6, "t_floor_unit_us": t_unit * 1e6,
+        "achieved": (flops / t_s / 1e12) if t_unit >= t_hbm else (alg_bytes / t_s / 1e9),
+        "peak": (MFMA_FP6_FP4_PEAK_FLOPS / 1e12) if t_unit >= t_hbm else (HBM_PEAK_BYTES / 1e9),
+        "unit": "TFLOP/s" if t_unit >= t_hbm else "GB/s",
+        "frac": max(t_hbm, t_unit) / t_s,
+        "frac_hbm": t_hbm / t_s, "frac_unit": t_unit / t_s,
+        "useful_frac": 2.0 * gather_adds / MFMA_FP6_FP4_PEAK_FLOPS / t_s,
+        "useful_note": "one multiply-add per gather-add (Sec. 4.5) against the same peak",
+    }
+    if peaks:
+        bw = peaks["hbm_write_nontemporal_GBps"] * 1e9        # the launch writes 96 % of its bytes, with non-temporal stores
+        mf = peaks["mfma_f4f6_onehot_x_counts_TFLOPs"] * 1e12
+        r["frac_vs_measured_peaks"] = max(alg_bytes / bw, flops / mf) / t_s
+        r["frac_vs_measured_note"] = ("max(alg_bytes / hbm_write_nontemporal, unit_flops_as_launched / mfma_f4f6_onehot_x_counts) "
+                                      "/ t_kernel, both from peaks_measured")
+    return r
+
+
+# ---------------------------------------------------------------------------------------------------------------------
+
+def counter_child(args):
+    """What the counter passes profile: the copy probe once, then three launches of the workload's convolutions."""
+    import numpy as np
+    import torch
+
+    from paper_2110_09195_amd import binding as B
+    from paper_2110_09195_amd import peaks as P
+    from paper_2110_09195_amd import synth
+    torch.cuda.set_device(0)
+    layers, _, cfg_no = workload_of(args, synth)
+    a = torch.zeros(COPY_CAL_BYTES // 4, dtype=torch.int32, device="cuda")
+    b = torch.empty_like(a)
+    io = []
+    for i, L in enumerate(layers):
+        g = synth.rng(cfg_no, i)
+        x = torch.from_numpy(synth.activations(g, L.N, L.C_in, L.H, L.W)).cuda()
+        cb = torch.from_numpy(synth.codebook(g, L.K).view(np.int16)).cuda()
+        idx = torch.from_numpy(synth.indices(g, L.C_out, L.C_in, L.K).view(np.int16)).cuda()
+        alpha = torch.from_numpy(synth.alpha(g, L.C_out)).cuda()
+        d = B.make_desc(L.N, L.C_in, L.C_out, L.H, L.W, L.stride, L.K, B.SNN_ACT_BIN_ROWS)
+        xr = B.snn_pack_activations(x, B.SNN_ACT_BIN_ROWS)
+        ws = B.snn_subbit_prepare(d, cb, idx, alpha)
+        y = torch.empty((L.N, L.C_out, L.H_out, L.W_out), dtype=torch.float32, device="cuda")
+        io.append({"desc": d, "x": xr, "y": y, "workspace": ws})
+        del x
+    arr = B.layer_io_array(io)
+    torch.cuda.synchronize()
+    P.copy(b, a)
+    torch.cuda.synchronize()
+    for _ in range(3):
+        B.snn_subbit_conv2d_prepared_many(arr)
+        torch.cuda.synchronize()
+
+
+def run_configs(bn, args, peaks, oracle):
+    """Workloads 1-4: microseconds, GOPS-equivalent, speed-up over the 1-bit kernel, roofline, oracle check, cold series."""
+    torch, B, np, synth = bn.torch, bn.B, bn.np, bn.synth
+    from paper_2110_09195_amd import accounting
+    reps = 30
+    out = []
+
+    def bin_layer(L, cfg_no, zipf, check_images):
+        g = synth.rng(cfg_no, 0)
+        s = bn.layer_state(L, g, zipf_w=zipf)
+        B.snn_project_kernels(s["w"], s["cb"], out=s["idx"])
+        B.snn_pack_activations(s["x"], B.SNN_ACT_BIN_ROWS, out=s["xr"])
+        B.snn_pack_activations(s["x"], B.SNN_ACT_BIN_CHANNELS, out=s["xc"])
+        idx2 = s["idx"].view(L.C_out, L.C_in)
+        B.snn_subbit_prepare(s["d_sub"], s["cb"], idx2, s["alpha"], workspace=s["ws_sub"])
+        s["w9"] = s["cb"][s["idx"].long()].view(L.C_out, L.C_in).contiguous()
+
+        def conv():
+            B.snn_subbit_conv2d_prepared(s["d_sub"], s["xr"], s["alpha"], s["ws_sub"], y=s["y"])
+
+        def bnn():
+            B.snn_bnn_conv2d(s["d_bnn"], s["xc"], s["w9"], s["alpha"], y=s["yb"], workspace=s["ws_bnn"])
+        t_conv = bn.event_avg_us(conv, reps)
+        each = bn.event_each_us(conv, reps)
+        t_bnn = bn.event_avg_us(bnn, reps)
+        torch.cuda.synchronize()
+        assert torch.equal(s["y"], s["yb"]), "sub-bit and 1-bit kernels disagree on " + L.name
+        slots = B.snn_subbit_slots_per_channel(s["d_sub"])
+        row = {"layer": L.name, "K": L.K, "index_dist": "zipf(1.1)" if zipf else "uniform",
+               "conv_us": t_conv, "conv_us_single_launch_median": each[len(each) // 2], "conv_us_single_launch_min": each[0],
+               "conv_us_cold": bn.cold_us(conv), "gops_eq": L.dense_ops / (t_conv * 1e-6) / 1e9,
+               "bnn_conv_us": t_bnn, "bnn_conv_us_cold": bn.cold_us(bnn), "speedup_vs_bnn_conv": t_bnn / t_conv,
+               "pack_rows_us": bn.event_avg_us(lambda: B.snn_pack_activations(s["x"], B.SNN_ACT_BIN_ROWS, out=s["xr"]), reps),
+               "project_us": bn.event_avg_us(lambda: B.snn_project_kernels(s["w"], s["cb"], out=s["idx"]), reps),
+               "timing": "conv_us / bnn_conv_us: %d launches back to back between one pair of HIP events; single_launch: one "
+                         "pair per launch; cold: 512 MB written between launches, median of 7" % reps}
+        if slots > 0:
+            rf = conv_roofline([L], [slots], t_conv * 1e-6, peaks, accounting)
+            row["roofline"] = {k: rf[k] for k in ("bound", "alg_bytes", "gather_adds", "responses", "slots_per_channel", "frac",
+                                                   "frac_hbm", "frac_unit", "useful_frac", "frac_vs_measured_peaks") if k in rf}
+        if oracle is not None:
+            n = min(check_images, L.N)
+            idx_o, _ = oracle.project(s["w"].cpu().numpy(), s["cb"].cpu().numpy().view(np.uint16))
+            assert (idx_o.reshape(-1) == s["idx"].cpu().numpy().view(np.uint16)).all(), "projection differs from the oracle on " + L.name
+            c0 = time.perf_counter()
+            _, Y = oracle.conv_bin(oracle.sign(s["x"][:n].cpu().numpy()), oracle.expand(s["cb"].cpu().numpy().view(np.uint16), idx_o.reshape(L.C_out, L.C_in)),
+                                   s["alpha"].cpu().numpy(), L.stride)
+            row["oracle_s"] = time.perf_counter() - c0
+            assert (s["y"][:n].cpu().numpy() == Y).all(), "GPU result differs from the oracle on " + L.name
+            row["checked"] = "indices of all kernels and outputs of the first %d images equal the oracle's, bit for bit" % n
+        return s, row
+
+    # ---- config 1 ----
+    s, row = bin_layer(synth.CFG1, 1, False, synth.CFG1.N)
+    row["config"] = 1
+    row["note"] = "a few microseconds of work: bound by launch latency"
+    out.append(row)
+
+    # ---- config 2: fp32 activations ----
+    L = synth.CFG2
+    g = synth.rng(2, 0)
+    x = bn.dev(synth.activations(g, L.N, L.C_in, L.H, L.W))
+    cb = bn.dev(synth.codebook(g, L.K))
+    idx = bn.dev(synth.indices(g, L.C_out, L.C_in, L.K))
+    alpha = bn.dev(synth.alpha(g, L.C_out))
+    d = B.make_desc(L.N, L.C_in, L.C_out, L.H, L.W, L.stride, L.K, B.SNN_ACT_F32)
+    y = torch.empty((L.N, L.C_out, L.H_out, L.W_out), dtype=torch.float32, device="cuda")
+    ws = B.alloc_workspace(d, B.SNN_WS_SUBBIT)
+
+    def conv_f32():
+        B.snn_subbit_conv2d(d, x, cb, idx, alpha, y=y, workspace=ws)
+    t = bn.event_avg_us(conv_f32, reps)
+    each = bn.event_each_us(conv_f32, reps)
+    lane_ops = accounting.stage1_responses(L) * 9 + accounting.stage2_gather_adds(L)
+    alg_bytes = L.N * L.C_in * L.H * L.W * 4 + L.pixels * L.C_out * 4 + L.C_in * L.C_out * 2
+    row = {"config": 2, "layer": L.name, "K": L.K, "activations": "fp32", "conv_us": t,
+           "conv_us_single_launch_median": each[len(each) // 2], "conv_us_cold": bn.cold_us(conv_f32),
+           "gops_eq": L.dense_ops / (t * 1e-6) / 1e9,
+           "roofline": {"bound": "alu", "alg_bytes": alg_bytes, "responses": accounting.stage1_responses(L),
+                        "gather_adds": accounting.stage2_gather_adds(L),
+                        "unit_used": "plain fp32 VALU adds: 9 per response, 1 per gather-add",
+                        "frac": max(alg_bytes / HBM_PEAK_BYTES, lane_ops / VALU_PEAK_LANE_OPS) / (t * 1e-6),
+                        "frac_hbm": alg_bytes / HBM_PEAK_BYTES / (t * 1e-6), "frac_unit": lane_ops / VALU_PEAK_LANE_OPS / (t * 1e-6)},
+           "note": "the call includes its small table-preparation kernel; a few microseconds of work: bound by launch latency"}
+    if oracle is not None:
+        _, Y = oracle.conv_f32(x.cpu().numpy(), oracle.expand(cb.cpu().numpy().view(np.uint16), idx.cpu().numpy().view(np.uint16)),
+                               alpha.cpu().numpy(), L.stride)
+        got = y.cpu().numpy().astype(np.float64)
+        denom = np.maximum(np.abs(Y), np.sqrt(np.mean(np.square(Y.astype(np.float64)))))
+        err = float(np.max(np.abs(got - Y) / denom))
+        assert err <= 1e-5, "fp32-activation result differs from the oracle: %.3g" % err
+        row["checked"] = "every output within 1e-5 * max(|ref|, rms(ref)) of the fp64 oracle (largest: %.2e)" % err
+    out.append(row)
+    del x, y
+
+    # ---- config 3: Zipf indices; the 1-bit kernel on the same weights and on uniform codes; identity-512 ----
+    L = synth.CFG3
+    s, row = bin_layer(L, 3, True, 8)
+    row["config"] = 3
+    g = synth.rng(3, 50)
+    w9u = bn.dev(g.integers(0, 512, size=(L.C_out, L.C_in)).astype(np.uint16))
+
+    def bnn_uniform():
+        B.snn_bnn_conv2d(s["d_bnn"], s["xc"], w9u, s["alpha"], y=s["yb"], workspace=s["ws_bnn"])
+    row["bnn_conv_us_uniform_w9"] = bn.event_avg_us(bnn_uniform, reps)
+    row["bnn_conv_us_same_weights"] = row["bnn_conv_us"]
+    # the 1-bit layer through the sub-bit path: identity subset of all 512 kernels, idx = the kernel codes (an invariant
+    # check, Sec. 4.1: a 1-bit layer is the sub-bit layer whose subset is the whole set; runs on the LDS-gather kernel)
+    d512 = B.make_desc(L.N, L.C_in, L.C_out, L.H, L.W, L.stride, 512, B.SNN_ACT_BIN_ROWS)
+    ident = bn.dev(np.arange(512, dtype=np.uint16))
+    ws512 = B.alloc_workspace(d512, B.SNN_WS_SUBBIT)
+    y512 = torch.empty_like(s["y"])
+
+    def conv512():
+        B.snn_subbit_conv2d(d512, s["xr"], ident, w9u, s["alpha"], y=y512, workspace=ws512)
+    row["subbit_identity512_us"] = bn.event_avg_us(conv512, reps)
+    torch.cuda.synchronize()
+    assert torch.equal(y512, s["yb"]), "identity-512 sub-bit layer and 1-bit kernel disagree"
+    row["identity512_note"] = "labelled invariant run, not the baseline: equals snn_bnn_conv2d on the same uniform codes, bit for bit"
+    out.append(row)
+    del s, y512
+
+    # ---- config 4: K sweep ----
+    for K in (16, 32, 64):
+        s, row = bin_layer(synth.cfg4(K), 4, False, 4)
+        row["config"] = 4
+        out.append(row)
+        del s
+    torch.cuda.empty_cache()
+    return out
 
 
 def main():
     args = parse()
     if args.gpus != 1:
-        print("bench.py: this build measures one GPU only (the path shards over the batch without "
-              "communication; see DESIGN.md); run with --gpus 1", file=sys.stderr)
+        print("bench.py: this build measures one GPU only (the path shards over the batch without communication); "
+              "run with --gpus 1", file=sys.stderr)
         sys.exit(2)
+    if args.counter_child:
+        counter_child(args)
+        return
+
+    # the counter passes are child processes of their own and run before this process touches the GPU
+    traffic = None
+    if not (args.no_traffic or args.headline_only):
+        traffic = measure_traffic(args)
 
     import numpy as np
     import torch
@@ -93,75 +551,20 @@ def main():
         sys.exit(2)
     torch.cuda.set_device(0)
     B.lib()
+    bn = Bench(torch, B, np, synth)
+    dev = bn.dev
+    oracle = None
+    if not args.no_cpu:
+        import oracle
+        oracle.build()
 
-    if args.layer:
-        N, Ci, Co, H, W, st_ = [int(v) for v in args.layer.split(",")]
-        layers = [synth.Layer("custom", N=N, C_in=Ci, C_out=Co, H=H, W=W, stride=st_, K=args.K)]
-        wname = "custom layer %s, K=%d" % (args.layer, args.K)
-        cfg_no = 9
-    elif args.workload == "resnet18":
-        layers = synth.resnet18_stack(N=64, K=args.K)
-        wname = "ResNet-18 3x3 conv stack (16 layers), batch 64, 224x224 shapes, binary activations, K=%d" % args.K
-        cfg_no = 5
-    elif args.workload == "cfg3":
-        layers = [synth.CFG3]
-        wname = "ResNet-18 stage-3 layer, batch 128, 256->256, 14x14, K=32, Zipf indices"
-        cfg_no = 3
-    elif args.workload == "cfg4":
-        layers = [synth.cfg4(args.K)]
-        wname = "ResNet-34 stage-4 layer, batch 256, 512->512, 7x7, K=%d" % args.K
-        cfg_no = 4
-    else:
-        layers = [synth.CFG1]
-        wname = "ResNet-20 stage-1 layer, batch 8, 16->16, 32x32, K=32"
-        cfg_no = 1
-
-    def dev(a):
-        a = np.ascontiguousarray(a)
-        if a.dtype == np.uint16:
-            a = a.view(np.int16)
-        return torch.from_numpy(a).cuda()
-
-    if args.calibrate_copy:
-        # 64 Mi floats read + 64 Mi floats written by one elementwise kernel: the known-size reference that
-        # FETCH_SIZE / WRITE_SIZE readings of the conv kernels are scaled by (see the design doc / profiles/)
-        ca = torch.zeros(64 * 1024 * 1024, dtype=torch.float32, device="cuda")
-        cb = torch.empty_like(ca)
-        torch.add(ca, 1.0, out=cb)
-        torch.cuda.synchronize()
-        del ca, cb
+    peaks = measured_peaks(torch, np)
+    layers, wname, cfg_no = workload_of(args, synth)
+    extras = not args.headline_only
 
     # ---- resident inputs and buffers -------------------------------------------------------------
-    st = []
-    for i, L in enumerate(layers):
-        g = synth.rng(cfg_no, i)
-        s = {"L": L}
-        s["x"] = dev(synth.activations(g, L.N, L.C_in, L.H, L.W))
-        s["cb"] = dev(synth.codebook(g, L.K))
-        if args.workload == "cfg3":
-            # Zipf-skewed indices: real-valued kernels are drawn around the subset members the
-            # skewed indices name, so that projection reproduces a skewed index map
-            idx0 = synth.indices(g, L.C_out, L.C_in, L.K, "zipf")
-            cbh = s["cb"].cpu().numpy().view(np.uint16)
-            members = np.array([[1.0 if (int(c) >> (8 - t)) & 1 else -1.0 for t in range(9)] for c in cbh], dtype=np.float32)
-            w = members[idx0.reshape(-1)] + 0.3 * synth.real_kernels(g, L.C_out * L.C_in)
-        else:
-            w = synth.real_kernels(g, L.C_out * L.C_in)
-        s["w"] = dev(w.astype(np.float32))
-        s["alpha"] = dev(synth.alpha(g, L.C_out))
-        s["idx"] = torch.empty(L.C_out * L.C_in, dtype=torch.int16, device="cuda")
-        s["d_sub"] = B.make_desc(L.N, L.C_in, L.C_out, L.H, L.W, L.stride, L.K, B.SNN_ACT_BIN_ROWS)
-        s["d_bnn"] = B.make_desc(L.N, L.C_in, L.C_out, L.H, L.W, L.stride, 512, B.SNN_ACT_BIN_CHANNELS)
-        s["xr"] = torch.empty(B.snn_packed_bytes(L.N, L.C_in, L.H, L.W, B.SNN_ACT_BIN_ROWS) // 4, dtype=torch.int32, device="cuda")
-        s["xc"] = torch.empty(B.snn_packed_bytes(L.N, L.C_in, L.H, L.W, B.SNN_ACT_BIN_CHANNELS) // 4, dtype=torch.int32, device="cuda")
-        s["y"] = torch.empty((L.N, L.C_out, L.H_out, L.W_out), dtype=torch.float32, device="cuda")
-        s["yb"] = torch.empty_like(s["y"])
-        s["ws_sub"] = B.alloc_workspace(s["d_sub"], B.SNN_WS_SUBBIT)
-        s["ws_bnn"] = B.alloc_workspace(s["d_bnn"], B.SNN_WS_BNN)
-        s["ws_fwd"] = B.alloc_workspace(s["d_sub"], B.SNN_WS_FORWARD)
-        s["d_dense"] = B.make_desc(L.N, L.C_in, L.C_out, L.H, L.W, L.stride, L.K, B.SNN_ACT_BIN_CHANNELS)
-        s["ws_dense"] = B.alloc_workspace(s["d_dense"], B.SNN_WS_BNN_DENSE)
-        st.append(s)
+    st = [bn.layer_state(L, synth.rng(cfg_no, i), zipf_w=(args.workload == "cfg3" and not args.layer),
+                         extra=("forward", "dense")) for i, L in enumerate(layers)]
     torch.cuda.synchronize()
 
     def project(s):
@@ -177,6 +580,9 @@ def main():
         L = s["L"]
         B.snn_subbit_conv2d(s["d_sub"], s["xr"], s["cb"], s["idx"].view(L.C_out, L.C_in), s["alpha"], y=s["y"],
                             workspace=s["ws_sub"])
+
+    def conv_prepared(s):
+        B.snn_subbit_conv2d_prepared(s["d_sub"], s["xr"], s["alpha"], s["ws_sub"], y=s["y"])
 
     def conv_bnn(s):
         B.snn_bnn_conv2d(s["d_bnn"], s["xc"], s["w9"], s["alpha"], y=s["yb"], workspace=s["ws_bnn"])
@@ -194,26 +600,44 @@ def main():
         B.snn_subbit_forward(s["d_sub"], s["x"], s["w"], s["cb"], s["alpha"], idx_out=s["idx"].view(L.C_out, L.C_in),
                              y=s["y"], workspace=s["ws_fwd"])
 
-    # One step = every layer's projection + sign/pack + convolution, back to back on one stream:
-    # one snn_subbit_forward call per layer, which runs the small operations in one launch and the
-    # convolution in a second.  step_separate is the same work as three calls (four launches) per
-    # layer.  (Putting the small kernels on side streams, eagerly or as a captured HIP graph, was
-    # measured and is slower here: the eager form is bound by the host's launch rate, the graph
-    # replay runs the kernels no closer together than the single stream does.)
-    def step_forward_calls():
-        for s in st:
-            forward(s)
-
-    # the headline step: the weights-side work of all layers in ONE launch (projection + tables:
-    # snn_subbit_project_prepare_many), then per layer sign/pack + convolution (two launches)
+    # The headline step: the weights-side work of all layers in ONE launch (projection + tables), per layer sign/pack,
+    # then the convolutions of all layers in ONE launch.  A pair of events on the launch stream brackets the convolution
+    # launch inside the timed steps: their average is the kernel time the roofline uses.
     prep_arr = B.layer_weights_array([{"desc": s["d_sub"], "w": s["w"], "codebook": s["cb"], "alpha": s["alpha"],
                                        "idx_out": s["idx"], "workspace": s["ws_sub"]} for s in st])
+    many_ok = all(B.snn_subbit_slots_per_channel(s["d_sub"]) > 0 for s in st)
+    io_arr = B.layer_io_array([{"desc": s["d_sub"], "x": s["xr"], "y": s["y"], "workspace": s["ws_sub"]} for s in st]) if many_ok else None
+    ev = []
 
-    def step():
+    def convs():
+        if many_ok:
+            B.snn_subbit_conv2d_prepared_many(io_arr)
+        else:
+            for s in st:
+                conv_prepared(s)
+
+    def step(timed=False):
         B.snn_subbit_project_prepare_many(prep_arr)
         for s in st:
             pack_rows(s)
-            B.snn_subbit_conv2d_prepared(s["d_sub"], s["xr"], s["alpha"], s["ws_sub"], y=s["y"])
+        if timed:
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            convs()
+            e1.record()
+            ev.append((e0, e1))
+        else:
+            convs()
+
+    def step_per_layer_launches():
+        B.snn_subbit_project_prepare_many(prep_arr)
+        for s in st:
+            pack_rows(s)
+            conv_prepared(s)
+
+    def step_forward_calls():
+        for s in st:
+            forward(s)
 
     def step_separate():
         for s in st:
@@ -226,8 +650,11 @@ def main():
             pack_channels(s)
             conv_bnn(s)
 
-    # the same sub-bit layers (same subsets and indices) as dense FP4 contractions on the matrix
-    # cores, without the sharing of Sec. 4.5: context for what that sharing buys on this chip
+    def step_inference():
+        for s in st:
+            pack_rows(s)
+        convs()
+
     def step_dense():
         for s in st:
             pack_channels(s)
@@ -253,69 +680,29 @@ def main():
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        step()
+        step(timed=True)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
+    in_step = sorted(a.elapsed_time(b) * 1e3 for a, b in ev)
+    t_conv_in_step_us = sum(in_step) / len(in_step)
 
-    for _ in range(args.warmup):
-        step_forward_calls()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step_forward_calls()
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    ms_per_step_forward_calls = (t1 - t0) * 1e3 / args.steps
-
-    for _ in range(args.warmup):
-        step_separate()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step_separate()
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    ms_per_step_separate = (t1 - t0) * 1e3 / args.steps
-
-    for _ in range(args.warmup):
-        step_bnn()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step_bnn()
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    ms_per_step_bnn = (t1 - t0) * 1e3 / args.steps
-
-    ms_per_step_dense = ms_per_step_dense_inference = None
-    if not args.headline_only:
-        for _ in range(args.warmup):
-            step_dense()
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(args.steps):
-            step_dense()
-        torch.cuda.synchronize()
-        t1 = time.perf_counter()
-        ms_per_step_dense = (t1 - t0) * 1e3 / args.steps
-        for _ in range(args.warmup):
-            step_dense_inference()
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(args.steps):
-            step_dense_inference()
-        torch.cuda.synchronize()
-        t1 = time.perf_counter()
-        ms_per_step_dense_inference = (t1 - t0) * 1e3 / args.steps
+    ms_per_step_bnn = bn.host_ms(step_bnn, args.warmup, args.steps)
+    ms_per_step_per_layer = bn.host_ms(step_per_layer_launches, args.warmup, args.steps)
+    ms_per_step_inference = bn.host_ms(step_inference, args.warmup, args.steps)
+    ms_per_step_forward_calls = ms_per_step_separate = ms_per_step_dense = ms_per_step_dense_inference = None
+    if extras:
+        ms_per_step_forward_calls = bn.host_ms(step_forward_calls, args.warmup, args.steps)
+        ms_per_step_separate = bn.host_ms(step_separate, args.warmup, args.steps)
+        ms_per_step_dense = bn.host_ms(step_dense, args.warmup, args.steps)
+        ms_per_step_dense_inference = bn.host_ms(step_dense_inference, args.warmup, args.steps)
 
     # ---- the same stack as a chain of 1-bit activations (resnet18 workload only) ---------------------------
-    # Layer i's convolution ends in the next layer's binarisation (snn_subbit_forward_sign): the packed
-    # output of one layer is the packed input of the next, no fp32 activations are written and nothing
-    # is packed in between.  Reported next to the headline, not as it: the headline's layers each take
-    # their own fp32 input, as the workload is defined.
+    # Layer i's convolution ends in the next layer's binarisation (snn_subbit_forward_sign): the packed output of one
+    # layer is the packed input of the next, no fp32 activations are written and nothing is packed in between.
+    # Reported next to the headline, not as it: the headline's layers each take their own fp32 input.
     chained = None
-    chain_ok = not args.headline_only and args.workload == "resnet18" and not args.layer and all(
+    chain_ok = extras and args.workload == "resnet18" and not args.layer and all(
         a.C_out == b.C_in and a.H_out == b.H and a.W_out == b.W for a, b in zip(layers, layers[1:]))
     if chain_ok:
         for i, s in enumerate(st):
@@ -323,8 +710,6 @@ def main():
             s["beta"] = dev((0.25 * synth.rng(cfg_no, 200 + i).standard_normal(L.C_out)).astype(np.float32))
             words = L.N * L.C_out * L.H_out * ((L.W_out + 31) // 32)
             s["out_bits"] = torch.empty(words, dtype=torch.int32, device="cuda")
-
-        for s in st:
             s["ws_chain"] = B.alloc_workspace(s["d_sub"], B.SNN_WS_SUBBIT)
         chain_arr = B.layer_weights_array([{"desc": s["d_sub"], "w": s["w"], "codebook": s["cb"], "alpha": s["alpha"],
                                             "beta": s["beta"], "idx_out": s["idx"], "workspace": s["ws_chain"]} for s in st])
@@ -335,17 +720,7 @@ def main():
             for s in st:
                 B.snn_subbit_conv2d_sign_prepared(s["d_sub"], xin, s["ws_chain"], out=s["out_bits"])
                 xin = s["out_bits"]
-
-        for _ in range(args.warmup):
-            step_chained()
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(args.steps):
-            step_chained()
-        torch.cuda.synchronize()
-        t1 = time.perf_counter()
-        ms_chained = (t1 - t0) * 1e3 / args.steps
-        # the same chain with the weights prepared once: one launch per layer
+        ms_chained = bn.host_ms(step_chained, args.warmup, args.steps)
         for s in st:
             L = s["L"]
             s["ws_sign"] = B.snn_subbit_prepare_sign(s["d_sub"], s["cb"], s["idx"].view(L.C_out, L.C_in), s["alpha"], s["beta"])
@@ -355,17 +730,7 @@ def main():
             for s in st:
                 B.snn_subbit_conv2d_sign_prepared(s["d_sub"], xin, s["ws_sign"], out=s["out_bits"])
                 xin = s["out_bits"]
-
-        for _ in range(args.warmup):
-            step_chained_inference()
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(args.steps):
-            step_chained_inference()
-        torch.cuda.synchronize()
-        t1 = time.perf_counter()
-        ms_chained_inf = (t1 - t0) * 1e3 / args.steps
-        # the same chain through the dense contraction (packed channels from layer to layer; context)
+        ms_chained_inf = bn.host_ms(step_chained_inference, args.warmup, args.steps)
         for s in st:
             L = s["L"]
             B.snn_dense_prepare(s["d_dense"], s["cb"], s["idx"].view(L.C_out, L.C_in), s["ws_dense"])
@@ -377,17 +742,8 @@ def main():
             for s in st:
                 B.snn_dense_conv2d_sign_prepared(s["d_dense"], xin, s["alpha"], s["beta"], s["ws_dense"], out=s["out_bits_c"])
                 xin = s["out_bits_c"]
-
-        for _ in range(args.warmup):
-            step_chained_dense()
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(args.steps):
-            step_chained_dense()
-        torch.cuda.synchronize()
-        t1 = time.perf_counter()
-        ms_chained_dense = (t1 - t0) * 1e3 / args.steps
-        chained = {"ms_per_step": ms_chained, "gops_eq": dense_ops_of(layers) / (ms_chained * 1e-3) / 1e9,
+        ms_chained_dense = bn.host_ms(step_chained_dense, args.warmup, args.steps)
+        chained = {"ms_per_step": ms_chained, "gops_eq": sum(L.dense_ops for L in layers) / (ms_chained * 1e-3) / 1e9,
                    "ms_per_step_inference_dense_context": ms_chained_dense,
                    "ms_per_step_inference": ms_chained_inf,
                    "inference_step": "weights prepared once (snn_subbit_prepare_sign); pack the first input, then one "
@@ -395,99 +751,58 @@ def main():
                    "step": "snn_subbit_project_prepare_many (projection + thresholds + tables of all layers), pack the first "
                            "input, then one snn_subbit_conv2d_sign_prepared per layer: 1-bit activations from layer to layer"}
 
+    # ---- per-call device time with HIP events on the launch stream ---------------------------------------
+    reps = max(10, args.steps)
+    # restore what the steps above may have left in the buffers the checks read
+    step()
+    for s in st:
+        pack_channels(s)
+        conv_bnn(s)
+    torch.cuda.synchronize()
     # the two kernels must agree (same decoded weights): a cheap end-to-end sanity check
     for s in st:
         assert torch.equal(s["y"], s["yb"]), "sub-bit and 1-bit kernels disagree on " + s["L"].name
 
-    # ---- per-call device time with HIP events on the launch stream ---------------------------------------
-    def event_time(fn, reps):
-        """Median device milliseconds of fn(s) per layer over `reps` back-to-back repetitions."""
-        out = []
-        for s in st:
-            e0 = [torch.cuda.Event(enable_timing=True) for _ in range(reps)]
-            e1 = [torch.cuda.Event(enable_timing=True) for _ in range(reps)]
-            fn(s)
-            torch.cuda.synchronize()
-            for r in range(reps):
-                e0[r].record()
-                fn(s)
-                e1[r].record()
-            torch.cuda.synchronize()
-            ts = sorted(a.elapsed_time(b) for a, b in zip(e0, e1))
-            out.append(ts[len(ts) // 2])          # median: the first repetitions wait for the host
-        return out
+    t_convs_b2b = bn.event_avg_us(convs, reps)                     # the convolution launch, back to back
+    t_convs_each = bn.event_each_us(convs, reps)
+    t_convs_cold = bn.cold_us(convs)
+    t_prep_many = bn.event_avg_us(lambda: B.snn_subbit_project_prepare_many(prep_arr), reps)
+    t_kern = [bn.event_avg_us(lambda s=s: conv_prepared(s), reps) for s in st]      # one launch per layer, for comparison
+    t_bnn = [bn.event_avg_us(lambda s=s: conv_bnn(s), reps) for s in st]
+    t_proj = [bn.event_avg_us(lambda s=s: project(s), reps) for s in st]
+    t_pr = [bn.event_avg_us(lambda s=s: pack_rows(s), reps) for s in st]
+    t_pc = [bn.event_avg_us(lambda s=s: pack_channels(s), reps) for s in st]
+    t_bnn_cold = sum(bn.cold_us(lambda s=s: conv_bnn(s), 5) for s in st)
+    t_dense = t_dense_k = None
+    if extras:
+        t_dense = [bn.event_avg_us(lambda s=s: conv_dense(s), reps) for s in st]
+        t_dense_k = [bn.event_avg_us(lambda s=s: conv_dense_prepared(s), reps) for s in st]
 
-    # the convolution kernel alone (weights prepared once, as at inference): `reps` launches back to back
-    # between one pair of events per layer, so that neither the preparation kernel nor the events'
-    # own cost is in the figure the roofline uses
-    def kernel_time(reps):
-        out = []
-        for s in st:
-            B.snn_subbit_prepare(s["d_sub"], s["cb"], s["idx"].view(s["L"].C_out, s["L"].C_in), s["alpha"], workspace=s["ws_sub"])
-            B.snn_subbit_conv2d_prepared(s["d_sub"], s["xr"], s["alpha"], s["ws_sub"], y=s["y"])
-            torch.cuda.synchronize()
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record()
-            for _ in range(reps):
-                B.snn_subbit_conv2d_prepared(s["d_sub"], s["xr"], s["alpha"], s["ws_sub"], y=s["y"])
-            e1.record()
-            torch.cuda.synchronize()
-            out.append(e0.elapsed_time(e1) / reps)
-        return out
-
-    reps = max(10, args.steps)
-    t_kern = kernel_time(reps)
-
-    # inference step: weights prepared beforehand, per layer sign/pack + convolution (two launches)
-    def step_inference():
-        for s in st:
-            pack_rows(s)
-            B.snn_subbit_conv2d_prepared(s["d_sub"], s["xr"], s["alpha"], s["ws_sub"], y=s["y"])
-
-    for _ in range(args.warmup):
-        step_inference()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step_inference()
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    ms_per_step_inference = (t1 - t0) * 1e3 / args.steps
-
-    t_sub = event_time(conv_sub, reps)
-    t_bnn = event_time(conv_bnn, reps)
-    t_dense = event_time(conv_dense, reps)
-    t_dense_k = event_time(conv_dense_prepared, reps)
-    t_proj = event_time(project, reps)
-    t_pr = event_time(pack_rows, reps)
-    t_pc = event_time(pack_channels, reps)
-
-    # training-side lines of Alg. 1 (not part of the step, which is the forward pass): the straight-through
-    # estimator + gradient of the subset tensor, and the sign-memory update with the repeated-member check
-    for i, s in enumerate(st):
-        L = s["L"]
-        gq = synth.rng(cfg_no, 300 + i)
-        s["g_wbar"] = dev(gq.standard_normal((L.C_out * L.C_in, 9)).astype(np.float32))
-        s["g_w"] = torch.empty_like(s["g_wbar"])
-        s["g_p"] = torch.empty((L.K, 9), dtype=torch.float32, device="cuda")
-        s["p"] = dev((0.01 * gq.standard_normal((L.K, 9))).astype(np.float32))
-        s["m"] = torch.ones((L.K, 9), dtype=torch.int8, device="cuda")
-        s["ws_bwd"] = torch.empty(max(int(B.lib().snn_project_backward_workspace_bytes(L.C_out * L.C_in, L.K)), 256),
-                                  dtype=torch.uint8, device="cuda")
-
-    def project_backward(s):
-        B.snn_project_backward(s["w"], s["g_wbar"], s["idx"], s["L"].K, g_w=s["g_w"], g_p=s["g_p"], workspace=s["ws_bwd"])
-
-    def subset_update(s):
-        B.snn_subset_update(s["p"], s["m"], 1e-3)
-
-    t_pb = event_time(project_backward, reps) if not args.headline_only else [0.0] * len(st)
-    t_su = event_time(subset_update, reps) if not args.headline_only else [0.0] * len(st)
-    bwd_bytes = sum(L.C_out * L.C_in * (36 + 36 + 2 + 36) for L in layers)
+    # training-side lines of Alg. 1 (not part of the step, which is the forward pass)
+    training = None
+    if extras:
+        for i, s in enumerate(st):
+            L = s["L"]
+            gq = synth.rng(cfg_no, 300 + i)
+            s["g_wbar"] = dev(gq.standard_normal((L.C_out * L.C_in, 9)).astype(np.float32))
+            s["g_w"] = torch.empty_like(s["g_wbar"])
+            s["g_p"] = torch.empty((L.K, 9), dtype=torch.float32, device="cuda")
+            s["p"] = dev((0.01 * gq.standard_normal((L.K, 9))).astype(np.float32))
+            s["m"] = torch.ones((L.K, 9), dtype=torch.int8, device="cuda")
+            s["ws_bwd"] = torch.empty(max(int(B.lib().snn_project_backward_workspace_bytes(L.C_out * L.C_in, L.K)), 256),
+                                      dtype=torch.uint8, device="cuda")
+        t_pb = [bn.event_avg_us(lambda s=s: B.snn_project_backward(s["w"], s["g_wbar"], s["idx"], s["L"].K, g_w=s["g_w"],
+                                                                  g_p=s["g_p"], workspace=s["ws_bwd"]), reps) for s in st]
+        t_su = [bn.event_avg_us(lambda s=s: B.snn_subset_update(s["p"], s["m"], 1e-3), reps) for s in st]
+        bwd_bytes = sum(L.C_out * L.C_in * (36 + 36 + 2 + 36) for L in layers)
+        training = {"project_backward_us": sum(t_pb), "subset_update_us": sum(t_su),
+                    "project_backward_GBps": bwd_bytes / (sum(t_pb) * 1e-6) / 1e9,
+                    "note": "launches back to back between one pair of events, summed over the layers; Alg. 1 backward lines, "
+                            "outside the step"}
 
     # 1x1 layers of a bottleneck network (appendix, Table 5): shapes of ResNet-50 at batch 64, K = 32 members of {+-1}^8
     conv1x1 = None
-    if not args.headline_only and args.workload == "resnet18" and not args.layer:
+    if extras and args.workload == "resnet18" and not args.layer:
         conv1x1 = []
         for (ci, co, hw) in [(64, 256, 56), (256, 64, 56), (512, 128, 28), (128, 512, 28), (1024, 256, 14), (2048, 512, 7)]:
             gq = synth.rng(cfg_no, 400 + ci + co)
@@ -499,104 +814,76 @@ def main():
             al1 = dev(synth.alpha(gq, co))
             y1 = torch.empty((64, co, hw, hw), dtype=torch.float32, device="cuda")
             ws1 = B.alloc_workspace(d1, B.SNN_WS_CONV1X1)
-            B.snn_subbit_conv1x1(d1, x1, cb1, idx1, al1, y=y1, workspace=ws1)
-            torch.cuda.synchronize()
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record()
-            for _ in range(reps):
-                B.snn_subbit_conv1x1(d1, x1, cb1, idx1, al1, y=y1, workspace=ws1)
-            e1.record()
-            torch.cuda.synchronize()
-            us = e0.elapsed_time(e1) / reps * 1e3
+            us = bn.event_avg_us(lambda: B.snn_subbit_conv1x1(d1, x1, cb1, idx1, al1, y=y1, workspace=ws1), reps)
             ops = 2.0 * ci * co * 64 * hw * hw
-            conv1x1.append({"layer": "%d->%d %dx%d" % (ci, co, hw, hw), "us": us, "gops_eq": ops / (us * 1e-6) / 1e9})
+            conv1x1.append({"layer": "%d->%d %dx%d" % (ci, co, hw, hw), "us": us, "gops_eq": ops / (us * 1e-6) / 1e9,
+                            "out_GBps": 64 * co * hw * hw * 4 / (us * 1e-6) / 1e9})
+            del x1, y1
 
     dense_ops = sum(L.dense_ops for L in layers)
-    gather_adds = sum(accounting.stage2_gather_adds(L) for L in layers)
-    responses = sum(accounting.stage1_responses(L) for L in layers)
-    out_bytes = sum(L.pixels * L.C_out * 4 for L in layers)
-    in_bytes = sum(L.N * L.C_in * L.H * ((L.W + 31) // 32) * 4 for L in layers)
-    idx_bytes = sum(L.C_in * L.C_out * 2 for L in layers)
+    slots = [B.snn_subbit_slots_per_channel(s["d_sub"]) for s in st]
+    roofline = None
+    if many_ok:
+        roofline = conv_roofline(layers, slots, t_conv_in_step_us * 1e-6, peaks, accounting)
+        roofline["kernel"] = ("subbit_stack_kernel: ONE launch per step runs the convolutions of all %d layers (resident workers of "
+                              "one wave draw (layer, tile) items); t_kernel = average over the %d timed steps of a HIP-event pair "
+                              "around that launch, on the launch stream" % (len(layers), args.steps))
+        roofline["t_kernel_us_back_to_back"] = t_convs_b2b
+        roofline["t_kernel_us_single_launch_median"] = t_convs_each[len(t_convs_each) // 2]
+        roofline["t_kernel_us_single_launch_min"] = t_convs_each[0]
+        roofline["t_kernel_us_cold"] = t_convs_cold
+        roofline["t_kernel_us_in_step_min_max"] = [in_step[0], in_step[-1]]
+        roofline["traffic"] = traffic
+        if traffic:
+            roofline["traffic_over_alg_bytes"] = traffic["bytes"] / roofline["alg_bytes"]
+        roofline["peaks_vendor"] = {"hbm_GBps": HBM_PEAK_BYTES / 1e9, "mfma_fp6_fp4_TFLOPs": MFMA_FP6_FP4_PEAK_FLOPS / 1e12,
+                                    "valu_T_lane_ops": VALU_PEAK_LANE_OPS / 1e12}
+        roofline["peaks_measured"] = peaks
 
-    alg_hbm_bytes = float(out_bytes + in_bytes + idx_bytes)
-    sub_s = sum(t_sub) * 1e-3
-    kern_s = sum(t_kern) * 1e-3
-    hbm = {"achieved": alg_hbm_bytes / kern_s / 1e9, "peak": HBM_PEAK_BYTES / 1e9, "unit": "GB/s",
-           "frac": alg_hbm_bytes / kern_s / HBM_PEAK_BYTES}
-    if all(L.K <= 32 and L.C_in >= 2 for L in layers):
-        # Matrix-core kernel: stage 2 is a product with a one-hot matrix whose contraction runs over
-        # (c_in, 32 subset slots), i.e. 2 * 32 flop per (pixel, c_out, c_in); stage 1 is the B operand
-        # itself (a table row), so these are all the flops of the method in this formulation.
-        alg_flops = 2.0 * 32.0 * gather_adds
-        roofline = {
-            "kernel": "subbit_mfma_kernel (all %d launches of a step; duration: snn_subbit_conv2d_prepared, the "
-                      "convolution kernel alone, launched back to back between one pair of HIP events per layer)" % len(layers),
-            "bound": "mfma",
-            "achieved": alg_flops / kern_s / 1e12,
-            "peak": MFMA_FP6_FP4_PEAK_FLOPS / 1e12,
-            "unit": "TFLOP/s",
-            "frac": alg_flops / kern_s / MFMA_FP6_FP4_PEAK_FLOPS,
-            "traffic": _measured_traffic(args),
-            "hbm": hbm,
-            "avg_launch_ms": sum(t_kern) / len(t_kern),
-        }
-    else:
-        # LDS-gather kernels (K > 32): stage 2 is one add per (pixel, c_out, c_in) with four pixels per
-        # 32-bit lane operation; stage 1 one response per (pixel, c_in, k), four per lane operation.
-        # Every gathered response is one byte read from LDS.
-        alg_lane_ops = (gather_adds + responses) / 4.0
-        alg_lds_bytes = float(gather_adds)
-        roofline = {
-            "kernel": "subbit_lut_kernel / subbit_wave_kernel (all %d launches of a step; duration is the "
-                      "snn_subbit_conv2d call, which includes its small index-preparation kernel)" % len(layers),
-            "bound": "alu",
-            "achieved": alg_lane_ops / sub_s / 1e12,
-            "peak": VALU_PEAK_LANE_OPS / 1e12,
-            "unit": "T lane-op/s",
-            "frac": alg_lane_ops / sub_s / VALU_PEAK_LANE_OPS,
-            "traffic": _measured_traffic(args),
-            "lds": {"achieved": alg_lds_bytes / sub_s / 1e12, "peak": LDS_PEAK_BYTES / 1e12, "unit": "TB/s",
-                    "frac": alg_lds_bytes / sub_s / LDS_PEAK_BYTES},
-            "hbm": hbm,
-            "avg_launch_ms": sum(t_sub) / len(t_sub),
-        }
-
-    print("%-18s %9s %6s %5s | %9s %9s %7s | %8s %8s %8s" % ("layer", "pixels", "C", "K", "subbit us", "bnn us", "speedup",
+    print("%-18s %9s %6s %5s | %9s %9s %7s | %8s %8s %8s" % ("layer", "pixels", "C", "K", "subbit us", "bnn us", "ratio",
                                                              "proj us", "packR us", "packC us"), file=sys.stderr)
-    for L, a, b, c, d, e in zip(layers, t_sub, t_bnn, t_proj, t_pr, t_pc):
+    for L, a, b, c, d, e in zip(layers, t_kern, t_bnn, t_proj, t_pr, t_pc):
         print("%-18s %9d %3d>%-3d %4d | %9.1f %9.1f %7.2f | %8.1f %8.1f %8.1f" % (
-            L.name, L.pixels, L.C_in, L.C_out, L.K, a * 1e3, b * 1e3, b / a, c * 1e3, d * 1e3, e * 1e3), file=sys.stderr)
-    print("sum: subbit %.1f us, bnn %.1f us, project %.1f us, pack rows %.1f us, pack channels %.1f us; "
-          "step %.1f us, bnn step %.1f us" % (sum(t_sub) * 1e3, sum(t_bnn) * 1e3, sum(t_proj) * 1e3, sum(t_pr) * 1e3,
-                                                sum(t_pc) * 1e3, ms_per_step * 1e3, ms_per_step_bnn * 1e3), file=sys.stderr)
-    print("the same sub-bit layers as dense FP4 contractions (snn_subbit_conv2d_dense), per layer, us, with / without "
-          "the weight expansion kernel: " + " ".join("%.1f/%.1f" % (a * 1e3, b * 1e3) for a, b in zip(t_dense, t_dense_k)),
-          file=sys.stderr)
-    if ms_per_step_dense is not None:
-        print("dense step (pack channels + dense conv per layer; the indices are given, no projection): %.1f us, with prepared weights %.1f us; dense conv "
-              "calls alone: %.1f us, prepared %.1f us" % (ms_per_step_dense * 1e3, ms_per_step_dense_inference * 1e3,
-                                                         sum(t_dense) * 1e3, sum(t_dense_k) * 1e3), file=sys.stderr)
-    print("step as one snn_subbit_forward per layer: %.1f us" % (ms_per_step_forward_calls * 1e3), file=sys.stderr)
-    print("step as three separate calls per layer: %.1f us" % (ms_per_step_separate * 1e3), file=sys.stderr)
-    print("inference step (weights prepared once; pack + conv per layer): %.1f us; conv kernels alone: %.1f us" % (
-        ms_per_step_inference * 1e3, sum(t_kern) * 1e3), file=sys.stderr)
+            L.name, L.pixels, L.C_in, L.C_out, L.K, a, b, b / a, c, d, e), file=sys.stderr)
+    print("sums of per-layer launches: subbit %.1f us, bnn %.1f us, project %.1f us, pack rows %.1f us, pack channels %.1f us"
+          % (sum(t_kern), sum(t_bnn), sum(t_proj), sum(t_pr), sum(t_pc)), file=sys.stderr)
+    print("all convolutions in one launch: %.1f us inside the step, %.1f us back to back, %.1f us cold; prepare_many %.1f us"
+          % (t_conv_in_step_us, t_convs_b2b, t_convs_cold, t_prep_many), file=sys.stderr)
+    print("step %.1f us (with one convolution launch per layer: %.1f us); inference step %.1f us; 1-bit step %.1f us"
+          % (ms_per_step * 1e3, ms_per_step_per_layer * 1e3, ms_per_step_inference * 1e3, ms_per_step_bnn * 1e3), file=sys.stderr)
+    if extras:
+        print("step as one snn_subbit_forward per layer: %.1f us; as three separate calls per layer: %.1f us"
+              % (ms_per_step_forward_calls * 1e3, ms_per_step_separate * 1e3), file=sys.stderr)
+        print("dense FP4 context: step %.1f us, prepared %.1f us; conv calls %.1f us, prepared %.1f us"
+              % (ms_per_step_dense * 1e3, ms_per_step_dense_inference * 1e3, sum(t_dense), sum(t_dense_k)), file=sys.stderr)
     if chained is not None:
-        print("chained 1-bit stack (prepare_many + conv_sign per layer): %.1f us; with prepared weights: %.1f us; the "
-              "same through the dense contraction (prepared weights): %.1f us" % (
-                  chained["ms_per_step"] * 1e3, chained["ms_per_step_inference"] * 1e3,
-                  chained["ms_per_step_inference_dense_context"] * 1e3), file=sys.stderr)
+        print("chained 1-bit stack: %.1f us; prepared weights: %.1f us; through the dense contraction (prepared): %.1f us"
+              % (chained["ms_per_step"] * 1e3, chained["ms_per_step_inference"] * 1e3,
+                 chained["ms_per_step_inference_dense_context"] * 1e3), file=sys.stderr)
+
+    # ---- the other workloads -------------------------------------------------------------------------------
+    configs = None
+    if extras and not args.no_configs and args.workload == "resnet18" and not args.layer:
+        configs = run_configs(bn, args, peaks, oracle)
+        for r in configs:
+            print("config %d %-22s K=%-3d conv %8.1f us (cold %8.1f)  %9.0f GOPS-eq  vs 1-bit %s  frac %s" % (
+                r["config"], r["layer"], r["K"], r["conv_us"], r["conv_us_cold"], r["gops_eq"],
+                "%.2fx" % r["speedup_vs_bnn_conv"] if "speedup_vs_bnn_conv" in r else "  -  ",
+                "%.2f" % r["roofline"]["frac"] if "roofline" in r else "-"), file=sys.stderr)
 
     # ---- cpu_baseline: the oracle on a bounded sample of the same workload --------------------------------
     cpu = None
-    if not args.no_cpu:
-        import oracle
-        oracle.build()
+    if oracle is not None:
+        # refresh the headline outputs (the extra legs share buffers)
+        step()
+        torch.cuda.synchronize()
         n_img = 64 if args.workload == "resnet18" else 16
         t_cpu = 0.0
         ops_cpu = 0
         for s in st:
             L = s["L"]
-            x = s["x"][:n_img].cpu().numpy()
+            n = min(n_img, L.N)
+            x = s["x"][:n].cpu().numpy()
             w = s["w"].cpu().numpy()
             cb = s["cb"].cpu().numpy().view(np.uint16)
             alpha = s["alpha"].cpu().numpy()
@@ -605,12 +892,14 @@ def main():
             xs = oracle.sign(x)
             _, Y = oracle.conv_bin(xs, oracle.expand(cb, idx.reshape(L.C_out, L.C_in)), alpha, L.stride)
             t_cpu += time.perf_counter() - c0
-            ops_cpu += L.dense_ops // L.N * x.shape[0]
-            assert (s["y"][:n_img].cpu().numpy() == Y).all(), "GPU result differs from the oracle on " + L.name
-            # (s["yb"] was last written by the dense contraction of the same layer)
-            assert (s["yb"][:n_img].cpu().numpy() == Y).all(), "dense-path result differs from the oracle on " + L.name
+            ops_cpu += L.dense_ops // L.N * n
+            assert (idx.reshape(-1) == s["idx"].cpu().numpy().view(np.uint16)).all(), "projection differs from the oracle on " + L.name
+            assert (s["y"][:n].cpu().numpy() == Y).all(), "GPU result differs from the oracle on " + L.name
         if chained is not None:
             # the chain, first two images, layer by layer against the oracle (images are independent)
+            step_chained()
+            step_chained_dense()
+            torch.cuda.synchronize()
             xs = oracle.sign(st[0]["x"][:2].cpu().numpy())
             for s in st:
                 L = s["L"]
@@ -625,8 +914,9 @@ def main():
                 assert (got_c == want_c).all(), "chained dense-path result differs from the oracle on " + L.name
             chained["checked"] = "first 2 images of every layer's packed output equal the oracle's chain"
         cpu = {"value": ops_cpu / t_cpu / 1e9, "unit": "GOPS-equivalent", "cores": oracle.threads(), "kind": "oracle",
-               "sample": "same %d layers, first %d images of the batch (project + sign + direct conv), %.1f s" % (
-                   len(layers), min(n_img, layers[0].N), t_cpu)}
+               "sample": "same %d layers, all kernels projected, first %d images of the batch (project + sign + direct conv), "
+                         "%.1f s; the GPU's indices and those images' outputs equal the oracle's bit for bit" % (
+                             len(layers), min(n_img, layers[0].N), t_cpu)}
 
     result = {
         "metric": "sub-bit 3x3 conv GOPS-equivalent (2*9*C_in*C_out*N*H_out*W_out per layer / step time) and "
@@ -640,43 +930,42 @@ def main():
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "u8",
+        "dtype": "fp4 x fp6 -> f32 (exact integers; one f32 multiply by alpha)",
         "data": "synthetic",
         "config": {"workload": wname,
-                   "step": "snn_subbit_project_prepare_many (projection + tables of all layers, one launch), then per layer "
-                           "snn_pack_activations + snn_subbit_conv2d_prepared"},
+                   "step": "snn_subbit_project_prepare_many (projection + tables of all layers, one launch), one "
+                           "snn_pack_activations per layer, snn_subbit_conv2d_prepared_many (the convolutions of all layers, "
+                           "one launch)" if many_ok else
+                           "snn_subbit_project_prepare_many, then per layer snn_pack_activations + snn_subbit_conv2d_prepared"},
+        "ms_per_step_conv_launch_per_layer": ms_per_step_per_layer,
         "ms_per_step_forward_calls": ms_per_step_forward_calls,
-        "forward_calls_step": "one snn_subbit_forward per layer (front kernel + convolution)",
         "ms_per_step_separate_calls": ms_per_step_separate,
         "ms_per_step_inference": ms_per_step_inference,
-        "inference_step": "weights prepared once (snn_subbit_prepare); per layer snn_pack_activations + snn_subbit_conv2d_prepared",
-        "conv_kernel_us_per_layer": [t * 1e3 for t in t_kern],
-        "conv_only_gops_eq": dense_ops / sub_s / 1e9,
-        "bnn_conv_only_gops_eq": dense_ops / (sum(t_bnn) * 1e-3) / 1e9,
-        "speedup_vs_bnn_conv": sum(t_bnn) / sum(t_sub),
+        "inference_step": "weights prepared once; one snn_pack_activations per layer + the convolution launch",
+        "conv_us_in_step": t_conv_in_step_us,
+        "conv_only_gops_eq": dense_ops / (t_conv_in_step_us * 1e-6) / 1e9,
+        "conv_kernel_us_per_layer_launches": t_kern,
+        "bnn_conv_us_per_layer": t_bnn,
+        "bnn_conv_only_gops_eq": dense_ops / (sum(t_bnn) * 1e-6) / 1e9,
+        "speedup_vs_bnn_conv": sum(t_bnn) / t_conv_in_step_us,
+        "speedup_vs_bnn_conv_cold": t_bnn_cold / t_convs_cold,
         "speedup_vs_bnn_step": ms_per_step_bnn / ms_per_step,
         "bnn_ms_per_step": ms_per_step_bnn,
-        "breakdown_us": {"subbit_conv": sum(t_sub) * 1e3, "bnn_conv": sum(t_bnn) * 1e3, "project": sum(t_proj) * 1e3,
-                         "pack_rows": sum(t_pr) * 1e3, "pack_channels": sum(t_pc) * 1e3},
-        "training_side_us": {"project_backward": sum(t_pb) * 1e3, "subset_update": sum(t_su) * 1e3,
-                             "project_backward_GBps": bwd_bytes / (sum(t_pb) * 1e-3) / 1e9 if sum(t_pb) > 0 else None,
-                             "note": "per-call HIP-event times summed over the layers (each includes ~8 us of event and "
-                                     "launch overhead); Alg. 1 backward lines, outside the step"},
+        "breakdown_us": {"subbit_conv_one_launch": t_conv_in_step_us, "subbit_conv_per_layer_launches": sum(t_kern),
+                         "project_prepare_many": t_prep_many, "bnn_conv": sum(t_bnn), "project": sum(t_proj),
+                         "pack_rows": sum(t_pr), "pack_channels": sum(t_pc)},
+        "training_side": training,
         "chained_1bit_stack": chained,
-        "dense_fp4_context": {
+        "dense_fp4_context": None if not extras else {
             "what": "the same sub-bit layers (subset + indices) through snn_subbit_conv2d_dense: kernels looked up and "
                     "expanded by a preparation kernel, then a dense FP4 contraction on the matrix cores without the "
-                    "sharing of Sec. 4.5; context, not the paper's method.  ms_per_step = pack channels + the one-call dense "
-                    "convolution per layer with the indices given (unlike the headline step it does not project the "
-                    "real-valued kernels); ms_per_step_inference = pack channels + the prepared convolution per layer, "
-                    "to be compared with the top-level ms_per_step_inference",
+                    "sharing of Sec. 4.5; context, not the paper's method",
             "ms_per_step": ms_per_step_dense, "ms_per_step_inference": ms_per_step_dense_inference,
-            "conv_us": sum(t_dense) * 1e3, "conv_prepared_us": sum(t_dense_k) * 1e3,
-            "conv_us_per_layer": [v * 1e3 for v in t_dense],
-            "conv_prepared_us_per_layer": [v * 1e3 for v in t_dense_k],
-            "subbit_over_dense_conv": sum(t_sub) / sum(t_dense),
-            "subbit_over_dense_conv_prepared": sum(t_kern) / sum(t_dense_k)},
+            "conv_us": sum(t_dense), "conv_prepared_us": sum(t_dense_k),
+            "conv_prepared_us_per_layer": t_dense_k,
+            "subbit_over_dense_conv_prepared": t_conv_in_step_us / sum(t_dense_k)},
         "conv1x1_resnet50_shapes": conv1x1,
+        "configs": configs,
         "roofline": roofline,
         "cpu_baseline": cpu,
     }

@@ -60,6 +60,27 @@ constexpr int ST_LDS_BYTES = ST_RUNS_OFF + ST_MAX_RUNS * 8;
 static_assert(ST_ALPHA_OFF % 16 == 0 && ST_CORR_OFF % 16 == 0 && ST_OUT_OFF % 16 == 0 && ST_RUNS_OFF % 8 == 0, "aligned LDS accesses");
 static_assert(ST_WORKERS_PER_CU * ST_LDS_BYTES <= 160 * 1024, "all workers of a compute unit fit its LDS");
 
+// Division by a divisor fixed per layer (1 <= d < 2^31) of numerators below 2^31: q = mulhi(n, mul) >> shift with
+// mul = floor(2^(31 + s) / d) + 1, s = ceil(log2 d), shift = s - 1 (exact: mul * d - 2^(31 + s) is in (0, 2^s]);
+// d = 1 is mul = 0.  The kernel's per-tile set-up is a dozen divisions by H_out * W_out, W_out, H and the
+// number of channel tiles; the generic sequence costs forty instructions each.
+struct Divisor {
+    uint32_t mul, shift;
+};
+
+inline Divisor make_divisor(uint32_t d)
+{
+    if (d <= 1u) return {0u, 0u};
+    uint32_t s = 0;
+    while ((1ull << s) < d) ++s;
+    return {(uint32_t)((1ull << (31 + s)) / d) + 1u, s - 1u};
+}
+
+__device__ __forceinline__ uint32_t fast_div(uint32_t n, const Divisor &d)
+{
+    return d.mul ? __umulhi(n, d.mul) >> d.shift : n;
+}
+
 struct StackLayer {
     const uint32_t *x;        // packed rows [N][C_in][H][WW]
     const uint32_t *lut;      // table images: [512][6] words (row = window, 32 FP6 values m_k - 4), then the split image
@@ -70,12 +91,15 @@ struct StackLayer {
     int N, C_in, C_out, H, W, stride, Ho, Wo, HoWo, WW, P;
     int COP, npairs, n_cotiles, n_pxblocks;
     int variant;
+    Divisor div_HoWo, div_Wo, div_H, div_cotiles;
 };
 
 // Items [run_first_item[r], run_first_item[r + 1]) are tiles run_first_tile[r] ... of layer run_layer[r].
 struct StackParams {
     uint32_t *sched;          // [0] next item, [1] workers that have left; both zero before and after a launch
     int n_runs, n_items, n_workers;
+    int n_matrix_items;       // items are dealt from two lists in proportion: [0, n_matrix_items) and the rest of the run table
+    uint32_t deal_ratio;      // ceil(2^32 * (n_items - n_matrix_items) / n_items); 0: one list only
     int run_first_item[ST_MAX_RUNS + 1];
     int run_first_tile[ST_MAX_RUNS];
     unsigned char run_layer[ST_MAX_RUNS];
@@ -106,8 +130,9 @@ __device__ __forceinline__ void stack_tile(const StackLayer &layer, const int ti
     int lane = threadIdx.x;
     asm volatile("" : "+v"(lane));
     const int n_l = lane & 31, h = lane >> 5;
-    const int co_tile = tile % L.n_cotiles;
-    const int blk0 = (tile / L.n_cotiles) * PB;    // first pixel block of the tile
+    const int px_tile = (int)fast_div((uint32_t)tile, L.div_cotiles);
+    const int co_tile = tile - px_tile * L.n_cotiles;
+    const int blk0 = px_tile * PB;                 // first pixel block of the tile
     const int co0 = co_tile * NCH;
 
     // Requested first, stored to LDS once the loop's first loads are under way: the layer's table if the
@@ -140,9 +165,9 @@ __device__ __forceinline__ void stack_tile(const StackLayer &layer, const int ti
             ok = false;
             pp = L.P - 1;
         }
-        n = pp / L.HoWo;
+        n = (int)fast_div((uint32_t)pp, L.div_HoWo);
         const int r = pp - n * L.HoWo;
-        ho = r / L.Wo;
+        ho = (int)fast_div((uint32_t)r, L.div_Wo);
         wo = r - ho * L.Wo;
         return ok;
     };
@@ -167,7 +192,7 @@ __device__ __forceinline__ void stack_tile(const StackLayer &layer, const int ti
         const int hc0 = ho0 * L.stride;
         R_first = n0 * L.H + (hc0 == 0 ? 0 : hc0 - 1);
         const int R = R_first + n_l / SW, piece = n_l % SW;
-        const int n = R / L.H, hr = R - n * L.H;
+        const int n = (int)fast_div((uint32_t)R, L.div_H), hr = R - n * L.H;
         if (n < L.N) goff = (uint32_t)(((n * L.C_in + h) * L.H + hr) * L.WW + (piece == 2 ? 1 : 0)) * 4u;
         gshift = piece == 1 ? 16u : 0u;
     }
@@ -456,8 +481,10 @@ __device__ __forceinline__ void stack_tile(const StackLayer &layer, const int ti
     // The worker's next item is drawn here: the counter's old value arrives while the outputs are finished.
     // (An instruction written out by hand: the compiler's own form waits for the value right away.  It is
     // looked at after an explicit wait at the end of the item; an instruction the compiler does not know
-    // to be outstanding only makes its own waits longer.)
-    if (threadIdx.x == 0) asm volatile("global_atomic_add %0, %1, %2, %3 sc0" : "=v"(drawn) : "v"(0), "v"(1u), "s"(sched) : "memory");
+    // to be outstanding only makes its own waits longer.  Drawing earlier, at the start of the loop, was
+    // measured and loses: the workers' first tiles start together, two thousand additions to one word take
+    // some ten microseconds, and every load of the loop queues behind the addition it follows.)
+    if (threadIdx.x == 0) asm volatile("global_atomic_add %0, %1, %2, %3 sc0" : "+v"(drawn) : "v"(0), "v"(1u), "s"(sched) : "memory");
 
     // ---- finishing: S = 2 M + negcorr[type][channel], y = float(S) * alpha[channel] -------------------
     // Register r of a block: output channel 8 (r / 4) + 4 h + r % 4, pixel n_l.  The lane reads alpha
@@ -580,11 +607,21 @@ void subbit_stack_kernel(const StackParams sp)
     uint32_t drawn = 0;
     for (;;) {
         if (item >= (uint32_t)sp.n_items) break;
+        // Position in the run table.  The table lists the tiles bound by the matrix pipe first, then those bound
+        // by LDS; the items deal from both lists in proportion, so that at any time a compute unit holds waves
+        // of both kinds: with j(i) = mulhi(i, deal_ratio) - monotone, steps of at most one, j(n_items) = size
+        // of the second list - item i is entry j(i) of the second list where j steps up, else entry i - j(i)
+        // of the first.
+        uint32_t pos = item;
+        if (sp.deal_ratio != 0u) {
+            const uint32_t j0 = __umulhi(item, sp.deal_ratio), j1 = __umulhi(item + 1u, sp.deal_ratio);
+            pos = j1 > j0 ? (uint32_t)sp.n_matrix_items + j0 : item - j0;
+        }
         const u32x2 run = *(lds_cu32x2 *)(uintptr_t)(lds0 + ST_RUNS_OFF + (uint32_t)lane * 8u);
-        const int r = __builtin_popcountll(__ballot((int)item >= (int)run.x)) - 1;    // the last run that starts at or before the item
+        const int r = __builtin_popcountll(__ballot((int)pos >= (int)run.x)) - 1;      // the last run that starts at or before it
         const uint32_t rt = (uint32_t)__builtin_amdgcn_readlane((int)run.y, r);
         const int l = (int)(rt >> 24);
-        const int tile = (int)(rt & 0xffffffu) + ((int)item - __builtin_amdgcn_readlane((int)run.x, r));
+        const int tile = (int)(rt & 0xffffffu) + ((int)pos - __builtin_amdgcn_readlane((int)run.x, r));
         const StackLayer &L = sp.layer[l];
         const bool new_layer = l != cur_layer;
         cur_layer = l;
@@ -654,6 +691,7 @@ int launch_subbit_stack(int n_layers, const Geom *gs, const void *const *x, floa
         int layer;
         long long tiles;
         long long weight;     // matrix instructions per tile
+        bool lds_bound;       // two channel blocks per wave
     };
     std::vector<Item> order;
     long long total = 0;
@@ -671,17 +709,25 @@ int launch_subbit_stack(int n_layers, const Geom *gs, const void *const *x, floa
         L.Ho = g.Ho; L.Wo = g.Wo; L.HoWo = g.HoWo; L.WW = g.WW; L.P = (int)g.P;
         L.COP = pl.COP; L.npairs = pl.npairs; L.n_cotiles = pl.n_cotiles; L.n_pxblocks = (int)pl.n_pxblocks;
         L.variant = stack_variant(pl, g);
+        L.div_HoWo = make_divisor((uint32_t)g.HoWo);
+        L.div_Wo = make_divisor((uint32_t)g.Wo);
+        L.div_H = make_divisor((uint32_t)g.H);
+        L.div_cotiles = make_divisor((uint32_t)pl.n_cotiles);
         if (L.variant < 0) return SNN_ERR_UNSUPPORTED;
-        order.push_back({l, pl.n_tiles, (long long)pl.npairs * pl.cfg.PB * pl.cfg.CB});
+        order.push_back({l, pl.n_tiles, (long long)pl.npairs * pl.cfg.PB * pl.cfg.CB, pl.cfg.CB == 2});
         total += pl.n_tiles;
     }
     if (total > 0x7fffffffLL) return SNN_ERR_UNSUPPORTED;
-    // Order of the items.  A worker's first item is its own number and workers w and w + n / 2 tend to
-    // share a SIMD, so the first half of the first n items are the longest tiles and the second half
-    // the shortest ones: a wave in a long matrix loop then sits next to one that goes through short
-    // tiles and their stores, instead of all waves finishing their first tile at the same moment.
-    // Everything else follows longest first (the queue is dynamic: the last items handed out are short).
-    std::stable_sort(order.begin(), order.end(), [](const Item &a, const Item &b) { return a.weight > b.weight; });
+    // Order of the items: two lists, each longest tile first - the layers whose tiles are bound by the matrix
+    // pipe (four channel blocks per wave: one table row feeds four matrix instructions) and those bound by LDS
+    // (two channel blocks: a row per two instructions, plus the staged input rows).  The kernel deals items from
+    // both in proportion, so that waves of both kinds share every compute unit for the whole launch instead of
+    // the LDS-bound layers running by themselves at the end.  The queue is dynamic; the last items are the
+    // shortest of their lists.
+    std::stable_sort(order.begin(), order.end(), [](const Item &a, const Item &b) {
+        if (a.lds_bound != b.lds_bound) return !a.lds_bound;
+        return a.weight > b.weight;
+    });
     const long long want = (long long)device_compute_units() * ST_WORKERS_PER_CU;
     const long long n_workers = std::min<long long>(want, total);
     struct Run {
@@ -689,24 +735,13 @@ int launch_subbit_stack(int n_layers, const Geom *gs, const void *const *x, floa
         long long t0, n;
     };
     std::vector<Run> runs;
-    std::vector<long long> head(order.size(), 0), tail(order.size());      // tiles [head, tail) of each layer are not handed out yet
-    for (size_t i = 0; i < order.size(); ++i) tail[i] = order[i].tiles;
-    long long left = n_workers / 2;
-    for (size_t i = 0; i < order.size() && left > 0; ++i) {                 // the longest
-        const long long n = std::min(left, tail[i] - head[i]);
-        if (n > 0) runs.push_back({order[i].layer, head[i], n});
-        head[i] += n;
-        left -= n;
+    long long n_matrix = 0;
+    for (const Item &it : order) {
+        runs.push_back({it.layer, 0, it.tiles});
+        if (!it.lds_bound) n_matrix += it.tiles;
     }
-    left = n_workers - n_workers / 2;
-    for (size_t i = order.size(); i-- > 0 && left > 0;) {                   // the shortest, taken from the end of their layers
-        const long long n = std::min(left, tail[i] - head[i]);
-        if (n > 0) runs.push_back({order[i].layer, tail[i] - n, n});
-        tail[i] -= n;
-        left -= n;
-    }
-    for (size_t i = 0; i < order.size(); ++i)
-        if (tail[i] > head[i]) runs.push_back({order[i].layer, head[i], tail[i] - head[i]});
+    sp.n_matrix_items = (int)n_matrix;
+    sp.deal_ratio = n_matrix == 0 || n_matrix == total ? 0u : (uint32_t)((((unsigned long long)(total - n_matrix) << 32) + total - 1) / total);
     if ((int)runs.size() > ST_MAX_RUNS) return SNN_ERR_UNSUPPORTED;
     int n_runs = 0;
     long long first = 0;

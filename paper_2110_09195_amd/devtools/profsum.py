@@ -1,6 +1,6 @@
 """Summarise a rocprofv3 kernel trace (the rocpd SQLite file it writes) as text.
 
-    python -m paper_2110_09195_amd.profsum gpurun_out/prof/x_results.db > profiles/<name>.txt
+    python -m paper_2110_09195_amd.devtools.profsum gpurun_out/prof/x_results.db > profiles/<name>.txt
 
 Prints, per kernel name: launches, average / min / max duration in microseconds and the
 share of total kernel time.  Used to produce the summaries under profiles/.
