@@ -13,7 +13,7 @@ WANTED = ("subbit_", "bnn_", "pack_", "dense_", "copy_kernel", "project")
 
 
 def short(name):
-    return name.replace("void ", "").replace("snn::(anonymous namespace)::", "").replace("snn::", "").split("(")[0]
+    return name.replace("void ", "").replace("(anonymous namespace)::", "").replace("snn::", "").split("(")[0]
 
 
 def main(paths, out=sys.stdout):
