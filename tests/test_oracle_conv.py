@@ -215,15 +215,17 @@ def test_two_stage_equals_direct_bin(oracle, stride):
     assert (S1 == S2).all() and (Y1 == Y2).all()
 
 
-def test_two_stage_equals_direct_f32(oracle):
-    g = np.random.default_rng(23)
+@pytest.mark.parametrize("stride", [1, 2])
+def test_two_stage_equals_direct_f32(oracle, stride):
+    g = np.random.default_rng(23 + stride)
     K, C_in, C_out = 16, 12, 10
-    x = g.standard_normal((2, C_in, 8, 8)).astype(np.float32)
+    x = g.standard_normal((2, C_in, 9, 8)).astype(np.float32)
     codebook = np.sort(g.choice(512, size=K, replace=False)).astype(np.uint16)
     idx = g.integers(0, K, size=(C_out, C_in)).astype(np.uint16)
     alpha = g.uniform(0.5, 1.5, size=C_out).astype(np.float32)
-    S1, _ = oracle.conv_f32(x, oracle.expand(codebook, idx), alpha, 1)
-    S2, _ = oracle.two_stage_f32(x, codebook, idx, alpha, 1)
+    S1, _ = oracle.conv_f32(x, oracle.expand(codebook, idx), alpha, stride)
+    S2, _ = oracle.two_stage_f32(x, codebook, idx, alpha, stride)
+    assert S1.shape == S2.shape == (2, C_out, (9 - 1) // stride + 1, (8 - 1) // stride + 1)
     rms = np.sqrt((S1 ** 2).mean())
     assert np.abs(S1 - S2).max() <= 1e-12 * rms * 100
 
