@@ -8,7 +8,7 @@ One "step" is one pass of the whole path over one batch of synthetic input, i.e.
 Alg. 1 for every 3x3 layer of the workload:
   * project the real-valued kernels of all layers onto their subsets and build the convolution's tables
     (Eq. 2 / Eq. 5; one launch, snn_subbit_project_prepare_many),
-  * binarise and pack each layer's fp32 input (snn_pack_activations, one launch per layer),
+  * binarise and pack every layer's fp32 input (one launch, snn_pack_activations_many),
   * the sub-bit convolutions of all layers (Sec. 4.5: stage 1, stage 2, alpha scaling; one launch,
     snn_subbit_conv2d_prepared_many).
 Inputs are resident in HBM before the timed region.  The same layers then run through the library's 1-bit
@@ -49,8 +49,9 @@ COPY_CAL_BYTES = 256 * 1024 * 1024           # the copy probe of the counter pas
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=100,
+                    help="untimed steps before each timed region (the chip needs some 25 ms of this work to settle its clocks)")
     ap.add_argument("--workload", default="resnet18", choices=["resnet18", "cfg3", "cfg4", "cfg1"])
     ap.add_argument("--K", type=int, default=32)
     ap.add_argument("--layer", default=None, help="one custom layer instead of a workload: N,C_in,C_out,H,W,stride")
@@ -558,7 +559,6 @@ def main():
         import oracle
         oracle.build()
 
-    peaks = measured_peaks(torch, np)
     layers, wname, cfg_no = workload_of(args, synth)
     extras = not args.headline_only
 
@@ -600,9 +600,9 @@ def main():
         B.snn_subbit_forward(s["d_sub"], s["x"], s["w"], s["cb"], s["alpha"], idx_out=s["idx"].view(L.C_out, L.C_in),
                              y=s["y"], workspace=s["ws_fwd"])
 
-    # The headline step: the weights-side work of all layers in ONE launch (projection + tables), per layer sign/pack,
-    # then the convolutions of all layers in ONE launch.  A pair of events on the launch stream brackets the convolution
-    # launch inside the timed steps: their average is the kernel time the roofline uses.
+    # The headline step, three launches: sign/pack of all layers' inputs, the weights-side work of all layers (projection +
+    # tables), the convolutions of all layers.  For the roofline the same steps run a second time with a pair of events
+    # on the launch stream around the convolution launch: their average is the kernel time it uses.
     prep_arr = B.layer_weights_array([{"desc": s["d_sub"], "w": s["w"], "codebook": s["cb"], "alpha": s["alpha"],
                                        "idx_out": s["idx"], "workspace": s["ws_sub"]} for s in st])
     many_ok = all(B.snn_subbit_slots_per_channel(s["d_sub"]) > 0 for s in st)
@@ -616,10 +616,23 @@ def main():
             for s in st:
                 conv_prepared(s)
 
+    # the same step as ONE call (snn_subbit_forward_many: the same three launches; its own workspaces and outputs)
+    fwd_many = None
+    if many_ok:
+        fwd_arr = B.layer_forward_array([{"desc": s["d_sub"], "x": s["x"], "w": s["w"], "codebook": s["cb"], "alpha": s["alpha"],
+                                          "idx_out": s["idx"], "y": s["y"], "workspace": s["ws_fwd"]} for s in st])
+
+        def fwd_many():
+            B.snn_subbit_forward_many(fwd_arr)
+
+    pack_arr = B.pack_item_array([(s["x"], s["xr"], B.SNN_ACT_BIN_ROWS) for s in st])
+
     def step(timed=False):
+        if not timed and fwd_many is not None:
+            fwd_many()                      # the same three launches as one call
+            return
+        B.snn_pack_activations_many(pack_arr)
         B.snn_subbit_project_prepare_many(prep_arr)
-        for s in st:
-            pack_rows(s)
         if timed:
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             e0.record()
@@ -634,6 +647,12 @@ def main():
         for s in st:
             pack_rows(s)
             conv_prepared(s)
+
+    def step_pack_per_layer():
+        B.snn_subbit_project_prepare_many(prep_arr)
+        for s in st:
+            pack_rows(s)
+        convs()
 
     def step_forward_calls():
         for s in st:
@@ -651,8 +670,7 @@ def main():
             conv_bnn(s)
 
     def step_inference():
-        for s in st:
-            pack_rows(s)
+        B.snn_pack_activations_many(pack_arr)
         convs()
 
     def step_dense():
@@ -680,15 +698,37 @@ def main():
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        step(timed=True)
+        step()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
+    # the same K steps once more with a pair of HIP events around the convolution launch of every step (kept out of
+    # the region above: an event pair costs the step some 15 us)
+    for _ in range(args.steps):
+        step(timed=True)
+    torch.cuda.synchronize()
     in_step = sorted(a.elapsed_time(b) * 1e3 for a, b in ev)
     t_conv_in_step_us = sum(in_step) / len(in_step)
 
     ms_per_step_bnn = bn.host_ms(step_bnn, args.warmup, args.steps)
     ms_per_step_per_layer = bn.host_ms(step_per_layer_launches, args.warmup, args.steps)
+    ms_per_step_pack_per_layer = bn.host_ms(step_pack_per_layer, args.warmup, args.steps)
+    ms_per_step_three_calls = None
+    if fwd_many is not None:
+        def three_calls():
+            B.snn_pack_activations_many(pack_arr)
+            B.snn_subbit_project_prepare_many(prep_arr)
+            convs()
+        ms_per_step_three_calls = bn.host_ms(three_calls, args.warmup, args.steps)
+        torch.cuda.synchronize()
+        want = [(s["y"].clone(), s["idx"].clone()) for s in st]
+        for s in st:
+            s["y"].fill_(float("nan"))
+        fwd_many()
+        torch.cuda.synchronize()
+        for s, (y3, i3) in zip(st, want):
+            assert torch.equal(s["y"], y3) and torch.equal(s["idx"], i3), "forward_many differs from the three calls on " + s["L"].name
+        del want
     ms_per_step_inference = bn.host_ms(step_inference, args.warmup, args.steps)
     ms_per_step_forward_calls = ms_per_step_separate = ms_per_step_dense = ms_per_step_dense_inference = None
     if extras:
@@ -751,8 +791,12 @@ def main():
                    "step": "snn_subbit_project_prepare_many (projection + thresholds + tables of all layers), pack the first "
                            "input, then one snn_subbit_conv2d_sign_prepared per layer: 1-bit activations from layer to layer"}
 
+    # the yardsticks (after the timed regions: the matrix probes heat the chip, and what runs right after them
+    # runs at a lower clock for a while)
+    peaks = measured_peaks(torch, np)
+
     # ---- per-call device time with HIP events on the launch stream ---------------------------------------
-    reps = max(10, args.steps)
+    reps = max(10, min(args.steps, 30))
     # restore what the steps above may have left in the buffers the checks read
     step()
     for s in st:
@@ -767,6 +811,7 @@ def main():
     t_convs_each = bn.event_each_us(convs, reps)
     t_convs_cold = bn.cold_us(convs)
     t_prep_many = bn.event_avg_us(lambda: B.snn_subbit_project_prepare_many(prep_arr), reps)
+    t_pack_many = bn.event_avg_us(lambda: B.snn_pack_activations_many(pack_arr), reps)
     t_kern = [bn.event_avg_us(lambda s=s: conv_prepared(s), reps) for s in st]      # one launch per layer, for comparison
     t_bnn = [bn.event_avg_us(lambda s=s: conv_bnn(s), reps) for s in st]
     t_proj = [bn.event_avg_us(lambda s=s: project(s), reps) for s in st]
@@ -826,8 +871,8 @@ def main():
     if many_ok:
         roofline = conv_roofline(layers, slots, t_conv_in_step_us * 1e-6, peaks, accounting)
         roofline["kernel"] = ("subbit_stack_kernel: ONE launch per step runs the convolutions of all %d layers (resident workers of "
-                              "one wave draw (layer, tile) items); t_kernel = average over the %d timed steps of a HIP-event pair "
-                              "around that launch, on the launch stream" % (len(layers), args.steps))
+                              "one wave draw (layer, tile) items); t_kernel = average over %d steps (the timed steps run a second time) of a "
+                              "HIP-event pair around that launch, on the launch stream" % (len(layers), args.steps))
         roofline["t_kernel_us_back_to_back"] = t_convs_b2b
         roofline["t_kernel_us_single_launch_median"] = t_convs_each[len(t_convs_each) // 2]
         roofline["t_kernel_us_single_launch_min"] = t_convs_each[0]
@@ -847,10 +892,13 @@ def main():
             L.name, L.pixels, L.C_in, L.C_out, L.K, a, b, b / a, c, d, e), file=sys.stderr)
     print("sums of per-layer launches: subbit %.1f us, bnn %.1f us, project %.1f us, pack rows %.1f us, pack channels %.1f us"
           % (sum(t_kern), sum(t_bnn), sum(t_proj), sum(t_pr), sum(t_pc)), file=sys.stderr)
-    print("all convolutions in one launch: %.1f us inside the step, %.1f us back to back, %.1f us cold; prepare_many %.1f us"
-          % (t_conv_in_step_us, t_convs_b2b, t_convs_cold, t_prep_many), file=sys.stderr)
-    print("step %.1f us (with one convolution launch per layer: %.1f us); inference step %.1f us; 1-bit step %.1f us"
-          % (ms_per_step * 1e3, ms_per_step_per_layer * 1e3, ms_per_step_inference * 1e3, ms_per_step_bnn * 1e3), file=sys.stderr)
+    print("all convolutions in one launch: %.1f us inside the step, %.1f us back to back, %.1f us cold; prepare_many %.1f us; "
+          "pack_many %.1f us" % (t_conv_in_step_us, t_convs_b2b, t_convs_cold, t_prep_many, t_pack_many), file=sys.stderr)
+    print("step %.1f us (as three calls: %s us; with one pack launch per layer: %.1f us; with one pack and one "
+          "convolution launch per layer: %.1f us); inference step %.1f us; 1-bit step %.1f us"
+          % (ms_per_step * 1e3, "%.1f" % (ms_per_step_three_calls * 1e3) if ms_per_step_three_calls else "-",
+             ms_per_step_pack_per_layer * 1e3, ms_per_step_per_layer * 1e3, ms_per_step_inference * 1e3, ms_per_step_bnn * 1e3),
+          file=sys.stderr)
     if extras:
         print("step as one snn_subbit_forward per layer: %.1f us; as three separate calls per layer: %.1f us"
               % (ms_per_step_forward_calls * 1e3, ms_per_step_separate * 1e3), file=sys.stderr)
@@ -933,15 +981,17 @@ def main():
         "dtype": "fp4 x fp6 -> f32 (exact integers; one f32 multiply by alpha)",
         "data": "synthetic",
         "config": {"workload": wname,
-                   "step": "snn_subbit_project_prepare_many (projection + tables of all layers, one launch), one "
-                           "snn_pack_activations per layer, snn_subbit_conv2d_prepared_many (the convolutions of all layers, "
-                           "one launch)" if many_ok else
+                   "step": "one snn_subbit_forward_many call = three launches: sign + pack of all layers' inputs "
+                           "(snn_pack_activations_many), projection + tables of all layers (snn_subbit_project_prepare_many), "
+                           "the convolutions of all layers (snn_subbit_conv2d_prepared_many)" if many_ok else
                            "snn_subbit_project_prepare_many, then per layer snn_pack_activations + snn_subbit_conv2d_prepared"},
-        "ms_per_step_conv_launch_per_layer": ms_per_step_per_layer,
+        "ms_per_step_three_calls": ms_per_step_three_calls,
+        "ms_per_step_pack_launch_per_layer": ms_per_step_pack_per_layer,
+        "ms_per_step_pack_and_conv_launch_per_layer": ms_per_step_per_layer,
         "ms_per_step_forward_calls": ms_per_step_forward_calls,
         "ms_per_step_separate_calls": ms_per_step_separate,
         "ms_per_step_inference": ms_per_step_inference,
-        "inference_step": "weights prepared once; one snn_pack_activations per layer + the convolution launch",
+        "inference_step": "weights prepared once; snn_pack_activations_many + the convolution launch",
         "conv_us_in_step": t_conv_in_step_us,
         "conv_only_gops_eq": dense_ops / (t_conv_in_step_us * 1e-6) / 1e9,
         "conv_kernel_us_per_layer_launches": t_kern,
@@ -952,7 +1002,7 @@ def main():
         "speedup_vs_bnn_step": ms_per_step_bnn / ms_per_step,
         "bnn_ms_per_step": ms_per_step_bnn,
         "breakdown_us": {"subbit_conv_one_launch": t_conv_in_step_us, "subbit_conv_per_layer_launches": sum(t_kern),
-                         "project_prepare_many": t_prep_many, "bnn_conv": sum(t_bnn), "project": sum(t_proj),
+                         "project_prepare_many": t_prep_many, "pack_many": t_pack_many, "bnn_conv": sum(t_bnn), "project": sum(t_proj),
                          "pack_rows": sum(t_pr), "pack_channels": sum(t_pc)},
         "training_side": training,
         "chained_1bit_stack": chained,

@@ -95,6 +95,21 @@ int snn_pack_activations(const float *x_nchw, void *packed, int N, int C, int H,
                          int layout, void *stream);
 
 /*
+ * snn_pack_activations for several tensors at once: the packed-rows items share launches (32 tensors each),
+ * packed-channels items get a launch of their own.  Results are those of one snn_pack_activations call per item.
+ * (The inputs of a stack of layers are mostly smaller than what the chip moves while a launch starts and drains.)
+ *   items[i].x_nchw  device, float [N][C][H][W];   items[i].packed  device, the packed tensor in items[i].layout
+ * Errors: INVALID_ARG (any item; nothing is enqueued); LAUNCH.
+ */
+typedef struct snn_pack_item {
+    const float *x_nchw;
+    void *packed;
+    int32_t N, C, H, W;
+    int32_t layout;
+} snn_pack_item;
+int snn_pack_activations_many(const snn_pack_item *items, int n_items, void *stream);
+
+/*
  * Eq. 2 / Eq. 5 / Alg. 1 forward: for each real-valued 3x3 kernel, the index of the nearest
  * member of the subset, arg min_k ||P_k - w||^2 = arg max_k <P_k, w> (all members have the
  * same norm).  The inner product is accumulated in fp32 from 0 over taps 0..8 in order,
@@ -285,6 +300,36 @@ typedef struct snn_layer_io {
     size_t ws_bytes;
 } snn_layer_io;
 int snn_subbit_conv2d_prepared_many(const snn_layer_io *layers, int n_layers, void *stream);
+
+/*
+ * Alg. 1 forward of a whole stack of independent layers in THREE launches: one binarises and packs every
+ * layer's fp32 input (snn_pack_activations_many), one projects every layer's real-valued kernels onto its subset
+ * (Eq. 2 / Eq. 5) and builds the convolution's tables (snn_subbit_project_prepare_many), the third is the launch
+ * of snn_subbit_conv2d_prepared_many over all layers.  (The first two are independent: a caller with two streams
+ * can issue these three calls itself and overlap them.)
+ * Results (idx_out, y_nchw) are those of one snn_subbit_forward call per layer, bit for bit.
+ *   layers[l].desc       host; act must be SNN_ACT_BIN_ROWS, K <= 64 (C_in >= 2 if K <= 32)
+ *   layers[l].x_nchw     device, float [N][C_in][H][W]
+ *   layers[l].w          device, float [C_out][C_in][9];   codebook  device, uint16 [K];   alpha  device, float [C_out]
+ *   layers[l].idx_out    device, uint16 [C_out][C_in], fully overwritten
+ *   layers[l].y_nchw     device, float [N][C_out][H_out][W_out], fully overwritten; outputs must not overlap
+ *   layers[l].workspace  device, >= snn_workspace_bytes(desc, SNN_WS_FORWARD) bytes, 256-byte aligned, one per layer;
+ *                        afterwards it holds the layer's tables and packed input (usable by the *_prepared calls)
+ * Errors: INVALID_ARG; UNSUPPORTED (a layer outside the matrix-core kernel); WORKSPACE; LAUNCH.  All layers are
+ * checked before anything is enqueued.
+ */
+typedef struct snn_layer_forward {
+    snn_conv_desc desc;
+    const float *x_nchw;
+    const float *w;
+    const uint16_t *codebook;
+    const float *alpha;
+    uint16_t *idx_out;
+    float *y_nchw;
+    void *workspace;
+    size_t ws_bytes;
+} snn_layer_forward;
+int snn_subbit_forward_many(const snn_layer_forward *layers, int n_layers, void *stream);
 
 /*
  * The same with the projection of the layer's real-valued kernels in front (Alg. 1 forward of a

@@ -29,12 +29,12 @@ SNN_WS_FORWARD = 2
 SNN_WS_CONV1X1 = 3
 SNN_WS_BNN_DENSE = 4
 
-EXPORTS = ("snn_pack_activations", "snn_project_kernels", "snn_subbit_conv2d", "snn_subbit_conv2d_noalloc", "snn_subbit_forward",
+EXPORTS = ("snn_pack_activations", "snn_pack_activations_many", "snn_project_kernels", "snn_subbit_conv2d", "snn_subbit_conv2d_noalloc", "snn_subbit_forward",
            "snn_subbit_prepare", "snn_subbit_conv2d_prepared", "snn_packed_index_bytes", "snn_pack_indices",
            "snn_subbit_prepare_packed", "snn_subbit_conv1x1", "snn_project_vectors8",
            "snn_subbit_conv2d_sign", "snn_subbit_forward_sign", "snn_subbit_prepare_sign",
            "snn_subbit_conv2d_sign_prepared", "snn_subbit_project_prepare_many", "snn_subbit_conv2d_prepared_many",
-           "snn_project_backward",
+           "snn_subbit_forward_many", "snn_project_backward",
            "snn_project_backward_workspace_bytes", "snn_subset_update", "snn_bnn_conv2d", "snn_bnn_conv2d_dense",
            "snn_subbit_conv2d_dense", "snn_dense_prepare", "snn_dense_conv2d_prepared",
            "snn_dense_conv2d_sign_prepared",
@@ -56,6 +56,17 @@ class snn_layer_weights(ctypes.Structure):
 
 class snn_layer_io(ctypes.Structure):
     _fields_ = [("desc", snn_conv_desc), ("x_packed", ctypes.c_void_p), ("y_nchw", ctypes.c_void_p),
+                ("workspace", ctypes.c_void_p), ("ws_bytes", ctypes.c_size_t)]
+
+
+class snn_pack_item(ctypes.Structure):
+    _fields_ = [("x_nchw", ctypes.c_void_p), ("packed", ctypes.c_void_p), ("N", ctypes.c_int32), ("C", ctypes.c_int32),
+                ("H", ctypes.c_int32), ("W", ctypes.c_int32), ("layout", ctypes.c_int32)]
+
+
+class snn_layer_forward(ctypes.Structure):
+    _fields_ = [("desc", snn_conv_desc), ("x_nchw", ctypes.c_void_p), ("w", ctypes.c_void_p), ("codebook", ctypes.c_void_p),
+                ("alpha", ctypes.c_void_p), ("idx_out", ctypes.c_void_p), ("y_nchw", ctypes.c_void_p),
                 ("workspace", ctypes.c_void_p), ("ws_bytes", ctypes.c_size_t)]
 
 
@@ -108,6 +119,10 @@ def lib():
         L.snn_subbit_project_prepare_many.restype = i32
         L.snn_subbit_conv2d_prepared_many.argtypes = [ctypes.POINTER(snn_layer_io), i32, vp]
         L.snn_subbit_conv2d_prepared_many.restype = i32
+        L.snn_pack_activations_many.argtypes = [ctypes.POINTER(snn_pack_item), i32, vp]
+        L.snn_pack_activations_many.restype = i32
+        L.snn_subbit_forward_many.argtypes = [ctypes.POINTER(snn_layer_forward), i32, vp]
+        L.snn_subbit_forward_many.restype = i32
         L.snn_subbit_forward_sign.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.snn_subbit_forward_sign.restype = i32
         L.snn_project_backward.argtypes = [vp, vp, vp, i64, i32, vp, vp, vp, sz, vp]
@@ -225,6 +240,27 @@ def snn_pack_activations(x, layout, out=None):
         raise ValueError("packed buffer too small")
     _check(lib().snn_pack_activations(_ptr(x), _ptr(out), N, C, H, W, layout, _stream()), "snn_pack_activations")
     return out
+
+
+def pack_item_array(items):
+    """items: list of (x float32 [N][C][H][W], out packed int32 tensor, layout) -> a ctypes array for
+    snn_pack_activations_many; build it once and reuse it (the tensors must stay alive)."""
+    arr = (snn_pack_item * len(items))()
+    for i, (x, out, layout) in enumerate(items):
+        _dev(x, torch.float32, "x")
+        _dev(out, torch.int32, "out")
+        N, C, H, W = x.shape
+        if out.numel() * 4 != snn_packed_bytes(N, C, H, W, layout):
+            raise ValueError("out has the wrong size")
+        arr[i].x_nchw = x.data_ptr()
+        arr[i].packed = out.data_ptr()
+        arr[i].N, arr[i].C, arr[i].H, arr[i].W = N, C, H, W
+        arr[i].layout = layout
+    return arr
+
+
+def snn_pack_activations_many(arr):
+    _check(lib().snn_pack_activations_many(arr, len(arr), _stream()), "snn_pack_activations_many")
 
 
 def snn_project_kernels(w, codebook, out=None):
@@ -439,6 +475,41 @@ def layer_io_array(layers):
 
 def snn_subbit_conv2d_prepared_many(arr):
     _check(lib().snn_subbit_conv2d_prepared_many(arr, len(arr), _stream()), "snn_subbit_conv2d_prepared_many")
+
+
+def layer_forward_array(layers):
+    """layers: list of dicts with keys desc, x (float32 NCHW), w (float32 [C_out*C_in][9]), codebook, alpha, idx_out
+    (int16 [C_out*C_in]), y (float32 output), workspace (SNN_WS_FORWARD bytes) -> a ctypes array for
+    snn_subbit_forward_many; build it once and reuse it (the tensors must stay alive)."""
+    arr = (snn_layer_forward * len(layers))()
+    for i, L in enumerate(layers):
+        d = L["desc"]
+        _dev(L["x"], torch.float32, "x")
+        _dev(L["w"], torch.float32, "w")
+        _dev(L["codebook"], torch.int16, "codebook")
+        _dev(L["alpha"], torch.float32, "alpha")
+        _dev(L["idx_out"], torch.int16, "idx_out")
+        _dev(L["y"], torch.float32, "y")
+        if L["x"].numel() != d.N * d.C_in * d.H * d.W or L["w"].numel() != d.C_out * d.C_in * 9:
+            raise ValueError("x or w has the wrong size")
+        if L["codebook"].numel() != d.K or L["alpha"].numel() != d.C_out or L["idx_out"].numel() != d.C_out * d.C_in:
+            raise ValueError("codebook, alpha or idx_out has the wrong size")
+        if L["y"].numel() != d.N * d.C_out * ((d.H - 1) // d.stride + 1) * ((d.W - 1) // d.stride + 1):
+            raise ValueError("y has the wrong size")
+        arr[i].desc = d
+        arr[i].x_nchw = L["x"].data_ptr()
+        arr[i].w = L["w"].data_ptr()
+        arr[i].codebook = L["codebook"].data_ptr()
+        arr[i].alpha = L["alpha"].data_ptr()
+        arr[i].idx_out = L["idx_out"].data_ptr()
+        arr[i].y_nchw = L["y"].data_ptr()
+        arr[i].workspace = L["workspace"].data_ptr()
+        arr[i].ws_bytes = L["workspace"].numel()
+    return arr
+
+
+def snn_subbit_forward_many(arr):
+    _check(lib().snn_subbit_forward_many(arr, len(arr), _stream()), "snn_subbit_forward_many")
 
 
 def snn_subbit_forward_sign(desc, x, w, codebook, alpha, beta, idx_out=None, out=None, workspace=None):

@@ -31,6 +31,24 @@ __global__ __launch_bounds__(256) void fill_kernel(u32x4 *__restrict__ dst, size
     }
 }
 
+// read-only stream: four 16-byte loads in flight per lane, folded into one word per lane
+template <bool NT>
+__global__ __launch_bounds__(256) void read_kernel(const u32x4 *__restrict__ src, size_t n16, uint32_t *__restrict__ out)
+{
+    u32x4 acc = {0u, 0u, 0u, 0u};
+    const size_t stride = (size_t)gridDim.x * 256;
+    size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    for (; i + 3 * stride < n16; i += 4 * stride) {
+        u32x4 v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) v[u] = NT ? __builtin_nontemporal_load(src + i + u * stride) : src[i + u * stride];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) acc ^= v[u];
+    }
+    for (; i < n16; i += stride) acc ^= NT ? __builtin_nontemporal_load(src + i) : src[i];
+    out[(size_t)blockIdx.x * 256 + threadIdx.x] = acc.x ^ acc.y ^ acc.z ^ acc.w;
+}
+
 // ---- integer VALU ---------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void valu_xor_bcnt_kernel(uint32_t *out, int iters)
 {
@@ -261,6 +279,16 @@ int snn_peak_fill(void *dst, size_t bytes, int nontemporal, void *stream)
     const unsigned blocks = (unsigned)(want < 256 * 16 ? want : 256 * 16);
     if (nontemporal) hipLaunchKernelGGL(fill_kernel<true>, dim3(blocks), dim3(256), 0, (hipStream_t)stream, (u32x4 *)dst, n16);
     else hipLaunchKernelGGL(fill_kernel<false>, dim3(blocks), dim3(256), 0, (hipStream_t)stream, (u32x4 *)dst, n16);
+    return launched();
+}
+
+int snn_peak_read(const void *src, size_t bytes, int nontemporal, uint32_t *out, void *stream)
+{
+    if (!src || !out || bytes == 0 || bytes % 4096) return -1;
+    const size_t n16 = bytes / 16;
+    const unsigned blocks = SNN_PEAK_READ_BLOCKS;
+    if (nontemporal) hipLaunchKernelGGL(read_kernel<true>, dim3(blocks), dim3(256), 0, (hipStream_t)stream, (const u32x4 *)src, n16, out);
+    else hipLaunchKernelGGL(read_kernel<false>, dim3(blocks), dim3(256), 0, (hipStream_t)stream, (const u32x4 *)src, n16, out);
     return launched();
 }
 

@@ -182,6 +182,34 @@ int snn_pack_activations(const float *x_nchw, void *packed, int N, int C, int H,
     return SNN_ERR_INVALID_ARG;
 }
 
+int snn_pack_activations_many(const snn_pack_item *items, int n_items, void *stream)
+{
+    if (n_items < 0 || (n_items > 0 && !items)) return SNN_ERR_INVALID_ARG;
+    std::vector<const float *> x;
+    std::vector<uint32_t *> out;
+    std::vector<int64_t> rows;
+    std::vector<int> widths;
+    for (int i = 0; i < n_items; ++i) {
+        const snn_pack_item &it = items[i];
+        if (!it.x_nchw || !it.packed || it.N < 1 || it.C < 1 || it.H < 1 || it.W < 1) return SNN_ERR_INVALID_ARG;
+        if (it.layout != SNN_ACT_BIN_ROWS && it.layout != SNN_ACT_BIN_CHANNELS) return SNN_ERR_INVALID_ARG;
+        if ((int64_t)it.N * it.C * it.H * it.W >= ((int64_t)1 << 40)) return SNN_ERR_INVALID_ARG;
+    }
+    for (int i = 0; i < n_items; ++i) {
+        const snn_pack_item &it = items[i];
+        if (it.layout == SNN_ACT_BIN_ROWS) {
+            x.push_back(it.x_nchw);
+            out.push_back((uint32_t *)it.packed);
+            rows.push_back((int64_t)it.N * it.C * it.H);
+            widths.push_back(it.W);
+        } else {
+            const int rc = launch_pack_channels(it.x_nchw, (uint32_t *)it.packed, it.N, it.C, it.H, it.W, (hipStream_t)stream);
+            if (rc != SNN_OK) return rc;
+        }
+    }
+    return launch_pack_rows_many((int)x.size(), x.data(), out.data(), rows.data(), widths.data(), (hipStream_t)stream);
+}
+
 int snn_project_kernels(const float *w, int64_t n, const uint16_t *codebook, int K, uint16_t *idx_out,
                         void *stream)
 {
@@ -375,6 +403,54 @@ int snn_subbit_conv2d_prepared_many(const snn_layer_io *layers, int n_layers, vo
     if (tuning(SNN_TUNE_STACK) != 0 && subbit_stack_supported(n_layers, gs.data()))
         return launch_subbit_stack(n_layers, gs.data(), x.data(), y.data(), ws.data(), (hipStream_t)stream);
     return launch_subbit_mfma_many(n_layers, gs.data(), x.data(), y.data(), ws.data(), (hipStream_t)stream);
+}
+
+int snn_subbit_forward_many(const snn_layer_forward *layers, int n_layers, void *stream)
+{
+    if (n_layers < 0 || (n_layers > 0 && !layers)) return SNN_ERR_INVALID_ARG;
+    if (n_layers == 0) return SNN_OK;
+    std::vector<Geom> gs(n_layers);
+    std::vector<const float *> x(n_layers), w(n_layers), alpha(n_layers);
+    std::vector<const uint16_t *> codebook(n_layers);
+    std::vector<uint16_t *> idx_out(n_layers);
+    std::vector<uint32_t *> xr(n_layers);
+    std::vector<const void *> xp(n_layers);
+    std::vector<float *> y(n_layers);
+    std::vector<void *> ws(n_layers);
+    for (int l = 0; l < n_layers; ++l) {
+        const snn_layer_forward &L = layers[l];
+        if (!desc_ok(&L.desc, true) || !L.x_nchw || !L.w || !L.codebook || !L.alpha || !L.idx_out || !L.y_nchw)
+            return SNN_ERR_INVALID_ARG;
+        if (L.desc.act != SNN_ACT_BIN_ROWS) return SNN_ERR_UNSUPPORTED;
+        gs[l] = make_geom(L.desc);
+        if (!subbit_mfma_supported(gs[l])) return SNN_ERR_UNSUPPORTED;
+        const size_t need = subbit_forward_workspace_bytes(gs[l]);
+        if (!L.workspace || L.ws_bytes < need || ((uintptr_t)L.workspace & 255u)) return SNN_ERR_WORKSPACE;
+        x[l] = L.x_nchw;
+        w[l] = L.w;
+        alpha[l] = L.alpha;
+        codebook[l] = L.codebook;
+        idx_out[l] = L.idx_out;
+        xr[l] = (uint32_t *)((char *)L.workspace + align_up(subbit_workspace_bytes(gs[l], SNN_ACT_BIN_ROWS), 256));
+        xp[l] = xr[l];
+        y[l] = L.y_nchw;
+        ws[l] = L.workspace;
+    }
+    std::vector<int64_t> rows(n_layers);
+    std::vector<int> widths(n_layers);
+    std::vector<const float *> no_beta(n_layers, nullptr);
+    for (int l = 0; l < n_layers; ++l) {
+        rows[l] = (int64_t)gs[l].N * gs[l].C_in * gs[l].H;
+        widths[l] = gs[l].W;
+    }
+    int rc = launch_pack_rows_many(n_layers, x.data(), xr.data(), rows.data(), widths.data(), (hipStream_t)stream);
+    if (rc != SNN_OK) return rc;
+    rc = launch_subbit_prepare_many(n_layers, gs.data(), w.data(), codebook.data(), alpha.data(), no_beta.data(), idx_out.data(),
+                                    ws.data(), (hipStream_t)stream);
+    if (rc != SNN_OK) return rc;
+    if (tuning(SNN_TUNE_STACK) != 0 && subbit_stack_supported(n_layers, gs.data()))
+        return launch_subbit_stack(n_layers, gs.data(), xp.data(), y.data(), ws.data(), (hipStream_t)stream);
+    return launch_subbit_mfma_many(n_layers, gs.data(), xp.data(), y.data(), ws.data(), (hipStream_t)stream);
 }
 
 int snn_subbit_forward_sign(const snn_conv_desc *desc, const void *x_packed, const float *w, const uint16_t *codebook,

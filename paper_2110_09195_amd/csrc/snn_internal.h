@@ -77,6 +77,8 @@ __host__ __device__ inline uint32_t code_to_window_order(uint32_t code)
 
 int launch_pack_rows(const float *x, uint32_t *out, int64_t rows, int W, hipStream_t s);
 int launch_pack_channels(const float *x, uint32_t *out, int N, int C, int H, int W, hipStream_t s);
+// several tensors -> packed rows in one launch per group of 32 tensors
+int launch_pack_rows_many(int n, const float *const *x, uint32_t *const *out, const int64_t *rows, const int *W, hipStream_t s);
 
 int launch_project(const float *w, int64_t n, const uint16_t *codebook, int K, uint16_t *idx_out,
                    hipStream_t s);

@@ -8,7 +8,7 @@ import os
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libsnn_peaks.so")
-EXPORTS = ["snn_peak_copy", "snn_peak_fill", "snn_peak_valu_xor_bcnt", "snn_peak_mfma_f4f6", "snn_peak_mfma_out_bytes",
+EXPORTS = ["snn_peak_copy", "snn_peak_fill", "snn_peak_read", "snn_peak_valu_xor_bcnt", "snn_peak_mfma_f4f6", "snn_peak_mfma_out_bytes",
            "snn_peak_swar_gather"]
 _lib = None
 
@@ -22,6 +22,7 @@ def lib():
         vp, sz, ci = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int
         L.snn_peak_copy.argtypes = [vp, vp, sz, vp]
         L.snn_peak_fill.argtypes = [vp, sz, ci, vp]
+        L.snn_peak_read.argtypes = [vp, sz, ci, vp, vp]
         L.snn_peak_valu_xor_bcnt.argtypes = [vp, ci, ci, vp]
         L.snn_peak_mfma_f4f6.argtypes = [vp, ci, ci, ci, ci, vp]
         L.snn_peak_mfma_out_bytes.argtypes = [ci]
@@ -50,6 +51,15 @@ def copy(dst, src):
 
 def fill(dst, nontemporal):
     _check(lib().snn_peak_fill(dst.data_ptr(), dst.numel() * dst.element_size(), int(nontemporal), _stream()), "snn_peak_fill")
+
+
+READ_BLOCKS = 4096
+
+
+def read(src, nontemporal, out):
+    assert out.numel() >= READ_BLOCKS * 256
+    _check(lib().snn_peak_read(src.data_ptr(), src.numel() * src.element_size(), int(nontemporal), out.data_ptr(), _stream()),
+           "snn_peak_read")
 
 
 def valu_xor_bcnt(out, iters, blocks):

@@ -51,6 +51,34 @@ def test_pack_channels(oracle, shape):
     assert (G.pack(x, B.SNN_ACT_BIN_CHANNELS) == oracle.pack_channels(x)).all()
 
 
+def test_pack_many(oracle):
+    """snn_pack_activations_many: 35 tensors (more than one launch holds) of both layouts in one call, ragged rows,
+    unaligned sizes, a one-element tensor; every output between guard bytes."""
+    import torch
+    g = np.random.default_rng(77)
+    shapes = [(2, 3, 5, 33), (1, 1, 1, 1), (3, 16, 7, 7), (2, 5, 9, 65), (1, 2, 3, 2050), (2, 64, 14, 14), (1, 7, 56, 56)] * 5
+    items, keep = [], []
+    for i, shape in enumerate(shapes):
+        x = g.standard_normal(shape, dtype=np.float32)
+        x.flat[::5] = 0.0
+        layout = B.SNN_ACT_BIN_CHANNELS if i % 4 == 3 else B.SNN_ACT_BIN_ROWS
+        gd = G.Guarded(B.snn_packed_bytes(*shape, layout) // 4, torch.int32, fill=-1)
+        items.append((G.dev(x), gd.t, layout))
+        keep.append((x, gd, layout))
+    _say("pack_many", len(items))
+    B.snn_pack_activations_many(B.pack_item_array(items))
+    for x, gd, layout in keep:
+        gd.check("packed output of %s" % (x.shape,))
+        want = oracle.pack_rows(x) if layout == B.SNN_ACT_BIN_ROWS else oracle.pack_channels(x)
+        assert (G.host_u32(gd.t) == want.reshape(-1)).all(), x.shape
+    assert B.lib().snn_pack_activations_many(None, 0, None) == 0
+    arr = B.pack_item_array(items[:2])
+    arr[1].layout = 7
+    with pytest.raises(B.SnnError) as e:
+        B.snn_pack_activations_many(arr)
+    assert e.value.status == -1
+
+
 def test_pack_special_values(oracle):
     x = np.array([0.0, -0.0, 1e-30, -1e-30, np.nan, np.inf, -np.inf, 1.0] * 8, dtype=np.float32).reshape(1, 1, 2, 32)
     assert (G.pack(x, B.SNN_ACT_BIN_ROWS) == oracle.pack_rows(x)).all()

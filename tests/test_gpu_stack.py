@@ -177,3 +177,90 @@ def test_config5_every_image_of_every_layer(oracle):
         assert (G.host_u16(s["idx"]) == idx).all(), "projection of " + L.name
         _, Y = oracle.conv_bin(oracle.sign(s["x"]), oracle.expand(s["cb"], idx.reshape(L.C_out, L.C_in)), s["alpha"], L.stride)
         assert (s["y"].cpu().numpy() == Y).all(), "convolution of " + L.name
+
+
+# ---- snn_subbit_forward_many: projection + tables + sign/pack of all layers in one launch, all convolutions in a second ----
+
+def _make_forward(oracle, seed, N, C_in, C_out, H, W, stride, K):
+    g = np.random.default_rng(3000 + seed)
+    x = g.standard_normal((N, C_in, H, W), dtype=np.float32)
+    x.flat[::11] = 0.0                      # sign(0) = +1
+    cb = synth.codebook(g, K)
+    w = synth.real_kernels(g, C_out * C_in)
+    w[::7] = 0.0                            # ties of the projection: lowest index wins
+    alpha = synth.alpha(g, C_out)
+    d = B.make_desc(N, C_in, C_out, H, W, stride, K, B.SNN_ACT_BIN_ROWS)
+    Ho, Wo = B.out_hw(d)
+    gw = G.guarded_workspace(d, B.SNN_WS_FORWARD)
+    gy = G.Guarded(N * C_out * Ho * Wo, torch.float32, fill=float("nan"))
+    gi = G.Guarded(C_out * C_in, torch.int16, fill=-1)
+    idx, _ = oracle.project(w, cb)
+    _, Y = oracle.conv_bin(oracle.sign(x), oracle.expand(cb, idx.reshape(C_out, C_in)), alpha, stride)
+    return {"desc": d, "x": G.dev(x), "w": G.dev(w), "codebook": G.dev(cb), "alpha": G.dev(alpha), "idx_out": gi.t,
+            "y": gy.t.view(N, C_out, Ho, Wo), "workspace": gw.t, "gy": gy, "gw": gw, "gi": gi, "Y": Y, "idx": idx,
+            "shape": (N, C_in, C_out, H, W, stride, K)}
+
+
+def _check_forward(layers, what):
+    _check(layers, what)
+    for L in layers:
+        L["gi"].check("idx_out of %s" % (L["shape"],))
+        assert (G.host_u16(L["idx_out"]) == L["idx"].reshape(-1)).all(), "%s: projection of %s" % (what, L["shape"])
+
+
+@pytest.mark.parametrize("stack", [None, 0])
+def test_forward_many_every_form(oracle, stack, tune):
+    if stack is not None:
+        tune("STACK", stack)
+    layers = [_make_forward(oracle, i, *c) for i, c in enumerate(FORMS)]
+    arr = B.layer_forward_array(layers)
+    for rep in range(2):
+        for L in layers:
+            L["y"].fill_(float("nan"))
+            L["idx_out"].fill_(-1)
+        _say("forward_many: %d layers, call %d" % (len(layers), rep))
+        B.snn_subbit_forward_many(arr)
+        _check_forward(layers, "call %d" % rep)
+
+
+def test_forward_many_more_layers_than_one_launch_holds(oracle):
+    cases = [(1, 4 + 2 * i, 8 + 8 * (i % 5), 5 + i % 3, 6 + i % 4, 1 + i % 2, 32) for i in range(19)]
+    layers = [_make_forward(oracle, 100 + i, *c) for i, c in enumerate(cases)]
+    _say("forward_many: 19 layers")
+    B.snn_subbit_forward_many(B.layer_forward_array(layers))
+    _check_forward(layers, "19 layers")
+
+
+def test_forward_many_equals_forward_per_layer(oracle):
+    cases = [(8, 64, 64, 56, 56, 1, 32), (8, 64, 128, 56, 56, 2, 32), (8, 256, 256, 14, 14, 1, 32), (8, 512, 512, 7, 7, 1, 32)]
+    layers = [_make_forward(oracle, 200 + i, *c) for i, c in enumerate(cases)]
+    B.snn_subbit_forward_many(B.layer_forward_array(layers))
+    _check_forward(layers, "multi-tile stack")
+    for L in layers:
+        d = L["desc"]
+        y1, idx1 = B.snn_subbit_forward(d, L["x"], L["w"], L["codebook"], L["alpha"])
+        assert torch.equal(y1.view(-1), L["y"].view(-1)) and torch.equal(idx1.view(-1), L["idx_out"].view(-1))
+
+
+def test_forward_many_rejections():
+    d = B.make_desc(2, 8, 8, 6, 6, 1, 32, B.SNN_ACT_BIN_ROWS)
+    L = {"desc": d, "x": torch.zeros((2, 8, 6, 6), device="cuda"), "w": torch.zeros((64, 9), device="cuda"),
+         "codebook": torch.arange(32, dtype=torch.int16, device="cuda"), "alpha": torch.ones(8, device="cuda"),
+         "idx_out": torch.zeros(64, dtype=torch.int16, device="cuda"), "y": torch.zeros((2, 8, 6, 6), device="cuda"),
+         "workspace": B.alloc_workspace(d, B.SNN_WS_FORWARD)}
+    arr = B.layer_forward_array([L])
+    arr[0].ws_bytes = B.snn_workspace_bytes(d, B.SNN_WS_SUBBIT)          # the convolution's share alone is too small
+    with pytest.raises(B.SnnError) as e:
+        B.snn_subbit_forward_many(arr)
+    assert e.value.status == -3
+    arr[0].ws_bytes = L["workspace"].numel()
+    arr[0].w = None
+    with pytest.raises(B.SnnError) as e:
+        B.snn_subbit_forward_many(arr)
+    assert e.value.status == -1
+    arr[0].w = L["w"].data_ptr()
+    arr[0].desc.K = 512
+    with pytest.raises(B.SnnError) as e:
+        B.snn_subbit_forward_many(arr)
+    assert e.value.status == -2
+    assert B.lib().snn_subbit_forward_many(None, 0, None) == 0
