@@ -268,6 +268,10 @@ def measured_peaks(torch, np):
     a = torch.zeros(COPY_CAL_BYTES // 4, dtype=torch.int32, device="cuda")
     b = torch.empty_like(a)
     out["hbm_copy_GBps"] = 2 * COPY_CAL_BYTES / timed(lambda: P.copy(b, a)) / 1e9
+    big = torch.ones(1024 * 1024 * 1024 // 4, dtype=torch.int32, device="cuda")      # 1 GiB: larger than the memory-side cache
+    ro = torch.empty(P.READ_BLOCKS * 256, dtype=torch.int32, device="cuda")
+    out["hbm_read_GBps"] = big.numel() * 4 / timed(lambda: P.read(big, 1, ro), 3) / 1e9
+    del big, ro
     out["hbm_write_GBps"] = COPY_CAL_BYTES / timed(lambda: P.fill(b, 0)) / 1e9
     out["hbm_write_nontemporal_GBps"] = COPY_CAL_BYTES / timed(lambda: P.fill(b, 1)) / 1e9
     del a, b
@@ -866,6 +870,7 @@ def main():
             del x1, y1
 
     dense_ops = sum(L.dense_ops for L in layers)
+    in_bytes_packed = sum(L.N * L.C_in * L.H * ((L.W + 31) // 32) * 4 for L in layers)
     slots = [B.snn_subbit_slots_per_channel(s["d_sub"]) for s in st]
     roofline = None
     if many_ok:
@@ -1004,6 +1009,18 @@ def main():
         "breakdown_us": {"subbit_conv_one_launch": t_conv_in_step_us, "subbit_conv_per_layer_launches": sum(t_kern),
                          "project_prepare_many": t_prep_many, "pack_many": t_pack_many, "bnn_conv": sum(t_bnn), "project": sum(t_proj),
                          "pack_rows": sum(t_pr), "pack_channels": sum(t_pc)},
+        "other_step_kernels": {
+            "pack_rows_many_kernel": {
+                "us": t_pack_many, "alg_bytes": sum(L.N * L.C_in * L.H * L.W * 4 for L in layers) + in_bytes_packed,
+                "bound": "hbm",
+                "frac": (sum(L.N * L.C_in * L.H * L.W * 4 for L in layers) + in_bytes_packed) / HBM_PEAK_BYTES / (t_pack_many * 1e-6),
+                "frac_vs_measured_read": (sum(L.N * L.C_in * L.H * L.W * 4 for L in layers) + in_bytes_packed)
+                / (peaks["hbm_read_GBps"] * 1e9) / (t_pack_many * 1e-6)},
+            "subbit_prepare_many_kernel": {
+                "us": t_prep_many, "alg_bytes": sum(L.C_in * L.C_out * 38 for L in layers), "bound": "hbm",
+                "frac": sum(L.C_in * L.C_out * 38 for L in layers) / HBM_PEAK_BYTES / (t_prep_many * 1e-6),
+                "note": "36 bytes in and 2 out per kernel (Eq. 2 / Eq. 5); the launch is bound by the latency of its 4000 "
+                        "dependent chains, not by memory"}},
         "training_side": training,
         "chained_1bit_stack": chained,
         "dense_fp4_context": None if not extras else {
