@@ -864,9 +864,12 @@ def main():
             y1 = torch.empty((64, co, hw, hw), dtype=torch.float32, device="cuda")
             ws1 = B.alloc_workspace(d1, B.SNN_WS_CONV1X1)
             us = bn.event_avg_us(lambda: B.snn_subbit_conv1x1(d1, x1, cb1, idx1, al1, y=y1, workspace=ws1), reps)
+            B.snn_subbit_conv1x1_prepare(d1, cb1, idx1, al1, workspace=ws1)
+            us_p = bn.event_avg_us(lambda: B.snn_subbit_conv1x1_prepared(d1, x1, ws1, y=y1), reps)
             ops = 2.0 * ci * co * 64 * hw * hw
-            conv1x1.append({"layer": "%d->%d %dx%d" % (ci, co, hw, hw), "us": us, "gops_eq": ops / (us * 1e-6) / 1e9,
-                            "out_GBps": 64 * co * hw * hw * 4 / (us * 1e-6) / 1e9})
+            conv1x1.append({"layer": "%d->%d %dx%d" % (ci, co, hw, hw), "us": us, "prepared_us": us_p,
+                            "gops_eq_prepared": ops / (us_p * 1e-6) / 1e9,
+                            "out_GBps_prepared": 64 * co * hw * hw * 4 / (us_p * 1e-6) / 1e9})
             del x1, y1
 
     dense_ops = sum(L.dense_ops for L in layers)

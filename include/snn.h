@@ -397,6 +397,16 @@ int snn_subbit_conv1x1(const snn_conv_desc *desc, const void *x, const uint16_t 
                        size_t ws_bytes, void *stream);
 
 /*
+ * snn_subbit_conv1x1 in two halves for weights that stay fixed (inference): the first builds the layer's tables in
+ * `workspace` (one small launch), the second is the convolution alone and may follow any number of times.  Same
+ * arguments, results and errors as snn_subbit_conv1x1; the workspace must not be touched in between.
+ */
+int snn_subbit_conv1x1_prepare(const snn_conv_desc *desc, const uint16_t *codebook8, const uint16_t *idx,
+                               const float *alpha, void *workspace, size_t ws_bytes, void *stream);
+int snn_subbit_conv1x1_prepared(const snn_conv_desc *desc, const void *x, float *y_nchw, void *workspace,
+                                size_t ws_bytes, void *stream);
+
+/*
  * The projection of Eq. 2 / Eq. 5 for 1x1 layers (appendix, Table 5): for each real-valued vector
  * of 8 consecutive input-channel weights, the index of the nearest member of the layer's subset of
  * {+-1}^8, arg max_k <P'_k, w>, accumulated in fp32 from 0 over elements 0..7 in order (add where

@@ -31,7 +31,8 @@ SNN_WS_BNN_DENSE = 4
 
 EXPORTS = ("snn_pack_activations", "snn_pack_activations_many", "snn_project_kernels", "snn_subbit_conv2d", "snn_subbit_conv2d_noalloc", "snn_subbit_forward",
            "snn_subbit_prepare", "snn_subbit_conv2d_prepared", "snn_packed_index_bytes", "snn_pack_indices",
-           "snn_subbit_prepare_packed", "snn_subbit_conv1x1", "snn_project_vectors8",
+           "snn_subbit_prepare_packed", "snn_subbit_conv1x1", "snn_subbit_conv1x1_prepare", "snn_subbit_conv1x1_prepared",
+           "snn_project_vectors8",
            "snn_subbit_conv2d_sign", "snn_subbit_forward_sign", "snn_subbit_prepare_sign",
            "snn_subbit_conv2d_sign_prepared", "snn_subbit_project_prepare_many", "snn_subbit_conv2d_prepared_many",
            "snn_subbit_forward_many", "snn_project_backward",
@@ -133,6 +134,10 @@ def lib():
         L.snn_subset_update.restype = i32
         L.snn_subbit_conv1x1.argtypes = [dp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.snn_subbit_conv1x1.restype = i32
+        L.snn_subbit_conv1x1_prepare.argtypes = [dp, vp, vp, vp, vp, sz, vp]
+        L.snn_subbit_conv1x1_prepare.restype = i32
+        L.snn_subbit_conv1x1_prepared.argtypes = [dp, vp, vp, vp, sz, vp]
+        L.snn_subbit_conv1x1_prepared.restype = i32
         L.snn_bnn_conv2d.argtypes = [dp, vp, vp, vp, vp, vp, sz, vp]
         L.snn_bnn_conv2d.restype = i32
         L.snn_bnn_conv2d_dense.argtypes = [dp, vp, vp, vp, vp, vp, sz, vp]
@@ -578,6 +583,26 @@ def snn_subbit_conv1x1(desc, x, codebook8, idx, alpha, y=None, workspace=None):
         workspace = alloc_workspace(desc, SNN_WS_CONV1X1, x.device)
     _check(lib().snn_subbit_conv1x1(ctypes.byref(desc), _ptr(x), _ptr(codebook8), _ptr(idx), _ptr(alpha), _ptr(y),
                                     _ptr(workspace), workspace.numel(), _stream()), "snn_subbit_conv1x1")
+    return y
+
+
+def snn_subbit_conv1x1_prepare(desc, codebook8, idx, alpha, workspace=None):
+    """Tables of a 1x1 layer -> `workspace` (returned); then any number of snn_subbit_conv1x1_prepared calls."""
+    _dev(codebook8, torch.int16, "codebook8")
+    _dev(idx, torch.int16, "idx")
+    _dev(alpha, torch.float32, "alpha")
+    if workspace is None:
+        workspace = alloc_workspace(desc, SNN_WS_CONV1X1, idx.device)
+    _check(lib().snn_subbit_conv1x1_prepare(ctypes.byref(desc), _ptr(codebook8), _ptr(idx), _ptr(alpha), _ptr(workspace),
+                                            workspace.numel(), _stream()), "snn_subbit_conv1x1_prepare")
+    return workspace
+
+
+def snn_subbit_conv1x1_prepared(desc, x, workspace, y=None):
+    _dev(x, torch.int32, "x")
+    y = _conv_out(desc, y, x.device)
+    _check(lib().snn_subbit_conv1x1_prepared(ctypes.byref(desc), _ptr(x), _ptr(y), _ptr(workspace), workspace.numel(), _stream()),
+           "snn_subbit_conv1x1_prepared")
     return y
 
 

@@ -501,6 +501,30 @@ int snn_subbit_conv1x1(const snn_conv_desc *desc, const void *x, const uint16_t 
     return launch_subbit_conv1x1(g, x, codebook8, idx, alpha, y_nchw, workspace, (hipStream_t)stream);
 }
 
+int snn_subbit_conv1x1_prepare(const snn_conv_desc *desc, const uint16_t *codebook8, const uint16_t *idx, const float *alpha,
+                               void *workspace, size_t ws_bytes, void *stream)
+{
+    if (!desc_ok(desc, true) || !codebook8 || !idx || !alpha || desc->K > 256) return SNN_ERR_INVALID_ARG;
+    if (desc->act != SNN_ACT_BIN_CHANNELS) return SNN_ERR_UNSUPPORTED;
+    const Geom g = make_geom(*desc);
+    if (!subbit_conv1x1_supported(g)) return SNN_ERR_UNSUPPORTED;
+    const size_t need = subbit_conv1x1_workspace_bytes(g);
+    if (!workspace || ws_bytes < need || ((uintptr_t)workspace & 255u)) return SNN_ERR_WORKSPACE;
+    return launch_subbit_conv1x1(g, nullptr, codebook8, idx, alpha, nullptr, workspace, (hipStream_t)stream, SNN_PHASE_PREPARE);
+}
+
+int snn_subbit_conv1x1_prepared(const snn_conv_desc *desc, const void *x, float *y_nchw, void *workspace, size_t ws_bytes,
+                                void *stream)
+{
+    if (!desc_ok(desc, true) || !x || !y_nchw || desc->K > 256) return SNN_ERR_INVALID_ARG;
+    if (desc->act != SNN_ACT_BIN_CHANNELS) return SNN_ERR_UNSUPPORTED;
+    const Geom g = make_geom(*desc);
+    if (!subbit_conv1x1_supported(g)) return SNN_ERR_UNSUPPORTED;
+    const size_t need = subbit_conv1x1_workspace_bytes(g);
+    if (!workspace || ws_bytes < need || ((uintptr_t)workspace & 255u)) return SNN_ERR_WORKSPACE;
+    return launch_subbit_conv1x1(g, x, nullptr, nullptr, nullptr, y_nchw, workspace, (hipStream_t)stream, SNN_PHASE_CONVOLVE);
+}
+
 int snn_bnn_conv2d(const snn_conv_desc *desc, const void *x, const uint16_t *w9, const float *alpha,
                    float *y_nchw, void *workspace, size_t ws_bytes, void *stream)
 {

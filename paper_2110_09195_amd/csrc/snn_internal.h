@@ -174,7 +174,7 @@ __device__ inline float mul_then_add(float a, float b, float c)
 bool subbit_conv1x1_supported(const Geom &g);
 size_t subbit_conv1x1_workspace_bytes(const Geom &g);
 int launch_subbit_conv1x1(const Geom &g, const void *x, const uint16_t *codebook, const uint16_t *idx, const float *alpha,
-                          float *y, void *ws, hipStream_t s);
+                          float *y, void *ws, hipStream_t s, int phases = SNN_PHASE_BOTH);
 
 // training side (Alg. 1 backward lines)
 size_t project_backward_workspace_bytes(int64_t n, int K);

@@ -1445,7 +1445,7 @@ bool subbit_conv1x1_supported(const Geom &g)
 size_t subbit_conv1x1_workspace_bytes(const Geom &g) { return mf_plan(groups_geom(g), false, true).bytes; }
 
 int launch_subbit_conv1x1(const Geom &g, const void *x, const uint16_t *codebook, const uint16_t *idx, const float *alpha,
-                          float *y, void *ws, hipStream_t s)
+                          float *y, void *ws, hipStream_t s, int phases)
 {
     const Geom gk = groups_geom(g);
     const MfPlan pl = mf_plan(gk, false, true);
@@ -1456,9 +1456,11 @@ int launch_subbit_conv1x1(const Geom &g, const void *x, const uint16_t *codebook
     const int sel_blocks = (pl.COP / 32) * ((gk.C_in + 31) / 32);
     const int corr_blocks = (pl.COP + 3) / 4;
     const int lut_blocks = (256 * (pl.pair ? 6 : 12) + 255) / 256;
-    hipLaunchKernelGGL(subbit_mfma_prep_kernel, dim3((unsigned)(sel_blocks + corr_blocks + lut_blocks)), dim3(256), 0, s, codebook,
-                       (const void *)idx, 0, gk.C_in, g.C_out, pl.COP, pl.cfg.CB, g.K, pl.pair ? 1 : 0, sel_blocks, lut_blocks, alpha,
-                       (uint32_t *)prm.sel, (uint2 *)prm.fin, (uint32_t *)prm.lut, (const float *)nullptr, 8, stack_tables(pl, ws));
+    if (phases & SNN_PHASE_PREPARE)
+        hipLaunchKernelGGL(subbit_mfma_prep_kernel, dim3((unsigned)(sel_blocks + corr_blocks + lut_blocks)), dim3(256), 0, s, codebook,
+                           (const void *)idx, 0, gk.C_in, g.C_out, pl.COP, pl.cfg.CB, g.K, pl.pair ? 1 : 0, sel_blocks, lut_blocks, alpha,
+                           (uint32_t *)prm.sel, (uint2 *)prm.fin, (uint32_t *)prm.lut, (const float *)nullptr, 8, stack_tables(pl, ws));
+    if (!(phases & SNN_PHASE_CONVOLVE)) return check_launch();
     return launch_mf_conv(pl, prm, s);
 }
 

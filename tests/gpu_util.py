@@ -208,5 +208,12 @@ def subbit_conv1x1(x, codebook8, idx, alpha, stride=1):
     d = B.make_desc(N, C_in, C_out, H, W, stride, int(codebook8.size), B.SNN_ACT_BIN_CHANNELS)
     xp = B.snn_pack_activations(dev(x), B.SNN_ACT_BIN_CHANNELS)
     y = B.snn_subbit_conv1x1(d, xp, dev(codebook8), dev(idx.astype(np.uint16)), dev(alpha))
+    # the same in two halves: tables once, then the convolution alone, twice
+    gw = guarded_workspace(d, B.SNN_WS_CONV1X1)
+    B.snn_subbit_conv1x1_prepare(d, dev(codebook8), dev(idx.astype(np.uint16)), dev(alpha), workspace=gw.t)
+    for _ in range(2):
+        y2 = B.snn_subbit_conv1x1_prepared(d, xp, gw.t)
+        assert torch.equal(y2, y), "prepared 1x1 convolution differs from the one-call form"
+    gw.check("the workspace of the prepared 1x1 convolution")
     torch.cuda.synchronize()
     return y.cpu().numpy()
