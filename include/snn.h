@@ -532,7 +532,8 @@ int snn_subbit_slots_per_channel(const snn_conv_desc *desc);
 #define SNN_TUNE_STACK       5 /* 0: snn_subbit_conv2d_prepared_many runs one workgroup per tile group */
 #define SNN_TUNE_BNN_REGS    6 /* 0: the 1-bit kernel without register-resident windows */
 #define SNN_TUNE_DENSE_TILE  7 /* 0 .. 4: tile shape of the dense contraction */
-#define SNN_TUNE_COUNT       8
+#define SNN_TUNE_F32_WAVES   8 /* 4, 8, 16: waves per workgroup of the fp32-activation sub-bit kernel */
+#define SNN_TUNE_COUNT       9
 int snn_set_tuning(int knob, int value);
 int snn_get_tuning(int knob); /* SNN_TUNE_AUTO for an unknown knob */
 

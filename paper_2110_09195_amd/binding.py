@@ -205,8 +205,8 @@ def snn_packed_bytes(N, C, H, W, layout):
 
 SNN_TUNE_AUTO = -1
 (SNN_TUNE_SUBBIT_MFMA, SNN_TUNE_MFMA_TILE, SNN_TUNE_MFMA_KS, SNN_TUNE_MFMA_STAGE, SNN_TUNE_MFMA_QUAD, SNN_TUNE_STACK,
- SNN_TUNE_BNN_REGS, SNN_TUNE_DENSE_TILE) = range(8)
-SNN_TUNE_COUNT = 8
+ SNN_TUNE_BNN_REGS, SNN_TUNE_DENSE_TILE, SNN_TUNE_F32_WAVES) = range(9)
+SNN_TUNE_COUNT = 9
 
 
 def snn_set_tuning(knob, value):

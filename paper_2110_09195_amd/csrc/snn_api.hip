@@ -47,6 +47,7 @@ bool tuning_value_ok(int knob, int v)
     case SNN_TUNE_MFMA_TILE: return v == 42 || v == 24 || v == 22 || v == 14 || v == 12;
     case SNN_TUNE_MFMA_KS: return v == 1 || v == 2 || v == 4;
     case SNN_TUNE_DENSE_TILE: return v >= 0 && v < 5;
+    case SNN_TUNE_F32_WAVES: return v == 4 || v == 8 || v == 16;
     default: return v == 0 || v == 1;
     }
 }
@@ -54,7 +55,8 @@ bool tuning_value_ok(int knob, int v)
 void tuning_from_environment()
 {
     static const char *const names[SNN_TUNE_COUNT] = {"SNN_SUBBIT_MFMA", "SNN_MFMA_TILE", "SNN_MFMA_KS", "SNN_MFMA_STAGE",
-                                                      "SNN_MFMA_QUAD",   "SNN_STACK",     "SNN_BNN_REGS", "SNN_DENSE_TILE"};
+                                                      "SNN_MFMA_QUAD",   "SNN_STACK",     "SNN_BNN_REGS", "SNN_DENSE_TILE",
+                                                      "SNN_F32_WAVES"};
     for (int k = 0; k < SNN_TUNE_COUNT; ++k) {
         int v = SNN_TUNE_AUTO;
         if (const char *e = getenv(names[k])) {

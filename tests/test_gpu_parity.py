@@ -385,6 +385,20 @@ def test_subbit_f32(oracle, case):
     G.assert_f32_close(G.subbit_f32(x, cb, idx, alpha, stride), Y)
 
 
+@pytest.mark.parametrize("waves", [4, 8, 16])
+@pytest.mark.parametrize("case", [(3, 13, 9, 7, 5, 2, 16), (2, 24, 70, 9, 9, 1, 7), (2, 20, 200, 4, 4, 1, 64),
+                                  (1, 40, 520, 5, 5, 1, 128), (70, 9, 33, 8, 8, 1, 32)])
+def test_subbit_f32_every_workgroup_size(oracle, tune, case, waves):
+    """The fp32-activation kernel in each of its launch shapes (4, 8, 16 waves per workgroup; the automatic choice
+    depends on the number of pixel tiles), on channel counts that leave waves and lanes without work."""
+    _say("subbit_f32_waves", (case, waves))
+    tune("F32_WAVES", waves)
+    N, C_in, C_out, H, W, stride, K = case
+    x, cb, idx, alpha = _inputs(sum(case) + 5, N, C_in, C_out, H, W, K)
+    _, Y = oracle.conv_f32(x, oracle.expand(cb, idx), alpha, stride)
+    G.assert_f32_close(G.subbit_f32(x, cb, idx, alpha, stride), Y)
+
+
 def test_config2_full(oracle):
     """ResNet-20 last stage, weight-only sub-bit (W/A 0.56/32): batch 256, 64 -> 64, 8x8, K = 32."""
     L = synth.CFG2
