@@ -23,6 +23,7 @@
 
 #include <algorithm>
 #include <type_traits>
+#include <utility>
 #include <vector>
 
 namespace snn {
@@ -107,6 +108,12 @@ struct StackParams {
     StackLayer layer[ST_MAX_LAYERS];
 };
 
+
+template <int... I, typename F>
+__device__ __forceinline__ void static_for(std::integer_sequence<int, I...>, F &&f)
+{
+    (f(std::integral_constant<int, I>{}), ...);
+}
 
 __device__ inline __amdgpu_buffer_rsrc_t make_rsrc(const void *base, uint32_t bytes)
 {
@@ -520,44 +527,71 @@ __device__ __forceinline__ void stack_tile(const StackLayer &layer, const int ti
         asm volatile("" : "+v"(chan_v));
         char *const y_lane = (char *)L.y + (uint64_t)chan_v * (uint32_t)(co0 + (lane_f >> 3));
         const int ch_left = L.C_out - co0 - (lane_f >> 3);             // the lane's channel exists if 8 (store number) < ch_left
-#pragma unroll
-        for (int cb = 0; cb < CB; ++cb) {
-            u32x4 al[4];
+        // The half blocks form a pipeline: while the LDS turns half block s around (eight writes, two reads back),
+        // the values of half block s + 1 are computed; its writes follow the reads of s in program order, and LDS
+        // serves a wave's accesses in order, so one buffer is enough.  (Finishing one half block after the other,
+        // each waiting for its own round trip through an LDS that seven other waves use, was two thirds of the
+        // step's duration.)  The finishing tables of the next block are requested as soon as the last values of the
+        // current one exist.
+        constexpr int NST = CB * PB * 2;
+        u32x4 al[4], pend[2];
+        u32x2 cr[4];
+        auto read_al = [&](int cb) {
 #pragma unroll
             for (int j = 0; j < 4; ++j) al[j] = *(lds_cu32x4 *)(uintptr_t)(lds0 + ST_ALPHA_OFF + (uint32_t)(cb * 32 + 8 * j + 4 * h_f) * 4u);
+        };
+        auto read_cr = [&](int cb, int pb) {
 #pragma unroll
-            for (int pb = 0; pb < PB; ++pb) {
-                u32x2 cr[4];
+            for (int j = 0; j < 4; ++j)
+                cr[j] = *(lds_cu32x2 *)(uintptr_t)(lds0 + ST_CORR_OFF + (uint32_t)(ptype[pb] * NCH + cb * 32 + 8 * j + 4 * h_f) * 2u);
+        };
+        auto store_half = [&](auto sc) {
+            constexpr int s = decltype(sc)::value;
+            constexpr int cb = s / (2 * PB), pb = (s / 2) % PB, jh = s % 2;
 #pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    cr[j] = *(lds_cu32x2 *)(uintptr_t)(lds0 + ST_CORR_OFF + (uint32_t)(ptype[pb] * NCH + cb * 32 + 8 * j + 4 * h_f) * 2u);
-#pragma unroll
-                for (int jh = 0; jh < 2; ++jh) {
-#pragma unroll
-                    for (int rr = 0; rr < 8; ++rr) {
-                        const int r = 8 * jh + rr;                             // row (rr / 4) * 8 + 4 h + rr % 4 of the half block
-                        *(lds_u32 *)(uintptr_t)(out_w + (uint32_t)(((rr / 4) * 8 + rr % 4) * ST_OUT_ROW) * 4u) =
-                            __float_as_uint(value(cb, pb, r, al, cr));
-                    }
-#pragma unroll
-                    for (int t = 0; t < 2; ++t) {
-                        const u32x4 v = *(lds_cu32x4 *)(uintptr_t)(out_r + (uint32_t)(8 * t * ST_OUT_ROW) * 4u);
-                        // (a global store, not a buffer store with the channel offset in a scalar register: the
-                        // instruction after such a 16-byte buffer store may overwrite its first data register before
-                        // the store has read it - seen as the next store's offset in the output - and the compiler
-                        // only keeps the two apart for the other store forms)
-                        // (everything the address and the test need sits in vector registers: when scalar registers
-                        // run short, a value the compiler knows to come from the kernel's arguments is read again from
-                        // memory at every use, and each such read waits for all of the wave's outstanding LDS traffic)
-                        if (voff[pb] != 0xffffffffu && cb * 32 + 16 * jh + 8 * t < ch_left) {
-                            u32x4 *dst = (u32x4 *)(y_lane + (uint64_t)chan_v * (uint32_t)(cb * 32 + 16 * jh + 8 * t) + voff[pb]);
-                            __builtin_nontemporal_store(v, dst);   // written once, never read here: kept out of L2 (measured: 30 us of 270 over the ResNet-18 stack)
-                        }
-                    }
-                    __builtin_amdgcn_sched_barrier(0);         // one half block at a time: nothing of the next one moves up here
+            for (int t = 0; t < 2; ++t) {
+                // (a global store, not a buffer store with the channel offset in a scalar register: the
+                // instruction after such a 16-byte buffer store may overwrite its first data register before
+                // the store has read it - seen as the next store's offset in the output - and the compiler
+                // only keeps the two apart for the other store forms)
+                // (everything the address and the test need sits in vector registers: when scalar registers
+                // run short, a value the compiler knows to come from the kernel's arguments is read again from
+                // memory at every use, and each such read waits for all of the wave's outstanding LDS traffic)
+                if (voff[pb] != 0xffffffffu && cb * 32 + 16 * jh + 8 * t < ch_left) {
+                    u32x4 *dst = (u32x4 *)(y_lane + (uint64_t)chan_v * (uint32_t)(cb * 32 + 16 * jh + 8 * t) + voff[pb]);
+                    __builtin_nontemporal_store(pend[t], dst);   // written once, never read here: kept out of L2 (measured: 30 us of 270 over the ResNet-18 stack)
                 }
             }
-        }
+        };
+        auto half = [&](auto sc) {
+            constexpr int s = decltype(sc)::value;
+            constexpr int cb = s / (2 * PB), pb = (s / 2) % PB, jh = s % 2;
+            uint32_t val[8];
+#pragma unroll
+            for (int rr = 0; rr < 8; ++rr) {
+                val[rr] = __float_as_uint(value(cb, pb, 8 * jh + rr, al, cr));
+                // (pinned here: the stores below sit in branches, and the compiler otherwise sinks this arithmetic
+                // past them to the LDS writes that use it - behind the wait it is meant to cover)
+                asm volatile("" : "+v"(val[rr]));
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            if constexpr (jh == 1 && s + 1 < NST) {
+                constexpr int ncb = (s + 1) / (2 * PB), npb = ((s + 1) / 2) % PB;
+                read_cr(ncb, npb);
+                if constexpr (ncb != cb) read_al(ncb);
+            }
+            if constexpr (s > 0) store_half(std::integral_constant<int, (s > 0 ? s - 1 : 0)>{});
+#pragma unroll
+            for (int rr = 0; rr < 8; ++rr)                                 // row (rr / 4) * 8 + 4 h + rr % 4 of the half block
+                *(lds_u32 *)(uintptr_t)(out_w + (uint32_t)(((rr / 4) * 8 + rr % 4) * ST_OUT_ROW) * 4u) = val[rr];
+#pragma unroll
+            for (int t = 0; t < 2; ++t) pend[t] = *(lds_cu32x4 *)(uintptr_t)(out_r + (uint32_t)(8 * t * ST_OUT_ROW) * 4u);
+            __builtin_amdgcn_sched_barrier(0);
+        };
+        read_al(0);
+        read_cr(0, 0);
+        static_for(std::make_integer_sequence<int, NST>{}, half);
+        store_half(std::integral_constant<int, NST - 1>{});
     } else {
         // any other plane size: one 4-byte store per output, 128 contiguous bytes per channel and lane half
         const int ch_left = L.C_out - co0 - 4 * h_f;                   // channel c of the tile (lane half 0) exists if c < ch_left
