@@ -623,8 +623,13 @@ __device__ __forceinline__ void stack_tile(const StackLayer &layer, const int ti
 __global__ __launch_bounds__(64, 2)
 void subbit_stack_kernel(const StackParams sp)
 {
-    extern __shared__ __align__(16) unsigned char smem[];
-    const uint32_t lds0 = (uint32_t)(uintptr_t)smem;
+    __shared__ __align__(16) unsigned char smem[ST_LDS_BYTES];
+    // (A static array, and its address taken from a pointer in the LDS address space: the compiler then knows the
+    // address as a constant and folds it into the offset fields of the LDS instructions.  The address of a
+    // dynamically sized array is only fixed at link time, and through a generic pointer it is a run-time value
+    // behind a null check: either way every table access paid an addition, an eighth of the loops' vector
+    // instructions.)
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)smem;
     const int lane = threadIdx.x;
     int cur_layer = -1;
     // The run table sits in the wave's LDS, one run per lane, so that finding an item's run is one read
@@ -806,7 +811,7 @@ int launch_subbit_stack(int n_layers, const Geom *gs, const void *const *x, floa
     sp.n_items = (int)total;
     sp.n_workers = (int)n_workers;
     sp.sched = (uint32_t *)((char *)ws[0] + mf_plan(gs[0]).off_sched);
-    hipLaunchKernelGGL(subbit_stack_kernel, dim3((unsigned)sp.n_workers), dim3(64), ST_LDS_BYTES, s, sp);
+    hipLaunchKernelGGL(subbit_stack_kernel, dim3((unsigned)sp.n_workers), dim3(64), 0, s, sp);
     return check_launch();
 }
 
