@@ -668,6 +668,9 @@ def main():
             pack_rows(s)
             conv_sub(s)
 
+    def conv_bnn_prepared(s):
+        B.snn_bnn_conv2d_prepared(s["d_bnn"], s["xc"], s["alpha"], s["ws_bnn"], y=s["yb"])
+
     def step_bnn():
         for s in st:
             pack_channels(s)
@@ -818,6 +821,13 @@ def main():
     t_pack_many = bn.event_avg_us(lambda: B.snn_pack_activations_many(pack_arr), reps)
     t_kern = [bn.event_avg_us(lambda s=s: conv_prepared(s), reps) for s in st]      # one launch per layer, for comparison
     t_bnn = [bn.event_avg_us(lambda s=s: conv_bnn(s), reps) for s in st]
+    # the same 1-bit convolutions from prepared weights (the workspaces hold them since conv_bnn above): the form to
+    # set beside the sub-bit launch, which also starts from prepared tables
+    t_bnn_k = [bn.event_avg_us(lambda s=s: conv_bnn_prepared(s), reps) for s in st]
+    for s in st:
+        assert torch.equal(s["y"], s["yb"]), "prepared 1-bit kernel disagrees on " + s["L"].name
+    # XOR + bit count: 2 lane-operations per 32-bit word of a tap (Sec. 3), 9 ceil(C_in / 32) words per output
+    bnn_lane_ops = sum(2 * 9 * ((L.C_in + 31) // 32) * L.N * L.H_out * L.W_out * L.C_out for L in layers)
     t_proj = [bn.event_avg_us(lambda s=s: project(s), reps) for s in st]
     t_pr = [bn.event_avg_us(lambda s=s: pack_rows(s), reps) for s in st]
     t_pc = [bn.event_avg_us(lambda s=s: pack_channels(s), reps) for s in st]
@@ -1006,6 +1016,13 @@ def main():
         "bnn_conv_us_per_layer": t_bnn,
         "bnn_conv_only_gops_eq": dense_ops / (sum(t_bnn) * 1e-6) / 1e9,
         "speedup_vs_bnn_conv": sum(t_bnn) / t_conv_in_step_us,
+        "bnn_conv_prepared_us_per_layer": t_bnn_k,
+        "speedup_vs_bnn_conv_prepared": sum(t_bnn_k) / t_conv_in_step_us,
+        "bnn_roofline": {"bound": "alu", "kernel": "bnn_regs_kernel (snn_bnn_conv2d_prepared, sixteen launches)",
+                         "lane_ops": bnn_lane_ops, "us": sum(t_bnn_k),
+                         "achieved": bnn_lane_ops / (sum(t_bnn_k) * 1e-6) / 1e12, "unit": "T lane-op/s",
+                         "peak": VALU_PEAK_LANE_OPS / 1e12, "frac": bnn_lane_ops / VALU_PEAK_LANE_OPS / (sum(t_bnn_k) * 1e-6),
+                         "frac_vs_measured_xor_bcnt": bnn_lane_ops / (peaks["valu_xor_bcnt_T_lane_ops"] * 1e12) / (sum(t_bnn_k) * 1e-6)},
         "speedup_vs_bnn_conv_cold": t_bnn_cold / t_convs_cold,
         "speedup_vs_bnn_step": ms_per_step_bnn / ms_per_step,
         "bnn_ms_per_step": ms_per_step_bnn,

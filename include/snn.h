@@ -435,6 +435,18 @@ int snn_bnn_conv2d(const snn_conv_desc *desc, const void *x, const uint16_t *w9,
                    void *stream);
 
 /*
+ * snn_bnn_conv2d in two halves, for weights that stay fixed over many calls (the form the 1-bit layer of
+ * Sec. 3 is timed in next to the prepared sub-bit calls): snn_bnn_prepare turns w9 into the bit planes
+ * and border corrections the kernel reads (all that depends on the weights) and writes them to the
+ * workspace; snn_bnn_conv2d_prepared runs the convolution from them.  Arguments as for snn_bnn_conv2d;
+ * the workspace (SNN_WS_BNN) carries the prepared data between the two calls and must not be written in
+ * between; the two calls together give exactly the result of snn_bnn_conv2d.  Same errors.
+ */
+int snn_bnn_prepare(const snn_conv_desc *desc, const uint16_t *w9, void *workspace, size_t ws_bytes, void *stream);
+int snn_bnn_conv2d_prepared(const snn_conv_desc *desc, const void *x, const float *alpha, float *y_nchw,
+                            void *workspace, size_t ws_bytes, void *stream);
+
+/*
  * The same 1-bit layer (Sec. 3) evaluated as a dense contraction on the matrix cores instead of
  * XNOR + bit count: +-1 weights and activations as FP4 operands, zero for taps outside the
  * image, fp32 accumulation (exact: |S| <= 9 C_in < 2^24).  Results are identical to

@@ -36,7 +36,7 @@ EXPORTS = ("snn_pack_activations", "snn_pack_activations_many", "snn_project_ker
            "snn_subbit_conv2d_sign", "snn_subbit_forward_sign", "snn_subbit_prepare_sign",
            "snn_subbit_conv2d_sign_prepared", "snn_subbit_project_prepare_many", "snn_subbit_conv2d_prepared_many",
            "snn_subbit_forward_many", "snn_project_backward",
-           "snn_project_backward_workspace_bytes", "snn_subset_update", "snn_bnn_conv2d", "snn_bnn_conv2d_dense",
+           "snn_project_backward_workspace_bytes", "snn_subset_update", "snn_bnn_conv2d", "snn_bnn_prepare", "snn_bnn_conv2d_prepared", "snn_bnn_conv2d_dense",
            "snn_subbit_conv2d_dense", "snn_dense_prepare", "snn_dense_conv2d_prepared",
            "snn_dense_conv2d_sign_prepared",
            "snn_workspace_bytes", "snn_packed_bytes", "snn_status_string", "snn_subbit_slots_per_channel",
@@ -140,6 +140,10 @@ def lib():
         L.snn_subbit_conv1x1_prepared.restype = i32
         L.snn_bnn_conv2d.argtypes = [dp, vp, vp, vp, vp, vp, sz, vp]
         L.snn_bnn_conv2d.restype = i32
+        L.snn_bnn_prepare.argtypes = [dp, vp, vp, sz, vp]
+        L.snn_bnn_prepare.restype = i32
+        L.snn_bnn_conv2d_prepared.argtypes = [dp, vp, vp, vp, vp, sz, vp]
+        L.snn_bnn_conv2d_prepared.restype = i32
         L.snn_bnn_conv2d_dense.argtypes = [dp, vp, vp, vp, vp, vp, sz, vp]
         L.snn_bnn_conv2d_dense.restype = i32
         L.snn_subbit_conv2d_dense.argtypes = [dp, vp, vp, vp, vp, vp, vp, sz, vp]
@@ -615,6 +619,22 @@ def snn_bnn_conv2d(desc, x, w9, alpha, y=None, workspace=None):
         workspace = alloc_workspace(desc, SNN_WS_BNN, x.device)
     _check(lib().snn_bnn_conv2d(ctypes.byref(desc), _ptr(x), _ptr(w9), _ptr(alpha), _ptr(y), _ptr(workspace),
                                 workspace.numel(), _stream()), "snn_bnn_conv2d")
+    return y
+
+
+def snn_bnn_prepare(desc, w9, workspace):
+    """The weights-side half of snn_bnn_conv2d: w9 -> bit planes and border corrections in `workspace`."""
+    _dev(w9, torch.int16, "w9")
+    _check(lib().snn_bnn_prepare(ctypes.byref(desc), _ptr(w9), _ptr(workspace), workspace.numel(), _stream()),
+           "snn_bnn_prepare")
+
+
+def snn_bnn_conv2d_prepared(desc, x, alpha, workspace, y=None):
+    """The convolution half of snn_bnn_conv2d, from a workspace snn_bnn_prepare has filled."""
+    _dev(alpha, torch.float32, "alpha")
+    y = _conv_out(desc, y, x.device)
+    _check(lib().snn_bnn_conv2d_prepared(ctypes.byref(desc), _ptr(x), _ptr(alpha), _ptr(y), _ptr(workspace),
+                                         workspace.numel(), _stream()), "snn_bnn_conv2d_prepared")
     return y
 
 

@@ -363,8 +363,9 @@ size_t bnn_workspace_bytes(const Geom &g, int act)
 }
 
 int launch_bnn(const Geom &g, int act, const void *x, const uint16_t *w9, const float *alpha, float *y,
-               void *ws, hipStream_t s)
+               void *ws, hipStream_t s, int phases)
 {
+    const bool prepare = (phases & SNN_PHASE_PREPARE) != 0, convolve = (phases & SNN_PHASE_CONVOLVE) != 0;
     const int64_t pblocks = (g.P + BNN_THREADS - 1) / BNN_THREADS;
     if (pblocks > 0x7fffffffLL) return SNN_ERR_INVALID_ARG;
 
@@ -373,9 +374,10 @@ int launch_bnn(const Geom &g, int act, const void *x, const uint16_t *w9, const 
         const int64_t nk = (int64_t)g.C_out * g.C_in;
         const int cgroups = (g.C_out + F32_CO - 1) / F32_CO;
         if (cgroups > 65535) return SNN_ERR_UNSUPPORTED;
-        hipLaunchKernelGGL(bnn_prep_f32_kernel, dim3((unsigned)((nk + 255) / 256)), dim3(256), 0, s, w9, nk, flips);
-        hipLaunchKernelGGL(bnn_f32_kernel, dim3((unsigned)pblocks, (unsigned)cgroups), dim3(BNN_THREADS), 0, s,
-                           (const float *)x, flips, alpha, y, g);
+        if (prepare) hipLaunchKernelGGL(bnn_prep_f32_kernel, dim3((unsigned)((nk + 255) / 256)), dim3(256), 0, s, w9, nk, flips);
+        if (convolve)
+            hipLaunchKernelGGL(bnn_f32_kernel, dim3((unsigned)pblocks, (unsigned)cgroups), dim3(BNN_THREADS), 0, s,
+                               (const float *)x, flips, alpha, y, g);
         return check_launch();
     }
 
@@ -392,8 +394,10 @@ int launch_bnn(const Geom &g, int act, const void *x, const uint16_t *w9, const 
         while (ch > 8 && pblocks * ((g.C_out + ch - 1) / ch) < 2048) ch /= 2;
         const int cgroups = (g.C_out + ch - 1) / ch;
         if (cgroups > 65535) return SNN_ERR_UNSUPPORTED;
-        hipLaunchKernelGGL(bnn_prep_bin_kernel, dim3((unsigned)((g.C_out + 3) / 4)), dim3(256), 0, s, w9, g.C_out,
-                           g.C_out, g.C_in, CWT, 1, wplanes, corr);
+        if (prepare)
+            hipLaunchKernelGGL(bnn_prep_bin_kernel, dim3((unsigned)((g.C_out + 3) / 4)), dim3(256), 0, s, w9, g.C_out,
+                               g.C_out, g.C_in, CWT, 1, wplanes, corr);
+        if (!convolve) return check_launch();
         const dim3 grid((unsigned)pblocks, (unsigned)cgroups), block(BNN_THREADS);
         const uint32_t *xp = (const uint32_t *)x;
 #define SNN_BNN_CASE(CWT_)                                                                                   \
@@ -421,8 +425,10 @@ int launch_bnn(const Geom &g, int act, const void *x, const uint16_t *w9, const 
     // the kernel addresses the packed input with 32-bit word offsets
     if ((int64_t)g.N * g.H * g.W * g.CW >= ((int64_t)1 << 31)) return SNN_ERR_UNSUPPORTED;
 
-    hipLaunchKernelGGL(bnn_prep_bin_kernel, dim3((unsigned)((COP + 3) / 4)), dim3(256), 0, s, w9, g.C_out, COP, g.C_in,
-                       g.CW, c.COG, wq, corr);
+    if (prepare)
+        hipLaunchKernelGGL(bnn_prep_bin_kernel, dim3((unsigned)((COP + 3) / 4)), dim3(256), 0, s, w9, g.C_out, COP, g.C_in,
+                           g.CW, c.COG, wq, corr);
+    if (!convolve) return check_launch();
 
     const dim3 grid((unsigned)pb, (unsigned)cgroups), block(BNN_THREADS);
     const uint32_t *xp = (const uint32_t *)x;

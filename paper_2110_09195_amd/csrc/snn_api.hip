@@ -538,6 +538,27 @@ int snn_bnn_conv2d(const snn_conv_desc *desc, const void *x, const uint16_t *w9,
     return launch_bnn(g, desc->act, x, w9, alpha, y_nchw, workspace, (hipStream_t)stream);
 }
 
+int snn_bnn_prepare(const snn_conv_desc *desc, const uint16_t *w9, void *workspace, size_t ws_bytes, void *stream)
+{
+    if (!desc_ok(desc, false) || !w9) return SNN_ERR_INVALID_ARG;
+    if (!bnn_supported(desc)) return SNN_ERR_UNSUPPORTED;
+    const Geom g = make_geom(*desc);
+    const size_t need = bnn_workspace_bytes(g, desc->act);
+    if (need > 0 && (!workspace || ws_bytes < need || ((uintptr_t)workspace & 255u))) return SNN_ERR_WORKSPACE;
+    return launch_bnn(g, desc->act, nullptr, w9, nullptr, nullptr, workspace, (hipStream_t)stream, SNN_PHASE_PREPARE);
+}
+
+int snn_bnn_conv2d_prepared(const snn_conv_desc *desc, const void *x, const float *alpha, float *y_nchw,
+                            void *workspace, size_t ws_bytes, void *stream)
+{
+    if (!desc_ok(desc, false) || !x || !alpha || !y_nchw) return SNN_ERR_INVALID_ARG;
+    if (!bnn_supported(desc)) return SNN_ERR_UNSUPPORTED;
+    const Geom g = make_geom(*desc);
+    const size_t need = bnn_workspace_bytes(g, desc->act);
+    if (need > 0 && (!workspace || ws_bytes < need || ((uintptr_t)workspace & 255u))) return SNN_ERR_WORKSPACE;
+    return launch_bnn(g, desc->act, x, nullptr, alpha, y_nchw, workspace, (hipStream_t)stream, SNN_PHASE_CONVOLVE);
+}
+
 namespace {
 int dense_call(const snn_conv_desc *desc, bool subbit, const void *x, const uint16_t *codebook, const uint16_t *codes,
                const float *alpha, float *y, void *workspace, size_t ws_bytes, void *stream, int phases,

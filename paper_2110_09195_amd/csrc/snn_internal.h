@@ -84,13 +84,13 @@ int launch_project(const float *w, int64_t n, const uint16_t *codebook, int K, u
                    hipStream_t s);
 int launch_project8(const float *w, int64_t n, const uint16_t *codebook8, int K, uint16_t *idx_out, hipStream_t s);
 
-size_t bnn_workspace_bytes(const Geom &g, int act);
-int launch_bnn(const Geom &g, int act, const void *x, const uint16_t *w9, const float *alpha,
-               float *y, void *ws, hipStream_t s);
-
-// A sub-bit convolution is a small preparation kernel (weights -> tables in the workspace) and the
+// A convolution is a small preparation kernel (weights -> tables in the workspace) and the
 // convolution proper; callers whose weights stay fixed run the two separately.
 enum : int { SNN_PHASE_PREPARE = 1, SNN_PHASE_CONVOLVE = 2, SNN_PHASE_BOTH = 3 };
+
+size_t bnn_workspace_bytes(const Geom &g, int act);
+int launch_bnn(const Geom &g, int act, const void *x, const uint16_t *w9, const float *alpha,
+               float *y, void *ws, hipStream_t s, int phases = SNN_PHASE_BOTH);
 
 // the same 1-bit layer as a dense FP4 contraction on the matrix cores (+-1 activations, packed channels)
 bool dense_fp4_supported(const Geom &g);

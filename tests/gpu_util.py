@@ -102,6 +102,12 @@ def bnn_bin(x, w9, alpha, stride=1):
     y = B.snn_bnn_conv2d(d, xp, dev(w9), dev(alpha), y=gy.t.view(N, C_out, Ho, Wo), workspace=gw.t)
     gy.check("y")
     gw.check("the workspace")
+    # the same layer in two calls (weights prepared once) gives the same bits
+    gw2 = guarded_workspace(d, B.SNN_WS_BNN)
+    B.snn_bnn_prepare(d, dev(w9), gw2.t)
+    y2 = B.snn_bnn_conv2d_prepared(d, xp, dev(alpha), gw2.t)
+    gw2.check("the workspace of the two-call form")
+    assert torch.equal(y, y2), "snn_bnn_prepare + snn_bnn_conv2d_prepared differ from snn_bnn_conv2d"
     return y.cpu().numpy()
 
 
@@ -135,7 +141,11 @@ def bnn_f32(x, w9, alpha, stride=1):
     C_out = w9.shape[0]
     d = B.make_desc(N, C_in, C_out, H, W, stride, 512, B.SNN_ACT_F32)
     y = B.snn_bnn_conv2d(d, dev(x), dev(w9), dev(alpha))
+    ws = B.alloc_workspace(d, B.SNN_WS_BNN)
+    B.snn_bnn_prepare(d, dev(w9), ws)
+    y2 = B.snn_bnn_conv2d_prepared(d, dev(x), dev(alpha), ws)
     torch.cuda.synchronize()
+    assert torch.equal(y, y2), "snn_bnn_prepare + snn_bnn_conv2d_prepared differ from snn_bnn_conv2d (fp32 activations)"
     return y.cpu().numpy()
 
 

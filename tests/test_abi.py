@@ -73,6 +73,8 @@ def test_invalid_arguments_are_status_codes_not_crashes(L):
     null = ctypes.c_void_p(0)
     assert L.snn_subbit_conv2d(ctypes.byref(d), null, null, null, null, null, null, 0, null) == binding.SNN_ERR_INVALID_ARG
     assert L.snn_bnn_conv2d(ctypes.byref(d), null, null, null, null, null, 0, null) == binding.SNN_ERR_INVALID_ARG
+    assert L.snn_bnn_prepare(ctypes.byref(d), null, null, 0, null) == binding.SNN_ERR_INVALID_ARG
+    assert L.snn_bnn_conv2d_prepared(ctypes.byref(d), null, null, null, null, 0, null) == binding.SNN_ERR_INVALID_ARG
     assert L.snn_subbit_forward(ctypes.byref(d), null, null, null, null, null, null, null, 0, null) == binding.SNN_ERR_INVALID_ARG
     assert L.snn_pack_activations(null, null, 1, 1, 1, 1, 0, null) == binding.SNN_ERR_INVALID_ARG
     assert L.snn_project_kernels(null, 4, null, 32, null, null) == binding.SNN_ERR_INVALID_ARG
