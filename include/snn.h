@@ -285,7 +285,7 @@ int snn_subbit_project_prepare_many(const snn_layer_weights *layers, int n_layer
  *                        different layers must not overlap
  *   layers[l].workspace  device, as prepared by snn_subbit_prepare / snn_subbit_prepare_packed /
  *                        snn_subbit_project_prepare_many (beta == NULL) for the same desc.  The tables
- *                        are only read.  Two scheduling words at the end of layers[0].workspace (zero after
+ *                        are only read.  The scheduling words at the end of layers[0].workspace (zero after
  *                        preparation) count work items while the call runs and are zero again when it
  *                        ends: calls that share that workspace must be ordered, like any two calls that
  *                        share a workspace.

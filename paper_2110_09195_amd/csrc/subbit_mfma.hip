@@ -207,7 +207,7 @@ __device__ inline void store_sel(uint32_t *__restrict__ sel, int COP, int C_in, 
 // Tables for the launch that walks a stack of layers (fp32 output): the finishing table again, laid out
 // so that a lane reads the entries of four consecutive output channels with one access:
 // negcorr[type][co] = -(2 corr + C_in (valid_taps(type) - 8)) as int16 (|.| <= 10 C_in, C_in <= 3000),
-// alphap[co] = alpha (0 for padding channels); and the two scheduling words, zeroed.
+// alphap[co] = alpha (0 for padding channels); and the scheduling words, zeroed.
 struct StackTables {
     int16_t *negcorr;
     float *alphap;
@@ -228,7 +228,8 @@ void subbit_mfma_prep_kernel(const uint16_t *__restrict__ codebook, const void *
 {
     const int tid = threadIdx.x;
     const int b = blockIdx.x;
-    if (b == (int)gridDim.x - 1 && tid < 2) st.sched[tid] = 0u;
+    if (b == (int)gridDim.x - 1)
+        for (int i = tid; i < MF_SCHED_WORDS; i += 256) st.sched[i] = 0u;
     if (b < sel_blocks) {
         // tile of 32 output channels x 32 input channels: read along c_in, write along c_out
         __shared__ uint16_t tile[32][33];
@@ -409,7 +410,8 @@ __device__ inline void weight_channel_block(const WeightParams &p, int co, uint3
         p.fin[co * 16 + tid] = fin_entry(2 * sum + (border_valid_taps(tid) - 8) * C_in, a, p.beta, co, real, C_in);
         if (!p.beta) store_stack_entry(p.st, co, tid, 2 * sum + (border_valid_taps(tid) - 8) * C_in, a);
     }
-    if (co == 0 && tid < 2) p.st.sched[tid] = 0u;
+    if (co == 0)
+        for (int i = tid; i < MF_SCHED_WORDS; i += 256) p.st.sched[i] = 0u;
 }
 
 struct FrontParams {

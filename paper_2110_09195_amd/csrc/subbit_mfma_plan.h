@@ -8,6 +8,11 @@ namespace snn {
 
 constexpr int MF_WAVES = 4;                    // waves per workgroup
 constexpr int MF_STAGE_SLOTS = 32;             // packed words a wave stages per input channel and step
+// scheduling words of the launch that walks a stack: one item counter per queue, 128 bytes apart (a queue per XCD:
+// its own cache line), then the count of workers that have left
+constexpr int MF_SCHED_QUEUES = 8;
+constexpr int MF_SCHED_STRIDE = 32;
+constexpr int MF_SCHED_WORDS = MF_SCHED_QUEUES * MF_SCHED_STRIDE + 1;
 constexpr int MF_STAGE_BYTES = 2 * MF_STAGE_SLOTS * 4 + 32;   // per wave: two channels + room for reads past the last slot
 // Table row stride in LDS: 24 bytes (32 FP6 values) per lane half, each half padded to 32 bytes in
 // the two-half form, the row padded to an odd number of 16-byte pieces (fewer bank conflicts).
@@ -34,7 +39,7 @@ struct MfPlan {
     // read by the launch that walks a stack of layers with one resident wave per work slot (fp32 output only):
     size_t off_negcorr;   // int16 [16][COP]: minus the finishing table's correction term, border type major
     size_t off_alphap;    // float [COP]: alpha padded with zeros
-    size_t off_sched;     // two words: next work item, workers that have left; zero between launches
+    size_t off_sched;     // MF_SCHED_WORDS scheduling words of the stack launch; zero between launches
 };
 
 // blocks of up to 32 pixels: 32 consecutive pixels each, or (sign epilogue) whole output words
@@ -117,7 +122,7 @@ inline MfPlan mf_plan(const Geom &g, bool aligned = false, bool one = false)
     pl.off_alphap = o;
     o += align_up((size_t)pl.COP * sizeof(float), 256);
     pl.off_sched = o;
-    o += 256;
+    o += align_up((size_t)MF_SCHED_WORDS * sizeof(uint32_t), 256);
     pl.bytes = o;
     return pl;
 }

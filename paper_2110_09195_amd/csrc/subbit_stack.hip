@@ -44,6 +44,8 @@ typedef __attribute__((address_space(3))) uint32_t lds_u32;
 constexpr int ST_MAX_LAYERS = 16;
 constexpr int ST_MAX_RUNS = 64;
 constexpr int ST_WORKERS_PER_CU = 8;           // two waves per SIMD: 256 vector registers each
+constexpr uint32_t ST_QUEUES = MF_SCHED_QUEUES; // item queues: one per XCD
+constexpr uint32_t ST_GROUP_LOG2 = 4, ST_GROUP = 1u << ST_GROUP_LOG2;      // consecutive items a queue owns at a time
 
 // LDS of a worker
 // The table (row = window, 32 FP6 values = 24 bytes) is kept as two arrays, the first 16 bytes of every row and
@@ -97,7 +99,7 @@ struct StackLayer {
 
 // Items [run_first_item[r], run_first_item[r + 1]) are tiles run_first_tile[r] ... of layer run_layer[r].
 struct StackParams {
-    uint32_t *sched;          // [0] next item, [1] workers that have left; both zero before and after a launch
+    uint32_t *sched;          // MF_SCHED_WORDS words: a draw counter per queue (MF_SCHED_STRIDE apart), workers that have left; all zero before and after a launch
     int n_runs, n_items, n_workers;
     int n_matrix_items;       // items are dealt from two lists in proportion: [0, n_matrix_items) and the rest of the run table
     uint32_t deal_ratio;      // ceil(2^32 * second list / dealt items); 0: one list only
@@ -490,9 +492,9 @@ __device__ __forceinline__ void stack_tile(const StackLayer &layer, const int ti
     // (An instruction written out by hand: the compiler's own form waits for the value right away.  It is
     // looked at after an explicit wait at the end of the item; an instruction the compiler does not know
     // to be outstanding only makes its own waits longer.  Drawing earlier, at the start of the loop, was
-    // measured and loses: the workers' first tiles start together, two thousand additions to one word take
-    // some ten microseconds, and every load of the loop queues behind the addition it follows.)
-    if (threadIdx.x == 0) asm volatile("global_atomic_add %0, %1, %2, %3 sc0" : "+v"(drawn) : "v"(0), "v"(1u), "s"(sched) : "memory");
+    // measured and loses: the workers' first tiles start together, their additions to the same few words take
+    // microseconds, and every load of the loop queues behind the addition it follows.)
+    if (threadIdx.x == 0) asm volatile("global_atomic_add %0, %1, %2, off sc0" : "+v"(drawn) : "v"(sched), "v"(1u) : "memory");
 
     // ---- finishing: S = 2 M + negcorr[type][channel], y = float(S) * alpha[channel] -------------------
     // Register r of a block: output channel 8 (r / 4) + 4 h + r % 4, pixel n_l.  The lane reads alpha
@@ -640,13 +642,48 @@ void subbit_stack_kernel(const StackParams sp)
         e.y = (uint32_t)sp.run_first_tile[lane] | (uint32_t)sp.run_layer[lane] << 24;       // tiles of a layer < 2^24
         *(__attribute__((address_space(3))) u32x2 *)(uintptr_t)(lds0 + ST_RUNS_OFF + (uint32_t)lane * 8u) = e;
     }
-    // The first item of a worker is its own number (2048 additions to one word would take longer than a
-    // tile); every later one comes from the counter, which starts at zero and counts from n_workers.
+    // Items are handed out by ST_QUEUES counters, one per XCD: queue q owns the groups q, q + ST_QUEUES, ... of
+    // ST_GROUP consecutive items, and its draw number j is item ((j / ST_GROUP) * ST_QUEUES + q) * ST_GROUP +
+    // j % ST_GROUP.  A worker draws from the queue of the XCD it runs on, so the tiles an XCD works on at any time
+    // are neighbours in their layers - they share the cache lines of their input rows (a 128-byte line of packed
+    // rows holds 16 or 32 image rows of a channel) and of the output planes' ends in that XCD's L2 instead of
+    // fetching them once per XCD - while all queues still advance through the item order at the same pace.  A
+    // worker whose queue is empty takes from the next queue that is not (a plain look at all counters picks it;
+    // an empty draw marks a queue as finished for this worker, so the search ends after at most ST_QUEUES
+    // rounds whatever the loads return), so every item is handed out whichever XCDs the workers sit on.
     // The next item is drawn while the current one's outputs are finished (see stack_tile).
-    uint32_t item = blockIdx.x;
+    auto item_of = [](uint32_t j, uint32_t q) { return (((j >> ST_GROUP_LOG2) * ST_QUEUES + q) << ST_GROUP_LOG2) | (j & (ST_GROUP - 1u)); };
+    uint32_t queue = (__builtin_amdgcn_s_getreg((20 << 0) | (0 << 6) | (3 << 11)) & 15u) % ST_QUEUES;      // XCC_ID
+    uint32_t finished = 0;                       // queues this worker has found empty
     uint32_t drawn = 0;
+    // The first draws of every queue are not drawn at all: worker b takes draw b / ST_QUEUES of queue b % ST_QUEUES
+    // (workgroups go to the XCDs in turn, so this is its own queue, and if not the item is still handed out
+    // once), and a counter's value c stands for draw n_static + c.  Two thousand additions at the start of a
+    // launch would take longer than the set-up of a tile.
+    const uint32_t n_static = (uint32_t)sp.n_workers / ST_QUEUES;
+    uint32_t item;
+    if (blockIdx.x < n_static * ST_QUEUES) {
+        item = item_of(blockIdx.x / ST_QUEUES, blockIdx.x % ST_QUEUES);
+    } else {
+        if (lane == 0) drawn = atomicAdd(sp.sched + queue * MF_SCHED_STRIDE, 1u);
+        item = item_of(n_static + (uint32_t)__builtin_amdgcn_readfirstlane((int)drawn), queue);
+    }
     for (;;) {
+        while (item >= (uint32_t)sp.n_items) {
+            finished |= 1u << queue;
+            uint32_t c = 0xffffffffu - n_static;
+            if (lane < (int)ST_QUEUES) c = __hip_atomic_load(sp.sched + lane * MF_SCHED_STRIDE, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const bool has = lane < (int)ST_QUEUES && item_of(n_static + c, (uint32_t)lane) < (uint32_t)sp.n_items;
+            const uint32_t open = (uint32_t)__ballot(has) & ~finished;
+            if (open == 0u) break;
+            // the first open queue after this one, cyclically
+            const uint32_t rot = ((open >> queue) | (open << (ST_QUEUES - queue))) & ((1u << ST_QUEUES) - 1u);
+            queue = (queue + (uint32_t)__builtin_ctz(rot)) % ST_QUEUES;
+            if (lane == 0) drawn = atomicAdd(sp.sched + queue * MF_SCHED_STRIDE, 1u);
+            item = item_of(n_static + (uint32_t)__builtin_amdgcn_readfirstlane((int)drawn), queue);
+        }
         if (item >= (uint32_t)sp.n_items) break;
+        uint32_t *const counter = sp.sched + queue * MF_SCHED_STRIDE;
         // Position in the run table.  The table lists the tiles bound by the matrix pipe first, then those bound
         // by LDS; the items deal from both lists in proportion, so that at any time a compute unit holds waves
         // of both kinds: with j(i) = mulhi(i, deal_ratio) - monotone, steps of at most one, j(n_items) = size
@@ -671,23 +708,24 @@ void subbit_stack_kernel(const StackParams sp)
         const bool new_layer = l != cur_layer;
         cur_layer = l;
         switch (L.variant) {
-        case 1: stack_tile<4, 2, 1, false>(L, tile, lds0, new_layer, sp.sched, drawn); break;
-        case 3: stack_tile<4, 2, 1, true>(L, tile, lds0, new_layer, sp.sched, drawn); break;
-        case 4: stack_tile<4, 2, 2, true>(L, tile, lds0, new_layer, sp.sched, drawn); break;
-        case 5: stack_tile<2, 4, 0, false>(L, tile, lds0, new_layer, sp.sched, drawn); break;
-        case 6: stack_tile<2, 4, 1, false>(L, tile, lds0, new_layer, sp.sched, drawn); break;
-        default: stack_tile<2, 4, 2, false>(L, tile, lds0, new_layer, sp.sched, drawn); break;
+        case 1: stack_tile<4, 2, 1, false>(L, tile, lds0, new_layer, counter, drawn); break;
+        case 3: stack_tile<4, 2, 1, true>(L, tile, lds0, new_layer, counter, drawn); break;
+        case 4: stack_tile<4, 2, 2, true>(L, tile, lds0, new_layer, counter, drawn); break;
+        case 5: stack_tile<2, 4, 0, false>(L, tile, lds0, new_layer, counter, drawn); break;
+        case 6: stack_tile<2, 4, 1, false>(L, tile, lds0, new_layer, counter, drawn); break;
+        default: stack_tile<2, 4, 2, false>(L, tile, lds0, new_layer, counter, drawn); break;
         }
         asm volatile("s_waitcnt vmcnt(0)" : "+v"(drawn) : : "memory");
-        item = (uint32_t)sp.n_workers + (uint32_t)__builtin_amdgcn_readfirstlane((int)drawn);
+        item = item_of(n_static + (uint32_t)__builtin_amdgcn_readfirstlane((int)drawn), queue);
     }
-    // The last worker to leave puts the two scheduling words back to zero for the next launch: by
+    // The last worker to leave puts the scheduling words back to zero for the next launch: by
     // then every other worker has drawn its last item and counted itself.
     if (lane == 0) {
-        const uint32_t left = atomicAdd(&sp.sched[1], 1u);
+        uint32_t *const leave = sp.sched + ST_QUEUES * MF_SCHED_STRIDE;
+        const uint32_t left = atomicAdd(leave, 1u);
         if (left == (uint32_t)sp.n_workers - 1u) {
-            atomicExch(&sp.sched[0], 0u);
-            atomicExch(&sp.sched[1], 0u);
+            for (uint32_t q = 0; q < ST_QUEUES; ++q) atomicExch(sp.sched + q * MF_SCHED_STRIDE, 0u);
+            atomicExch(leave, 0u);
         }
     }
 }

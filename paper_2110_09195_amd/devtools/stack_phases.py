@@ -48,7 +48,7 @@ SUBSTITUTIONS = [
      '            trow[8] = __builtin_amdgcn_s_getreg((4 << 0) | (0 << 6) | (31 << 11));      // HW_ID\n'
      '            trow[9] = __builtin_amdgcn_s_getreg((20 << 0) | (0 << 6) | (31 << 11));     // XCC_ID\n'
      '            trow[10] = (unsigned long long)l;\n        }\n        ST_MARK(1);\n', False),
-    ('new_layer, sp.sched, drawn); break;', 'new_layer, sp.sched, drawn, trow); break;', True),
+    ('new_layer, counter, drawn); break;', 'new_layer, counter, drawn, trow); break;', True),
     ('        asm volatile("s_waitcnt vmcnt(0)" : "+v"(drawn) : : "memory");\n',
      '        asm volatile("s_waitcnt vmcnt(0)" : "+v"(drawn) : : "memory");\n        ST_MARK(7);\n', False),
     ('    hipLaunchKernelGGL(subbit_stack_kernel, dim3((unsigned)sp.n_workers)',
