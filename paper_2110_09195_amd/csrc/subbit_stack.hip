@@ -524,11 +524,22 @@ __device__ __forceinline__ void stack_tile(const StackLayer &layer, const int ti
 #pragma unroll
         for (int pb = 0; pb < PB; ++pb)
             voff[pb] = (uint32_t)__builtin_amdgcn_ds_bpermute(16 * (lane_f & 7), (int)yoff[pb]);      // y offset of lane 4 (lane % 8): its pixel, channel 0
-        // the lane stores channel co0 + 8 (store number inside the tile) + lane / 8
+        // The lane stores channel co0 + 8 (store number inside the tile) + lane / 8: a 16-byte buffer store whose
+        // offset is that of the lane's four pixels in its first channel plus a multiple of eight channel planes,
+        // or lies outside the tensor for a block past the end or a channel past C_out.  (The offset is all in the
+        // vector register: with the channel part in a scalar register, the instruction after such a store may
+        // overwrite its first data register before the store has read it - seen as the next store's offset in
+        // the output - and the compiler keeps the two apart only when the scalar offset is not a register.)
         uint32_t chan_v = chan_bytes;
         asm volatile("" : "+v"(chan_v));
-        char *const y_lane = (char *)L.y + (uint64_t)chan_v * (uint32_t)(co0 + (lane_f >> 3));
         const int ch_left = L.C_out - co0 - (lane_f >> 3);             // the lane's channel exists if 8 (store number) < ch_left
+        uint32_t sbase[PB];
+        int lim[PB];
+#pragma unroll
+        for (int pb = 0; pb < PB; ++pb) {
+            sbase[pb] = voff[pb] + chan_v * (uint32_t)(co0 + (lane_f >> 3));
+            lim[pb] = voff[pb] != 0xffffffffu ? ch_left : 0;
+        }
         // The half blocks form a pipeline: while the LDS turns half block s around (eight writes, two reads back),
         // the values of half block s + 1 are computed; its writes follow the reads of s in program order, and LDS
         // serves a wave's accesses in order, so one buffer is enough.  (Finishing one half block after the other,
@@ -552,17 +563,10 @@ __device__ __forceinline__ void stack_tile(const StackLayer &layer, const int ti
             constexpr int cb = s / (2 * PB), pb = (s / 2) % PB, jh = s % 2;
 #pragma unroll
             for (int t = 0; t < 2; ++t) {
-                // (a global store, not a buffer store with the channel offset in a scalar register: the
-                // instruction after such a 16-byte buffer store may overwrite its first data register before
-                // the store has read it - seen as the next store's offset in the output - and the compiler
-                // only keeps the two apart for the other store forms)
-                // (everything the address and the test need sits in vector registers: when scalar registers
-                // run short, a value the compiler knows to come from the kernel's arguments is read again from
-                // memory at every use, and each such read waits for all of the wave's outstanding LDS traffic)
-                if (voff[pb] != 0xffffffffu && cb * 32 + 16 * jh + 8 * t < ch_left) {
-                    u32x4 *dst = (u32x4 *)(y_lane + (uint64_t)chan_v * (uint32_t)(cb * 32 + 16 * jh + 8 * t) + voff[pb]);
-                    __builtin_nontemporal_store(pend[t], dst);   // written once, never read here: kept out of L2 (measured: 30 us of 270 over the ResNet-18 stack)
-                }
+                const int c8 = cb * 32 + 16 * jh + 8 * t;                  // first of the eight channels of this store
+                const uint32_t at = c8 < lim[pb] ? sbase[pb] + chan_v * (uint32_t)c8 : 0xffffffffu;
+                // non-temporal: written once, never read here: kept out of L2 (measured: 30 us of 270 over the ResNet-18 stack)
+                __builtin_amdgcn_raw_buffer_store_b128(pend[t], yres, (int)at, 0, 2 /* nt */);
             }
         };
         auto half = [&](auto sc) {
