@@ -1037,10 +1037,15 @@ def main():
                 "frac_vs_measured_read": (sum(L.N * L.C_in * L.H * L.W * 4 for L in layers) + in_bytes_packed)
                 / (peaks["hbm_read_GBps"] * 1e9) / (t_pack_many * 1e-6)},
             "subbit_prepare_many_kernel": {
-                "us": t_prep_many, "alg_bytes": sum(L.C_in * L.C_out * 38 for L in layers), "bound": "hbm",
-                "frac": sum(L.C_in * L.C_out * 38 for L in layers) / HBM_PEAK_BYTES / (t_prep_many * 1e-6),
-                "note": "36 bytes in and 2 out per kernel (Eq. 2 / Eq. 5); the launch is bound by the latency of its 4000 "
-                        "dependent chains, not by memory"}},
+                "us": t_prep_many, "alg_bytes": sum(L.C_in * L.C_out * 38 for L in layers),
+                "lane_ops": sum(L.C_in * L.C_out * L.K * 10 for L in layers), "bound": "alu",
+                "frac": max(sum(L.C_in * L.C_out * 38 for L in layers) / HBM_PEAK_BYTES,
+                            sum(L.C_in * L.C_out * L.K * 10 for L in layers) / VALU_PEAK_LANE_OPS) / (t_prep_many * 1e-6),
+                "frac_hbm": sum(L.C_in * L.C_out * 38 for L in layers) / HBM_PEAK_BYTES / (t_prep_many * 1e-6),
+                "note": "Eq. 2 / Eq. 5: per kernel and subset member nine sequential fp32 add/subtracts and one comparison "
+                        "(10 lane-operations; 36 bytes in and 2 out per kernel).  As built a member costs 12 vector "
+                        "instructions (the comparison is a compare and two selects), and the selector words, tables and "
+                        "ballots of the block come on top: the launch is bound by vector issue at five waves per SIMD"}},
         "training_side": training,
         "chained_1bit_stack": chained,
         "dense_fp4_context": None if not extras else {
