@@ -161,6 +161,32 @@ __device__ __forceinline__ void stack_tile(const StackLayer &layer, const int ti
         const int e = q * 64 + lane, type = e / CR, pc = e - type * CR;
         tab_c[q] = *(const u32x4 *)(L.negcorr + (size_t)type * L.COP + co0 + pc * 8);
     }
+    constexpr int RAW_REGS = (STG ? 0 : PB * (WM == 1 ? 3 : 6)) + CB;
+    constexpr int RING = !STG && PB <= 2 && RAW_REGS <= 14 ? 3 : 2;
+    // selectors of the lane's CB channel blocks are contiguous: [step][half][tile][channel in block][block]
+    const uint32_t sel_step_bytes = 2u * (uint32_t)L.COP * 4u;
+    const __amdgpu_buffer_rsrc_t sres = make_rsrc(L.sel, (uint32_t)L.npairs * sel_step_bytes);
+    const uint32_t sel_lane = (uint32_t)(h * L.COP + co0 + n_l * CB) * 4u;
+    auto load_sel = [&](int c, uint32_t (&s)[CB]) {
+        static_assert(CB == 2 || CB == 4, "selector loads are 8 or 16 bytes");
+        if constexpr (CB == 4) {
+            const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(sres, (int)sel_lane, (int)((uint32_t)c * sel_step_bytes), 0);
+            s[0] = v.x;
+            s[1] = v.y;
+            s[2] = v.z;
+            s[3] = v.w;
+        } else {
+            const u32x2 v = __builtin_amdgcn_raw_buffer_load_b64(sres, (int)sel_lane, (int)((uint32_t)c * sel_step_bytes), 0);
+            s[0] = v.x;
+            s[1] = v.y;
+        }
+    };
+    // the selector words of the first steps depend on nothing but the tile's channels: requested before the
+    // window geometry is worked out, they arrive while it is
+    const int last = L.npairs - 1;
+    uint32_t sel[RING][CB];
+#pragma unroll
+    for (int u = 0; u < RING; ++u) load_sel(min(u, last), sel[u]);
     __builtin_amdgcn_sched_barrier(0);
 
     // ---- per-lane window geometry of the PB pixels (pixel n_l of every block) ----------------------
@@ -206,6 +232,23 @@ __device__ __forceinline__ void stack_tile(const StackLayer &layer, const int ti
         if (n < L.N) goff = (uint32_t)(((n * L.C_in + h) * L.H + hr) * L.WW + (piece == 2 ? 1 : 0)) * 4u;
         gshift = piece == 1 ? 16u : 0u;
     }
+    const __amdgpu_buffer_rsrc_t xres = make_rsrc(L.x, (uint32_t)L.N * (uint32_t)L.C_in * plane_bytes);
+    // step c -> first channel of the pair (the last step of an odd C_in starts one channel early)
+    const int last_first = L.C_in - 2;
+    typedef std::conditional_t<WM == 2, u32x2, uint32_t> Staged;
+    auto load_stage = [&](int c) -> Staged {
+        const uint32_t cof = (uint32_t)min(2 * c, last_first) * plane_bytes;
+        if constexpr (WM == 2) return __builtin_amdgcn_raw_buffer_load_b64(xres, (int)goff, (int)cof, 0);
+        else return __builtin_amdgcn_raw_buffer_load_b32(xres, (int)goff, (int)cof, 0);
+    };
+    constexpr int SRING = 4;
+    Staged stg[SRING];
+    // the staged words of the first steps are requested as soon as the tile's first row is known
+    if constexpr (STG) {
+#pragma unroll
+        for (int u = 0; u < SRING; ++u) stg[u] = load_stage(min(u, last));
+    }
+    if constexpr (STG) __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int pb = 0; pb < PB; ++pb) {
         int n, ho, wo;
@@ -226,14 +269,11 @@ __device__ __forceinline__ void stack_tile(const StackLayer &layer, const int ti
         xoff[pb] = (uint32_t)(((n * L.C_in + h) * L.H + (hc == 0 ? 0 : hc - 1)) * L.WW + jlo) * 4u;
         loff[pb] = stage_wave + (uint32_t)(h * MF_STAGE_SLOTS + (n * L.H + (hc == 0 ? 0 : hc - 1) - R_first) * SW + piece) * 4u;
     }
-    const __amdgpu_buffer_rsrc_t xres = make_rsrc(L.x, (uint32_t)L.N * (uint32_t)L.C_in * plane_bytes);
 
     constexpr bool ONE_WORD = WM == 1 || STG;      // a lane cuts its window row out of one 32-bit piece
     struct Raw {
         uint32_t lo[PB][3], hi[ONE_WORD ? 1 : PB][3];
     };
-    // step c -> first channel of the pair (the last step of an odd C_in starts one channel early)
-    const int last_first = L.C_in - 2;
     const uint32_t row_bytes = (uint32_t)L.WW * 4u;
     auto load_raw = [&](int c, Raw &r) {
         const uint32_t cof = (uint32_t)min(2 * c, last_first) * plane_bytes;
@@ -263,12 +303,6 @@ __device__ __forceinline__ void stack_tile(const StackLayer &layer, const int ti
             }
         }
     };
-    typedef std::conditional_t<WM == 2, u32x2, uint32_t> Staged;
-    auto load_stage = [&](int c) -> Staged {
-        const uint32_t cof = (uint32_t)min(2 * c, last_first) * plane_bytes;
-        if constexpr (WM == 2) return __builtin_amdgcn_raw_buffer_load_b64(xres, (int)goff, (int)cof, 0);
-        else return __builtin_amdgcn_raw_buffer_load_b32(xres, (int)goff, (int)cof, 0);
-    };
     // the staged piece goes to LDS, the lane's rows come back (LDS serves a wave's accesses in order)
     const uint32_t stage_lane = stage_wave + (uint32_t)lane * 4u;
     auto restage = [&](const Staged &v, Raw &r) {
@@ -278,24 +312,6 @@ __device__ __forceinline__ void stack_tile(const StackLayer &layer, const int ti
         for (int pb = 0; pb < PB; ++pb)
 #pragma unroll
             for (int dy = 0; dy < 3; ++dy) r.lo[pb][dy] = *(lds_cu32 *)(uintptr_t)(loff[pb] + (uint32_t)(dy * SW) * 4u);
-    };
-    // selectors of the lane's CB channel blocks are contiguous: [step][half][tile][channel in block][block]
-    const uint32_t sel_step_bytes = 2u * (uint32_t)L.COP * 4u;
-    const __amdgpu_buffer_rsrc_t sres = make_rsrc(L.sel, (uint32_t)L.npairs * sel_step_bytes);
-    const uint32_t sel_lane = (uint32_t)(h * L.COP + co0 + n_l * CB) * 4u;
-    auto load_sel = [&](int c, uint32_t (&s)[CB]) {
-        static_assert(CB == 2 || CB == 4, "selector loads are 8 or 16 bytes");
-        if constexpr (CB == 4) {
-            const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(sres, (int)sel_lane, (int)((uint32_t)c * sel_step_bytes), 0);
-            s[0] = v.x;
-            s[1] = v.y;
-            s[2] = v.z;
-            s[3] = v.w;
-        } else {
-            const u32x2 v = __builtin_amdgcn_raw_buffer_load_b64(sres, (int)sel_lane, (int)((uint32_t)c * sel_step_bytes), 0);
-            s[0] = v.x;
-            s[1] = v.y;
-        }
     };
     // LDS address of the table row of pixel block pb's window (24 bytes: 32 FP6 values), and the row -> B operand
     auto row_addr = [&](const Raw &r, int pb) -> uint32_t {
@@ -327,7 +343,6 @@ __device__ __forceinline__ void stack_tile(const StackLayer &layer, const int ti
     v16f acc[CB][PB];
 
     const int c_end = L.npairs;
-    const int last = L.npairs - 1;
 
     // Pipeline.  Memory loads run RING steps ahead (a ring of RING register sets; with staging one staged
     // word per step in a ring of SRING, and the rows come out of LDS one step ahead).  The one-hot operands
@@ -337,23 +352,13 @@ __device__ __forceinline__ void stack_tile(const StackLayer &layer, const int ti
     // arrive.  A step is cut into slots by scheduling fences (nothing moves across one): each slot starts
     // with the matrix instructions of one pixel block (or half of them) and carries its share of the
     // address arithmetic, LDS traffic and loads, which run while the matrix pipe works.
-    constexpr int RAW_REGS = (STG ? 0 : PB * (WM == 1 ? 3 : 6)) + CB;
-    constexpr int RING = !STG && PB <= 2 && RAW_REGS <= 14 ? 3 : 2;
-    constexpr int SRING = 4;
     constexpr int UNROLL = STG ? SRING : RING % 2 == 0 ? RING : 2 * RING;
     static_assert(UNROLL % RING == 0 && UNROLL % 2 == 0 && (!STG || UNROLL % SRING == 0), "register sets rotate with the unrolled steps");
     Raw raw[STG ? 1 : RING];
-    Staged stg[SRING];
-    uint32_t sel[RING][CB];
     v8i A[2][CB], B[PB];
-    if constexpr (STG) {
-#pragma unroll
-        for (int u = 0; u < SRING; ++u) stg[u] = load_stage(min(u, last));
-    }
 #pragma unroll
     for (int u = 0; u < RING; ++u) {
         if constexpr (!STG) load_raw(min(u, last), raw[u]);
-        load_sel(min(u, last), sel[u]);
         __builtin_amdgcn_sched_barrier(0);
     }
     // ---- the tables requested at the start -> LDS (only this wave reads them)

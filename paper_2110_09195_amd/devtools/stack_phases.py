@@ -33,8 +33,8 @@ SUBSTITUTIONS = [
      '#define ST_MARK(i) do { if (threadIdx.x == 0) trow[(i)] = wall_clock64(); } while (0)\ntemplate <int... I, typename F>', False),
     ('uint32_t *const sched, uint32_t &drawn)\n{',
      'uint32_t *const sched, uint32_t &drawn, unsigned long long *const trow)\n{', False),
-    ('    const __amdgpu_buffer_rsrc_t xres = make_rsrc(L.x,',
-     '    ST_MARK(2);\n    const __amdgpu_buffer_rsrc_t xres = make_rsrc(L.x,', False),
+    ('    constexpr bool ONE_WORD = WM == 1 || STG;',
+     '    ST_MARK(2);\n    constexpr bool ONE_WORD = WM == 1 || STG;', False),
     ('    int c = 0;\n    for (; c + UNROLL <= c_end; c += UNROLL) group(c, std::false_type{});\n'
      '    if (c < c_end) group(c, std::true_type{});\n',
      '    ST_MARK(3);\n    if (threadIdx.x == 0) trow[11] = clock64();\n    int c = 0;\n'
