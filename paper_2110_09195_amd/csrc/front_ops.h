@@ -116,6 +116,68 @@ __device__ inline void pack_rows_block(const float *__restrict__ x, uint32_t *__
     }
 }
 
+// The same for blocks [b0, b1) of rows in one workgroup, as a stream: the loads of the next two blocks are in flight while
+// the current one is packed, and the bit stream alternates between two LDS buffers (one barrier per block).  For
+// rows that fit a pass (W <= PACK_CHUNK) whose blocks start 16-byte aligned (`vec`); `bits`: 2 x PACK_LDS_WORDS.
+__device__ inline void pack_rows_stream(const float *__restrict__ x, uint32_t *__restrict__ out, int64_t rows, int W,
+                                        int WW, int rows_per_block, int64_t b0, int64_t b1, uint32_t *bits)
+{
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    auto load_block = [&](int64_t b, float4 (&v)[PACK_U]) {
+        const int64_t r0 = b * rows_per_block;
+        const int cnt = (int)min((int64_t)rows_per_block, rows - r0) * W;
+        const float *src = x + r0 * W;
+#pragma unroll
+        for (int u = 0; u < PACK_U; ++u) {
+            const int e = (u * PACK_THREADS + tid) * 4;
+            if (e + 3 < cnt) {
+                v[u] = load_once4(src + e);
+            } else {
+                v[u].x = e < cnt ? src[e] : -1.0f;
+                v[u].y = e + 1 < cnt ? src[e + 1] : -1.0f;
+                v[u].z = e + 2 < cnt ? src[e + 2] : -1.0f;
+                v[u].w = e + 3 < cnt ? src[e + 3] : -1.0f;
+            }
+        }
+    };
+    float4 v[PACK_U], nx[PACK_U], nx2[PACK_U];
+    if (b0 < b1) load_block(b0, v);
+    if (b0 + 1 < b1) load_block(b0 + 1, nx);
+    for (int64_t b = b0; b < b1; ++b) {
+        if (b + 2 < b1) load_block(b + 2, nx2);
+        uint32_t *bb = bits + (int)(b & 1) * PACK_LDS_WORDS;
+#pragma unroll
+        for (int u = 0; u < PACK_U; ++u) {
+            const uint32_t nib = (v[u].x >= 0.0f ? 1u : 0u) | (v[u].y >= 0.0f ? 2u : 0u) | (v[u].z >= 0.0f ? 4u : 0u) |
+                                 (v[u].w >= 0.0f ? 8u : 0u);
+            uint32_t w = nib << (4 * (lane & 7));
+            w |= __shfl_xor(w, 1);
+            w |= __shfl_xor(w, 2);
+            w |= __shfl_xor(w, 4);
+            if ((lane & 7) == 0) bb[(u * PACK_THREADS + tid) >> 3] = w;
+        }
+        __syncthreads();
+        const int64_t r0 = b * rows_per_block;
+        const int nwords = (int)min((int64_t)rows_per_block, rows - r0) * WW;
+        for (int q = tid; q < nwords; q += PACK_THREADS) {
+            const int rl = q / WW, j = q - rl * WW;
+            const int o = rl * W + 32 * j;
+            const int nb = min(32, W - 32 * j);
+            const int sh = o & 31;
+            uint32_t wv = bb[o >> 5] >> sh;
+            if (sh + nb > 32) wv |= bb[(o >> 5) + 1] << (32 - sh);
+            if (nb < 32) wv &= (1u << nb) - 1u;
+            out[r0 * WW + q] = wv;
+        }
+#pragma unroll
+        for (int u = 0; u < PACK_U; ++u) {
+            v[u] = nx[u];
+            nx[u] = nx2[u];
+        }
+    }
+}
+
 // ---- projection ------------------------------------------------------------------------------------
 // coef[K][12]: +1.0f / -1.0f for taps 0..8 of every subset member (+3 pad): three 16-byte reads
 __device__ inline void project_fill_coef(float *coef, const uint16_t *__restrict__ codebook, int K, int tid, int nthreads)

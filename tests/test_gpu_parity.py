@@ -41,6 +41,18 @@ def test_pack_rows(oracle, shape):
     assert (G.pack(x, B.SNN_ACT_BIN_ROWS) == oracle.pack_rows(x)).all()
 
 
+@pytest.mark.parametrize("shape", [(96, 128, 56, 50), (130, 64, 56, 56), (700, 512, 7, 7)])
+def test_pack_rows_long_runs(oracle, shape):
+    """Tensors large enough that a workgroup packs a run of several blocks of rows as a stream (loads two blocks
+    ahead, alternating LDS buffers), with a last block that is not full; every word against the oracle."""
+    _say("pack_rows_long_runs", shape)
+    g = np.random.default_rng(sum(shape))
+    x = g.standard_normal(shape, dtype=np.float32)
+    x.flat[:: 13] = 0.0
+    x.flat[5:: 17] = -0.0
+    assert (G.pack(x, B.SNN_ACT_BIN_ROWS) == oracle.pack_rows(x)).all()
+
+
 @pytest.mark.parametrize("shape", [(2, 1, 4, 5), (2, 16, 32, 32), (3, 32, 7, 7), (2, 40, 5, 3), (2, 64, 8, 8),
                                    (1, 100, 3, 3), (2, 256, 14, 14), (1, 512, 7, 7), (1, 33, 1, 1)])
 def test_pack_channels(oracle, shape):
