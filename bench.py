@@ -248,20 +248,23 @@ class Bench:
 
 
 def measured_peaks(torch, np):
-    """The yardsticks of the roofline, from the probes of include/snn_peaks.h (median of 5 launches each)."""
+    """The yardsticks of the roofline, from the probes of include/snn_peaks.h (median of 5 measurements each; a
+    measurement is four launches back to back between one pair of events, so that the 10-20 us around a single
+    launch do not count against a probe of 50-200 us)."""
     from paper_2110_09195_amd import peaks as P
 
-    def timed(fn, reps=5):
+    def timed(fn, reps=5, inner=4):
         fn()
         torch.cuda.synchronize()
         ts = []
         for _ in range(reps):
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             e0.record()
-            fn()
+            for _ in range(inner):
+                fn()
             e1.record()
             torch.cuda.synchronize()
-            ts.append(e0.elapsed_time(e1) * 1e-3)
+            ts.append(e0.elapsed_time(e1) * 1e-3 / inner)
         return sorted(ts)[len(ts) // 2]
 
     out = {}

@@ -27,11 +27,11 @@ int snn_peak_copy(void *dst, const void *src, size_t bytes, void *stream);
  * kernel that writes its output once.  Work: `bytes` written. */
 int snn_peak_fill(void *dst, size_t bytes, int nontemporal, void *stream);
 
-/* Read-only stream of 16-byte loads (non-temporal when `nontemporal` != 0), four in flight per lane: the pattern of
- * a kernel that reads its input once (sign + pack).  Work: `bytes` read.  A buffer larger than the 256 MB
+/* Read-only stream of 16-byte loads (non-temporal when `nontemporal` != 0), four in flight per lane, every block
+ * reading one contiguous piece: the pattern of a kernel that reads its input once (sign + pack).  Work: `bytes` read.  A buffer larger than the 256 MB
  * memory-side cache measures HBM, a smaller one read again measures that cache.
  * out: SNN_PEAK_READ_BLOCKS * 256 words (one folded word per lane). */
-#define SNN_PEAK_READ_BLOCKS 4096
+#define SNN_PEAK_READ_BLOCKS 16384
 int snn_peak_read(const void *src, size_t bytes, int nontemporal, uint32_t *out, void *stream);
 
 /* Plain integer VALU: a loop of v_xor_b32 + v_bcnt_u32_b32 (the 1-bit kernel's pair).

@@ -35,22 +35,30 @@ __global__ __launch_bounds__(256) void fill_kernel(u32x4 *__restrict__ dst, size
     }
 }
 
-// read-only stream: four 16-byte loads in flight per lane, folded into one word per lane
+// read-only stream: every block reads one contiguous piece (measured faster than pieces interleaved over the
+// blocks: 7.1 against 5.9 TB/s with non-temporal loads), four 16-byte loads in flight per lane, folded into one
+// word per lane
 template <bool NT>
 __global__ __launch_bounds__(256) void read_kernel(const u32x4 *__restrict__ src, size_t n16, uint32_t *__restrict__ out)
 {
     u32x4 acc = {0u, 0u, 0u, 0u};
-    const size_t stride = (size_t)gridDim.x * 256;
-    size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
-    for (; i + 3 * stride < n16; i += 4 * stride) {
+    const size_t piece = (n16 + gridDim.x - 1) / gridDim.x;
+    const size_t first = (size_t)blockIdx.x * piece;
+    const size_t end = first + piece < n16 ? first + piece : n16;
+    size_t i = first + threadIdx.x;
+    for (; i + 768 < end; i += 1024) {
         u32x4 v[4];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) v[u] = NT ? __builtin_nontemporal_load(src + i + u * stride) : src[i + u * stride];
+        for (int u = 0; u < 4; ++u) v[u] = NT ? __builtin_nontemporal_load(src + i + u * 256) : src[i + u * 256];
 #pragma unroll
         for (int u = 0; u < 4; ++u) acc ^= v[u];
     }
-    for (; i < n16; i += stride) acc ^= NT ? __builtin_nontemporal_load(src + i) : src[i];
-    out[(size_t)blockIdx.x * 256 + threadIdx.x] = acc.x ^ acc.y ^ acc.z ^ acc.w;
+    for (; i < end; i += 256) acc ^= NT ? __builtin_nontemporal_load(src + i) : src[i];
+    // one word per wave leaves (a word per lane would be 16 MB of writes in the read stream)
+    uint32_t f = acc.x ^ acc.y ^ acc.z ^ acc.w;
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) f ^= __shfl_xor(f, d);
+    if ((threadIdx.x & 63) == 0) out[(size_t)blockIdx.x * 256 + threadIdx.x] = f;
 }
 
 // ---- integer VALU ---------------------------------------------------------------------------------

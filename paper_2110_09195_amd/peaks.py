@@ -53,7 +53,7 @@ def fill(dst, nontemporal):
     _check(lib().snn_peak_fill(dst.data_ptr(), dst.numel() * dst.element_size(), int(nontemporal), _stream()), "snn_peak_fill")
 
 
-READ_BLOCKS = 4096
+READ_BLOCKS = 16384
 
 
 def read(src, nontemporal, out):
