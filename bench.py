@@ -37,7 +37,7 @@ if ROOT not in sys.path:
 
 # Vendor peaks of MI355X.
 HBM_PEAK_BYTES = 8.0e12
-MFMA_FP6_FP4_PEAK_FLOPS = 10.1e15          # dense FP6 / FP4 operands (v_mfma_scale_f32_32x32x64_f8f6f4)
+MFMA_FP6_FP4_PEAK_FLOPS = 10.1e15          # dense FP6 / FP4 operands (v_mfma_f32_32x32x64_f8f6f4)
 # 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz plain 32-bit VALU operations per second (= the 157.3 TFLOP/s fp32
 # vector peak / 2 for FMA / 2 for the packed form)
 VALU_PEAK_LANE_OPS = 256 * 4 * 16 * 2.4e9
@@ -341,7 +341,7 @@ def conv_roofline(layers, slots, t_s, peaks, accounting):
         "bound": "mfma" if t_unit >= t_hbm else "hbm",
         "alg_bytes": alg_bytes, "alg_bytes_split": {"in_packed": in_bytes, "out_f32": out_bytes, "idx_u16": idx_bytes},
         "gather_adds": gather_adds, "responses": responses,
-        "unit_used": "contraction slots of v_mfma_scale_f32_32x32x64_f8f6f4 (FP4 one-hot selector x FP6 match counts, fp32 "
+        "unit_used": "contraction slots of v_mfma_f32_32x32x64_f8f6f4 (FP4 one-hot selector x FP6 match counts, fp32 "
                      "accumulators): stage 1 is a table row per window (no arithmetic), stage 2 spends `slots_per_channel` "
                      "multiply-adds per gather-add, of which one is not a multiplication by zero",
         "slots_per_channel": sorted(set(slots)) if len(set(slots)) > 1 else slots[0],

@@ -40,8 +40,8 @@ int snn_peak_read(const void *src, size_t bytes, int nontemporal, uint32_t *out,
 int snn_peak_valu_xor_bcnt(uint32_t *out, int iters, int blocks, void *stream);
 
 /* Matrix cores, FP4 (e2m1) x FP6 (e2m3) operands, fp32 accumulators, 8 independent accumulator
- * sets per wave.  shape 0: v_mfma_scale_f32_32x32x64_f8f6f4 (131072 flop per instruction);
- * shape 1: v_mfma_scale_f32_16x16x128_f8f6f4 (65536 flop).  pattern 0: every operand slot holds a
+ * sets per wave.  shape 0: v_mfma_f32_32x32x64_f8f6f4 (131072 flop per instruction);
+ * shape 1: v_mfma_f32_16x16x128_f8f6f4 (65536 flop).  pattern 0: every operand slot holds a
  * random code; 1: the operands of the sub-bit kernel (A: a one-hot row per 32 slots, B: small
  * integers -4 .. 5); 2: zeros.  `blocks` workgroups of 4 waves; work: blocks * 4 * iters * 8
  * instructions.  out: blocks * 256 floats, then (at out + blocks * 256) per workgroup two 64-bit

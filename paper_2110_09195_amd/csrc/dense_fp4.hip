@@ -5,7 +5,7 @@
 //   S[p][co] = sum over taps t and input channels c of  x(p, t, c) * w(co, c, t)
 //
 // with x, w in {+1, -1} (0 for taps outside the image and for padding channels) held as FP4
-// (e2m1: +1 = 0b0010, -1 = 0b1010, 0 = 0), v_mfma_scale_f32_32x32x64_f8f6f4 with both operands FP4 and
+// (e2m1: +1 = 0b0010, -1 = 0b1010, 0 = 0), v_mfma_f32_32x32x64_f8f6f4 with both operands FP4 and
 // unit scales.  All products are +-1 or 0 and |S| <= 9 C_in <= 36864 < 2^24, so the fp32 accumulator
 // holds S exactly and  y = (float)S * alpha  is the one rounding of the definition.
 //
@@ -263,7 +263,7 @@ void dense_fp4_kernel(DenseParams p)
                 const v8i A = {(int)a[0], (int)a[1], (int)a[2], (int)a[3], 0, 0, 0, 0};
 #pragma unroll
                 for (int pb = 0; pb < PB; ++pb)
-                    acc[cb][pb] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(A, B[pb], acc[cb][pb], 4, 4, 0, 127, 0, 127);
+                    acc[cb][pb] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(A, B[pb], acc[cb][pb], 4, 4, 0, 0, 0, 0);
             }
         }
     }

@@ -131,7 +131,7 @@ __global__ __launch_bounds__(256) void mfma_f4f6_kernel(float *out, unsigned lon
         for (int it = 0; it < iters; ++it) {
 #pragma unroll
             for (int i = 0; i < 8; ++i)
-                acc[i] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, acc[i], 4 /* A: FP4 */, 2 /* B: FP6 e2m3 */, 0, 127, 0, 127);
+                acc[i] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, acc[i], 4 /* A: FP4 */, 2 /* B: FP6 e2m3 */, 0, 0, 0, 0);
         }
 #pragma unroll
         for (int i = 0; i < 8; ++i)
@@ -144,7 +144,7 @@ __global__ __launch_bounds__(256) void mfma_f4f6_kernel(float *out, unsigned lon
         for (int it = 0; it < iters; ++it) {
 #pragma unroll
             for (int i = 0; i < 8; ++i)
-                acc[i] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a, b, acc[i], 4, 2, 0, 127, 0, 127);
+                acc[i] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a, b, acc[i], 4, 2, 0, 0, 0, 0);
         }
 #pragma unroll
         for (int i = 0; i < 8; ++i)

@@ -6,7 +6,7 @@
 // corrected at the end.  Stage 2 (gather by index, sum over c_in) is written as a product with a
 // one-hot matrix, contracted over (c_in, k):
 //     M[co][pixel] = sum_ci sum_k  onehot(idx[co][ci])[k] * m_k(window[ci][pixel])
-// One v_mfma_scale_f32_32x32x64_f8f6f4 covers 32 output channels x 32 pixels and 64 contraction
+// One v_mfma_f32_32x32x64_f8f6f4 covers 32 output channels x 32 pixels and 64 contraction
 // slots, of which lanes 0-31 supply the first 32 and lanes 32-63 the rest.  For K <= 32 the slots
 // are (channel parity, subset member k): TWO input channels per instruction, the even one in the
 // low lanes.  For 32 < K <= 64 they are the members k of ONE input channel.  For K <= 16 a lane
@@ -874,9 +874,9 @@ __device__ __forceinline__ void mf_tile_body(const MfParams &p, const unsigned b
 #pragma unroll
             for (int cb = 0; cb < CB; ++cb)
 #pragma unroll
-                for (int pb = 0; pb < PB; ++pb)
+                for (int pb = 0; pb < PB; ++pb)      // (scale operands of zero select the form without block scales)
                     acc[cb][pb] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(A[cur][cb], B[cur][pb], acc[cb][pb], 4 /* A: FP4 */,
-                                                                                  2 /* B: FP6 e2m3 */, 0, 127, 0, 127);
+                                                                                  2 /* B: FP6 e2m3 */, 0, 0, 0, 0);
             constexpr int NMF = CB * PB;
             constexpr int NCH = QUAD ? 2 : 1;
             constexpr int NVM = (STG ? 1 : NCH * PB * (WM == 1 || WM == 3 ? 1 : WM == 2 ? 2 : 3)) + NCH;   // loads of a step

@@ -3,7 +3,7 @@
 //
 // The arithmetic is that of subbit_mfma.hip: stage 1 is a lookup of the 9-bit window in a 512-row
 // table of match counts m_k - 4 (FP6), stage 2 the product of that row with the one-hot row (FP4) of
-// every output channel's index, two input channels per v_mfma_scale_f32_32x32x64_f8f6f4, exact fp32
+// every output channel's index, two input channels per v_mfma_f32_32x32x64_f8f6f4, exact fp32
 // sums; S = 2 M - correction(channel, border type), y = float(S) * alpha.  What differs is how the
 // work reaches the chip:
 //   * a worker is ONE wave (a workgroup of 64 lanes) that stays resident and takes (layer, tile)
@@ -388,8 +388,10 @@ __device__ __forceinline__ void stack_tile(const StackLayer &layer, const int ti
     auto mfma_block = [&](int cur, int pb, int cb_from, int cb_to) {
 #pragma unroll
         for (int cb = cb_from; cb < cb_to; ++cb)
+            // (scale operands of zero: the compiler then selects the instruction form without block scales, one
+            // instruction word pair less to issue per matrix instruction than the scaled form with scales of 1.0)
             acc[cb][pb] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(A[cur][cb], B[pb], acc[cb][pb], 4 /* A: FP4 */, 2 /* B: FP6 e2m3 */,
-                                                                          0, 127, 0, 127);
+                                                                          0, 0, 0, 0);
     };
     auto fence = [] { __builtin_amdgcn_sched_barrier(0); };
     // u = c % UNROLL selects the register sets
