@@ -195,32 +195,39 @@ template <int Q>
 __device__ inline void project_argmax(const float (&wt)[Q][9], const float *coef, int K, int (&best)[Q])
 {
     float best_score[Q];
-#pragma unroll
-    for (int q = 0; q < Q; ++q) {
-        best[q] = 0;
-        best_score[q] = 0.0f;
-    }
-    // unrolled so that the coefficient reads of several members are in flight and their chains interleave
-#pragma unroll 4
-    for (int k = 0; k < K; ++k) {
+    auto score = [&](int k, float (&acc)[Q]) {
         const float4 ca = *(const float4 *)(coef + k * 12);          // wave-uniform address: broadcast
         const float4 cb = *(const float4 *)(coef + k * 12 + 4);
         const float c8 = coef[k * 12 + 8];
 #pragma unroll
         for (int q = 0; q < Q; ++q) {
-            float acc = 0.0f;
-            acc = __builtin_fmaf(wt[q][0], ca.x, acc);
-            acc = __builtin_fmaf(wt[q][1], ca.y, acc);
-            acc = __builtin_fmaf(wt[q][2], ca.z, acc);
-            acc = __builtin_fmaf(wt[q][3], ca.w, acc);
-            acc = __builtin_fmaf(wt[q][4], cb.x, acc);
-            acc = __builtin_fmaf(wt[q][5], cb.y, acc);
-            acc = __builtin_fmaf(wt[q][6], cb.z, acc);
-            acc = __builtin_fmaf(wt[q][7], cb.w, acc);
-            acc = __builtin_fmaf(wt[q][8], c8, acc);
-            if (k == 0 || acc > best_score[q]) {
+            float a = 0.0f;
+            a = __builtin_fmaf(wt[q][0], ca.x, a);
+            a = __builtin_fmaf(wt[q][1], ca.y, a);
+            a = __builtin_fmaf(wt[q][2], ca.z, a);
+            a = __builtin_fmaf(wt[q][3], ca.w, a);
+            a = __builtin_fmaf(wt[q][4], cb.x, a);
+            a = __builtin_fmaf(wt[q][5], cb.y, a);
+            a = __builtin_fmaf(wt[q][6], cb.z, a);
+            a = __builtin_fmaf(wt[q][7], cb.w, a);
+            a = __builtin_fmaf(wt[q][8], c8, a);
+            acc[q] = a;
+        }
+    };
+    // member 0 starts as the best (no test for "first member" inside the loop)
+    score(0, best_score);
+#pragma unroll
+    for (int q = 0; q < Q; ++q) best[q] = 0;
+    // unrolled so that the coefficient reads of several members are in flight and their chains interleave
+#pragma unroll 4
+    for (int k = 1; k < K; ++k) {
+        float acc[Q];
+        score(k, acc);
+#pragma unroll
+        for (int q = 0; q < Q; ++q) {
+            if (acc[q] > best_score[q]) {
                 best[q] = k;
-                best_score[q] = acc;
+                best_score[q] = acc[q];
             }
         }
     }
