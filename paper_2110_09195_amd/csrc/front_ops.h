@@ -19,6 +19,17 @@ __device__ inline float4 load_once4(const float *p)
 }
 __device__ inline float load_once(const float *p) { return __builtin_nontemporal_load(p); }
 
+// OR over the eight lanes 8 g .. 8 g + 7, valid in lane 8 g (all that the packing needs): two quad permutations
+// and a shift by four lanes inside the row of sixteen, as data-parallel-primitive operands of the vector unit
+// (the generic shuffle goes through the LDS pipeline with an address per lane).
+__device__ inline uint32_t or_of_eight_lanes(uint32_t w)
+{
+    w |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)w, 0xB1 /* quad_perm [1,0,3,2] */, 0xF, 0xF, true);
+    w |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)w, 0x4E /* quad_perm [2,3,0,1] */, 0xF, 0xF, true);
+    w |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)w, 0x104 /* row_shl:4: lane i reads lane i + 4 */, 0xF, 0xF, true);
+    return w;
+}
+
 constexpr int PACK_THREADS = 256;
 constexpr int PACK_U = 2;                                  // 16-byte loads in flight per thread (2: 7 % faster than 4 on 51 MB inputs)
 constexpr int PACK_CHUNK = PACK_THREADS * 4 * PACK_U;      // elements whose sign bits are staged in LDS per pass
@@ -85,9 +96,7 @@ __device__ inline void pack_rows_block(const float *__restrict__ x, uint32_t *__
             const uint32_t nib = (v[u].x >= 0.0f ? 1u : 0u) | (v[u].y >= 0.0f ? 2u : 0u) | (v[u].z >= 0.0f ? 4u : 0u) |
                                  (v[u].w >= 0.0f ? 8u : 0u);
             uint32_t w = nib << (4 * (lane & 7));
-            w |= __shfl_xor(w, 1);
-            w |= __shfl_xor(w, 2);
-            w |= __shfl_xor(w, 4);
+            w = or_of_eight_lanes(w);
             if ((lane & 7) == 0) bits[(u * PACK_THREADS + tid) >> 3] = w;
         }
         __syncthreads();
@@ -152,9 +161,7 @@ __device__ inline void pack_rows_stream(const float *__restrict__ x, uint32_t *_
             const uint32_t nib = (v[u].x >= 0.0f ? 1u : 0u) | (v[u].y >= 0.0f ? 2u : 0u) | (v[u].z >= 0.0f ? 4u : 0u) |
                                  (v[u].w >= 0.0f ? 8u : 0u);
             uint32_t w = nib << (4 * (lane & 7));
-            w |= __shfl_xor(w, 1);
-            w |= __shfl_xor(w, 2);
-            w |= __shfl_xor(w, 4);
+            w = or_of_eight_lanes(w);
             if ((lane & 7) == 0) bb[(u * PACK_THREADS + tid) >> 3] = w;
         }
         __syncthreads();
