@@ -56,11 +56,9 @@ constexpr int ST_LUT_BYTES = 512 * 24;
 constexpr int ST_STAGE_OFF = ST_LUT_BYTES;
 constexpr int ST_ALPHA_OFF = ST_STAGE_OFF + MF_STAGE_BYTES;    // float [128]
 constexpr int ST_CORR_OFF = ST_ALPHA_OFF + 128 * 4;            // int16 [16][32 CB]
-constexpr int ST_OUT_OFF = ST_CORR_OFF + 16 * 128 * 2;         // float [16][ST_OUT_ROW]: half a block of outputs on its way to memory
-constexpr int ST_OUT_ROW = 36;                                 // 32 pixels + 4 (16-byte rows, lane halves on different banks)
-constexpr int ST_RUNS_OFF = ST_OUT_OFF + 16 * ST_OUT_ROW * 4;   // {first item, first tile | layer << 24} of the 64 runs
+constexpr int ST_RUNS_OFF = ST_CORR_OFF + 16 * 128 * 2;        // {first item, first tile | layer << 24} of the 64 runs
 constexpr int ST_LDS_BYTES = ST_RUNS_OFF + ST_MAX_RUNS * 8;
-static_assert(ST_ALPHA_OFF % 16 == 0 && ST_CORR_OFF % 16 == 0 && ST_OUT_OFF % 16 == 0 && ST_RUNS_OFF % 8 == 0, "aligned LDS accesses");
+static_assert(ST_ALPHA_OFF % 16 == 0 && ST_CORR_OFF % 16 == 0 && ST_RUNS_OFF % 8 == 0, "aligned LDS accesses");
 static_assert(ST_WORKERS_PER_CU * ST_LDS_BYTES <= 160 * 1024, "all workers of a compute unit fit its LDS");
 
 // Division by a divisor fixed per layer (1 <= d < 2^31) of numerators below 2^31: q = mulhi(n, mul) >> shift with
@@ -509,7 +507,7 @@ __device__ __forceinline__ void stack_tile(const StackLayer &layer, const int ti
     // multiply-add is exact (integers below 2^24), so y is the one rounding of float(S) * alpha.
     int lane_f = threadIdx.x;
     asm volatile("" : "+v"(lane_f));
-    const int h_f = lane_f >> 5, n_f = lane_f & 31;
+    const int h_f = lane_f >> 5;
     const __amdgpu_buffer_rsrc_t yres = make_rsrc(L.y, (uint32_t)((size_t)L.N * L.C_out * L.HoWo * 4u));
     const uint32_t chan_bytes = (uint32_t)L.HoWo * 4u;
     auto value = [&](int cb, int pb, int r, const u32x4 (&al)[4], const u32x2 (&cr)[4]) -> float {
@@ -519,116 +517,31 @@ __device__ __forceinline__ void stack_tile(const StackLayer &layer, const int ti
         const float a = __uint_as_float(i == 0 ? al[j].x : i == 1 ? al[j].y : i == 2 ? al[j].z : al[j].w);
         return __builtin_fmaf(acc[cb][pb][r], 2.0f, (float)nc) * a;
     };
-    if ((L.HoWo & 3) == 0) {
-        // Channel planes are whole groups of four pixels, and so is every block: the outputs leave as
-        // 16-byte stores, 128 contiguous bytes per channel and eight channels per instruction (the
-        // memory pipeline takes about as long for a 4-byte store).  Half a block at a time (16 channels
-        // x 32 pixels) changes hands in LDS: written as [channel][pixel], read back four pixels wide.
-        const uint32_t out_w = lds0 + ST_OUT_OFF + (uint32_t)((4 * h_f) * ST_OUT_ROW + n_f) * 4u;
-        const uint32_t out_r = lds0 + ST_OUT_OFF + (uint32_t)((lane_f >> 3) * ST_OUT_ROW + 4 * (lane_f & 7)) * 4u;
-        // offset of the four pixels the lane stores (pixels 4 (lane % 8) .. + 3 of a block), channel lane / 8
-        uint32_t voff[PB];
+    // One 4-byte non-temporal store per output: the 32 lanes of a half write 128 contiguous bytes of one channel
+    // plane.  (Measured against 16-byte stores of four pixels after a transposition of half blocks through LDS: that
+    // form needs a quarter of the store instructions but pays eight LDS writes and two reads per half block, and the
+    // launch is 1.5 % slower with it.)
+    const int ch_left = L.C_out - co0 - 4 * h_f;                   // channel c of the tile (lane half 0) exists if c < ch_left
 #pragma unroll
-        for (int pb = 0; pb < PB; ++pb)
-            voff[pb] = (uint32_t)__builtin_amdgcn_ds_bpermute(16 * (lane_f & 7), (int)yoff[pb]);      // y offset of lane 4 (lane % 8): its pixel, channel 0
-        // The lane stores channel co0 + 8 (store number inside the tile) + lane / 8: a 16-byte buffer store whose
-        // offset is that of the lane's four pixels in its first channel plus a multiple of eight channel planes,
-        // or lies outside the tensor for a block past the end or a channel past C_out.  (The offset is all in the
-        // vector register: with the channel part in a scalar register, the instruction after such a store may
-        // overwrite its first data register before the store has read it - seen as the next store's offset in
-        // the output - and the compiler keeps the two apart only when the scalar offset is not a register.)
-        uint32_t chan_v = chan_bytes;
-        asm volatile("" : "+v"(chan_v));
-        const int ch_left = L.C_out - co0 - (lane_f >> 3);             // the lane's channel exists if 8 (store number) < ch_left
-        uint32_t sbase[PB];
-        int lim[PB];
+    for (int cb = 0; cb < CB; ++cb) {
+        u32x4 al[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) al[j] = *(lds_cu32x4 *)(uintptr_t)(lds0 + ST_ALPHA_OFF + (uint32_t)(cb * 32 + 8 * j + 4 * h_f) * 4u);
 #pragma unroll
         for (int pb = 0; pb < PB; ++pb) {
-            sbase[pb] = voff[pb] + chan_v * (uint32_t)(co0 + (lane_f >> 3));
-            lim[pb] = voff[pb] != 0xffffffffu ? ch_left : 0;
-        }
-        // The half blocks form a pipeline: while the LDS turns half block s around (eight writes, two reads back),
-        // the values of half block s + 1 are computed; its writes follow the reads of s in program order, and LDS
-        // serves a wave's accesses in order, so one buffer is enough.  (Finishing one half block after the other,
-        // each waiting for its own round trip through an LDS that seven other waves use, was two thirds of the
-        // step's duration.)  The finishing tables of the next block are requested as soon as the last values of the
-        // current one exist.
-        constexpr int NST = CB * PB * 2;
-        u32x4 al[4], pend[2];
-        u32x2 cr[4];
-        auto read_al = [&](int cb) {
-#pragma unroll
-            for (int j = 0; j < 4; ++j) al[j] = *(lds_cu32x4 *)(uintptr_t)(lds0 + ST_ALPHA_OFF + (uint32_t)(cb * 32 + 8 * j + 4 * h_f) * 4u);
-        };
-        auto read_cr = [&](int cb, int pb) {
+            u32x2 cr[4];
 #pragma unroll
             for (int j = 0; j < 4; ++j)
                 cr[j] = *(lds_cu32x2 *)(uintptr_t)(lds0 + ST_CORR_OFF + (uint32_t)(ptype[pb] * NCH + cb * 32 + 8 * j + 4 * h_f) * 2u);
-        };
-        auto store_half = [&](auto sc) {
-            constexpr int s = decltype(sc)::value;
-            constexpr int cb = s / (2 * PB), pb = (s / 2) % PB, jh = s % 2;
 #pragma unroll
-            for (int t = 0; t < 2; ++t) {
-                const int c8 = cb * 32 + 16 * jh + 8 * t;                  // first of the eight channels of this store
-                const uint32_t at = c8 < lim[pb] ? sbase[pb] + chan_v * (uint32_t)c8 : 0xffffffffu;
-                // non-temporal: written once, never read here: kept out of L2 (measured: 30 us of 270 over the ResNet-18 stack)
-                __builtin_amdgcn_raw_buffer_store_b128(pend[t], yres, (int)at, 0, 2 /* nt */);
-            }
-        };
-        auto half = [&](auto sc) {
-            constexpr int s = decltype(sc)::value;
-            constexpr int cb = s / (2 * PB), pb = (s / 2) % PB, jh = s % 2;
-            uint32_t val[8];
-#pragma unroll
-            for (int rr = 0; rr < 8; ++rr) {
-                val[rr] = __float_as_uint(value(cb, pb, 8 * jh + rr, al, cr));
-                // (pinned here: the stores below sit in branches, and the compiler otherwise sinks this arithmetic
-                // past them to the LDS writes that use it - behind the wait it is meant to cover)
-                asm volatile("" : "+v"(val[rr]));
+            for (int r = 0; r < 16; ++r) {
+                const int cs = co0 + cb * 32 + 8 * (r / 4) + r % 4;      // wave-uniform part of the channel
+                // channels past C_out (padding of the last block) are not stored: their lanes get an offset outside the tensor
+                const uint32_t at = cb * 32 + 8 * (r / 4) + r % 4 < ch_left ? yoff[pb] : 0xffffffffu;
+                __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(value(cb, pb, r, al, cr)), yres, (int)at,
+                                                      (int)((uint32_t)cs * chan_bytes), 2 /* nt */);
             }
             __builtin_amdgcn_sched_barrier(0);
-            if constexpr (jh == 1 && s + 1 < NST) {
-                constexpr int ncb = (s + 1) / (2 * PB), npb = ((s + 1) / 2) % PB;
-                read_cr(ncb, npb);
-                if constexpr (ncb != cb) read_al(ncb);
-            }
-            if constexpr (s > 0) store_half(std::integral_constant<int, (s > 0 ? s - 1 : 0)>{});
-#pragma unroll
-            for (int rr = 0; rr < 8; ++rr)                                 // row (rr / 4) * 8 + 4 h + rr % 4 of the half block
-                *(lds_u32 *)(uintptr_t)(out_w + (uint32_t)(((rr / 4) * 8 + rr % 4) * ST_OUT_ROW) * 4u) = val[rr];
-#pragma unroll
-            for (int t = 0; t < 2; ++t) pend[t] = *(lds_cu32x4 *)(uintptr_t)(out_r + (uint32_t)(8 * t * ST_OUT_ROW) * 4u);
-            __builtin_amdgcn_sched_barrier(0);
-        };
-        read_al(0);
-        read_cr(0, 0);
-        static_for(std::make_integer_sequence<int, NST>{}, half);
-        store_half(std::integral_constant<int, NST - 1>{});
-    } else {
-        // any other plane size: one 4-byte store per output, 128 contiguous bytes per channel and lane half
-        const int ch_left = L.C_out - co0 - 4 * h_f;                   // channel c of the tile (lane half 0) exists if c < ch_left
-#pragma unroll
-        for (int cb = 0; cb < CB; ++cb) {
-            u32x4 al[4];
-#pragma unroll
-            for (int j = 0; j < 4; ++j) al[j] = *(lds_cu32x4 *)(uintptr_t)(lds0 + ST_ALPHA_OFF + (uint32_t)(cb * 32 + 8 * j + 4 * h_f) * 4u);
-#pragma unroll
-            for (int pb = 0; pb < PB; ++pb) {
-                u32x2 cr[4];
-#pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    cr[j] = *(lds_cu32x2 *)(uintptr_t)(lds0 + ST_CORR_OFF + (uint32_t)(ptype[pb] * NCH + cb * 32 + 8 * j + 4 * h_f) * 2u);
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int cs = co0 + cb * 32 + 8 * (r / 4) + r % 4;      // wave-uniform part of the channel
-                    // channels past C_out (padding of the last block) are not stored: their lanes get an offset outside the tensor
-                    const uint32_t at = cb * 32 + 8 * (r / 4) + r % 4 < ch_left ? yoff[pb] : 0xffffffffu;
-                    __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(value(cb, pb, r, al, cr)), yres, (int)at,
-                                                          (int)((uint32_t)cs * chan_bytes), 2 /* nt */);
-                }
-                __builtin_amdgcn_sched_barrier(0);
-            }
         }
     }
 }
