@@ -522,28 +522,35 @@ __device__ __forceinline__ void stack_tile(const StackLayer &layer, const int ti
     // form needs a quarter of the store instructions but pays eight LDS writes and two reads per half block, and the
     // launch is 1.5 % slower with it.)
     const int ch_left = L.C_out - co0 - 4 * h_f;                   // channel c of the tile (lane half 0) exists if c < ch_left
+    // A tile whose channels all exist (every tile unless C_out is not a multiple of the tile's channels, and then
+    // only the last channel tile) skips the per-store test: a quarter of the finishing step's instructions.
+    auto finish = [&](auto full_c) {
+        constexpr bool FULL = decltype(full_c)::value;
 #pragma unroll
-    for (int cb = 0; cb < CB; ++cb) {
-        u32x4 al[4];
+        for (int cb = 0; cb < CB; ++cb) {
+            u32x4 al[4];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) al[j] = *(lds_cu32x4 *)(uintptr_t)(lds0 + ST_ALPHA_OFF + (uint32_t)(cb * 32 + 8 * j + 4 * h_f) * 4u);
+            for (int j = 0; j < 4; ++j) al[j] = *(lds_cu32x4 *)(uintptr_t)(lds0 + ST_ALPHA_OFF + (uint32_t)(cb * 32 + 8 * j + 4 * h_f) * 4u);
 #pragma unroll
-        for (int pb = 0; pb < PB; ++pb) {
-            u32x2 cr[4];
+            for (int pb = 0; pb < PB; ++pb) {
+                u32x2 cr[4];
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
-                cr[j] = *(lds_cu32x2 *)(uintptr_t)(lds0 + ST_CORR_OFF + (uint32_t)(ptype[pb] * NCH + cb * 32 + 8 * j + 4 * h_f) * 2u);
+                for (int j = 0; j < 4; ++j)
+                    cr[j] = *(lds_cu32x2 *)(uintptr_t)(lds0 + ST_CORR_OFF + (uint32_t)(ptype[pb] * NCH + cb * 32 + 8 * j + 4 * h_f) * 2u);
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int cs = co0 + cb * 32 + 8 * (r / 4) + r % 4;      // wave-uniform part of the channel
-                // channels past C_out (padding of the last block) are not stored: their lanes get an offset outside the tensor
-                const uint32_t at = cb * 32 + 8 * (r / 4) + r % 4 < ch_left ? yoff[pb] : 0xffffffffu;
-                __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(value(cb, pb, r, al, cr)), yres, (int)at,
-                                                      (int)((uint32_t)cs * chan_bytes), 2 /* nt */);
+                for (int r = 0; r < 16; ++r) {
+                    const int cs = co0 + cb * 32 + 8 * (r / 4) + r % 4;      // wave-uniform part of the channel
+                    // channels past C_out (padding of the last block) are not stored: their lanes get an offset outside the tensor
+                    const uint32_t at = FULL || cb * 32 + 8 * (r / 4) + r % 4 < ch_left ? yoff[pb] : 0xffffffffu;
+                    __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(value(cb, pb, r, al, cr)), yres, (int)at,
+                                                          (int)((uint32_t)cs * chan_bytes), 2 /* nt */);
+                }
+                __builtin_amdgcn_sched_barrier(0);
             }
-            __builtin_amdgcn_sched_barrier(0);
         }
-    }
+    };
+    if (co0 + NCH <= L.C_out) finish(std::true_type{});
+    else finish(std::false_type{});
 }
 
 __global__ __launch_bounds__(64, 2)
