@@ -377,23 +377,20 @@ __device__ __forceinline__ void stack_tile(const StackLayer &layer, const int ti
     make_A(sel[0], A[0]);
     if constexpr (STG) restage(stg[1 % SRING], raw[0]);
     __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-    for (int cb = 0; cb < CB; ++cb)
-#pragma unroll
-        for (int pb = 0; pb < PB; ++pb)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[cb][pb][r] = 0.0f;
-    auto mfma_block = [&](int cur, int pb, int cb_from, int cb_to) {
+    // (in the first step of a tile the sums start from a zero operand instead of 128 registers set to zero)
+    auto mfma_block = [&](auto first_c, int cur, int pb, int cb_from, int cb_to) {
+        constexpr bool FIRST = decltype(first_c)::value;
+        const v16f zero = {0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
         for (int cb = cb_from; cb < cb_to; ++cb)
             // (scale operands of zero: the compiler then selects the instruction form without block scales, one
             // instruction word pair less to issue per matrix instruction than the scaled form with scales of 1.0)
-            acc[cb][pb] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(A[cur][cb], B[pb], acc[cb][pb], 4 /* A: FP4 */, 2 /* B: FP6 e2m3 */,
+            acc[cb][pb] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(A[cur][cb], B[pb], FIRST ? zero : acc[cb][pb], 4 /* A: FP4 */, 2 /* B: FP6 e2m3 */,
                                                                           0, 0, 0, 0);
     };
     auto fence = [] { __builtin_amdgcn_sched_barrier(0); };
     // u = c % UNROLL selects the register sets
-    auto step = [&](int c, auto uc) {
+    auto step = [&](int c, auto uc, auto first_c) {
         constexpr int u = decltype(uc)::value;
         constexpr int cur = u % 2, nxt = (u + 1) % 2;
         constexpr int slot_next = (u + 1) % RING, slot_load = u % RING;
@@ -401,25 +398,25 @@ __device__ __forceinline__ void stack_tile(const StackLayer &layer, const int ti
         if constexpr (STG) {
             static_assert(!STG || (PB == 4 && CB == 2), "slots of the staged form");
             // slot 0: block 0; three row addresses of the next step
-            mfma_block(cur, 0, 0, 2);
+            mfma_block(first_c, cur, 0, 0, 2);
             addr[0] = row_addr(raw[0], 0);
             B[0] = read_B(addr[0]);
             addr[1] = row_addr(raw[0], 1);
             addr[2] = row_addr(raw[0], 2);
             fence();
             // slot 1: block 1; the last address; then the rows of step c + 2 replace those of step c + 1
-            mfma_block(cur, 1, 0, 2);
+            mfma_block(first_c, cur, 1, 0, 2);
             B[1] = read_B(addr[1]);
             addr[3] = row_addr(raw[0], 3);
             restage(stg[(u + 2) % SRING], raw[0]);
             fence();
             // slot 2: block 2; the one-hot operands of the next step
-            mfma_block(cur, 2, 0, 2);
+            mfma_block(first_c, cur, 2, 0, 2);
             B[2] = read_B(addr[2]);
             make_A(sel[slot_next], A[nxt]);
             fence();
             // slot 3: block 3; the loads of later steps
-            mfma_block(cur, 3, 0, 2);
+            mfma_block(first_c, cur, 3, 0, 2);
             B[3] = read_B(addr[3]);
             stg[u % SRING] = load_stage(min(c + SRING, last));
             load_sel(min(c + RING, last), sel[slot_load]);
@@ -428,52 +425,52 @@ __device__ __forceinline__ void stack_tile(const StackLayer &layer, const int ti
             static_assert(STG || CB == 2 || (PB == 2 && CB == 4), "slots of the plain forms");
             if constexpr (CB == 4) {
                 // slot 0: first half of block 0; the loads of later steps, the row addresses of the next step
-                mfma_block(cur, 0, 0, 2);
+                mfma_block(first_c, cur, 0, 0, 2);
                 load_raw(min(c + RING, last), raw[slot_load]);
                 load_sel(min(c + RING, last), sel[slot_load]);
                 addr[0] = row_addr(raw[slot_next], 0);
                 fence();
                 // slot 1: second half of block 0, then its next row
-                mfma_block(cur, 0, 2, 4);
+                mfma_block(first_c, cur, 0, 2, 4);
                 B[0] = read_B(addr[0]);
                 addr[1] = row_addr(raw[slot_next], 1);
                 fence();
                 // slots 2 and 3: block 1; the one-hot operands of the next step
-                mfma_block(cur, 1, 0, 2);
+                mfma_block(first_c, cur, 1, 0, 2);
                 make_A(sel[slot_next], A[nxt]);
                 fence();
-                mfma_block(cur, 1, 2, 4);
+                mfma_block(first_c, cur, 1, 2, 4);
                 B[1] = read_B(addr[1]);
                 fence();
             } else {
                 // four pixel blocks of two channel blocks, rows loaded directly (short rows that cannot be staged)
-                mfma_block(cur, 0, 0, 2);
+                mfma_block(first_c, cur, 0, 0, 2);
                 load_raw(min(c + RING, last), raw[slot_load]);
                 load_sel(min(c + RING, last), sel[slot_load]);
                 addr[0] = row_addr(raw[slot_next], 0);
                 B[0] = read_B(addr[0]);
                 addr[1] = row_addr(raw[slot_next], 1);
                 fence();
-                mfma_block(cur, 1, 0, 2);
+                mfma_block(first_c, cur, 1, 0, 2);
                 B[1] = read_B(addr[1]);
                 addr[2] = row_addr(raw[slot_next], 2);
                 addr[3] = row_addr(raw[slot_next], 3);
                 fence();
-                mfma_block(cur, 2, 0, 2);
+                mfma_block(first_c, cur, 2, 0, 2);
                 B[2] = read_B(addr[2]);
                 make_A(sel[slot_next], A[nxt]);
                 fence();
-                mfma_block(cur, 3, 0, 2);
+                mfma_block(first_c, cur, 3, 0, 2);
                 B[3] = read_B(addr[3]);
                 fence();
             }
         }
     };
-    auto group = [&](int c, auto guarded) {
+    auto group = [&](int c, auto guarded, auto first_group) {
         // UNROLL consecutive steps; the guarded form (the tail) stops at c_end
         auto run = [&](auto uc) {
             constexpr int u = decltype(uc)::value;
-            if (!decltype(guarded)::value || c + u < c_end) step(c + u, uc);
+            if (!decltype(guarded)::value || c + u < c_end) step(c + u, uc, std::integral_constant<bool, decltype(first_group)::value && u == 0>{});
         };
         run(std::integral_constant<int, 0>{});
         run(std::integral_constant<int, 1>{});
@@ -491,8 +488,19 @@ __device__ __forceinline__ void stack_tile(const StackLayer &layer, const int ti
         }
     };
     int c = 0;
-    for (; c + UNROLL <= c_end; c += UNROLL) group(c, std::false_type{});
-    if (c < c_end) group(c, std::true_type{});
+    if (UNROLL <= c_end) {
+        group(0, std::false_type{}, std::true_type{});
+        c = UNROLL;
+    } else {                                       // fewer steps than one unrolled group: the guarded form adds to zeros
+#pragma unroll
+        for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+            for (int pb = 0; pb < PB; ++pb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[cb][pb][r] = 0.0f;
+    }
+    for (; c + UNROLL <= c_end; c += UNROLL) group(c, std::false_type{}, std::false_type{});
+    if (c < c_end) group(c, std::true_type{}, std::false_type{});
     // The worker's next item is drawn here: the counter's old value arrives while the outputs are finished.
     // (An instruction written out by hand: the compiler's own form waits for the value right away.  It is
     // looked at after an explicit wait at the end of the item; an instruction the compiler does not know

@@ -35,11 +35,11 @@ SUBSTITUTIONS = [
      'uint32_t *const sched, uint32_t &drawn, unsigned long long *const trow)\n{', False),
     ('    constexpr bool ONE_WORD = WM == 1 || STG;',
      '    ST_MARK(2);\n    constexpr bool ONE_WORD = WM == 1 || STG;', False),
-    ('    int c = 0;\n    for (; c + UNROLL <= c_end; c += UNROLL) group(c, std::false_type{});\n'
-     '    if (c < c_end) group(c, std::true_type{});\n',
-     '    ST_MARK(3);\n    if (threadIdx.x == 0) trow[11] = clock64();\n    int c = 0;\n'
-     '    for (; c + UNROLL <= c_end; c += UNROLL) group(c, std::false_type{});\n'
-     '    if (c < c_end) group(c, std::true_type{});\n    ST_MARK(4);\n    if (threadIdx.x == 0) trow[12] = clock64();\n', False),
+    ('    int c = 0;\n    if (UNROLL <= c_end) {\n',
+     '    ST_MARK(3);\n    if (threadIdx.x == 0) trow[11] = clock64();\n    int c = 0;\n    if (UNROLL <= c_end) {\n', False),
+    ('    if (c < c_end) group(c, std::true_type{}, std::false_type{});\n',
+     '    if (c < c_end) group(c, std::true_type{}, std::false_type{});\n    ST_MARK(4);\n'
+     '    if (threadIdx.x == 0) trow[12] = clock64();\n', False),
     ('        const u32x2 run = *(lds_cu32x2 *)',
      '        unsigned long long *const trow = sp.trace + (size_t)item * 16;\n        ST_MARK(0);\n'
      '        const u32x2 run = *(lds_cu32x2 *)', False),
