@@ -539,22 +539,25 @@ __device__ __forceinline__ void stack_tile(const StackLayer &layer, const int ti
             u32x4 al[4];
 #pragma unroll
             for (int j = 0; j < 4; ++j) al[j] = *(lds_cu32x4 *)(uintptr_t)(lds0 + ST_ALPHA_OFF + (uint32_t)(cb * 32 + 8 * j + 4 * h_f) * 4u);
+            u32x2 cr[PB][4];
 #pragma unroll
-            for (int pb = 0; pb < PB; ++pb) {
-                u32x2 cr[4];
+            for (int pb = 0; pb < PB; ++pb)
 #pragma unroll
                 for (int j = 0; j < 4; ++j)
-                    cr[j] = *(lds_cu32x2 *)(uintptr_t)(lds0 + ST_CORR_OFF + (uint32_t)(ptype[pb] * NCH + cb * 32 + 8 * j + 4 * h_f) * 2u);
+                    cr[pb][j] = *(lds_cu32x2 *)(uintptr_t)(lds0 + ST_CORR_OFF + (uint32_t)(ptype[pb] * NCH + cb * 32 + 8 * j + 4 * h_f) * 2u);
+            // a channel's pixel blocks one after the other: consecutive blocks of an image are adjacent in its plane
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int cs = co0 + cb * 32 + 8 * (r / 4) + r % 4;      // wave-uniform part of the channel
+            for (int r = 0; r < 16; ++r) {
+                const int cs = co0 + cb * 32 + 8 * (r / 4) + r % 4;      // wave-uniform part of the channel
+#pragma unroll
+                for (int pb = 0; pb < PB; ++pb) {
                     // channels past C_out (padding of the last block) are not stored: their lanes get an offset outside the tensor
                     const uint32_t at = FULL || cb * 32 + 8 * (r / 4) + r % 4 < ch_left ? yoff[pb] : 0xffffffffu;
-                    __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(value(cb, pb, r, al, cr)), yres, (int)at,
+                    __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(value(cb, pb, r, al, cr[pb])), yres, (int)at,
                                                           (int)((uint32_t)cs * chan_bytes), 2 /* nt */);
                 }
-                __builtin_amdgcn_sched_barrier(0);
             }
+            __builtin_amdgcn_sched_barrier(0);
         }
     };
     if (co0 + NCH <= L.C_out) finish(std::true_type{});
